@@ -1,0 +1,152 @@
+/*
+ * pqcache.h -- C ABI of libpqcache: the decode-time hot path of PQ-based KV-cache
+ * retrieval (PQCache, arxiv 2407.12820) for one attention layer on one AMD MI355X.
+ *
+ * What one decode step computes (paper, Section 3.1 steps 4-6; Algorithm 2,
+ * "PQSearch", "AllKV = InitKV + TopkKV + LocalKV", attention):
+ *
+ *   1. look-up table: the decode query, cut into M partitions, is multiplied with
+ *      every PQ centroid of its partition (Section 2.2, search phase);
+ *   2. code scan: every cached token's approximate score is the sum over the
+ *      partitions of the table entries its PQ code names;
+ *   3. top-k: the K middle tokens with the largest approximate scores;
+ *   4. the attended set is the initial window, those K tokens, the local window;
+ *   5. softmax attention of every query head over the K/V rows of that set only.
+ *
+ * With grouped-query attention the G = Hq/Hkv query heads that share a KV head
+ * share one selection: the group's score is the sum of its heads' scores.
+ *
+ * Notation: B sequences, Hq query heads, Hkv key/value heads, D = d_h head
+ * dimension, N cached tokens, M partitions, C centroids per partition, Dm = D/M,
+ * I/L initial/local window sizes, K retrieved tokens.  "Middle" tokens are
+ * [I, N-L).  A "unit" is one (sequence, KV head) pair; units are independent.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers to contiguous row-major memory owned
+ *     by the caller; inputs are read-only, outputs are fully overwritten.  16-byte
+ *     alignment is required for every tensor pointer.
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls
+ *     only enqueue work on that stream: they never synchronise the host, never
+ *     allocate or free device memory.  Results are ready when the stream reaches
+ *     the end of the enqueued work.
+ *   - Return value: PQC_OK (0) or a negative pqc_status.  Nothing throws or aborts.
+ *   - A context is bound to one configuration and one workspace; it is not
+ *     thread-safe, and calls that share a context must be ordered on one stream.
+ *     Workspace contents are private to the library between calls.
+ *   - Codes must satisfy code < C.  Tensors must hold finite values; the ranking
+ *     of NaN scores is unspecified.
+ *
+ * Floating-point contract of the ranking (steps 1-3).  Scores are evaluated in
+ * fp32 in this fixed order, so that a selection is reproducible bit for bit:
+ *   qs[d]      = ((q_0[d] + q_1[d]) + ...)   over the group's heads, in head order;
+ *   table[j,c] = fused multiply-add chain over e = 0..Dm-1 of qs[j*Dm+e]*cent[j,c,e],
+ *                starting from 0;
+ *   score[t]   = ((table[0,code0] + table[1,code1]) + table[2,code2]) + ...
+ * Ties are broken towards the lower token index.
+ */
+#ifndef PQCACHE_H_
+#define PQCACHE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pqc_ctx pqc_ctx; /* opaque, host memory, owned by the library */
+
+typedef enum pqc_status {
+  PQC_OK = 0,
+  PQC_EINVAL = -1,      /* null pointer, malformed or inconsistent configuration   */
+  PQC_EUNSUPPORTED = -2,/* well-formed configuration outside the supported shapes   */
+  PQC_EWORKSPACE = -3,  /* workspace missing, misaligned or smaller than required   */
+  PQC_EHIP = -4         /* a HIP call failed; see pqc_last_hip_error()              */
+} pqc_status;
+
+typedef enum pqc_dtype { PQC_F32 = 0, PQC_BF16 = 1 } pqc_dtype;
+
+/* Shape of one decode step.  Supported: head_dim = 128; pq_m in {1,2,4,8};
+ * 1 <= pq_centroids <= 256; n_q_heads / n_kv_heads in {1,2,4,8};
+ * n_init + topk + n_local <= n_tokens and >= 1; n_tokens < 2^24. */
+typedef struct pqc_config {
+  int32_t batch;         /* B                                                        */
+  int32_t n_q_heads;     /* Hq                                                       */
+  int32_t n_kv_heads;    /* Hkv, divides Hq                                          */
+  int32_t head_dim;      /* D                                                        */
+  int32_t n_tokens;      /* N, tokens in the K/V cache (same for every sequence)     */
+  int32_t pq_m;          /* M, divides D                                             */
+  int32_t pq_centroids;  /* C = 2^b (any value up to 256 is accepted)                */
+  int32_t topk;          /* K, retrieved middle tokens per KV head                   */
+  int32_t n_init;        /* I, always-attended first tokens                          */
+  int32_t n_local;       /* L, always-attended most recent tokens                    */
+  int32_t kv_dtype;      /* pqc_dtype of q, k_cache and v_cache                      */
+  float softmax_scale;   /* factor on q.k before softmax; <= 0 means 1/sqrt(D)       */
+} pqc_config;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int pqc_version(void);
+
+/* Static, human-readable text for a status code. */
+const char* pqc_strerror(int status);
+
+/* Bytes of device workspace a context of this configuration needs
+ * (0 when the configuration is invalid or unsupported). */
+size_t pqc_workspace_bytes(const pqc_config* cfg);
+
+/* Create a context.  `workspace` is device memory of at least
+ * pqc_workspace_bytes(cfg) bytes, 256-byte aligned, which must stay valid and
+ * untouched by the caller until pqc_destroy.  Host-only: enqueues nothing. */
+int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t workspace_bytes);
+
+/* Free the host-side context (the workspace stays the caller's). NULL is allowed. */
+void pqc_destroy(pqc_ctx* ctx);
+
+/* hipError_t value of the last failed HIP call on this context (0 if none). */
+int pqc_last_hip_error(const pqc_ctx* ctx);
+
+/*
+ * The whole decode step, steps 1-5 above (Algorithm 2: PQSearch, fetch of the
+ * retrieved K/V, attention over initial + retrieved + local tokens).
+ *
+ *   q          [B][Hq][D]            kv_dtype   decode query of every head
+ *   centroids  [B][Hkv][M][C][Dm]    f32        PQ centroids of the keys
+ *   codes      [B][Hkv][N][M]        uint8      PQ codes of the keys
+ *   k_cache    [B][Hkv][N][D]        kv_dtype
+ *   v_cache    [B][Hkv][N][D]        kv_dtype
+ *   out_idx    [B][Hkv][I+K+L]       int32      attended tokens: 0..I-1, then the K
+ *                                               retrieved tokens in ascending order
+ *                                               of (admission class, token index) --
+ *                                               compare as a set --, then N-L..N-1
+ *   out_attn   [B][Hq][D]            f32        attention output
+ *
+ * Codes of tokens inside the initial and local windows are ignored.
+ */
+int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes,
+               const void* k_cache, const void* v_cache, int32_t* out_idx, float* out_attn,
+               void* stream);
+
+/* ---- the same path, one stage at a time (unit tests, per-kernel profiling) ---- */
+
+/* Step 1 (Section 2.2 search / Section 3.1 step 4, "multiply the query with the PQ
+ * centroids"):  table [B][Hkv][M][C] f32, per KV head (group-summed query). */
+int pqc_lut(pqc_ctx* ctx, const void* q, const float* centroids, float* table, void* stream);
+
+/* Step 2 (Section 3.1 step 4, "gather and reduce using PQ codes"):
+ * scores [B][Hkv][N] f32; positions inside the initial and local windows hold -inf. */
+int pqc_scan(pqc_ctx* ctx, const float* table, const uint8_t* codes, float* scores, void* stream);
+
+/* Steps 3-4 (Section 3.1 steps 4-5, Section 3.2 top-k): from scores [B][Hkv][N] to
+ * out_idx [B][Hkv][I+K+L] as in pqc_decode.  Window positions are not read. */
+int pqc_topk(pqc_ctx* ctx, const float* scores, int32_t* out_idx, void* stream);
+
+/* Step 5 (Section 2.1 attention restricted to the retrieved set, Section 3.1 step
+ * 6): idx [B][Hkv][I+K+L] int32, every entry in [0, N) -> out_attn [B][Hq][D] f32.
+ * Each listed K/V row is read once and shared by the G heads of its group. */
+int pqc_gather_attn(pqc_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
+                    const int32_t* idx, float* out_attn, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PQCACHE_H_ */

@@ -1,0 +1,208 @@
+"""ctypes binding over the C ABI of libpqcache (include/pqcache.h).
+
+Argument marshalling only: every step of the decode path runs in the HIP kernels of
+the shared library.  PyTorch supplies device memory and the current stream.  There
+is no fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch
+
+from .workloads import Workload
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpqcache.so")
+
+PQC_F32, PQC_BF16 = 0, 1
+STATUS = {0: "PQC_OK", -1: "PQC_EINVAL", -2: "PQC_EUNSUPPORTED", -3: "PQC_EWORKSPACE", -4: "PQC_EHIP"}
+
+
+class Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("batch", "n_q_heads", "n_kv_heads", "head_dim", "n_tokens", "pq_m",
+                                         "pq_centroids", "topk", "n_init", "n_local", "kv_dtype")] + [
+                                             ("softmax_scale", C.c_float)]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libpqcache.so; raises if it has not been built (there is no other path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2407_12820_amd.build` "
+                           "(the decode path has no CPU or PyTorch fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, cp = C.c_void_p, C.POINTER(Config)
+    lib.pqc_version.restype = C.c_int
+    lib.pqc_strerror.restype = C.c_char_p
+    lib.pqc_strerror.argtypes = [C.c_int]
+    lib.pqc_workspace_bytes.restype = C.c_size_t
+    lib.pqc_workspace_bytes.argtypes = [cp]
+    lib.pqc_create.restype = C.c_int
+    lib.pqc_create.argtypes = [C.POINTER(vp), cp, vp, C.c_size_t]
+    lib.pqc_destroy.restype = None
+    lib.pqc_destroy.argtypes = [vp]
+    lib.pqc_last_hip_error.restype = C.c_int
+    lib.pqc_last_hip_error.argtypes = [vp]
+    lib.pqc_decode.restype = C.c_int
+    lib.pqc_decode.argtypes = [vp] * 9
+    lib.pqc_lut.restype = C.c_int
+    lib.pqc_lut.argtypes = [vp] * 5
+    lib.pqc_scan.restype = C.c_int
+    lib.pqc_scan.argtypes = [vp] * 5
+    lib.pqc_topk.restype = C.c_int
+    lib.pqc_topk.argtypes = [vp] * 4
+    lib.pqc_gather_attn.restype = C.c_int
+    lib.pqc_gather_attn.argtypes = [vp] * 7
+    _lib = lib
+    return lib
+
+
+def make_config(w: Workload, softmax_scale: float = 0.0) -> Config:
+    return Config(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_tokens, w.pq_m, w.pq_centroids, w.topk,
+                  w.n_init, w.n_local, PQC_F32 if w.dtype == "f32" else PQC_BF16, softmax_scale)
+
+
+class PQCacheError(RuntimeError):
+    def __init__(self, status: int, what: str, hip: int = 0):
+        self.status = status
+        msg = load().pqc_strerror(status).decode()
+        super().__init__(f"{what}: {STATUS.get(status, status)} ({msg})" + (f", hipError {hip}" if hip else ""))
+
+
+class PQCache:
+    """One decode context: a configuration plus its device workspace."""
+
+    def __init__(self, w: Workload, device: str = "cuda:0", softmax_scale: float = 0.0):
+        self.lib = load()
+        self.w = w
+        self.device = torch.device(device)
+        self.cfg = make_config(w, softmax_scale)
+        nbytes = self.lib.pqc_workspace_bytes(C.byref(self.cfg))
+        if nbytes == 0:
+            # let pqc_create say why
+            h = C.c_void_p()
+            raise PQCacheError(self.lib.pqc_create(C.byref(h), C.byref(self.cfg), None, 0), "pqc_create")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.handle = C.c_void_p()
+        rc = self.lib.pqc_create(C.byref(self.handle), C.byref(self.cfg), self.workspace.data_ptr(), nbytes)
+        if rc != 0:
+            raise PQCacheError(rc, "pqc_create")
+        self.kv_torch = torch.float32 if w.dtype == "f32" else torch.bfloat16
+
+    def close(self) -> None:
+        if getattr(self, "handle", None) is not None and self.handle.value:
+            self.lib.pqc_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- marshalling helpers
+    def _ptr(self, t: torch.Tensor, dtype, shape) -> int:
+        if t.device != self.device or not t.is_contiguous():
+            raise ValueError("tensor must be contiguous and on the context's device")
+        if t.dtype != dtype or tuple(t.shape) != tuple(shape):
+            raise ValueError(f"expected {dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+        return t.data_ptr()
+
+    def _stream(self, stream) -> int:
+        s = stream if stream is not None else torch.cuda.current_stream(self.device)
+        return s.cuda_stream
+
+    def _check(self, rc: int, what: str) -> None:
+        if rc != 0:
+            raise PQCacheError(rc, what, self.lib.pqc_last_hip_error(self.handle))
+
+    # -- shapes
+    @property
+    def shapes(self):
+        w = self.w
+        return {
+            "q": (w.batch, w.n_q_heads, w.head_dim),
+            "centroids": (w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids, w.sub_dim),
+            "codes": (w.batch, w.n_kv_heads, w.n_tokens, w.pq_m),
+            "kv": (w.batch, w.n_kv_heads, w.n_tokens, w.head_dim),
+            "idx": (w.batch, w.n_kv_heads, w.n_selected),
+            "out": (w.batch, w.n_q_heads, w.head_dim),
+            "table": (w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids),
+            "scores": (w.batch, w.n_kv_heads, w.n_tokens),
+        }
+
+    def empty_outputs(self) -> Tuple[torch.Tensor, torch.Tensor]:
+        sh = self.shapes
+        return (torch.empty(sh["idx"], dtype=torch.int32, device=self.device),
+                torch.empty(sh["out"], dtype=torch.float32, device=self.device))
+
+    # -- entry points (same names as the C ABI)
+    def decode(self, q, centroids, codes, k_cache, v_cache, out_idx=None, out_attn=None, stream=None):
+        sh = self.shapes
+        if out_idx is None or out_attn is None:
+            out_idx, out_attn = self.empty_outputs()
+        rc = self.lib.pqc_decode(self.handle, self._ptr(q, self.kv_torch, sh["q"]),
+                                 self._ptr(centroids, torch.float32, sh["centroids"]),
+                                 self._ptr(codes, torch.uint8, sh["codes"]),
+                                 self._ptr(k_cache, self.kv_torch, sh["kv"]), self._ptr(v_cache, self.kv_torch, sh["kv"]),
+                                 self._ptr(out_idx, torch.int32, sh["idx"]), self._ptr(out_attn, torch.float32, sh["out"]),
+                                 self._stream(stream))
+        self._check(rc, "pqc_decode")
+        return out_idx, out_attn
+
+    def lut(self, q, centroids, table=None, stream=None):
+        sh = self.shapes
+        if table is None:
+            table = torch.empty(sh["table"], dtype=torch.float32, device=self.device)
+        rc = self.lib.pqc_lut(self.handle, self._ptr(q, self.kv_torch, sh["q"]),
+                              self._ptr(centroids, torch.float32, sh["centroids"]),
+                              self._ptr(table, torch.float32, sh["table"]), self._stream(stream))
+        self._check(rc, "pqc_lut")
+        return table
+
+    def scan(self, table, codes, scores=None, stream=None):
+        sh = self.shapes
+        if scores is None:
+            scores = torch.empty(sh["scores"], dtype=torch.float32, device=self.device)
+        rc = self.lib.pqc_scan(self.handle, self._ptr(table, torch.float32, sh["table"]),
+                               self._ptr(codes, torch.uint8, sh["codes"]),
+                               self._ptr(scores, torch.float32, sh["scores"]), self._stream(stream))
+        self._check(rc, "pqc_scan")
+        return scores
+
+    def topk(self, scores, out_idx=None, stream=None):
+        sh = self.shapes
+        if out_idx is None:
+            out_idx = torch.empty(sh["idx"], dtype=torch.int32, device=self.device)
+        rc = self.lib.pqc_topk(self.handle, self._ptr(scores, torch.float32, sh["scores"]),
+                               self._ptr(out_idx, torch.int32, sh["idx"]), self._stream(stream))
+        self._check(rc, "pqc_topk")
+        return out_idx
+
+    def gather_attn(self, q, k_cache, v_cache, idx, out_attn=None, stream=None):
+        sh = self.shapes
+        if out_attn is None:
+            out_attn = torch.empty(sh["out"], dtype=torch.float32, device=self.device)
+        rc = self.lib.pqc_gather_attn(self.handle, self._ptr(q, self.kv_torch, sh["q"]),
+                                      self._ptr(k_cache, self.kv_torch, sh["kv"]), self._ptr(v_cache, self.kv_torch, sh["kv"]),
+                                      self._ptr(idx, torch.int32, sh["idx"]), self._ptr(out_attn, torch.float32, sh["out"]),
+                                      self._stream(stream))
+        self._check(rc, "pqc_gather_attn")
+        return out_attn
+
+
+def to_device(a, dtype: str, device="cuda:0") -> torch.Tensor:
+    """Upload a numpy array produced by `workloads` (bf16 arrives as uint16 bit patterns)."""
+    import numpy as np
+
+    if a.dtype == np.uint16 and dtype == "bf16":
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)

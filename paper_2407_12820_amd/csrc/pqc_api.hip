@@ -1,0 +1,317 @@
+// Host side of libpqcache: the C ABI of include/pqcache.h, configuration checks,
+// workspace carving and kernel dispatch.  No device memory is allocated here and
+// nothing synchronises the host: every entry point only enqueues kernels.
+#include "../../include/pqcache.h"
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "pqc_kernels.h"
+
+namespace {
+
+using namespace pqc;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Plan {
+  Shape s;
+  size_t off_ctl, off_lut, off_hist, off_stage, off_cnt, off_part, total;
+};
+
+int env_int(const char* name, int fallback) {
+  const char* v = std::getenv(name);
+  if (!v || !*v) return fallback;
+  const int x = std::atoi(v);
+  return x > 0 ? x : fallback;
+}
+
+int make_plan(const pqc_config* c, Plan* p) {
+  if (!c) return PQC_EINVAL;
+  if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1 || c->n_tokens < 1 || c->pq_m < 1 ||
+      c->pq_centroids < 1 || c->topk < 0 || c->n_init < 0 || c->n_local < 0)
+    return PQC_EINVAL;
+  if (c->n_q_heads % c->n_kv_heads || c->head_dim % c->pq_m) return PQC_EINVAL;
+  if ((long long)c->n_init + c->topk + c->n_local > c->n_tokens || c->n_init + c->topk + c->n_local < 1) return PQC_EINVAL;
+  if (c->kv_dtype != PQC_F32 && c->kv_dtype != PQC_BF16) return PQC_EINVAL;
+  if (!(c->softmax_scale == c->softmax_scale) || std::isinf(c->softmax_scale)) return PQC_EINVAL;
+  const int G = c->n_q_heads / c->n_kv_heads;
+  if (c->head_dim != kD) return PQC_EUNSUPPORTED;
+  if (c->pq_m != 1 && c->pq_m != 2 && c->pq_m != 4 && c->pq_m != 8) return PQC_EUNSUPPORTED;
+  if (c->pq_centroids > 256) return PQC_EUNSUPPORTED;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return PQC_EUNSUPPORTED;
+  if (c->n_tokens > (1 << 22)) return PQC_EUNSUPPORTED;
+  if ((long long)c->batch * c->n_kv_heads > 65535) return PQC_EUNSUPPORTED;
+
+  Shape& s = p->s;
+  s.B = c->batch; s.Hq = c->n_q_heads; s.Hkv = c->n_kv_heads; s.G = G; s.N = c->n_tokens;
+  s.M = c->pq_m; s.C = c->pq_centroids; s.Dm = c->head_dim / c->pq_m;
+  s.K = c->topk; s.I = c->n_init; s.L = c->n_local; s.Ktot = s.I + s.K + s.L;
+  const float scale = c->softmax_scale > 0.0f ? c->softmax_scale : 1.0f / std::sqrt((float)c->head_dim);
+  s.scale_log2e = scale * 1.4426950408889634f;
+  const long long units = (long long)s.B * s.Hkv;
+
+  // histogram kernel: few, large workgroups (contended bins serialise per workgroup)
+  int tokA = env_int("PQC_TOK_A", 0);
+  if (!tokA) {
+    tokA = 4096;
+    while (tokA < 16384 && ((s.N + tokA - 1) / tokA) > 8) tokA *= 2;
+    while ((s.N + tokA - 1) / tokA > 64) tokA *= 2;
+  }
+  s.tokA = tokA; s.nblkA = (s.N + tokA - 1) / tokA;
+  // select kernel: aim for a few workgroups per compute unit
+  int tokC = env_int("PQC_TOK_C", 0);
+  if (!tokC) {
+    tokC = 2048;
+    while (tokC < 8192 && units * ((s.N + tokC - 1) / tokC) > 1024) tokC *= 2;
+  }
+  if (tokC % 256 || tokC > 8192) return PQC_EINVAL;
+  s.tokC = tokC; s.nblkC = (s.N + tokC - 1) / tokC;
+  s.rowsP = env_int("PQC_ROWS_P", 256);
+  s.nblkP = (s.Ktot + s.rowsP - 1) / s.rowsP;
+  s.npart = s.nblkC > s.nblkP ? s.nblkC : s.nblkP;
+
+  size_t off = 0;
+  p->off_ctl = off;   off = align_up(off + sizeof(float2) * units);
+  p->off_lut = off;   off = align_up(off + sizeof(float) * units * s.M * s.C);
+  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * units * kNB);
+  p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * s.nblkC * s.tokC);
+  p->off_cnt = off;   off = align_up(off + sizeof(int2) * units * s.nblkC);
+  p->off_part = off;  off = align_up(off + sizeof(float) * units * s.npart * s.G * (kD + 2));
+  p->total = off;
+  return PQC_OK;
+}
+
+}  // namespace
+
+struct pqc_ctx {
+  pqc_config cfg;
+  Plan plan;
+  Workspace ws;
+  bool hist_clean;  // the histogram is known to be all zero
+  int last_hip;
+};
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_launch(pqc_ctx* ctx) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    ctx->last_hip = (int)e;
+    ctx->hist_clean = false;
+    return PQC_EHIP;
+  }
+  return PQC_OK;
+}
+
+int ensure_clean_hist(pqc_ctx* ctx, hipStream_t st) {
+  if (ctx->hist_clean) return PQC_OK;
+  const Shape& s = ctx->plan.s;
+  const size_t n = (size_t)s.B * s.Hkv * kNB;
+  hipLaunchKernelGGL(reset_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, ctx->ws.hist, n);
+  return check_launch(ctx);
+}
+
+// ---- template dispatch -------------------------------------------------------
+template <typename T, int G, int M>
+void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const void* k,
+                       const void* v, int32_t* out_idx, float* out_attn, hipStream_t st) {
+  const Shape& s = ctx->plan.s;
+  const unsigned units = (unsigned)(s.B * s.Hkv);
+  const T* qt = static_cast<const T*>(q);
+  const T* kt = static_cast<const T*>(k);
+  const T* vt = static_cast<const T*>(v);
+  hipLaunchKernelGGL((hist_kernel<T, CodeSource<M>>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, qt, cent,
+                     static_cast<const void*>(codes));
+  hipLaunchKernelGGL((select_kernel<T, G, CodeSource<M>, true>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(int), st,
+                     s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));
+  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(1, units), dim3(512), 2 * (s.nblkC + 1) * sizeof(int), st, s,
+                     ctx->ws, qt, kt, vt, out_idx, out_attn);
+}
+
+template <typename T, int G>
+void launch_decode_tg(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const void* k, const void* v,
+                      int32_t* out_idx, float* out_attn, hipStream_t st) {
+  switch (ctx->plan.s.M) {
+    case 1: launch_decode_tgm<T, G, 1>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
+    case 2: launch_decode_tgm<T, G, 2>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
+    case 4: launch_decode_tgm<T, G, 4>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
+    default: launch_decode_tgm<T, G, 8>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
+  }
+}
+
+template <typename T>
+void launch_decode_t(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const void* k, const void* v,
+                     int32_t* out_idx, float* out_attn, hipStream_t st) {
+  switch (ctx->plan.s.G) {
+    case 1: launch_decode_tg<T, 1>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
+    case 2: launch_decode_tg<T, 2>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
+    case 4: launch_decode_tg<T, 4>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
+    default: launch_decode_tg<T, 8>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
+  }
+}
+
+template <typename T, int G>
+void launch_attn_tg(pqc_ctx* ctx, const void* q, const void* k, const void* v, const int32_t* idx, float* out,
+                    hipStream_t st) {
+  const Shape& s = ctx->plan.s;
+  const unsigned units = (unsigned)(s.B * s.Hkv);
+  hipLaunchKernelGGL((attn_list_kernel<T, G>), dim3(s.nblkP, units), dim3(256), 0, st, s, ctx->ws,
+                     static_cast<const T*>(q), static_cast<const T*>(k), static_cast<const T*>(v), idx);
+  hipLaunchKernelGGL((merge_kernel<G>), dim3(1, units), dim3(256), 0, st, s, ctx->ws, s.nblkP, out);
+}
+
+template <typename T>
+void launch_attn_t(pqc_ctx* ctx, const void* q, const void* k, const void* v, const int32_t* idx, float* out,
+                   hipStream_t st) {
+  switch (ctx->plan.s.G) {
+    case 1: launch_attn_tg<T, 1>(ctx, q, k, v, idx, out, st); break;
+    case 2: launch_attn_tg<T, 2>(ctx, q, k, v, idx, out, st); break;
+    case 4: launch_attn_tg<T, 4>(ctx, q, k, v, idx, out, st); break;
+    default: launch_attn_tg<T, 8>(ctx, q, k, v, idx, out, st); break;
+  }
+}
+
+template <int M>
+void launch_scan_m(pqc_ctx* ctx, const float* table, const uint8_t* codes, float* scores, hipStream_t st) {
+  const Shape& s = ctx->plan.s;
+  hipLaunchKernelGGL((scan_kernel<M>), dim3((s.N + 2047) / 2048, (unsigned)(s.B * s.Hkv)), dim3(256), 0, st, s, table,
+                     codes, scores);
+}
+
+}  // namespace
+
+extern "C" {
+
+int pqc_version(void) { return 100; }
+
+const char* pqc_strerror(int status) {
+  switch (status) {
+    case PQC_OK: return "ok";
+    case PQC_EINVAL: return "invalid argument or configuration";
+    case PQC_EUNSUPPORTED: return "configuration outside the supported shapes";
+    case PQC_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case PQC_EHIP: return "HIP call failed";
+    default: return "unknown status";
+  }
+}
+
+size_t pqc_workspace_bytes(const pqc_config* cfg) {
+  Plan p;
+  if (make_plan(cfg, &p) != PQC_OK) return 0;
+  return p.total;
+}
+
+int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t workspace_bytes) {
+  if (!out) return PQC_EINVAL;
+  *out = nullptr;
+  Plan p;
+  const int rc = make_plan(cfg, &p);
+  if (rc != PQC_OK) return rc;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) || workspace_bytes < p.total) return PQC_EWORKSPACE;
+  pqc_ctx* ctx = new (std::nothrow) pqc_ctx;
+  if (!ctx) return PQC_EINVAL;
+  ctx->cfg = *cfg;
+  ctx->plan = p;
+  char* base = static_cast<char*>(workspace);
+  ctx->ws.ctl = reinterpret_cast<float2*>(base + p.off_ctl);
+  ctx->ws.lut = reinterpret_cast<float*>(base + p.off_lut);
+  ctx->ws.hist = reinterpret_cast<unsigned*>(base + p.off_hist);
+  ctx->ws.stage = reinterpret_cast<unsigned long long*>(base + p.off_stage);
+  ctx->ws.stage_cnt = reinterpret_cast<int2*>(base + p.off_cnt);
+  ctx->ws.partials = reinterpret_cast<float*>(base + p.off_part);
+  ctx->hist_clean = false;
+  ctx->last_hip = 0;
+  *out = ctx;
+  return PQC_OK;
+}
+
+void pqc_destroy(pqc_ctx* ctx) { delete ctx; }
+
+int pqc_last_hip_error(const pqc_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes, const void* k_cache,
+               const void* v_cache, int32_t* out_idx, float* out_attn, void* stream) {
+  if (!ctx || !q || !centroids || !codes || !k_cache || !v_cache || !out_idx || !out_attn) return PQC_EINVAL;
+  if (!aligned16(q) || !aligned16(centroids) || !aligned16(codes) || !aligned16(k_cache) || !aligned16(v_cache) ||
+      !aligned16(out_idx) || !aligned16(out_attn))
+    return PQC_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = ensure_clean_hist(ctx, st);
+  if (rc != PQC_OK) return rc;
+  ctx->hist_clean = false;
+  if (ctx->cfg.kv_dtype == PQC_F32)
+    launch_decode_t<float>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st);
+  else
+    launch_decode_t<bf16_t>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st);
+  rc = check_launch(ctx);
+  if (rc == PQC_OK) ctx->hist_clean = true;  // finalize_kernel re-zeroes the histogram
+  return rc;
+}
+
+int pqc_lut(pqc_ctx* ctx, const void* q, const float* centroids, float* table, void* stream) {
+  if (!ctx || !q || !centroids || !table) return PQC_EINVAL;
+  if (!aligned16(q) || !aligned16(centroids) || !aligned16(table)) return PQC_EINVAL;
+  const Shape& s = ctx->plan.s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const dim3 grid(1, (unsigned)(s.B * s.Hkv));
+  if (ctx->cfg.kv_dtype == PQC_F32)
+    hipLaunchKernelGGL((lut_kernel<float>), grid, dim3(256), 0, st, s, static_cast<const float*>(q), centroids, table);
+  else
+    hipLaunchKernelGGL((lut_kernel<bf16_t>), grid, dim3(256), 0, st, s, static_cast<const bf16_t*>(q), centroids, table);
+  return check_launch(ctx);
+}
+
+int pqc_scan(pqc_ctx* ctx, const float* table, const uint8_t* codes, float* scores, void* stream) {
+  if (!ctx || !table || !codes || !scores) return PQC_EINVAL;
+  if (!aligned16(table) || !aligned16(codes) || !aligned16(scores)) return PQC_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  switch (ctx->plan.s.M) {
+    case 1: launch_scan_m<1>(ctx, table, codes, scores, st); break;
+    case 2: launch_scan_m<2>(ctx, table, codes, scores, st); break;
+    case 4: launch_scan_m<4>(ctx, table, codes, scores, st); break;
+    default: launch_scan_m<8>(ctx, table, codes, scores, st); break;
+  }
+  return check_launch(ctx);
+}
+
+int pqc_topk(pqc_ctx* ctx, const float* scores, int32_t* out_idx, void* stream) {
+  if (!ctx || !scores || !out_idx) return PQC_EINVAL;
+  if (!aligned16(scores) || !aligned16(out_idx)) return PQC_EINVAL;
+  const Shape& s = ctx->plan.s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = ensure_clean_hist(ctx, st);
+  if (rc != PQC_OK) return rc;
+  ctx->hist_clean = false;
+  const unsigned units = (unsigned)(s.B * s.Hkv);
+  const float* nof = nullptr;
+  hipLaunchKernelGGL(minmax_kernel, dim3(1, units), dim3(1024), 0, st, s, scores, ctx->ws.ctl);
+  hipLaunchKernelGGL((hist_kernel<float, ScoreSource>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, nof, nof,
+                     static_cast<const void*>(scores));
+  hipLaunchKernelGGL((select_kernel<float, 1, ScoreSource, false>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(int), st,
+                     s, ctx->ws, nof, nof, nof, static_cast<const void*>(scores));
+  hipLaunchKernelGGL((finalize_kernel<float, 1, false>), dim3(1, units), dim3(512), 2 * (s.nblkC + 1) * sizeof(int), st, s,
+                     ctx->ws, nof, nof, nof, out_idx, static_cast<float*>(nullptr));
+  rc = check_launch(ctx);
+  if (rc == PQC_OK) ctx->hist_clean = true;
+  return rc;
+}
+
+int pqc_gather_attn(pqc_ctx* ctx, const void* q, const void* k_cache, const void* v_cache, const int32_t* idx,
+                    float* out_attn, void* stream) {
+  if (!ctx || !q || !k_cache || !v_cache || !idx || !out_attn) return PQC_EINVAL;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(idx) || !aligned16(out_attn)) return PQC_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (ctx->cfg.kv_dtype == PQC_F32)
+    launch_attn_t<float>(ctx, q, k_cache, v_cache, idx, out_attn, st);
+  else
+    launch_attn_t<bf16_t>(ctx, q, k_cache, v_cache, idx, out_attn, st);
+  return check_launch(ctx);
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the
+header declares, and its host logic (configuration checks, workspace sizing) behaves."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2407_12820_amd import binding, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(pqc_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    names = _declared()
+    assert {"pqc_decode", "pqc_lut", "pqc_scan", "pqc_topk", "pqc_gather_attn", "pqc_create", "pqc_destroy",
+            "pqc_workspace_bytes", "pqc_strerror", "pqc_version", "pqc_last_hip_error"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_messages():
+    lib = binding.load()
+    assert lib.pqc_version() >= 100
+    assert lib.pqc_strerror(0) == b"ok"
+    assert len({lib.pqc_strerror(s) for s in (0, -1, -2, -3, -4, -99)}) == 6
+
+
+def test_workspace_bytes_for_the_benchmark_shapes():
+    lib = binding.load()
+    for name in wl.CONFIG_ORDER:
+        w = wl.CONFIGS[name]
+        n = lib.pqc_workspace_bytes(C.byref(binding.make_config(w)))
+        assert n > 0 and n % 256 == 0
+        # a few words per cached token at most (staging of selected ids / candidates)
+        assert n < 64 * w.batch * w.n_kv_heads * w.n_tokens + (1 << 22)
+
+
+@pytest.mark.parametrize("change,status", [
+    (dict(batch=0), -1), (dict(n_tokens=0), -1), (dict(n_kv_heads=3), -1), (dict(pq_m=3), -1),
+    (dict(topk=4096), -1), (dict(topk=0, n_init=0, n_local=0), -1), (dict(dtype_code=7), -1),
+    (dict(head_dim=64), -2), (dict(pq_centroids=257), -2), (dict(n_q_heads=16, n_kv_heads=1), -2),
+    (dict(pq_m=16), -2), (dict(n_tokens=(1 << 22) + 1), -2),
+])
+def test_rejected_configurations(change, status):
+    lib = binding.load()
+    cfg = binding.make_config(wl.CONFIGS["tiny_f32"])
+    for k, v in change.items():
+        setattr(cfg, "kv_dtype" if k == "dtype_code" else k, v)
+    assert lib.pqc_workspace_bytes(C.byref(cfg)) == 0
+    h = C.c_void_p(123)
+    assert lib.pqc_create(C.byref(h), C.byref(cfg), C.c_void_p(256), 1 << 30) == status
+    assert not h.value
+
+
+def test_create_checks_workspace_and_null_arguments():
+    lib = binding.load()
+    cfg = binding.make_config(wl.CONFIGS["tiny_f32"])
+    need = lib.pqc_workspace_bytes(C.byref(cfg))
+    h = C.c_void_p()
+    assert lib.pqc_create(C.byref(h), C.byref(cfg), None, need) == -3
+    assert lib.pqc_create(C.byref(h), C.byref(cfg), C.c_void_p(4096), need - 1) == -3
+    assert lib.pqc_create(C.byref(h), C.byref(cfg), C.c_void_p(4096 + 16), need) == -3
+    assert lib.pqc_create(None, C.byref(cfg), C.c_void_p(4096), need) == -1
+    assert lib.pqc_create(C.byref(h), None, C.c_void_p(4096), need) == -1
+    # a well-formed create is host-only: no device call happens until an entry point is used
+    assert lib.pqc_create(C.byref(h), C.byref(cfg), C.c_void_p(4096), need) == 0 and h.value
+    assert lib.pqc_decode(h, None, None, None, None, None, None, None, None) == -1
+    assert lib.pqc_decode(None, *([C.c_void_p(16)] * 7), None) == -1
+    assert lib.pqc_topk(h, C.c_void_p(8), C.c_void_p(16), None) == -1  # misaligned pointer
+    assert lib.pqc_last_hip_error(h) == 0
+    lib.pqc_destroy(h)
+    lib.pqc_destroy(None)

@@ -1,0 +1,200 @@
+"""GPU parity tests: the HIP decode path, called through the C ABI, against the CPU
+oracle on the same seeded inputs.  Index sets must match exactly (near-ties within
+1e-4 relative of the K-th score would be reported, none are expected because both
+sides rank the same fp32 scores); attention outputs within 2e-3 (bf16 inputs) or
+1e-5 (fp32 inputs) of the double-precision oracle, relative to the head's largest
+output magnitude."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2407_12820_amd import workloads as wl
+
+from parity_utils import ATTN_TOL, attn_error, build_problem, check_indices, check_structure
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def pqc():
+    from paper_2407_12820_amd import binding
+    binding.load()
+    return binding
+
+
+def upload(pqc, p):
+    w = p.w
+    return dict(q=pqc.to_device(p.q, w.dtype, DEV), k=pqc.to_device(p.k, w.dtype, DEV), v=pqc.to_device(p.v, w.dtype, DEV),
+                centroids=torch.from_numpy(p.centroids).to(DEV), codes=torch.from_numpy(p.codes).to(DEV))
+
+
+def run_decode(pqc, p, ctx=None, dev=None):
+    ctx = ctx or pqc.PQCache(p.w, DEV)
+    dev = dev or upload(pqc, p)
+    idx, out = ctx.decode(dev["q"], dev["centroids"], dev["codes"], dev["k"], dev["v"])
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), out.cpu().numpy()
+
+
+def full_check(p, idx, out):
+    near = check_indices(p, idx)
+    assert near == 0, f"{near} near-tie substitutions (allowed by the contract, but not expected)"
+    err = attn_error(p, idx, out)
+    assert err <= ATTN_TOL[p.w.dtype], f"attention error {err:.3e}"
+    check_structure(p, idx, out)
+    return err
+
+
+SCALED = {
+    "tiny_f32": {},
+    "llama8b_32k": dict(n_tokens=10007),
+    "llama8b_128k": dict(n_tokens=20011),
+    "batch8_32k": dict(batch=2, n_tokens=6151),
+    "llama70b_128k": dict(batch=1, n_tokens=9001),
+}
+
+
+@pytest.mark.parametrize("name", wl.CONFIG_ORDER)
+def test_decode_matches_oracle_scaled(pqc, name):
+    w = wl.get(name, **SCALED[name])
+    print(f"[case] decode scaled {w}", flush=True)
+    p = build_problem(w, seed=1)
+    idx, out = run_decode(pqc, p)
+    full_check(p, idx, out)
+
+
+@pytest.mark.parametrize("name", ["tiny_f32", "llama8b_32k", "batch8_32k", "llama70b_128k"])
+def test_stages_match_oracle(pqc, name):
+    w = wl.get(name, **SCALED[name])
+    print(f"[case] stages {w}", flush=True)
+    p = build_problem(w, seed=2)
+    dev = upload(pqc, p)
+    ctx = pqc.PQCache(w, DEV)
+    I, K, L, N = w.n_init, w.topk, w.n_local, w.n_tokens
+    s32, _ = oracle.scores(p.q, w.dtype, p.centroids, p.codes)
+    # table + scan: scores equal the oracle's fp32 scores bit for bit; windows hold -inf
+    table = ctx.lut(dev["q"], dev["centroids"])
+    scores = ctx.scan(table, dev["codes"])
+    torch.cuda.synchronize()
+    sg = scores.cpu().numpy()
+    np.testing.assert_array_equal(sg[:, :, I:N - L].view(np.uint32), s32[:, :, I:N - L].view(np.uint32))
+    assert np.all(np.isneginf(sg[:, :, :I])) and np.all(np.isneginf(sg[:, :, N - L:]))
+    # table itself: entry = group query . centroid (double reference, tolerance of an fp32 dot product)
+    qv = wl.to_f32(p.q, w.dtype).astype(np.float64).reshape(w.batch, w.n_kv_heads, w.group, w.pq_m, w.sub_dim).sum(2)
+    ref = np.einsum("bgjd,bgjcd->bgjc", qv, p.centroids.astype(np.float64))
+    np.testing.assert_allclose(table.cpu().numpy(), ref, rtol=0, atol=1e-4 * np.abs(ref).max())
+    # top-k stage on the oracle's scores
+    want = oracle.select(s32, K, I, L)
+    idx = ctx.topk(torch.from_numpy(s32).to(DEV))
+    torch.cuda.synchronize()
+    ig = idx.cpu().numpy()
+    np.testing.assert_array_equal(np.sort(ig, axis=-1), np.sort(want, axis=-1))
+    # attention stage on the oracle's index list (best-first order: any order must do)
+    out = ctx.gather_attn(dev["q"], dev["k"], dev["v"], torch.from_numpy(want).to(DEV))
+    torch.cuda.synchronize()
+    err = attn_error(p, want, out.cpu().numpy())
+    assert err <= ATTN_TOL[w.dtype], f"attention error {err:.3e}"
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["llama8b_32k", "llama8b_128k"])
+def test_decode_matches_oracle_full_size(pqc, name):
+    w = wl.get(name)
+    print(f"[case] decode full size {w}", flush=True)
+    p = build_problem(w, seed=0)
+    idx, out = run_decode(pqc, p)
+    err = full_check(p, idx, out)
+    print(f"[result] {name}: attention error {err:.3e}", flush=True)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name,units", [("batch8_32k", [0, 37]), ("llama70b_128k", [5, 30])])
+def test_decode_full_size_sampled_units(pqc, name, units):
+    # The full launch shape; the oracle checks two units completely (their PQ structures
+    # come from its K-Means), every other unit is checked through invariants.
+    w = wl.get(name)
+    print(f"[case] decode full size, sampled units {units}: {w}", flush=True)
+    p = build_problem(w, seed=0, checked_units=units)
+    idx, out = run_decode(pqc, p)
+    err = full_check(p, idx, out)
+    print(f"[result] {name}: attention error {err:.3e}", flush=True)
+
+
+# ----------------------------------------------------------------------- edge cases
+def _small(**kw):
+    base = dict(name="edge", batch=1, n_q_heads=4, n_kv_heads=2, head_dim=128, n_tokens=3000, pq_m=2, pq_centroids=16,
+                topk=300, n_init=4, n_local=64, dtype="bf16", kmeans_iters=2, recipe="plain")
+    base.update(kw)
+    return wl.Workload(**base)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(topk=0),                                   # windows only
+    dict(topk=3000 - 68),                           # every token attended: dense attention
+    dict(n_tokens=70, topk=2),                      # two middle tokens
+    dict(n_tokens=69, topk=1),                      # one middle token
+    dict(n_init=0, n_local=0, topk=17),             # no windows
+    dict(n_init=0, n_local=0, topk=1, n_tokens=1),  # a single cached token
+    dict(pq_m=1, pq_centroids=2, topk=700),         # two distinct scores: huge tie classes
+    dict(pq_m=8, pq_centroids=256, n_q_heads=2, n_kv_heads=2, topk=257),
+    dict(pq_m=4, pq_centroids=7, n_q_heads=16, n_kv_heads=2, topk=999, n_tokens=4097),
+    dict(dtype="f32", n_q_heads=8, n_kv_heads=1, topk=511, n_tokens=2500),
+    dict(batch=3, n_tokens=2049, topk=100),
+], ids=lambda kw: ",".join(f"{k}={v}" for k, v in kw.items()))
+def test_edge_shapes(pqc, kw):
+    w = _small(**kw)
+    print(f"[case] edge {kw}", flush=True)
+    p = build_problem(w, seed=3)
+    idx, out = run_decode(pqc, p)
+    full_check(p, idx, out)
+
+
+def test_all_scores_equal_takes_lowest_indices(pqc):
+    # A zero query ties every token: the K lowest middle indices win, attention is a plain mean.
+    w = _small(topk=1500)
+    p = build_problem(w, seed=4)
+    p = type(p)(w, np.zeros_like(p.q), p.k, p.v, p.centroids, p.codes, p.checked_units)
+    idx, out = run_decode(pqc, p)
+    assert np.all(np.sort(idx[0, 0, 4:1504]) == np.arange(4, 1504))
+    full_check(p, idx, out)
+
+
+def test_context_reuse_and_two_contexts(pqc):
+    # Calls on one context leave the workspace ready for the next call; contexts do not interfere.
+    wa, wb = _small(topk=123), _small(n_tokens=5000, topk=900, pq_m=4)
+    pa1, pa2, pb = build_problem(wa, 5), build_problem(wa, 6), build_problem(wb, 7)
+    ca, cb = pqc.PQCache(wa, DEV), pqc.PQCache(wb, DEV)
+    for _ in range(2):
+        for p, c in ((pa1, ca), (pb, cb), (pa2, ca), (pa1, ca)):
+            idx, out = run_decode(pqc, p, ctx=c)
+            full_check(p, idx, out)
+    # stage call between decode calls shares the same workspace
+    s32, _ = oracle.scores(pa1.q, wa.dtype, pa1.centroids, pa1.codes)
+    ig = ca.topk(torch.from_numpy(s32).to(DEV)).cpu().numpy()
+    np.testing.assert_array_equal(np.sort(ig, -1), np.sort(oracle.select(s32, wa.topk, wa.n_init, wa.n_local), -1))
+    idx, out = run_decode(pqc, pa2, ctx=ca)
+    full_check(pa2, idx, out)
+
+
+def test_decode_is_deterministic(pqc):
+    w = wl.get("llama8b_128k", n_tokens=20011)
+    p = build_problem(w, seed=1)
+    dev, ctx = upload(pqc, p), pqc.PQCache(w, DEV)
+    a = run_decode(pqc, p, ctx, dev)
+    b = run_decode(pqc, p, ctx, dev)
+    np.testing.assert_array_equal(a[0], b[0])
+    np.testing.assert_array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
+
+
+def test_runs_on_a_side_stream(pqc):
+    w = _small(topk=200)
+    p = build_problem(w, seed=8)
+    dev, ctx = upload(pqc, p), pqc.PQCache(w, DEV)
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream(device=DEV)
+    idx, out = ctx.decode(dev["q"], dev["centroids"], dev["codes"], dev["k"], dev["v"], stream=st)
+    st.synchronize()
+    full_check(p, idx.cpu().numpy(), out.cpu().numpy())
