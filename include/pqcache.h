@@ -68,7 +68,8 @@ typedef enum pqc_dtype { PQC_F32 = 0, PQC_BF16 = 1 } pqc_dtype;
 
 /* Shape of one decode step.  Supported: head_dim = 128; pq_m in {1,2,4,8};
  * 1 <= pq_centroids <= 256; n_q_heads / n_kv_heads in {1,2,4,8};
- * n_init + topk + n_local <= n_tokens and >= 1; n_tokens < 2^24. */
+ * n_init + topk + n_local <= n_tokens and >= 1; n_tokens <= 2^22;
+ * B * Hkv <= 65535. */
 typedef struct pqc_config {
   int32_t batch;         /* B                                                        */
   int32_t n_q_heads;     /* Hq                                                       */
@@ -126,6 +127,15 @@ int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_
                const void* k_cache, const void* v_cache, int32_t* out_idx, float* out_attn,
                void* stream);
 
+/* Profiling aid: pqc_decode with HIP events recorded on `stream` around each of its
+ * kernels.  Unlike every other entry point it creates and destroys events and
+ * SYNCHRONISES the stream before returning.  kernel_ms is HOST memory for
+ * PQC_DECODE_KERNELS floats, in launch order: histogram, select+attention, finalize. */
+#define PQC_DECODE_KERNELS 3
+int pqc_decode_profile(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes,
+                       const void* k_cache, const void* v_cache, int32_t* out_idx, float* out_attn,
+                       void* stream, float* kernel_ms);
+
 /* ---- the same path, one stage at a time (unit tests, per-kernel profiling) ---- */
 
 /* Step 1 (Section 2.2 search / Section 3.1 step 4, "multiply the query with the PQ
@@ -145,6 +155,45 @@ int pqc_topk(pqc_ctx* ctx, const float* scores, int32_t* out_idx, void* stream);
  * Each listed K/V row is read once and shared by the G heads of its group. */
 int pqc_gather_attn(pqc_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
                     const int32_t* idx, float* out_attn, void* stream);
+
+/* ---- PQ construction and maintenance (context-free; shapes come from cfg) ---- */
+
+/* Bytes of device workspace pqc_pq_build needs (0 for an invalid configuration). */
+size_t pqc_pq_build_workspace_bytes(const pqc_config* cfg);
+
+/*
+ * PQ construction (Section 2.2 index construction; Section 3.1 step 2): for every
+ * (sequence, KV head, partition) Lloyd K-Means of the keys' sub-vectors into C
+ * centroids.  Start: centroid c of partition j is the sub-vector of token
+ * init_idx[b][h][j][c] (clamped into [0,N)).  `iters` rounds of (assign every token
+ * to its nearest centroid in squared L2 distance, lowest index on ties; replace each
+ * centroid by the mean of its members, an empty cluster keeps its centroid), then a
+ * final assignment, so that the returned codes are the nearest centroids of the
+ * returned centroids.  Distances are evaluated in fp32; centroid sums are exact
+ * integer sums of the keys rounded to 2^-20, hence independent of execution order.
+ *
+ *   keys       [B][Hkv][N][D]        kv_dtype   (in)
+ *   init_idx   [B][Hkv][M][C]        int32      (in)
+ *   centroids  [B][Hkv][M][C][Dm]    f32        (out)
+ *   codes      [B][Hkv][N][M]        uint8      (out)
+ *   workspace  device memory, 256-byte aligned, >= pqc_pq_build_workspace_bytes(cfg)
+ * The fields topk, n_init, n_local and softmax_scale of cfg are validated but unused.
+ */
+int pqc_pq_build(const pqc_config* cfg, const void* keys, const int32_t* init_idx, int32_t iters,
+                 float* centroids, uint8_t* codes, void* workspace, size_t workspace_bytes,
+                 void* stream);
+
+/* Assignment step alone: codes[b][h][t][j] = nearest centroid of keys[b][h][t]'s j-th
+ * sub-vector, for all N tokens (same arithmetic and tie rule as pqc_pq_build). */
+int pqc_pq_assign(const pqc_config* cfg, const void* keys, const float* centroids, uint8_t* codes,
+                  void* stream);
+
+/* Code of one new token per (sequence, KV head) (Section 3.1: a token leaving the
+ * local window is given the codes of its nearest centroids; Algorithm 2,
+ * "PQArgNearest" then "Codes.append"):  key [B][Hkv][D] kv_dtype; writes
+ * codes[b][h][position][0..M-1] inside the [B][Hkv][N][M] code tensor; 0 <= position < N. */
+int pqc_pq_encode_token(const pqc_config* cfg, const void* key, const float* centroids,
+                        uint8_t* codes, int32_t position, void* stream);
 
 #ifdef __cplusplus
 }

@@ -53,6 +53,8 @@ def load() -> C.CDLL:
     lib.pqc_last_hip_error.argtypes = [vp]
     lib.pqc_decode.restype = C.c_int
     lib.pqc_decode.argtypes = [vp] * 9
+    lib.pqc_decode_profile.restype = C.c_int
+    lib.pqc_decode_profile.argtypes = [vp] * 9 + [C.POINTER(C.c_float)]
     lib.pqc_lut.restype = C.c_int
     lib.pqc_lut.argtypes = [vp] * 5
     lib.pqc_scan.restype = C.c_int
@@ -61,6 +63,14 @@ def load() -> C.CDLL:
     lib.pqc_topk.argtypes = [vp] * 4
     lib.pqc_gather_attn.restype = C.c_int
     lib.pqc_gather_attn.argtypes = [vp] * 7
+    lib.pqc_pq_build_workspace_bytes.restype = C.c_size_t
+    lib.pqc_pq_build_workspace_bytes.argtypes = [cp]
+    lib.pqc_pq_build.restype = C.c_int
+    lib.pqc_pq_build.argtypes = [cp, vp, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
+    lib.pqc_pq_assign.restype = C.c_int
+    lib.pqc_pq_assign.argtypes = [cp, vp, vp, vp, vp]
+    lib.pqc_pq_encode_token.restype = C.c_int
+    lib.pqc_pq_encode_token.argtypes = [cp, vp, vp, vp, C.c_int32, vp]
     _lib = lib
     return lib
 
@@ -158,6 +168,19 @@ class PQCache:
         self._check(rc, "pqc_decode")
         return out_idx, out_attn
 
+    def decode_profile(self, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream=None):
+        """pqc_decode with per-kernel HIP-event timing -> list of milliseconds (synchronises the stream)."""
+        sh = self.shapes
+        ms = (C.c_float * 3)()
+        rc = self.lib.pqc_decode_profile(self.handle, self._ptr(q, self.kv_torch, sh["q"]),
+                                         self._ptr(centroids, torch.float32, sh["centroids"]),
+                                         self._ptr(codes, torch.uint8, sh["codes"]),
+                                         self._ptr(k_cache, self.kv_torch, sh["kv"]), self._ptr(v_cache, self.kv_torch, sh["kv"]),
+                                         self._ptr(out_idx, torch.int32, sh["idx"]), self._ptr(out_attn, torch.float32, sh["out"]),
+                                         self._stream(stream), ms)
+        self._check(rc, "pqc_decode_profile")
+        return list(ms)
+
     def lut(self, q, centroids, table=None, stream=None):
         sh = self.shapes
         if table is None:
@@ -197,6 +220,64 @@ class PQCache:
                                       self._stream(stream))
         self._check(rc, "pqc_gather_attn")
         return out_attn
+
+
+def _kv_dtype(w: Workload):
+    return torch.float32 if w.dtype == "f32" else torch.bfloat16
+
+
+def _need(t: torch.Tensor, dtype, shape, what: str) -> int:
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype or tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{what}: expected contiguous device {dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+def pq_build(w: Workload, keys: torch.Tensor, init_idx: torch.Tensor, iters: Optional[int] = None, stream=None):
+    """K-Means PQ construction on the GPU -> (centroids [B,Hkv,M,C,Dm] f32, codes [B,Hkv,N,M] u8)."""
+    lib = load()
+    cfg = make_config(w)
+    dev = keys.device
+    iters = w.kmeans_iters if iters is None else iters
+    nbytes = lib.pqc_pq_build_workspace_bytes(C.byref(cfg))
+    if nbytes == 0:
+        raise PQCacheError(-1, "pqc_pq_build_workspace_bytes")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    cent = torch.empty((w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids, w.sub_dim), dtype=torch.float32, device=dev)
+    codes = torch.empty((w.batch, w.n_kv_heads, w.n_tokens, w.pq_m), dtype=torch.uint8, device=dev)
+    st = (stream if stream is not None else torch.cuda.current_stream(dev)).cuda_stream
+    rc = lib.pqc_pq_build(C.byref(cfg), _need(keys, _kv_dtype(w), (w.batch, w.n_kv_heads, w.n_tokens, w.head_dim), "keys"),
+                          _need(init_idx, torch.int32, (w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids), "init_idx"),
+                          iters, cent.data_ptr(), codes.data_ptr(), ws.data_ptr(), nbytes, st)
+    if rc != 0:
+        raise PQCacheError(rc, "pqc_pq_build")
+    return cent, codes
+
+
+def pq_assign(w: Workload, keys: torch.Tensor, centroids: torch.Tensor, stream=None) -> torch.Tensor:
+    lib = load()
+    cfg = make_config(w)
+    dev = keys.device
+    codes = torch.empty((w.batch, w.n_kv_heads, w.n_tokens, w.pq_m), dtype=torch.uint8, device=dev)
+    st = (stream if stream is not None else torch.cuda.current_stream(dev)).cuda_stream
+    rc = lib.pqc_pq_assign(C.byref(cfg), _need(keys, _kv_dtype(w), (w.batch, w.n_kv_heads, w.n_tokens, w.head_dim), "keys"),
+                           _need(centroids, torch.float32, (w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids, w.sub_dim), "centroids"),
+                           codes.data_ptr(), st)
+    if rc != 0:
+        raise PQCacheError(rc, "pqc_pq_assign")
+    return codes
+
+
+def pq_encode_token(w: Workload, key: torch.Tensor, centroids: torch.Tensor, codes: torch.Tensor, position: int,
+                    stream=None) -> None:
+    """Write the nearest-centroid codes of one new key per (sequence, KV head) at `position` of `codes`."""
+    lib = load()
+    cfg = make_config(w)
+    st = (stream if stream is not None else torch.cuda.current_stream(key.device)).cuda_stream
+    rc = lib.pqc_pq_encode_token(C.byref(cfg), _need(key, _kv_dtype(w), (w.batch, w.n_kv_heads, w.head_dim), "key"),
+                                 _need(centroids, torch.float32, (w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids, w.sub_dim), "centroids"),
+                                 _need(codes, torch.uint8, (w.batch, w.n_kv_heads, w.n_tokens, w.pq_m), "codes"), position, st)
+    if rc != 0:
+        raise PQCacheError(rc, "pqc_pq_encode_token")
 
 
 def to_device(a, dtype: str, device="cuda:0") -> torch.Tensor:

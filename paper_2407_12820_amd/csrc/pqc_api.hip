@@ -8,6 +8,7 @@
 #include <cstring>
 #include <new>
 
+#include "pqc_build_kernels.h"
 #include "pqc_kernels.h"
 
 namespace {
@@ -19,7 +20,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
   Shape s;
-  size_t off_ctl, off_lut, off_hist, off_stage, off_cnt, off_part, total;
+  size_t off_ctl, off_lut, off_hist, off_stage, off_cnt, off_part, off_trace, total;
 };
 
 int env_int(const char* name, int fallback) {
@@ -55,32 +56,37 @@ int make_plan(const pqc_config* c, Plan* p) {
   const long long units = (long long)s.B * s.Hkv;
 
   // histogram kernel: few, large workgroups (contended bins serialise per workgroup)
+  // (a unit's first 16-byte code chunk may start up to 15 phantom tokens early: + 15)
   int tokA = env_int("PQC_TOK_A", 0);
   if (!tokA) {
     tokA = 4096;
-    while (tokA < 16384 && ((s.N + tokA - 1) / tokA) > 8) tokA *= 2;
-    while ((s.N + tokA - 1) / tokA > 64) tokA *= 2;
+    const int cap = 4096 * (16 / s.M) < 16384 ? 4096 * (16 / s.M) : 16384;  // kMaxVecA chunks per thread
+    while (tokA < cap && ((s.N + 15 + tokA - 1) / tokA) > 8) tokA *= 2;
   }
-  s.tokA = tokA; s.nblkA = (s.N + tokA - 1) / tokA;
+  if (tokA % 1024 || tokA > 16384 || tokA > 4096 * (16 / s.M)) return PQC_EINVAL;
+  s.tokA = tokA; s.nblkA = (s.N + 15 + tokA - 1) / tokA;
   // select kernel: aim for a few workgroups per compute unit
   int tokC = env_int("PQC_TOK_C", 0);
   if (!tokC) {
     tokC = 2048;
-    while (tokC < 8192 && units * ((s.N + tokC - 1) / tokC) > 1024) tokC *= 2;
+    while (tokC < 8192 && units * ((s.N + 15 + tokC - 1) / tokC) > 1024) tokC *= 2;
   }
   if (tokC % 256 || tokC > 8192) return PQC_EINVAL;
-  s.tokC = tokC; s.nblkC = (s.N + tokC - 1) / tokC;
+  s.tokC = tokC; s.nblkC = (s.N + 15 + tokC - 1) / tokC;
   s.rowsP = env_int("PQC_ROWS_P", 256);
   s.nblkP = (s.Ktot + s.rowsP - 1) / s.rowsP;
   s.npart = s.nblkC > s.nblkP ? s.nblkC : s.nblkP;
 
   size_t off = 0;
-  p->off_ctl = off;   off = align_up(off + sizeof(float2) * units);
+  p->off_ctl = off;   off = align_up(off + sizeof(BinParams) * units);
   p->off_lut = off;   off = align_up(off + sizeof(float) * units * s.M * s.C);
   p->off_hist = off;  off = align_up(off + sizeof(unsigned) * units * kNB);
   p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * s.nblkC * s.tokC);
   p->off_cnt = off;   off = align_up(off + sizeof(int2) * units * s.nblkC);
   p->off_part = off;  off = align_up(off + sizeof(float) * units * s.npart * s.G * (kD + 2));
+#ifdef PQC_TRACE
+  p->off_trace = off; off = align_up(off + sizeof(unsigned long long) * 3 * kTraceWgs * kTraceSlots);
+#endif
   p->total = off;
   return PQC_OK;
 }
@@ -118,41 +124,46 @@ int ensure_clean_hist(pqc_ctx* ctx, hipStream_t st) {
 }
 
 // ---- template dispatch -------------------------------------------------------
+// ev: nullptr, or PQC_DECODE_KERNELS+1 events recorded before, between and after the launches
 template <typename T, int G, int M>
 void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const void* k,
-                       const void* v, int32_t* out_idx, float* out_attn, hipStream_t st) {
+                       const void* v, int32_t* out_idx, float* out_attn, hipStream_t st, hipEvent_t* ev) {
   const Shape& s = ctx->plan.s;
   const unsigned units = (unsigned)(s.B * s.Hkv);
   const T* qt = static_cast<const T*>(q);
   const T* kt = static_cast<const T*>(k);
   const T* vt = static_cast<const T*>(v);
-  hipLaunchKernelGGL((hist_kernel<T, CodeSource<M>>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, qt, cent,
+  if (ev) (void)hipEventRecord(ev[0], st);
+  hipLaunchKernelGGL((hist_kernel<T, CodeChunks<M>>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, qt, cent,
                      static_cast<const void*>(codes));
-  hipLaunchKernelGGL((select_kernel<T, G, CodeSource<M>, true>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(int), st,
+  if (ev) (void)hipEventRecord(ev[1], st);
+  hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(int), st,
                      s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));
+  if (ev) (void)hipEventRecord(ev[2], st);
   hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(1, units), dim3(512), 2 * (s.nblkC + 1) * sizeof(int), st, s,
                      ctx->ws, qt, kt, vt, out_idx, out_attn);
+  if (ev) (void)hipEventRecord(ev[3], st);
 }
 
 template <typename T, int G>
 void launch_decode_tg(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const void* k, const void* v,
-                      int32_t* out_idx, float* out_attn, hipStream_t st) {
+                      int32_t* out_idx, float* out_attn, hipStream_t st, hipEvent_t* ev) {
   switch (ctx->plan.s.M) {
-    case 1: launch_decode_tgm<T, G, 1>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
-    case 2: launch_decode_tgm<T, G, 2>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
-    case 4: launch_decode_tgm<T, G, 4>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
-    default: launch_decode_tgm<T, G, 8>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
+    case 1: launch_decode_tgm<T, G, 1>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
+    case 2: launch_decode_tgm<T, G, 2>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
+    case 4: launch_decode_tgm<T, G, 4>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
+    default: launch_decode_tgm<T, G, 8>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
   }
 }
 
 template <typename T>
 void launch_decode_t(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const void* k, const void* v,
-                     int32_t* out_idx, float* out_attn, hipStream_t st) {
+                     int32_t* out_idx, float* out_attn, hipStream_t st, hipEvent_t* ev) {
   switch (ctx->plan.s.G) {
-    case 1: launch_decode_tg<T, 1>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
-    case 2: launch_decode_tg<T, 2>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
-    case 4: launch_decode_tg<T, 4>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
-    default: launch_decode_tg<T, 8>(ctx, q, cent, codes, k, v, out_idx, out_attn, st); break;
+    case 1: launch_decode_tg<T, 1>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
+    case 2: launch_decode_tg<T, 2>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
+    case 4: launch_decode_tg<T, 4>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
+    default: launch_decode_tg<T, 8>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
   }
 }
 
@@ -174,6 +185,17 @@ void launch_attn_t(pqc_ctx* ctx, const void* q, const void* k, const void* v, co
     case 2: launch_attn_tg<T, 2>(ctx, q, k, v, idx, out, st); break;
     case 4: launch_attn_tg<T, 4>(ctx, q, k, v, idx, out, st); break;
     default: launch_attn_tg<T, 8>(ctx, q, k, v, idx, out, st); break;
+  }
+}
+
+template <typename T>
+void launch_lut_t(const Shape& s, const T* q, const float* cent, float* table, hipStream_t st) {
+  const dim3 grid(1, (unsigned)(s.B * s.Hkv));
+  switch (s.M) {
+    case 1: hipLaunchKernelGGL((lut_kernel<T, 1>), grid, dim3(256), 0, st, s, q, cent, table); break;
+    case 2: hipLaunchKernelGGL((lut_kernel<T, 2>), grid, dim3(256), 0, st, s, q, cent, table); break;
+    case 4: hipLaunchKernelGGL((lut_kernel<T, 4>), grid, dim3(256), 0, st, s, q, cent, table); break;
+    default: hipLaunchKernelGGL((lut_kernel<T, 8>), grid, dim3(256), 0, st, s, q, cent, table); break;
   }
 }
 
@@ -201,6 +223,14 @@ const char* pqc_strerror(int status) {
   }
 }
 
+#ifdef PQC_TRACE
+size_t pqc_debug_trace_offset(const pqc_config* cfg) {
+  Plan p;
+  if (make_plan(cfg, &p) != PQC_OK) return 0;
+  return p.off_trace;
+}
+#endif
+
 size_t pqc_workspace_bytes(const pqc_config* cfg) {
   Plan p;
   if (make_plan(cfg, &p) != PQC_OK) return 0;
@@ -219,12 +249,15 @@ int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t wor
   ctx->cfg = *cfg;
   ctx->plan = p;
   char* base = static_cast<char*>(workspace);
-  ctx->ws.ctl = reinterpret_cast<float2*>(base + p.off_ctl);
+  ctx->ws.ctl = reinterpret_cast<BinParams*>(base + p.off_ctl);
   ctx->ws.lut = reinterpret_cast<float*>(base + p.off_lut);
   ctx->ws.hist = reinterpret_cast<unsigned*>(base + p.off_hist);
   ctx->ws.stage = reinterpret_cast<unsigned long long*>(base + p.off_stage);
   ctx->ws.stage_cnt = reinterpret_cast<int2*>(base + p.off_cnt);
   ctx->ws.partials = reinterpret_cast<float*>(base + p.off_part);
+#ifdef PQC_TRACE
+  ctx->ws.trace = reinterpret_cast<unsigned long long*>(base + p.off_trace);
+#endif
   ctx->hist_clean = false;
   ctx->last_hip = 0;
   *out = ctx;
@@ -235,8 +268,8 @@ void pqc_destroy(pqc_ctx* ctx) { delete ctx; }
 
 int pqc_last_hip_error(const pqc_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
 
-int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes, const void* k_cache,
-               const void* v_cache, int32_t* out_idx, float* out_attn, void* stream) {
+static int decode_impl(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes, const void* k_cache,
+                       const void* v_cache, int32_t* out_idx, float* out_attn, void* stream, hipEvent_t* ev) {
   if (!ctx || !q || !centroids || !codes || !k_cache || !v_cache || !out_idx || !out_attn) return PQC_EINVAL;
   if (!aligned16(q) || !aligned16(centroids) || !aligned16(codes) || !aligned16(k_cache) || !aligned16(v_cache) ||
       !aligned16(out_idx) || !aligned16(out_attn))
@@ -246,11 +279,45 @@ int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_
   if (rc != PQC_OK) return rc;
   ctx->hist_clean = false;
   if (ctx->cfg.kv_dtype == PQC_F32)
-    launch_decode_t<float>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st);
+    launch_decode_t<float>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st, ev);
   else
-    launch_decode_t<bf16_t>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st);
+    launch_decode_t<bf16_t>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st, ev);
   rc = check_launch(ctx);
   if (rc == PQC_OK) ctx->hist_clean = true;  // finalize_kernel re-zeroes the histogram
+  return rc;
+}
+
+int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes, const void* k_cache,
+               const void* v_cache, int32_t* out_idx, float* out_attn, void* stream) {
+  return decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, nullptr);
+}
+
+int pqc_decode_profile(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes, const void* k_cache,
+                       const void* v_cache, int32_t* out_idx, float* out_attn, void* stream, float* kernel_ms) {
+  if (!ctx || !kernel_ms) return PQC_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = ensure_clean_hist(ctx, st);  // keep the one-off reset out of the timed span
+  if (rc != PQC_OK) return rc;
+  hipEvent_t ev[PQC_DECODE_KERNELS + 1];
+  int made = 0;
+  for (; made <= PQC_DECODE_KERNELS; ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) break;
+  if (made <= PQC_DECODE_KERNELS) {
+    ctx->last_hip = (int)hipGetLastError();
+    rc = PQC_EHIP;
+  } else {
+    rc = decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, ev);
+    if (rc == PQC_OK && hipStreamSynchronize(st) != hipSuccess) {
+      ctx->last_hip = (int)hipGetLastError();
+      rc = PQC_EHIP;
+    }
+    for (int i = 0; rc == PQC_OK && i < PQC_DECODE_KERNELS; ++i)
+      if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) {
+        ctx->last_hip = (int)hipGetLastError();
+        rc = PQC_EHIP;
+      }
+  }
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
   return rc;
 }
 
@@ -259,11 +326,10 @@ int pqc_lut(pqc_ctx* ctx, const void* q, const float* centroids, float* table, v
   if (!aligned16(q) || !aligned16(centroids) || !aligned16(table)) return PQC_EINVAL;
   const Shape& s = ctx->plan.s;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const dim3 grid(1, (unsigned)(s.B * s.Hkv));
   if (ctx->cfg.kv_dtype == PQC_F32)
-    hipLaunchKernelGGL((lut_kernel<float>), grid, dim3(256), 0, st, s, static_cast<const float*>(q), centroids, table);
+    launch_lut_t<float>(s, static_cast<const float*>(q), centroids, table, st);
   else
-    hipLaunchKernelGGL((lut_kernel<bf16_t>), grid, dim3(256), 0, st, s, static_cast<const bf16_t*>(q), centroids, table);
+    launch_lut_t<bf16_t>(s, static_cast<const bf16_t*>(q), centroids, table, st);
   return check_launch(ctx);
 }
 
@@ -290,10 +356,10 @@ int pqc_topk(pqc_ctx* ctx, const float* scores, int32_t* out_idx, void* stream) 
   ctx->hist_clean = false;
   const unsigned units = (unsigned)(s.B * s.Hkv);
   const float* nof = nullptr;
-  hipLaunchKernelGGL(minmax_kernel, dim3(1, units), dim3(1024), 0, st, s, scores, ctx->ws.ctl);
-  hipLaunchKernelGGL((hist_kernel<float, ScoreSource>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, nof, nof,
+  hipLaunchKernelGGL(score_stats_kernel, dim3(1, units), dim3(1024), 0, st, s, scores, ctx->ws.ctl);
+  hipLaunchKernelGGL((hist_kernel<float, ScoreChunks>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, nof, nof,
                      static_cast<const void*>(scores));
-  hipLaunchKernelGGL((select_kernel<float, 1, ScoreSource, false>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(int), st,
+  hipLaunchKernelGGL((select_kernel<float, 1, ScoreChunks, false>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(int), st,
                      s, ctx->ws, nof, nof, nof, static_cast<const void*>(scores));
   hipLaunchKernelGGL((finalize_kernel<float, 1, false>), dim3(1, units), dim3(512), 2 * (s.nblkC + 1) * sizeof(int), st, s,
                      ctx->ws, nof, nof, nof, out_idx, static_cast<float*>(nullptr));
@@ -312,6 +378,118 @@ int pqc_gather_attn(pqc_ctx* ctx, const void* q, const void* k_cache, const void
   else
     launch_attn_t<bf16_t>(ctx, q, k_cache, v_cache, idx, out_attn, st);
   return check_launch(ctx);
+}
+
+
+}  // extern "C"
+
+/* ------------------------------------------------------------ PQ construction */
+namespace {
+
+struct BuildPlan {
+  BuildShape s;
+  size_t off_sums, off_counts, total;
+};
+
+int make_build_plan(const pqc_config* cfg, BuildPlan* bp) {
+  Plan p;
+  const int rc = make_plan(cfg, &p);
+  if (rc != PQC_OK) return rc;
+  bp->s.units = p.s.B * p.s.Hkv;
+  bp->s.N = p.s.N; bp->s.M = p.s.M; bp->s.C = p.s.C; bp->s.Dm = p.s.Dm;
+  const size_t n = (size_t)bp->s.units * p.s.M * p.s.C;
+  bp->off_sums = 0;
+  bp->off_counts = align_up(sizeof(unsigned long long) * n * p.s.Dm);
+  bp->total = align_up(bp->off_counts + sizeof(unsigned) * n);
+  return PQC_OK;
+}
+
+template <typename T>
+void launch_assign(const BuildShape& s, const T* keys, int64_t unit_stride, int n_tokens, int pos0, const float* cent,
+                   uint8_t* codes, hipStream_t st) {
+  const dim3 grid((n_tokens + kAssignTok - 1) / kAssignTok, (unsigned)(s.units * s.M));
+  switch (s.Dm) {
+    case 16: hipLaunchKernelGGL((pq_assign_kernel<T, 16>), grid, dim3(256), 0, st, s, keys, unit_stride, n_tokens, pos0, cent, codes); break;
+    case 32: hipLaunchKernelGGL((pq_assign_kernel<T, 32>), grid, dim3(256), 0, st, s, keys, unit_stride, n_tokens, pos0, cent, codes); break;
+    case 64: hipLaunchKernelGGL((pq_assign_kernel<T, 64>), grid, dim3(256), 0, st, s, keys, unit_stride, n_tokens, pos0, cent, codes); break;
+    default: hipLaunchKernelGGL((pq_assign_kernel<T, 128>), grid, dim3(256), 0, st, s, keys, unit_stride, n_tokens, pos0, cent, codes); break;
+  }
+}
+
+template <typename T>
+int pq_build_t(const BuildPlan& bp, const T* keys, const int32_t* init_idx, int iters, float* cent, uint8_t* codes,
+               char* wsp, hipStream_t st) {
+  const BuildShape& s = bp.s;
+  unsigned long long* sums = reinterpret_cast<unsigned long long*>(wsp + bp.off_sums);
+  unsigned* counts = reinterpret_cast<unsigned*>(wsp + bp.off_counts);
+  const unsigned uj = (unsigned)(s.units * s.M);
+  const size_t nacc = bp.total / sizeof(unsigned long long);  // sums and counts, zeroed together
+  const size_t ncent = (size_t)uj * s.C * s.Dm;
+  hipLaunchKernelGGL((pq_init_kernel<T>), dim3(1, uj), dim3(256), 0, st, s, keys, init_idx, cent);
+  for (int it = 0; it < iters; ++it) {
+    launch_assign<T>(s, keys, (int64_t)s.N * kD, s.N, 0, cent, codes, st);
+    hipLaunchKernelGGL(pq_zero_kernel, dim3((unsigned)((nacc + 255) / 256)), dim3(256), 0, st, sums, nacc);
+    hipLaunchKernelGGL((pq_accum_kernel<T>), dim3((s.N + kAccumTok - 1) / kAccumTok, uj), dim3(256), 0, st, s, keys, codes,
+                       sums, counts);
+    hipLaunchKernelGGL(pq_mean_kernel, dim3((unsigned)((ncent + 255) / 256)), dim3(256), 0, st, s, sums, counts, cent);
+  }
+  launch_assign<T>(s, keys, (int64_t)s.N * kD, s.N, 0, cent, codes, st);
+  return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t pqc_pq_build_workspace_bytes(const pqc_config* cfg) {
+  BuildPlan bp;
+  if (make_build_plan(cfg, &bp) != PQC_OK) return 0;
+  return bp.total;
+}
+
+int pqc_pq_build(const pqc_config* cfg, const void* keys, const int32_t* init_idx, int32_t iters, float* centroids,
+                 uint8_t* codes, void* workspace, size_t workspace_bytes, void* stream) {
+  BuildPlan bp;
+  const int rc = make_build_plan(cfg, &bp);
+  if (rc != PQC_OK) return rc;
+  if (!keys || !init_idx || !centroids || !codes || iters < 0) return PQC_EINVAL;
+  if (!aligned16(keys) || !aligned16(init_idx) || !aligned16(centroids) || !aligned16(codes)) return PQC_EINVAL;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) || workspace_bytes < bp.total) return PQC_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* wsp = static_cast<char*>(workspace);
+  if (cfg->kv_dtype == PQC_F32) return pq_build_t<float>(bp, static_cast<const float*>(keys), init_idx, iters, centroids, codes, wsp, st);
+  return pq_build_t<bf16_t>(bp, static_cast<const bf16_t*>(keys), init_idx, iters, centroids, codes, wsp, st);
+}
+
+int pqc_pq_assign(const pqc_config* cfg, const void* keys, const float* centroids, uint8_t* codes, void* stream) {
+  BuildPlan bp;
+  const int rc = make_build_plan(cfg, &bp);
+  if (rc != PQC_OK) return rc;
+  if (!keys || !centroids || !codes) return PQC_EINVAL;
+  if (!aligned16(keys) || !aligned16(centroids) || !aligned16(codes)) return PQC_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const BuildShape& s = bp.s;
+  if (cfg->kv_dtype == PQC_F32)
+    launch_assign<float>(s, static_cast<const float*>(keys), (int64_t)s.N * kD, s.N, 0, centroids, codes, st);
+  else
+    launch_assign<bf16_t>(s, static_cast<const bf16_t*>(keys), (int64_t)s.N * kD, s.N, 0, centroids, codes, st);
+  return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
+}
+
+int pqc_pq_encode_token(const pqc_config* cfg, const void* key, const float* centroids, uint8_t* codes, int32_t position,
+                        void* stream) {
+  BuildPlan bp;
+  const int rc = make_build_plan(cfg, &bp);
+  if (rc != PQC_OK) return rc;
+  if (!key || !centroids || !codes || position < 0 || position >= bp.s.N) return PQC_EINVAL;
+  if (!aligned16(key) || !aligned16(centroids) || !aligned16(codes)) return PQC_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const BuildShape& s = bp.s;
+  if (cfg->kv_dtype == PQC_F32)
+    launch_assign<float>(s, static_cast<const float*>(key), (int64_t)kD, 1, position, centroids, codes, st);
+  else
+    launch_assign<bf16_t>(s, static_cast<const bf16_t*>(key), (int64_t)kD, 1, position, centroids, codes, st);
+  return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
 }
 
 }  // extern "C"

@@ -1,0 +1,132 @@
+// PQ construction on the GPU (paper, Section 2.2 "index construction" and Section 3.1
+// step 2): per (sequence, KV head, partition) Lloyd K-Means over the keys' sub-vectors,
+// and the nearest-centroid code of a token that leaves the local window (Section 3.1,
+// last paragraph; Algorithm 2 "PQArgNearest").
+//
+// Grid layout: blockIdx.y = unit * M + partition j, blockIdx.x = token chunk.
+// Distances are evaluated in fp32 as sum_e (x_e - c_e)^2, e ascending; the lowest
+// centroid index wins ties.  Centroid sums are accumulated in 64-bit fixed point
+// (2^-20 resolution), which makes the update independent of summation order and
+// therefore reproducible; an empty cluster keeps its centroid.
+#pragma once
+#include "pqc_device.h"
+
+namespace pqc {
+
+constexpr int kFixShift = 20;
+constexpr int kAssignTok = 256;   // tokens per workgroup of the assignment kernel
+constexpr int kAccumTok = 2048;   // tokens per workgroup of the accumulation kernel
+
+struct BuildShape {
+  int units, N, M, C, Dm;
+};
+
+// centroids[u][j][c][:] = keys[u][init_idx[u][j][c]][j*Dm : (j+1)*Dm]
+template <typename T>
+__global__ __launch_bounds__(256) void pq_init_kernel(BuildShape s, const T* __restrict__ keys,
+                                                      const int* __restrict__ init_idx, float* __restrict__ cent) {
+  const int uj = blockIdx.y, u = uj / s.M, j = uj % s.M;
+  for (int i = threadIdx.x; i < s.C * s.Dm; i += 256) {
+    const int c = i / s.Dm, e = i % s.Dm;
+    int t = init_idx[(size_t)uj * s.C + c];
+    t = max(0, min(s.N - 1, t));
+    cent[(size_t)uj * s.C * s.Dm + i] = load_as_float<T>(keys, ((size_t)u * s.N + t) * kD + j * s.Dm + e);
+  }
+}
+
+// codes[u][t][j] = argmin_c || keys[u][t][j*Dm..] - cent[u][j][c] ||^2
+// One thread per token; centroids staged through LDS 32 at a time.
+template <typename T, int DM>
+__global__ __launch_bounds__(256) void pq_assign_kernel(BuildShape s, const T* __restrict__ keys, int64_t key_unit_stride,
+                                                        int n_tokens, int code_pos0, const float* __restrict__ cent,
+                                                        uint8_t* __restrict__ codes) {
+  constexpr int CG = 32;
+  __shared__ float cs[CG * DM];
+  const int uj = blockIdx.y, u = uj / s.M, j = uj % s.M;
+  const int t = blockIdx.x * kAssignTok + threadIdx.x;
+  const bool live = t < n_tokens;
+  float x[DM];
+  if (live) {
+#pragma unroll
+    for (int e = 0; e < DM; ++e) x[e] = load_as_float<T>(keys, (size_t)u * key_unit_stride + (size_t)t * kD + j * DM + e);
+  } else {
+#pragma unroll
+    for (int e = 0; e < DM; ++e) x[e] = 0.0f;
+  }
+  float best = INFINITY;
+  int arg = 0;
+  for (int c0 = 0; c0 < s.C; c0 += CG) {
+    const int nc = min(CG, s.C - c0);
+    __syncthreads();
+    for (int i = threadIdx.x; i < nc * DM; i += 256) cs[i] = cent[((size_t)uj * s.C + c0) * DM + i];
+    __syncthreads();
+    for (int c = 0; c < nc; ++c) {
+      float d2 = 0.0f;
+#pragma unroll
+      for (int e = 0; e < DM; ++e) {
+        const float df = x[e] - cs[c * DM + e];
+        d2 = fmaf(df, df, d2);
+      }
+      if (d2 < best) {
+        best = d2;
+        arg = c0 + c;
+      }
+    }
+  }
+  if (live) codes[((size_t)u * s.N + code_pos0 + t) * s.M + j] = (uint8_t)arg;
+}
+
+__global__ void pq_zero_kernel(unsigned long long* p, size_t n) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0ull;
+}
+
+// sums[u][j][c][e] += fix(keys[u][t][j*Dm+e]) for every token t with code c; counts[u][j][c] += 1.
+// LDS accumulators for 16 KiB worth of centroids at a time; integer adds commute, so the
+// result does not depend on the order in which waves run.
+template <typename T>
+__global__ __launch_bounds__(256) void pq_accum_kernel(BuildShape s, const T* __restrict__ keys,
+                                                       const uint8_t* __restrict__ codes,
+                                                       unsigned long long* __restrict__ sums,
+                                                       unsigned* __restrict__ counts) {
+  __shared__ unsigned long long acc[2048];
+  __shared__ unsigned cnt[256];
+  const int uj = blockIdx.y, u = uj / s.M, j = uj % s.M;
+  const int t0 = blockIdx.x * kAccumTok, t1 = min(t0 + kAccumTok, s.N);
+  const int cg = max(1, 2048 / s.Dm);  // centroids per pass
+  for (int c0 = 0; c0 < s.C; c0 += cg) {
+    const int nc = min(cg, s.C - c0);
+    __syncthreads();
+    for (int i = threadIdx.x; i < nc * s.Dm; i += 256) acc[i] = 0ull;
+    if (threadIdx.x < nc) cnt[threadIdx.x] = 0u;
+    __syncthreads();
+    for (int t = t0 + threadIdx.x; t < t1; t += 256) {
+      const int c = (int)codes[((size_t)u * s.N + t) * s.M + j] - c0;
+      if (c >= 0 && c < nc) {
+        atomicAdd(&cnt[c], 1u);
+        for (int i = 0; i < s.Dm; ++i) {
+          const int e = (i + threadIdx.x) & (s.Dm - 1);  // stagger lanes over LDS banks (Dm is a power of two)
+          const float xv = load_as_float<T>(keys, ((size_t)u * s.N + t) * kD + j * s.Dm + e);
+          const long long fx = __float2ll_rn(xv * (float)(1 << kFixShift));
+          atomicAdd(&acc[c * s.Dm + e], (unsigned long long)fx);
+        }
+      }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nc * s.Dm; i += 256)
+      if (acc[i]) atomicAdd(&sums[((size_t)uj * s.C + c0) * s.Dm + i], acc[i]);
+    if (threadIdx.x < nc && cnt[threadIdx.x]) atomicAdd(&counts[(size_t)uj * s.C + c0 + threadIdx.x], cnt[threadIdx.x]);
+  }
+}
+
+// cent = sums / counts where counts > 0
+__global__ __launch_bounds__(256) void pq_mean_kernel(BuildShape s, const unsigned long long* __restrict__ sums,
+                                                      const unsigned* __restrict__ counts, float* __restrict__ cent) {
+  const size_t i = blockIdx.x * (size_t)256 + threadIdx.x;
+  const size_t n = (size_t)s.units * s.M * s.C * s.Dm;
+  if (i >= n) return;
+  const unsigned k = counts[i / s.Dm];
+  if (k) cent[i] = (float)((double)(long long)sums[i] * (1.0 / (double)(1 << kFixShift)) / (double)k);
+}
+
+}  // namespace pqc

@@ -32,14 +32,34 @@ struct Shape {
 };
 
 // Device pointers carved out of the caller's workspace.
+struct BinParams;
 struct Workspace {
-  float2* ctl;                 // [units]            (lo, bins per unit of score)
+  BinParams* ctl;              // [units]            score -> bin map of the unit
   float* lut;                  // [units][M][C]
   unsigned* hist;              // [units][kNB]       zero between calls
   unsigned long long* stage;   // [units][nblkC][tokC] selected ids (front, int32) / candidates (back, u64)
   int2* stage_cnt;             // [units][nblkC]     (selected, candidates)
   float* partials;             // [units][npart][G][kD+2]
+#ifdef PQC_TRACE
+  unsigned long long* trace;   // [3 kernels][kTraceWgs][kTraceSlots] cycle stamps (debug builds only)
+#endif
 };
+
+// Phase time stamps for debug builds (-DPQC_TRACE); compiled out otherwise.
+#ifdef PQC_TRACE
+constexpr int kTraceWgs = 4096, kTraceSlots = 16;
+#define PQC_MARK(ws, kid, slot)                                                                              \
+  do {                                                                                                       \
+    if (threadIdx.x == 0) {                                                                                  \
+      const size_t wg_ = (size_t)blockIdx.y * gridDim.x + blockIdx.x;                                        \
+      if (wg_ < (size_t)kTraceWgs) (ws).trace[((size_t)(kid)*kTraceWgs + wg_) * kTraceSlots + (slot)] = wall_clock64(); \
+    }                                                                                                        \
+  } while (0)
+#else
+#define PQC_MARK(ws, kid, slot) \
+  do {                          \
+  } while (0)
+#endif
 
 // ---------------------------------------------------------------- small helpers
 __device__ __forceinline__ unsigned score_key(float f) {
@@ -58,11 +78,41 @@ __device__ __forceinline__ int composite_token(unsigned long long c) {
   return (int)(0xffffffffu - (unsigned)(c & 0xffffffffull));
 }
 
-__device__ __forceinline__ int score_bin(float s, float lo, float inv_w) {
-  // monotone non-decreasing in s: subtraction, multiplication by a non-negative
-  // constant and truncation all preserve order
-  int b = __float2int_rz((s - lo) * inv_w);
-  return max(0, min(kNB - 1, b));
+// Monotone map score -> bin.  Three linear pieces: kTailBins coarse bins below c0,
+// kNB - 2*kTailBins fine bins over [c0, c1], kTailBins coarse bins above c1.  The
+// piece is chosen by exact comparisons and each piece is clamped to its own bin
+// range, so the map is non-decreasing in s whatever the parameters are (inside a
+// piece: subtraction, multiplication by a non-negative constant and truncation all
+// preserve order).  Only the number of boundary-bin candidates depends on how well
+// [c0, c1] brackets the K-th largest score; the selection itself never does.
+constexpr int kTailBins = 64;
+constexpr int kFineBins = kNB - 2 * kTailBins;
+struct BinParams {
+  float lo, c0, c1, inv_lo, inv_c, inv_hi, pad0, pad1;
+};
+__device__ __forceinline__ int score_bin(float s, const BinParams& bp) {
+  if (s < bp.c0) return max(0, min(kTailBins - 1, __float2int_rz((s - bp.lo) * bp.inv_lo)));
+  if (s <= bp.c1) return kTailBins + max(0, min(kFineBins - 1, __float2int_rz((s - bp.c0) * bp.inv_c)));
+  return kTailBins + kFineBins + max(0, min(kTailBins - 1, __float2int_rz((s - bp.c1) * bp.inv_hi)));
+}
+// Bin layout from bounds lo <= score <= hi and a location/spread estimate of the scores:
+// the fine piece covers [mean - 3 sd, mean + 5 sd] (the K-th largest score of a
+// selection of a few percent to a half of the tokens lies there for bell-shaped scores).
+__device__ __forceinline__ BinParams make_bins(float lo, float hi, float mean, float sd) {
+  BinParams bp;
+  bp.lo = lo;
+  bp.c0 = fmaxf(lo, mean - 3.0f * sd);
+  bp.c1 = fminf(hi, mean + 5.0f * sd);
+  if (!(bp.c1 > bp.c0)) {  // degenerate spread: one fine piece over everything
+    bp.c0 = lo;
+    bp.c1 = hi;
+  }
+  const float wl = bp.c0 - lo, wc = bp.c1 - bp.c0, wh = hi - bp.c1;
+  bp.inv_lo = (wl > 1e-30f && wl < 3e38f) ? (float)kTailBins / wl : 0.0f;
+  bp.inv_c = (wc > 1e-30f && wc < 3e38f) ? (float)kFineBins / wc : 0.0f;
+  bp.inv_hi = (wh > 1e-30f && wh < 3e38f) ? (float)kTailBins / wh : 0.0f;
+  bp.pad0 = bp.pad1 = 0.0f;
+  return bp;
 }
 
 // Exclusive prefix sum over the threads of a workgroup (NT threads, multiple of 64).
@@ -114,60 +164,110 @@ __device__ __forceinline__ float load_as_float<bf16_t>(const bf16_t* p, int i) {
   return __uint_as_float((unsigned)p[i].bits << 16);
 }
 
-template <typename T, int NT>
-__device__ __forceinline__ void build_lut(const T* __restrict__ q /* [G][kD] of this unit */,
-                                          const float* __restrict__ cent /* [M][C][Dm] */, int G, int M,
-                                          int C, int Dm, float* lut, float* qs, float* red, float* lo_out,
-                                          float* inv_w_out) {
+// Centroids travel global -> registers (coalesced, all loads in flight at once) -> a
+// padded LDS tile of kLutTileFloats floats -> one thread per table entry runs the chain.
+constexpr int kLutTileFloats = 8192;
+template <typename T, int NT, int M>
+__device__ __forceinline__ BinParams build_lut(const T* __restrict__ q /* [G][kD] of this unit */,
+                                               const float* __restrict__ cent /* [M][C][Dm] */, int G, int C,
+                                               float* lut, float* qs, float* red /* [4*8] */,
+                                               float* tile /* [kLutTileFloats + kLutTileFloats/Dm] */) {
+  constexpr int Dm = kD / M;
+  constexpr int VPG = kLutTileFloats / (4 * NT);      // float4 per thread per tile
+  constexpr int NG = (256 * kD) / kLutTileFloats;      // tiles at the largest C
+  constexpr bool kPrefetchAll = (VPG * NG <= 8);       // keep every tile's loads in flight
   const int tid = threadIdx.x;
+  const int total = M * C * Dm;                        // floats, a multiple of 4
+  const float4* cent4 = reinterpret_cast<const float4*>(cent);
+  float4 v[kPrefetchAll ? NG : 1][VPG];
+  if constexpr (kPrefetchAll) {
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+      for (int x = 0; x < VPG; ++x) {
+        const int f = g * (kLutTileFloats / 4) + x * NT + tid;
+        if (4 * f < total) v[g][x] = cent4[f];
+      }
+  }
   if (tid < kD) {
     float a = load_as_float<T>(q, tid);
     for (int h = 1; h < G; ++h) a = __fadd_rn(a, load_as_float<T>(q, h * kD + tid));
     qs[tid] = a;
   }
-  __syncthreads();
-  for (int e = tid; e < M * C; e += NT) {
-    const int j = e / C, c = e - j * C;
-    const float4* row = reinterpret_cast<const float4*>(cent + (size_t)e * Dm);
-    const float* qj = qs + j * Dm;
-    float p = 0.0f;
-    for (int x = 0; x < Dm / 4; ++x) {
-      float4 cv = row[x];
-      p = __fmaf_rn(qj[4 * x + 0], cv.x, p);
-      p = __fmaf_rn(qj[4 * x + 1], cv.y, p);
-      p = __fmaf_rn(qj[4 * x + 2], cv.z, p);
-      p = __fmaf_rn(qj[4 * x + 3], cv.w, p);
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    if (g * kLutTileFloats < total) {  // uniform
+      if constexpr (!kPrefetchAll) {
+#pragma unroll
+        for (int x = 0; x < VPG; ++x) {
+          const int f = g * (kLutTileFloats / 4) + x * NT + tid;
+          if (4 * f < total) v[0][x] = cent4[f];
+        }
+      }
+      if (g > 0) __syncthreads();  // previous tile fully consumed
+#pragma unroll
+      for (int x = 0; x < VPG; ++x) {
+        const int fl = (x * NT + tid) * 4;  // float index inside the tile
+        if (g * kLutTileFloats + fl < total) {
+          const float4 cv = v[kPrefetchAll ? g : 0][x];
+          const int row = fl / Dm, col = fl % Dm;  // Dm is a multiple of 4: one row per float4
+          float* dst = tile + row * (Dm + 1) + col;
+          dst[0] = cv.x; dst[1] = cv.y; dst[2] = cv.z; dst[3] = cv.w;
+        }
+      }
+      __syncthreads();  // tile (and, first time round, qs) visible
+      const int rows = min(kLutTileFloats, total - g * kLutTileFloats) / Dm;
+      for (int r = tid; r < rows; r += NT) {
+        const int e = g * (kLutTileFloats / Dm) + r;
+        const int j = e / C, c = e - j * C;
+        const float* qj = qs + j * Dm;
+        const float* cr = tile + r * (Dm + 1);
+        float p = 0.0f;
+#pragma unroll
+        for (int x = 0; x < Dm; ++x) p = __fmaf_rn(qj[x], cr[x], p);
+        lut[j * kLutRow + c] = p;
+      }
     }
-    lut[j * kLutRow + c] = p;
   }
   __syncthreads();
+  // per table: min, max, sum, sum of squares (one wave per table, fixed reduction tree)
   const int lane = tid & 63, w = tid >> 6;
   for (int j = w; j < M; j += NT / 64) {
-    float mn = INFINITY, mx = -INFINITY;
+    float mn = INFINITY, mx = -INFINITY, sm = 0.0f, sq = 0.0f;
     for (int c = lane; c < C; c += 64) {
-      float v = lut[j * kLutRow + c];
+      const float v = lut[j * kLutRow + c];
       mn = fminf(mn, v);
       mx = fmaxf(mx, v);
+      sm += v;
+      sq = fmaf(v, v, sq);
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {
       mn = fminf(mn, __shfl_xor(mn, o));
       mx = fmaxf(mx, __shfl_xor(mx, o));
+      sm += __shfl_xor(sm, o);
+      sq += __shfl_xor(sq, o);
     }
     if (lane == 0) {
       red[j] = mn;
       red[8 + j] = mx;
+      red[16 + j] = sm;
+      red[24 + j] = sq;
     }
   }
   __syncthreads();
+  // bounds are added in the same order as a score, so lo <= score <= hi holds in fp32
   float lo = red[0], hi = red[8];
+  const float invC = 1.0f / (float)C;
+  float mean = red[16] * invC, var = fmaxf(0.0f, red[24] * invC - (red[16] * invC) * (red[16] * invC));
   for (int j = 1; j < M; ++j) {
     lo = __fadd_rn(lo, red[j]);
     hi = __fadd_rn(hi, red[8 + j]);
+    const float mj = red[16 + j] * invC;
+    mean += mj;
+    var += fmaxf(0.0f, red[24 + j] * invC - mj * mj);
   }
-  const float width = hi - lo;
-  *lo_out = lo;
-  *inv_w_out = (width > 1e-30f) ? (float)kNB / width : 0.0f;
+  return make_bins(lo, hi, mean, sqrtf(var));
 }
 
 // ------------------------------------------------------------------- code scan
@@ -200,22 +300,20 @@ __device__ __forceinline__ float score_from_word(typename CodeWord<M>::type w, c
   return s;
 }
 
-// Where a kernel takes its scores from: PQ codes through the LDS table (the decode
-// path) or a score array in global memory (the stand-alone top-k stage).
-template <int M_>
-struct CodeSource {
-  static constexpr int M = M_;
-  static constexpr bool kFromCodes = true;
-  const typename CodeWord<M_>::type* codes;  // this unit's [N] code words
-  const float* lut;                          // LDS
-  __device__ __forceinline__ float score(int t) const { return score_from_word<M_>(codes[t], lut); }
-};
-struct ScoreSource {
-  static constexpr int M = 0;
-  static constexpr bool kFromCodes = false;
-  const float* scores;  // this unit's [N] scores
-  __device__ __forceinline__ float score(int t) const { return scores[t]; }
-};
+// 16 bytes of codes = P = 16/M consecutive tokens; word i of the chunk.
+template <int M>
+__device__ __forceinline__ typename CodeWord<M>::type chunk_word(const uint4& raw, int i) {
+  const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
+  if constexpr (M == 8) {
+    return ((unsigned long long)w[2 * i + 1] << 32) | w[2 * i];
+  } else if constexpr (M == 4) {
+    return w[i];
+  } else if constexpr (M == 2) {
+    return (uint16_t)(w[i >> 1] >> (16 * (i & 1)));
+  } else {
+    return (uint8_t)(w[i >> 2] >> (8 * (i & 3)));
+  }
+}
 
 // ------------------------------------------------------------ threshold search
 // Section 3.2 (k-th largest score).  The unit's histogram over kNB monotone score
@@ -343,11 +441,16 @@ __device__ __forceinline__ void load_query(const T* __restrict__ q /* [G][kD] */
     for (int e = 0; e < 8; ++e) qr[h][e] = load_as_float<T>(q, h * kD + owned_dim<T>(sub, e)) * scale_log2e;
 }
 
+// Sum over the 16 lanes of a DPP row; every lane of the row receives the total.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
 __device__ __forceinline__ float group16_sum(float x) {
-  x += __shfl_xor(x, 1);
-  x += __shfl_xor(x, 2);
-  x += __shfl_xor(x, 4);
-  x += __shfl_xor(x, 8);
+  x += dpp_move<0xB1>(x);   // quad_perm [1,0,3,2]: neighbour in the pair
+  x += dpp_move<0x4E>(x);   // quad_perm [2,3,0,1]: other pair of the quad
+  x += dpp_move<0x141>(x);  // row_half_mirror: other quad of the half row
+  x += dpp_move<0x140>(x);  // row_mirror: other half of the row
   return x;
 }
 
