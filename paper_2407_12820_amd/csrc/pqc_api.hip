@@ -20,7 +20,8 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
   Shape s;
-  size_t off_ctl, off_lut, off_hist, off_stage, off_cnt, off_part, off_trace, total;
+  size_t off_ctl, off_lut, off_range, off_hist, off_crec, off_stage, off_cnt, off_part, off_trace, total;
+  int rec_stride;
 };
 
 int env_int(const char* name, int fallback) {
@@ -55,32 +56,54 @@ int make_plan(const pqc_config* c, Plan* p) {
   s.scale_log2e = scale * 1.4426950408889634f;
   const long long units = (long long)s.B * s.Hkv;
 
-  // histogram kernel: few, large workgroups (contended bins serialise per workgroup)
-  // (a unit's first 16-byte code chunk may start up to 15 phantom tokens early: + 15)
+  // A unit's codes start at byte u*N*M; when that is not always 16-byte aligned the first
+  // chunk of a unit begins with up to 15 phantom tokens that the grids must cover as well.
+  const int lead = ((long long)s.N * s.M) % 16 == 0 ? 0 : 15;
+  // histogram kernel: about one 1024-thread workgroup per compute unit over all units
+  const int maxA = 4096 * (16 / s.M) < 16384 ? 4096 * (16 / s.M) : 16384;  // kMaxVecA chunks per thread
   int tokA = env_int("PQC_TOK_A", 0);
   if (!tokA) {
-    tokA = 4096;
-    const int cap = 4096 * (16 / s.M) < 16384 ? 4096 * (16 / s.M) : 16384;  // kMaxVecA chunks per thread
-    while (tokA < cap && ((s.N + 15 + tokA - 1) / tokA) > 8) tokA *= 2;
+    tokA = 1024;
+    while (tokA < maxA && units * ((s.N + lead + tokA - 1) / tokA) > 320) tokA *= 2;
   }
-  if (tokA % 1024 || tokA > 16384 || tokA > 4096 * (16 / s.M)) return PQC_EINVAL;
-  s.tokA = tokA; s.nblkA = (s.N + 15 + tokA - 1) / tokA;
-  // select kernel: aim for a few workgroups per compute unit
+  if (tokA % 1024 || tokA > maxA) return PQC_EINVAL;
+  s.tokA = tokA; s.nblkA = (s.N + lead + tokA - 1) / tokA;
+  // select kernel: 256-thread workgroups, two resident per compute unit
   int tokC = env_int("PQC_TOK_C", 0);
   if (!tokC) {
-    tokC = 2048;
-    while (tokC < 8192 && units * ((s.N + 15 + tokC - 1) / tokC) > 1024) tokC *= 2;
+    tokC = 1024;
+    while (tokC < 4096 && units * ((s.N + lead + tokC - 1) / tokC) > 512) tokC *= 2;
   }
-  if (tokC % 256 || tokC > 8192) return PQC_EINVAL;
-  s.tokC = tokC; s.nblkC = (s.N + 15 + tokC - 1) / tokC;
+  if (tokC % 256 || tokC > 4096) return PQC_EINVAL;
+  s.tokC = tokC; s.nblkC = (s.N + lead + tokC - 1) / tokC;
   s.rowsP = env_int("PQC_ROWS_P", 256);
   s.nblkP = (s.Ktot + s.rowsP - 1) / s.rowsP;
   s.npart = s.nblkC > s.nblkP ? s.nblkC : s.nblkP;
+  s.parity = 0;
+  // candidate records: a fixed number of slots per select workgroup, <= 2048 per unit
+  int rec = 16;
+  while (rec > 1 && (long long)rec * s.nblkC > 256 * kSlotsPerThread) rec /= 2;
+  if ((long long)rec * s.nblkC > 256 * kSlotsPerThread) return PQC_EUNSUPPORTED;
+  s.recPerWg = rec;
+  p->rec_stride = (int)sizeof(CandHeader) + kD * (c->kv_dtype == PQC_F32 ? 4 : 2);
+  // sample ranks that bracket the K-th largest score by 5 standard errors (+2)
+  const int nmid = s.N - s.I - s.L;
+  s.sampleN = nmid < 1024 ? (nmid > 0 ? nmid : 1) : 1024;
+  {
+    const double pr = nmid > 0 ? (double)s.K / (double)nmid : 0.0;
+    const double centre = pr * s.sampleN, hw = 5.0 * std::sqrt(s.sampleN * pr * (1.0 - pr)) + 2.0;
+    s.rankHi = (int)std::floor(centre - hw);                       // < 1: the window reaches the upper bound
+    s.rankLo = (int)std::ceil(centre + hw);
+    if (s.rankLo > s.sampleN) s.rankLo = 0;                        // 0: the window reaches the lower bound
+    if (s.rankHi < 1) s.rankHi = 0;
+  }
 
   size_t off = 0;
   p->off_ctl = off;   off = align_up(off + sizeof(BinParams) * units);
   p->off_lut = off;   off = align_up(off + sizeof(float) * units * s.M * s.C);
-  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * units * kNB);
+  p->off_range = off; off = align_up(off + sizeof(float2) * units);
+  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * 2 * units * kHistCopies * kNB);
+  p->off_crec = off;  off = align_up(off + (size_t)p->rec_stride * s.recPerWg * s.nblkC * units);
   p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * s.nblkC * s.tokC);
   p->off_cnt = off;   off = align_up(off + sizeof(int2) * units * s.nblkC);
   p->off_part = off;  off = align_up(off + sizeof(float) * units * s.npart * s.G * (kD + 2));
@@ -115,12 +138,16 @@ int check_launch(pqc_ctx* ctx) {
   return PQC_OK;
 }
 
+// Both parities' histograms must be zero before a call uses them; finalize_kernel restores
+// that for the set it did not use.
 int ensure_clean_hist(pqc_ctx* ctx, hipStream_t st) {
   if (ctx->hist_clean) return PQC_OK;
   const Shape& s = ctx->plan.s;
-  const size_t n = (size_t)s.B * s.Hkv * kNB;
-  hipLaunchKernelGGL(reset_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, ctx->ws.hist, n);
-  return check_launch(ctx);
+  const size_t na = (size_t)2 * s.B * s.Hkv * kHistCopies * kNB;
+  hipLaunchKernelGGL(reset_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, st, ctx->ws.hist, na);
+  const int rc = check_launch(ctx);
+  if (rc == PQC_OK) ctx->plan.s.parity = 0;
+  return rc;
 }
 
 // ---- template dispatch -------------------------------------------------------
@@ -140,7 +167,7 @@ void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uin
   hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(int), st,
                      s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));
   if (ev) (void)hipEventRecord(ev[2], st);
-  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(1, units), dim3(512), 2 * (s.nblkC + 1) * sizeof(int), st, s,
+  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
                      ctx->ws, qt, kt, vt, out_idx, out_attn);
   if (ev) (void)hipEventRecord(ev[3], st);
 }
@@ -252,6 +279,9 @@ int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t wor
   ctx->ws.ctl = reinterpret_cast<BinParams*>(base + p.off_ctl);
   ctx->ws.lut = reinterpret_cast<float*>(base + p.off_lut);
   ctx->ws.hist = reinterpret_cast<unsigned*>(base + p.off_hist);
+  ctx->ws.range = reinterpret_cast<float2*>(base + p.off_range);
+  ctx->ws.cand_rec = reinterpret_cast<unsigned char*>(base + p.off_crec);
+  ctx->ws.rec_stride = p.rec_stride;
   ctx->ws.stage = reinterpret_cast<unsigned long long*>(base + p.off_stage);
   ctx->ws.stage_cnt = reinterpret_cast<int2*>(base + p.off_cnt);
   ctx->ws.partials = reinterpret_cast<float*>(base + p.off_part);
@@ -283,7 +313,10 @@ static int decode_impl(pqc_ctx* ctx, const void* q, const float* centroids, cons
   else
     launch_decode_t<bf16_t>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st, ev);
   rc = check_launch(ctx);
-  if (rc == PQC_OK) ctx->hist_clean = true;  // finalize_kernel re-zeroes the histogram
+  if (rc == PQC_OK) {
+    ctx->hist_clean = true;  // finalize_kernel zeroed the other parity's set, which the next call uses
+    ctx->plan.s.parity ^= 1;
+  }
   return rc;
 }
 
@@ -356,15 +389,18 @@ int pqc_topk(pqc_ctx* ctx, const float* scores, int32_t* out_idx, void* stream) 
   ctx->hist_clean = false;
   const unsigned units = (unsigned)(s.B * s.Hkv);
   const float* nof = nullptr;
-  hipLaunchKernelGGL(score_stats_kernel, dim3(1, units), dim3(1024), 0, st, s, scores, ctx->ws.ctl);
+  hipLaunchKernelGGL(score_range_kernel, dim3(1, units), dim3(1024), 0, st, s, scores, ctx->ws.range);
   hipLaunchKernelGGL((hist_kernel<float, ScoreChunks>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, nof, nof,
                      static_cast<const void*>(scores));
   hipLaunchKernelGGL((select_kernel<float, 1, ScoreChunks, false>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(int), st,
                      s, ctx->ws, nof, nof, nof, static_cast<const void*>(scores));
-  hipLaunchKernelGGL((finalize_kernel<float, 1, false>), dim3(1, units), dim3(512), 2 * (s.nblkC + 1) * sizeof(int), st, s,
+  hipLaunchKernelGGL((finalize_kernel<float, 1, false>), dim3(1, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
                      ctx->ws, nof, nof, nof, out_idx, static_cast<float*>(nullptr));
   rc = check_launch(ctx);
-  if (rc == PQC_OK) ctx->hist_clean = true;
+  if (rc == PQC_OK) {
+    ctx->hist_clean = true;
+    ctx->plan.s.parity ^= 1;
+  }
   return rc;
 }
 

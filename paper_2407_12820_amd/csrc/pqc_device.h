@@ -1,10 +1,9 @@
 // Device-side building blocks of libpqcache (gfx950, wave64).
 //
 // Everything here is a __device__ template; the kernels that use them live in
-// pqc_kernels.h and are instantiated by the launch files.  Citations are to the
-// paper's sections (PQ search: Section 2.2 and Section 3.1 step 4; top-k: Section
-// 3.1 steps 4-5 and Section 3.2; selective attention: Section 2.1 and Section 3.1
-// step 6).
+// pqc_kernels.h.  Citations are to the paper's sections (PQ search: Section 2.2 and
+// Section 3.1 step 4; top-k: Section 3.1 steps 4-5 and Section 3.2; selective
+// attention: Section 2.1 and Section 3.1 step 6).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -12,14 +11,19 @@
 namespace pqc {
 
 constexpr int kNB = 2048;        // score bins of the one-pass threshold search
+constexpr int kHistCopies = 4;   // histogram replicas per unit (spreads contended atomics)
 constexpr int kD = 128;          // head dimension
 constexpr int kLutRow = 256;     // LDS stride of one partition's table (max centroids)
-constexpr int kCandLds = 1024;   // boundary-bin candidates resolved inside LDS
+constexpr int kCandRec = 1024;   // boundary-bin candidates the finalize kernel ranks inside LDS
 constexpr float kNegBig = -1.0e30f;
 
 struct bf16_t {
   uint16_t bits;
 };
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 // Geometry of one decode step, passed by value to every kernel.
 struct Shape {
@@ -28,20 +32,35 @@ struct Shape {
   int tokC, nblkC;  // select kernel: tokens per workgroup, workgroups per unit
   int rowsP, nblkP; // list-attention kernel: rows per workgroup, workgroups per unit
   int npart;        // partial slots per unit
+  int parity;       // which of the two histogram sets this call uses
+  int sampleN;      // tokens sampled per unit to place the fine bins (<= 1024)
+  int rankHi, rankLo;  // sample ranks (from the top) that bracket the K-th largest score
+  int recPerWg;     // candidate record slots per select workgroup
   float scale_log2e;
 };
 
-// Device pointers carved out of the caller's workspace.
+// Record of one boundary-bin candidate: enough for the finalize kernel to rank it and,
+// if admitted, to add it to the attention output without touching the K/V cache again.
+struct CandHeader {
+  unsigned long long composite;  // (score key, ~token): larger ranks first
+  float logit[8];                // q_h . k for the group's heads (raw, unscaled)
+  unsigned pad[6];
+};                               // 64 bytes, followed by the V row
+
 struct BinParams;
+// Device pointers carved out of the caller's workspace.
 struct Workspace {
-  BinParams* ctl;              // [units]            score -> bin map of the unit
+  BinParams* ctl;              // [units]                       score -> bin map of the unit
   float* lut;                  // [units][M][C]
-  unsigned* hist;              // [units][kNB]       zero between calls
-  unsigned long long* stage;   // [units][nblkC][tokC] selected ids (front, int32) / candidates (back, u64)
+  float2* range;               // [units]                       (min, max) score, stand-alone top-k only
+  unsigned* hist;              // [2][units][kHistCopies][kNB]   zero between uses
+  unsigned char* cand_rec;     // [units][nblkC][recPerWg] records of rec_stride bytes
+  unsigned long long* stage;   // [units][nblkC][tokC] selected ids (front, int32) / candidate composites (back, u64)
   int2* stage_cnt;             // [units][nblkC]     (selected, candidates)
   float* partials;             // [units][npart][G][kD+2]
+  int rec_stride;
 #ifdef PQC_TRACE
-  unsigned long long* trace;   // [3 kernels][kTraceWgs][kTraceSlots] cycle stamps (debug builds only)
+  unsigned long long* trace;   // [3 kernels][kTraceWgs][kTraceSlots] time stamps (debug builds only)
 #endif
 };
 
@@ -55,11 +74,27 @@ constexpr int kTraceWgs = 4096, kTraceSlots = 16;
       if (wg_ < (size_t)kTraceWgs) (ws).trace[((size_t)(kid)*kTraceWgs + wg_) * kTraceSlots + (slot)] = wall_clock64(); \
     }                                                                                                        \
   } while (0)
+#define PQC_NOTE(ws, kid, slot, val)                                                                         \
+  do {                                                                                                       \
+    if (threadIdx.x == 0) {                                                                                  \
+      const size_t wg_ = (size_t)blockIdx.y * gridDim.x + blockIdx.x;                                        \
+      if (wg_ < (size_t)kTraceWgs) (ws).trace[((size_t)(kid)*kTraceWgs + wg_) * kTraceSlots + (slot)] = (unsigned long long)(val); \
+    }                                                                                                        \
+  } while (0)
 #else
 #define PQC_MARK(ws, kid, slot) \
   do {                          \
   } while (0)
+#define PQC_NOTE(ws, kid, slot, val) \
+  do {                               \
+  } while (0)
 #endif
+
+// Marks the end of a group of independent loads: the instruction scheduler may not move
+// anything across this point, so the loads above are all issued before their first use
+// (left alone it tends to interleave load and use to save registers, which turns one
+// memory round trip into many).
+#define PQC_LOADS_ISSUED() __builtin_amdgcn_sched_barrier(0)
 
 // ---------------------------------------------------------------- small helpers
 __device__ __forceinline__ unsigned score_key(float f) {
@@ -79,31 +114,40 @@ __device__ __forceinline__ int composite_token(unsigned long long c) {
 }
 
 // Monotone map score -> bin.  Three linear pieces: kTailBins coarse bins below c0,
-// kNB - 2*kTailBins fine bins over [c0, c1], kTailBins coarse bins above c1.  The
-// piece is chosen by exact comparisons and each piece is clamped to its own bin
-// range, so the map is non-decreasing in s whatever the parameters are (inside a
-// piece: subtraction, multiplication by a non-negative constant and truncation all
-// preserve order).  Only the number of boundary-bin candidates depends on how well
-// [c0, c1] brackets the K-th largest score; the selection itself never does.
-constexpr int kTailBins = 64;
+// kFineBins fine bins over [c0, c1], kTailBins coarse bins above c1.  The piece is
+// chosen by exact comparisons and each piece is clamped to its own bin range, so the
+// map is non-decreasing in s whatever the parameters are (inside a piece: subtraction,
+// multiplication by a non-negative constant and truncation all preserve order).  Only
+// the number of boundary-bin candidates depends on how well [c0, c1] brackets the K-th
+// largest score; the selection itself never does.
+constexpr int kTailBins = 256;
 constexpr int kFineBins = kNB - 2 * kTailBins;
 struct BinParams {
-  float lo, c0, c1, inv_lo, inv_c, inv_hi, pad0, pad1;
+  float lo, c0, c1, inv_lo, inv_c, inv_hi, hi, pad;
 };
-__device__ __forceinline__ int score_bin(float s, const BinParams& bp) {
-  if (s < bp.c0) return max(0, min(kTailBins - 1, __float2int_rz((s - bp.lo) * bp.inv_lo)));
-  if (s <= bp.c1) return kTailBins + max(0, min(kFineBins - 1, __float2int_rz((s - bp.c0) * bp.inv_c)));
-  return kTailBins + kFineBins + max(0, min(kTailBins - 1, __float2int_rz((s - bp.c1) * bp.inv_hi)));
+// The layout as six scalars held in registers (selecting among the fields of a struct in
+// memory makes the compiler index it like an array, which lands it in scratch or LDS).
+struct Bins {
+  float lo, c0, c1, inv_lo, inv_c, inv_hi;
+};
+__device__ __forceinline__ int score_bin(float s, float lo, float c0, float c1, float inv_lo, float inv_c, float inv_hi) {
+  const int b_lo = min(kTailBins - 1, __float2int_rz((s - lo) * inv_lo));
+  const int b_c = kTailBins + min(kFineBins - 1, __float2int_rz((s - c0) * inv_c));
+  const int b_hi = kTailBins + kFineBins + min(kTailBins - 1, __float2int_rz((s - c1) * inv_hi));
+  int b = s < c0 ? b_lo : b_c;
+  b = s > c1 ? b_hi : b;
+  return max(0, b);
 }
-// Bin layout from bounds lo <= score <= hi and a location/spread estimate of the scores:
-// the fine piece covers [mean - 3 sd, mean + 5 sd] (the K-th largest score of a
-// selection of a few percent to a half of the tokens lies there for bell-shaped scores).
-__device__ __forceinline__ BinParams make_bins(float lo, float hi, float mean, float sd) {
+#define PQC_BIN(s, bp) score_bin((s), (bp).lo, (bp).c0, (bp).c1, (bp).inv_lo, (bp).inv_c, (bp).inv_hi)
+// Bin layout from bounds lo <= score <= hi and a window [q_lo, q_hi] expected to hold
+// the K-th largest score.
+__device__ __forceinline__ BinParams make_bins(float lo, float hi, float q_lo, float q_hi) {
   BinParams bp;
   bp.lo = lo;
-  bp.c0 = fmaxf(lo, mean - 3.0f * sd);
-  bp.c1 = fminf(hi, mean + 5.0f * sd);
-  if (!(bp.c1 > bp.c0)) {  // degenerate spread: one fine piece over everything
+  bp.hi = hi;
+  bp.c0 = fmaxf(lo, q_lo);
+  bp.c1 = fminf(hi, q_hi);
+  if (!(bp.c1 > bp.c0)) {  // degenerate window: one fine piece over everything
     bp.c0 = lo;
     bp.c1 = hi;
   }
@@ -111,8 +155,58 @@ __device__ __forceinline__ BinParams make_bins(float lo, float hi, float mean, f
   bp.inv_lo = (wl > 1e-30f && wl < 3e38f) ? (float)kTailBins / wl : 0.0f;
   bp.inv_c = (wc > 1e-30f && wc < 3e38f) ? (float)kFineBins / wc : 0.0f;
   bp.inv_hi = (wh > 1e-30f && wh < 3e38f) ? (float)kTailBins / wh : 0.0f;
-  bp.pad0 = bp.pad1 = 0.0f;
+  bp.pad = 0.0f;
   return bp;
+}
+
+// ------------------------------------------------------------ cross-lane helpers
+// DPP moves: a lane whose source is outside its row (or masked out) keeps `identity`.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ int dpp_i(int identity, int x) {
+  return __builtin_amdgcn_update_dpp(identity, x, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ float dpp_f(float identity, float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(x), CTRL, ROW_MASK, 0xf, false));
+}
+// row_shr:1,2,4,8 then row_bcast:15 (rows 1,3) and row_bcast:31 (rows 2,3)
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  v += dpp_i<0x111>(0, v);
+  v += dpp_i<0x112>(0, v);
+  v += dpp_i<0x114>(0, v);
+  v += dpp_i<0x118>(0, v);
+  v += dpp_i<0x142, 0xa>(0, v);
+  v += dpp_i<0x143, 0xc>(0, v);
+  return v;
+}
+__device__ __forceinline__ int wave_last(int v) { return __builtin_amdgcn_readlane(v, 63); }
+__device__ __forceinline__ float wave_sum(float v) {
+  v += dpp_f<0x111>(0.0f, v);
+  v += dpp_f<0x112>(0.0f, v);
+  v += dpp_f<0x114>(0.0f, v);
+  v += dpp_f<0x118>(0.0f, v);
+  v += dpp_f<0x142, 0xa>(0.0f, v);
+  v += dpp_f<0x143, 0xc>(0.0f, v);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, dpp_f<0x111>(-INFINITY, v));
+  v = fmaxf(v, dpp_f<0x112>(-INFINITY, v));
+  v = fmaxf(v, dpp_f<0x114>(-INFINITY, v));
+  v = fmaxf(v, dpp_f<0x118>(-INFINITY, v));
+  v = fmaxf(v, dpp_f<0x142, 0xa>(-INFINITY, v));
+  v = fmaxf(v, dpp_f<0x143, 0xc>(-INFINITY, v));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ float wave_min(float v) { return -wave_max(-v); }
+
+// Sum over the 16 lanes of a DPP row; every lane of the row receives the total.
+__device__ __forceinline__ float group16_sum(float x) {
+  x += dpp_f<0xB1>(0.0f, x);   // quad_perm [1,0,3,2]: neighbour in the pair
+  x += dpp_f<0x4E>(0.0f, x);   // quad_perm [2,3,0,1]: other pair of the quad
+  x += dpp_f<0x141>(0.0f, x);  // row_half_mirror: other quad of the half row
+  x += dpp_f<0x140>(0.0f, x);  // row_mirror: other half of the row
+  return x;
 }
 
 // Exclusive prefix sum over the threads of a workgroup (NT threads, multiple of 64).
@@ -120,27 +214,17 @@ template <int NT>
 __device__ __forceinline__ int block_exclusive_scan(int v, int* total, int* sm /* [2*(NT/64)+1] */) {
   constexpr int NW = NT / 64;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    int n = __shfl_up(inc, o);
-    if (lane >= o) inc += n;
-  }
+  const int inc = wave_inclusive_scan(v);
   if (lane == 63) sm[w] = inc;
   __syncthreads();
   if (w == 0) {
-    int s = lane < NW ? sm[lane] : 0;
-    int si = s;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      int n = __shfl_up(si, o);
-      if (lane >= o) si += n;
-    }
+    const int s = lane < NW ? sm[lane] : 0;
+    const int si = wave_inclusive_scan(s);
     if (lane < NW) sm[NW + lane] = si - s;
     if (lane == NW - 1) sm[2 * NW] = si;
   }
   __syncthreads();
-  int res = inc - v + sm[NW + w];
+  const int res = inc - v + sm[NW + w];
   *total = sm[2 * NW];
   __syncthreads();
   return res;
@@ -149,10 +233,10 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* total, int* sm /
 // --------------------------------------------------------------- look-up table
 // Section 2.2 (search) / Section 3.1 step 4: table[j][c] = qs[j*Dm..] . cent[j][c][..]
 // with qs the sum of the group's query heads.  Fixed fp32 order: head order for
-// the sum, one fused multiply-add chain per entry.  Also derives bounds on every
-// possible score: lo = sum_j min_c table[j][c], hi likewise with max, added in the
-// same order as a score, so that lo <= score <= hi holds in fp32.
-//   lut   LDS [M][kLutRow]      qs  LDS [kD]      red LDS [2*8]
+// the sum, one fused multiply-add chain per entry.  Also derives the score -> bin map
+// from bounds on every possible score (lo = sum_j min_c table[j][c], hi likewise with
+// max, added in the same order as a score, so that lo <= score <= hi holds in fp32)
+// and from the mean and spread the scores would have under uniform code usage.
 template <typename T>
 __device__ __forceinline__ float load_as_float(const T* p, int i);
 template <>
@@ -168,7 +252,7 @@ __device__ __forceinline__ float load_as_float<bf16_t>(const bf16_t* p, int i) {
 // padded LDS tile of kLutTileFloats floats -> one thread per table entry runs the chain.
 constexpr int kLutTileFloats = 8192;
 template <typename T, int NT, int M>
-__device__ __forceinline__ BinParams build_lut(const T* __restrict__ q /* [G][kD] of this unit */,
+__device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] of this unit */,
                                                const float* __restrict__ cent /* [M][C][Dm] */, int G, int C,
                                                float* lut, float* qs, float* red /* [4*8] */,
                                                float* tile /* [kLutTileFloats + kLutTileFloats/Dm] */) {
@@ -186,13 +270,23 @@ __device__ __forceinline__ BinParams build_lut(const T* __restrict__ q /* [G][kD
 #pragma unroll
       for (int x = 0; x < VPG; ++x) {
         const int f = g * (kLutTileFloats / 4) + x * NT + tid;
-        if (4 * f < total) v[g][x] = cent4[f];
+        v[g][x] = cent4[min(f, total / 4 - 1)];
       }
   }
-  if (tid < kD) {
-    float a = load_as_float<T>(q, tid);
-    for (int h = 1; h < G; ++h) a = __fadd_rn(a, load_as_float<T>(q, h * kD + tid));
-    qs[tid] = a;
+  {
+    // the group's query heads: all loads first (clamped, straight-line), then the sum in head order
+    const int dq = tid & (kD - 1);
+    float qv[8];
+#pragma unroll
+    for (int h = 0; h < 8; ++h) qv[h] = load_as_float<T>(q, min(h, G - 1) * kD + dq);
+    PQC_LOADS_ISSUED();
+    float a = qv[0];
+#pragma unroll
+    for (int h = 1; h < 8; ++h) {
+      const float t = __fadd_rn(a, qv[h]);
+      a = h < G ? t : a;  // select, not branch: keeps the eight loads above in flight together
+    }
+    if (tid < kD) qs[tid] = a;
   }
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
@@ -201,7 +295,7 @@ __device__ __forceinline__ BinParams build_lut(const T* __restrict__ q /* [G][kD
 #pragma unroll
         for (int x = 0; x < VPG; ++x) {
           const int f = g * (kLutTileFloats / 4) + x * NT + tid;
-          if (4 * f < total) v[0][x] = cent4[f];
+          v[0][x] = cent4[min(f, total / 4 - 1)];
         }
       }
       if (g > 0) __syncthreads();  // previous tile fully consumed
@@ -230,44 +324,76 @@ __device__ __forceinline__ BinParams build_lut(const T* __restrict__ q /* [G][kD
     }
   }
   __syncthreads();
-  // per table: min, max, sum, sum of squares (one wave per table, fixed reduction tree)
+  // per table: min and max (one wave per table)
   const int lane = tid & 63, w = tid >> 6;
   for (int j = w; j < M; j += NT / 64) {
-    float mn = INFINITY, mx = -INFINITY, sm = 0.0f, sq = 0.0f;
+    float mn = INFINITY, mx = -INFINITY;
     for (int c = lane; c < C; c += 64) {
-      const float v = lut[j * kLutRow + c];
-      mn = fminf(mn, v);
-      mx = fmaxf(mx, v);
-      sm += v;
-      sq = fmaf(v, v, sq);
+      const float x = lut[j * kLutRow + c];
+      mn = fminf(mn, x);
+      mx = fmaxf(mx, x);
     }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-      mn = fminf(mn, __shfl_xor(mn, o));
-      mx = fmaxf(mx, __shfl_xor(mx, o));
-      sm += __shfl_xor(sm, o);
-      sq += __shfl_xor(sq, o);
-    }
+    mn = wave_min(mn);
+    mx = wave_max(mx);
     if (lane == 0) {
       red[j] = mn;
       red[8 + j] = mx;
-      red[16 + j] = sm;
-      red[24 + j] = sq;
     }
   }
   __syncthreads();
   // bounds are added in the same order as a score, so lo <= score <= hi holds in fp32
   float lo = red[0], hi = red[8];
-  const float invC = 1.0f / (float)C;
-  float mean = red[16] * invC, var = fmaxf(0.0f, red[24] * invC - (red[16] * invC) * (red[16] * invC));
   for (int j = 1; j < M; ++j) {
     lo = __fadd_rn(lo, red[j]);
     hi = __fadd_rn(hi, red[8 + j]);
-    const float mj = red[16 + j] * invC;
-    mean += mj;
-    var += fmaxf(0.0f, red[24 + j] * invC - mj * mj);
   }
-  return make_bins(lo, hi, mean, sqrtf(var));
+  return make_float2(lo, hi);
+}
+
+// Where the fine bins go: every workgroup of a unit scores the same `n` sampled tokens,
+// histograms them over kNB uniform bins of [lo, hi] and takes the bins that hold the
+// sample's rank_hi-th and rank_lo-th largest scores as the window.  The ranks bracket
+// the K-th largest of all tokens by several standard errors of the sample quantile, so
+// the window almost always holds it (and when it does not, only speed is lost).
+//   hist  LDS [kNB], zero on entry, zero again on return      sm  LDS [2*(NT/64)+1+2]
+template <int NT>
+__device__ __forceinline__ BinParams sample_window(float lo, float hi, float my_score, bool have_sample, int rank_hi,
+                                                   int rank_lo, unsigned* hist, int* sm) {
+  constexpr int PER = kNB / NT, NW = NT / 64;
+  const int tid = threadIdx.x;
+  const float width = hi - lo;
+  const float inv_u = (width > 1e-30f && width < 3e38f) ? (float)kNB / width : 0.0f;
+  if (have_sample) atomicAdd(&hist[max(0, min(kNB - 1, __float2int_rz((my_score - lo) * inv_u)))], 1u);
+  __syncthreads();
+  unsigned h[PER];
+  int sum = 0;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    h[e] = hist[kNB - 1 - (tid * PER + e)];
+    sum += (int)h[e];
+  }
+  int total;
+  int cum = block_exclusive_scan<NT>(sum, &total, sm);
+  int* res = sm + 2 * NW + 1;
+  if (tid == 0) {
+    res[0] = -1;
+    res[1] = -1;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const int b = kNB - 1 - (tid * PER + e);
+    if (rank_hi >= 1 && cum < rank_hi && cum + (int)h[e] >= rank_hi) res[0] = b;
+    if (rank_lo >= 1 && cum < rank_lo && cum + (int)h[e] >= rank_lo) res[1] = b;
+    cum += (int)h[e];
+    hist[b] = 0u;
+  }
+  __syncthreads();
+  const float wu = width * (1.0f / (float)kNB);
+  const float q_hi = res[0] >= 0 ? lo + (float)(res[0] + 1) * wu : hi;
+  const float q_lo = res[1] >= 0 ? lo + (float)res[1] * wu : lo;
+  __syncthreads();
+  return make_bins(lo, hi, q_lo, q_hi);
 }
 
 // ------------------------------------------------------------------- code scan
@@ -326,49 +452,73 @@ struct Threshold {
   int n_cand;   // tokens in bin bstar
 };
 
+// Two steps so that a kernel can issue the histogram loads together with its other
+// loads: load() only reads (ghist: the unit's kHistCopies replicas), resolve() sums the
+// replicas and searches.  Thread tid owns bins [kNB - (tid+1)*PER, kNB - tid*PER).
 template <int NT>
-__device__ __forceinline__ Threshold find_threshold(const unsigned* __restrict__ ghist, int K, int* sm /* [2*(NT/64)+1+4] */) {
-  constexpr int PER = kNB / NT;
-  constexpr int NW = NT / 64;
-  const int tid = threadIdx.x;
-  unsigned h[PER];
-  int sum = 0;
+struct ThresholdSearch {
+  static constexpr int PER = kNB / NT;
+  static_assert(PER % 4 == 0, "bins per thread must allow 16-byte loads");
+  uint4 x[kHistCopies][PER / 4];
+  __device__ __forceinline__ void load(const unsigned* __restrict__ ghist) {
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    h[e] = ghist[kNB - 1 - (tid * PER + e)];
-    sum += (int)h[e];
-  }
-  int total;
-  int cum = block_exclusive_scan<NT>(sum, &total, sm);
-  int* res = sm + 2 * NW + 1;
-  if (tid == 0) {
-    res[0] = kNB;
-    res[1] = 0;
-    res[2] = 0;
-    res[3] = 0;
-  }
-  __syncthreads();
+    for (int c = 0; c < kHistCopies; ++c) {
+      const uint4* src = reinterpret_cast<const uint4*>(ghist + c * kNB + kNB - (threadIdx.x + 1) * PER);
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    if (K > 0 && cum < K && cum + (int)h[e] >= K) {
-      res[0] = kNB - 1 - (tid * PER + e);
-      res[1] = cum;
-      res[2] = K - cum;
-      res[3] = (int)h[e];
+      for (int v = 0; v < PER / 4; ++v) x[c][v] = src[v];
     }
-    cum += (int)h[e];
   }
-  __syncthreads();
-  Threshold t{res[0], res[1], res[2], res[3]};
-  __syncthreads();
-  return t;
-}
+  __device__ __forceinline__ Threshold resolve(int K, int* sm /* [2*(NT/64)+1+4] */) const {
+    constexpr int NW = NT / 64;
+    const int tid = threadIdx.x;
+    unsigned h[PER];  // descending bins: h[e] is bin kNB-1-(tid*PER+e)
+#pragma unroll
+    for (int e = 0; e < PER; ++e) h[e] = 0u;
+#pragma unroll
+    for (int c = 0; c < kHistCopies; ++c)
+#pragma unroll
+      for (int v = 0; v < PER / 4; ++v) {
+        h[PER - 1 - (4 * v + 0)] += x[c][v].x;
+        h[PER - 1 - (4 * v + 1)] += x[c][v].y;
+        h[PER - 1 - (4 * v + 2)] += x[c][v].z;
+        h[PER - 1 - (4 * v + 3)] += x[c][v].w;
+      }
+    int sum = 0;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) sum += (int)h[e];
+    int total;
+    int cum = block_exclusive_scan<NT>(sum, &total, sm);
+    int* res = sm + 2 * NW + 1;
+    if (tid == 0) {
+      res[0] = kNB;
+      res[1] = 0;
+      res[2] = 0;
+      res[3] = 0;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      if (K > 0 && cum < K && cum + (int)h[e] >= K) {
+        res[0] = kNB - 1 - (tid * PER + e);
+        res[1] = cum;
+        res[2] = K - cum;
+        res[3] = (int)h[e];
+      }
+      cum += (int)h[e];
+    }
+    __syncthreads();
+    Threshold t{res[0], res[1], res[2], res[3]};
+    __syncthreads();
+    return t;
+  }
+};
 
-// ------------------------------------------------------------------- attention
+// ------------------------------------------------------- attention, vector ALU
 // Section 2.1 restricted to listed tokens (Section 3.1 step 6).  Lane layout inside
 // a wave: sub = lane & 15 owns 8 of the 128 dimensions of a row, slot = lane >> 4
 // picks one of 4 rows handled at once; a 16-lane group reads one contiguous row.
 // Logits are kept in the log2 domain (q is pre-multiplied by scale*log2(e)).
+// Used for fp32 caches, for candidate logits and for the rare slow finalize path.
 template <typename T>
 struct RowRaw;
 template <>
@@ -376,6 +526,9 @@ struct RowRaw<bf16_t> {
   uint4 a;
   __device__ __forceinline__ void load(const bf16_t* base, int t, int sub) {
     a = *reinterpret_cast<const uint4*>(base + (size_t)t * kD + sub * 8);
+  }
+  __device__ __forceinline__ void load_row(const void* row, int sub) {
+    a = *reinterpret_cast<const uint4*>(static_cast<const unsigned char*>(row) + sub * 16);
   }
   __device__ __forceinline__ void zero() { a = make_uint4(0, 0, 0, 0); }
   __device__ __forceinline__ void unpack(float (&f)[8]) const {
@@ -388,6 +541,7 @@ struct RowRaw<bf16_t> {
     f[6] = __uint_as_float(a.w << 16);
     f[7] = __uint_as_float(a.w & 0xffff0000u);
   }
+  __device__ __forceinline__ void store(unsigned char* dst, int sub) const { *reinterpret_cast<uint4*>(dst + sub * 16) = a; }
 };
 template <>
 struct RowRaw<float> {
@@ -396,6 +550,10 @@ struct RowRaw<float> {
     a = *reinterpret_cast<const float4*>(base + (size_t)t * kD + sub * 4);
     b = *reinterpret_cast<const float4*>(base + (size_t)t * kD + 64 + sub * 4);
   }
+  __device__ __forceinline__ void load_row(const void* row, int sub) {
+    a = *reinterpret_cast<const float4*>(static_cast<const unsigned char*>(row) + sub * 16);
+    b = *reinterpret_cast<const float4*>(static_cast<const unsigned char*>(row) + 256 + sub * 16);
+  }
   __device__ __forceinline__ void zero() {
     a = make_float4(0, 0, 0, 0);
     b = a;
@@ -403,6 +561,10 @@ struct RowRaw<float> {
   __device__ __forceinline__ void unpack(float (&f)[8]) const {
     f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
     f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+  }
+  __device__ __forceinline__ void store(unsigned char* dst, int sub) const {
+    *reinterpret_cast<float4*>(dst + sub * 16) = a;
+    *reinterpret_cast<float4*>(dst + 256 + sub * 16) = b;
   }
 };
 
@@ -433,25 +595,12 @@ struct AttnState {
 };
 
 template <typename T, int G>
-__device__ __forceinline__ void load_query(const T* __restrict__ q /* [G][kD] */, float scale_log2e, float (&qr)[G][8]) {
+__device__ __forceinline__ void load_query(const T* __restrict__ q /* [G][kD] */, float factor, float (&qr)[G][8]) {
   const int sub = threadIdx.x & 15;
 #pragma unroll
   for (int h = 0; h < G; ++h)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) qr[h][e] = load_as_float<T>(q, h * kD + owned_dim<T>(sub, e)) * scale_log2e;
-}
-
-// Sum over the 16 lanes of a DPP row; every lane of the row receives the total.
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float x) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
-}
-__device__ __forceinline__ float group16_sum(float x) {
-  x += dpp_move<0xB1>(x);   // quad_perm [1,0,3,2]: neighbour in the pair
-  x += dpp_move<0x4E>(x);   // quad_perm [2,3,0,1]: other pair of the quad
-  x += dpp_move<0x141>(x);  // row_half_mirror: other quad of the half row
-  x += dpp_move<0x140>(x);  // row_mirror: other half of the row
-  return x;
+    for (int e = 0; e < 8; ++e) qr[h][e] = load_as_float<T>(q, h * kD + owned_dim<T>(sub, e)) * factor;
 }
 
 // Attend the rows list(p), p in [first, count) stepping by `stride`, where every
@@ -480,6 +629,7 @@ __device__ __forceinline__ void attend_rows(const T* __restrict__ kbase, const T
         vr[r].zero();
       }
     }
+    PQC_LOADS_ISSUED();
     float s[R][G];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -544,10 +694,8 @@ __device__ __forceinline__ void merge_slots(AttnState<G>& st) {
   }
 }
 
-// Combine the waves of a workgroup through LDS and return, for output element
-// (h, d) = (o / kD, o % kD), o = threadIdx.x + i*NT, the merged (m, l, acc).
-//   red  LDS [NW][G][kD+2]
-template <typename T, int G, int NW>
+// Per-wave softmax state in LDS: red[w][h] = { m, l, acc[kD] }.
+template <typename T, int G>
 __device__ __forceinline__ void stash_wave_state(AttnState<G>& st, float* red) {
   merge_slots<G>(st);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -578,6 +726,189 @@ __device__ __forceinline__ void combine_waves(const float* red, int h, int d, fl
     const float f = __builtin_amdgcn_exp2f(src[0] - m);
     l = fmaf(src[1], f, l);
     acc = fmaf(src[2 + d], f, acc);
+  }
+}
+
+// ------------------------------------------------------ attention, matrix cores
+// bf16 caches.  Per wave and per tile of 16 listed rows:
+//   S[token][head] = K_tile[16 x 128] . Q^T[128 x 16]     4 x v_mfma_f32_16x16x32_bf16
+//   O[head][dim]  += P[head][token]  . V_tile[16 x 128]   8 x 2 x v_mfma_f32_16x16x16_bf16
+// Operand layouts (lane l, quad = l / 16, col = l % 16):
+//   16x16x32: A[m=col][k=8*quad+e], B[k=8*quad+e][n=col], D[m=4*quad+i][n=col]
+//   16x16x16: A[m=col][k=4*quad+e], B[k=4*quad+e][n=col], D[m=4*quad+i][n=col]
+// so the QK output (tokens 4*quad+i of head col) is, lane for lane, the A operand of
+// the PV product.  Heads G..15 are zero padding.  K rows feed the matrix core straight
+// from global memory (lane: row col, 16 bytes at dims 32*kk + 8*quad); V rows are
+// transposed through a wave-private LDS tile (row stride 264 bytes: the four quads of
+// a transposed read land in different banks).  P is split into two bf16 terms
+// (p = hi + lo, error 2^-17) because one bf16 term alone would cost 2^-9 of the result.
+//
+// Softmax: a wave first computes the logits of a chunk of up to kMfmaTiles tiles,
+// takes its maximum per head, rescales O once if the maximum grew, then accumulates.
+constexpr int kMfmaTiles = 4;          // tiles (of 16 rows) per chunk and wave
+constexpr int kVTileStride = 264;      // bytes per V row in the LDS transpose tile
+constexpr int kVTileBytes = 16 * kVTileStride;
+
+struct MfmaState {
+  f32x4_t o[8];  // O[head 4*quad+i][dim 16*j + col]
+  float m, l;    // head col, over this lane's tokens (log2 domain); merged across quads at the end
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    m = kNegBig;
+    l = 0.0f;
+  }
+};
+
+// Q^T fragments (B operand of the QK product) for this lane; heads >= G are zero.
+__device__ __forceinline__ void load_q_frags(const bf16_t* __restrict__ q /* [G][kD] */, int G, bf16x8_t (&qf)[4]) {
+  const int lane = threadIdx.x & 63, col = lane & 15, quad = lane >> 4;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    uint4 raw = make_uint4(0, 0, 0, 0);
+    if (col < G) raw = *reinterpret_cast<const uint4*>(q + (size_t)col * kD + 32 * kk + 8 * quad);
+    __builtin_memcpy(&qf[kk], &raw, 16);
+  }
+}
+
+__device__ __forceinline__ unsigned bf16_round_bits(float f) {  // round to nearest even, finite inputs
+  const unsigned u = __float_as_uint(f);
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <class ListFn>
+__device__ __forceinline__ void mfma_attend(const bf16_t* __restrict__ kbase, const bf16_t* __restrict__ vbase, int N,
+                                            ListFn list, int count, int first, int stride, float scale_log2e,
+                                            const bf16x8_t (&qf)[4], unsigned char* vt /* wave-private LDS [kVTileBytes] */,
+                                            MfmaState& st) {
+  const int lane = threadIdx.x & 63, col = lane & 15, quad = lane >> 4;
+  // chunk = kMfmaTiles tiles of 16 consecutive list positions, starting at `base`
+  for (int base = first; base < count; base += stride) {
+    uint4 kr[kMfmaTiles][4], vr[kMfmaTiles][4];
+#pragma unroll
+    for (int tl = 0; tl < kMfmaTiles; ++tl) {
+      const int p = base + tl * 16 + col;
+      if (base + tl * 16 < count) {  // wave-uniform
+        int t = list(min(p, count - 1));
+        t = max(0, min(N - 1, t));
+        const uint4* kp = reinterpret_cast<const uint4*>(kbase + (size_t)t * kD + 8 * quad);
+        const uint4* vp = reinterpret_cast<const uint4*>(vbase + (size_t)t * kD + 8 * quad);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          kr[tl][kk] = kp[4 * kk];  // dims 32*kk + 8*quad .. +7
+          vr[tl][kk] = vp[4 * kk];
+        }
+      }
+    }
+    PQC_LOADS_ISSUED();
+    // logits of the chunk
+    f32x4_t s[kMfmaTiles];
+    float mx = kNegBig;
+#pragma unroll
+    for (int tl = 0; tl < kMfmaTiles; ++tl) {
+      s[tl] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      if (base + tl * 16 < count) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          bf16x8_t a;
+          __builtin_memcpy(&a, &kr[tl][kk], 16);
+          s[tl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[kk], s[tl], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool ok = base + tl * 16 + 4 * quad + i < count;
+          s[tl][i] = ok ? s[tl][i] * scale_log2e : kNegBig;
+          mx = fmaxf(mx, s[tl][i]);
+        }
+      }
+    }
+    // the chunk's maximum per head (over the four quads), and the one-off rescale of O
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float mnew = fmaxf(st.m, mx);
+    const float corr = __builtin_amdgcn_exp2f(st.m - mnew);
+    st.l *= corr;
+    st.m = mnew;
+    if (__any(corr != 1.0f)) {
+      float cr[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) cr[i] = __shfl(corr, 4 * quad + i);  // corr of head 4*quad+i lives in lane col == that head
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) st.o[j][i] *= cr[i];
+    }
+    // accumulate
+#pragma unroll
+    for (int tl = 0; tl < kMfmaTiles; ++tl) {
+      if (base + tl * 16 < count) {
+        // V tile -> LDS, row `col`, bytes 64*kk + 16*quad (two 8-byte stores: rows are 8-byte aligned)
+        unsigned char* vrow = vt + col * kVTileStride + 16 * quad;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          *reinterpret_cast<uint2*>(vrow + 64 * kk) = make_uint2(vr[tl][kk].x, vr[tl][kk].y);
+          *reinterpret_cast<uint2*>(vrow + 64 * kk + 8) = make_uint2(vr[tl][kk].z, vr[tl][kk].w);
+        }
+        // P = exp2(S - m), as hi + lo bf16 terms (masked rows hold kNegBig: P = 0)
+        unsigned hi[4], lo[4];
+        float psum = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float p = __builtin_amdgcn_exp2f(s[tl][i] - mnew);
+          psum += p;
+          hi[i] = bf16_round_bits(p);
+          lo[i] = bf16_round_bits(p - __uint_as_float(hi[i] << 16));
+        }
+        st.l += psum;
+        s16x4_t pa_hi, pa_lo;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          pa_hi[i] = (short)hi[i];
+          pa_lo[i] = (short)lo[i];
+        }
+        // the wave's LDS stores must land before its lanes read each other's rows
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const unsigned short* vt16 = reinterpret_cast<const unsigned short*>(vt);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          s16x4_t vb;  // B[k = token 4*quad+e][n = dim 16*j + col]
+#pragma unroll
+          for (int e = 0; e < 4; ++e) vb[e] = (short)vt16[(4 * quad + e) * (kVTileStride / 2) + 16 * j + col];
+          st.o[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa_hi, vb, st.o[j], 0, 0, 0);
+          st.o[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa_lo, vb, st.o[j], 0, 0, 0);
+        }
+        // tile fully read before the next tile overwrites it
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
+    }
+  }
+}
+
+// Per-wave state -> red[w][h] = { m, l, acc[kD] } (same slots as the vector path).
+template <int G>
+__device__ __forceinline__ void mfma_stash_wave_state(MfmaState& st, float* red) {
+  const int lane = threadIdx.x & 63, col = lane & 15, quad = lane >> 4, w = threadIdx.x >> 6;
+  // the four quads of head `col` hold partial sums under one shared maximum
+  float l = st.l;
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  if (quad == 0 && col < G) {
+    float* dst = red + ((size_t)w * G + col) * (kD + 2);
+    dst[0] = st.m;
+    dst[1] = l;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int h = 4 * quad + i;
+    if (h < G) {
+      float* dst = red + ((size_t)w * G + h) * (kD + 2) + 2;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dst[16 * j + col] = st.o[j][i];
+    }
   }
 }
 

@@ -1,15 +1,16 @@
-// Kernels of libpqcache (gfx950).  Grid layout everywhere: blockIdx.y = unit
-// (sequence b, KV head g), blockIdx.x = workgroup inside the unit.
+// Kernels of libpqcache (gfx950).  Grid layout: blockIdx.y = unit (sequence b, KV
+// head g); blockIdx.x = workgroup inside the unit (query head for finalize_kernel).
 //
 // Decode path (pqc_decode), three launches, every dependency at a kernel boundary:
 //   hist_kernel      table -> scan codes -> histogram of scores over kNB bins
 //   select_kernel    threshold bin from the histogram -> scan codes again -> tokens
 //                    above the bin (and the two windows) are listed in ascending order
-//                    without atomics and attended at once; tokens inside the bin are
-//                    staged as candidates
-//   finalize_kernel  ranks the candidates, attends the admitted ones, merges all
-//                    partial softmax states, writes indices and output, and leaves
-//                    the histogram zeroed for the next call
+//                    without atomics and attended at once; tokens inside the bin
+//                    ("candidates") are recorded with their logits and V row
+//   finalize_kernel  one workgroup per query head: ranks the candidates, folds the
+//                    admitted ones and all partial softmax states into the output,
+//                    writes the indices, and zeroes the other parity's histogram and
+//                    counters for the next call
 //
 // Codes are read 16 bytes at a time (P = 16/M tokens).  A unit's codes start at byte
 // u*N*M, which need not be 16-byte aligned: chunks are laid over the aligned-down
@@ -21,7 +22,7 @@
 namespace pqc {
 
 constexpr int kMaxVecA = 4;   // 16-byte code chunks per thread, histogram kernel
-constexpr int kMaxVecC = 16;  // 16-byte code chunks per lane, select kernel
+constexpr int kMaxVecC = 8;   // 16-byte code chunks per lane, select kernel (tokC <= 4096)
 
 // ------------------------------------------------------------------ sources
 // Where a kernel takes its scores from: PQ codes through the LDS table (the decode
@@ -45,22 +46,38 @@ struct CodeChunks {
     lead = (int)((ob - unit_byte0) / M);
     lut = lut_;
   }
+  // Unconditional 16-byte load (straight-line code keeps many loads in flight): a chunk at
+  // or beyond the tensor's last full 16 bytes is redirected to that last full chunk, and
+  // fix_tail() patches the one chunk that holds the tensor's ragged end afterwards.
   __device__ __forceinline__ Raw load(int chunk) const {
+    const long long last_full = (total_bytes & ~15ll) - 16;  // < 0 for tensors under 16 bytes
+    long long off = unit_byte0 + 16ll * chunk;
+    off = off < last_full ? off : last_full;
+    off = off > 0 ? off : 0;
+    if (total_bytes < 16) return make_uint4(0u, 0u, 0u, 0u);  // uniform
+    return *reinterpret_cast<const uint4*>(all + off);
+  }
+  __device__ __forceinline__ void fix_tail(Raw& r, int chunk) const {
     const long long off = unit_byte0 + 16ll * chunk;
-    if (off + 16 <= total_bytes) return *reinterpret_cast<const uint4*>(all + off);
-    unsigned w[4] = {0u, 0u, 0u, 0u};  // the tensor's last, partial chunk (or beyond it)
-    for (int b = 0; b < 16; ++b)
-      if (off + b < total_bytes) w[b >> 2] |= (unsigned)all[off + b] << (8 * (b & 3));
-    return make_uint4(w[0], w[1], w[2], w[3]);
+    if (off + 16 > total_bytes && off < total_bytes) {  // at most one chunk in the whole tensor
+      unsigned w[4] = {0u, 0u, 0u, 0u};
+      for (int b = 0; b < 16; ++b)
+        if (off + b < total_bytes) w[b >> 2] |= (unsigned)all[off + b] << (8 * (b & 3));
+      r = make_uint4(w[0], w[1], w[2], w[3]);
+    }
   }
   __device__ __forceinline__ float score(const Raw& r, int i) const { return score_from_word<M>(chunk_word<M>(r, i), lut); }
-  __device__ __forceinline__ float score_of_token(int t, int u, int N) const {
+  // one token: the load (issue early) and the table look-up (after the table is ready)
+  using One = typename CodeWord<M>::type;
+  __device__ __forceinline__ One load_one(int t, int u, int N) const {
     const uint8_t* p = all + ((long long)u * N + t) * M;
-    typename CodeWord<M>::type w = 0;
+    One w = 0;
 #pragma unroll
-    for (int j = 0; j < M; ++j) w |= (typename CodeWord<M>::type)p[j] << (8 * j);
-    return score_from_word<M>(w, lut);
+    for (int j = 0; j < M; ++j) w |= (One)p[j] << (8 * j);
+    return w;
   }
+  __device__ __forceinline__ float score_one(One w) const { return score_from_word<M>(w, lut); }
+  __device__ __forceinline__ float score_of_token(int t, int u, int N) const { return score_one(load_one(t, u, N)); }
 };
 
 struct ScoreChunks {
@@ -82,19 +99,24 @@ struct ScoreChunks {
     Raw r;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const long long t = (long long)chunk * 4 + i;
-      r.f[i] = t < n ? scores[t] : 0.0f;
+      long long t = (long long)chunk * 4 + i;
+      t = t < n ? t : n - 1;  // clamped: straight-line loads; tokens >= n are masked by the caller
+      r.f[i] = scores[t];
     }
     return r;
   }
+  __device__ __forceinline__ void fix_tail(Raw&, int) const {}
   __device__ __forceinline__ float score(const Raw& r, int i) const { return r.f[i]; }
+  using One = float;
+  __device__ __forceinline__ One load_one(int t, int, int) const { return scores[t]; }
+  __device__ __forceinline__ float score_one(One w) const { return w; }
   __device__ __forceinline__ float score_of_token(int t, int, int) const { return scores[t]; }
 };
 
 // ------------------------------------------------------------------ utilities
-__global__ void reset_kernel(unsigned* hist, size_t n) {
-  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  if (i < n) hist[i] = 0u;
+__global__ void reset_kernel(unsigned* a, size_t na) {
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i < na) a[i] = 0u;
 }
 
 // Stand-alone table (pqc_lut).
@@ -128,53 +150,39 @@ __global__ __launch_bounds__(256) void scan_kernel(Shape s, const float* __restr
   }
 }
 
-// Bin layout from the middle tokens of a score array (stand-alone top-k only): range,
-// mean and spread, reduced in a fixed order by one workgroup per unit.
-__global__ __launch_bounds__(1024) void score_stats_kernel(Shape s, const float* __restrict__ scores,
-                                                           BinParams* __restrict__ ctl) {
+// Score range of the middle tokens of a score array (stand-alone top-k only).
+__global__ __launch_bounds__(1024) void score_range_kernel(Shape s, const float* __restrict__ scores,
+                                                           float2* __restrict__ range) {
   __shared__ float smn[16], smx[16];
-  __shared__ double ssum[16], ssq[16];
   const int u = blockIdx.y;
   float mn = INFINITY, mx = -INFINITY;
-  double sum = 0.0, sq = 0.0;
   for (int t = s.I + threadIdx.x; t < s.N - s.L; t += 1024) {
     const float v = scores[(size_t)u * s.N + t];
     mn = fminf(mn, v);
     mx = fmaxf(mx, v);
-    sum += (double)v;
-    sq += (double)v * (double)v;
   }
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) {
-    mn = fminf(mn, __shfl_xor(mn, o));
-    mx = fmaxf(mx, __shfl_xor(mx, o));
-    sum += __shfl_xor(sum, o);
-    sq += __shfl_xor(sq, o);
-  }
+  mn = wave_min(mn);
+  mx = wave_max(mx);
   if ((threadIdx.x & 63) == 0) {
     smn[threadIdx.x >> 6] = mn;
     smx[threadIdx.x >> 6] = mx;
-    ssum[threadIdx.x >> 6] = sum;
-    ssq[threadIdx.x >> 6] = sq;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
     for (int w = 1; w < 16; ++w) {
       mn = fminf(mn, smn[w]);
       mx = fmaxf(mx, smx[w]);
-      sum += ssum[w];
-      sq += ssq[w];
     }
-    const double n = (double)max(1, s.N - s.L - s.I);
-    const double mean = sum / n, var = fmax(0.0, sq / n - mean * mean);
-    const bool finite = mn > -3.0e38f && mx < 3.0e38f && mean == mean && var == var;
-    ctl[u] = finite ? make_bins(mn, mx, (float)mean, (float)sqrt(var)) : make_bins(mn, mx, mn, 0.0f);
+    range[u] = make_float2(mn, mx);
   }
 }
 
 // ------------------------------------------------------------- 1. histogram
-// SRC = CodeChunks<M>: builds the unit's table first (workgroup 0 also publishes it
-// together with the bin layout).  SRC = ScoreChunks: layout comes from score_stats_kernel.
+// SRC = CodeChunks<M>: builds the unit's table first; score bounds come from the table.
+// SRC = ScoreChunks: bounds come from score_range_kernel.  Every workgroup of a unit
+// then derives the same bin layout from the same sampled tokens (workgroup 0 publishes
+// table and layout for the select kernel) and counts its own tokens.  Workgroups of a
+// unit spread their counts over kHistCopies replicas.
 template <typename T, class SRC>
 __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const T* __restrict__ q,
                                                     const float* __restrict__ cent, const void* __restrict__ src_ptr) {
@@ -185,31 +193,41 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   __shared__ float red[32];
   __shared__ float tile[SRC::kFromCodes ? kLutTileFloats + kLutTileFloats / (kD / LM) : 1];
   __shared__ unsigned hist[kNB];
-  const int u = blockIdx.y, tid = threadIdx.x;
+  __shared__ int scan_sm[2 * (NT / 64) + 1 + 2];
+  const int u = blockIdx.y, tid = threadIdx.x, units = s.B * s.Hkv;
   PQC_MARK(ws, 0, 0);
   SRC src;
-  src.init(src_ptr, u, s.N, s.B * s.Hkv, lut);
-  // this workgroup's chunks: issue the loads before anything else
+  src.init(src_ptr, u, s.N, units, lut);
+  // this workgroup's chunks and this thread's sample: issue the loads before anything else
   const int chunks = s.tokA / P, chunk0 = blockIdx.x * chunks;
   typename SRC::Raw raw[kMaxVecA];
 #pragma unroll
-  for (int v = 0; v < kMaxVecA; ++v)
-    if (v * NT + tid < chunks) raw[v] = src.load(chunk0 + v * NT + tid);
+  for (int v = 0; v < kMaxVecA; ++v) raw[v] = src.load(chunk0 + min(v * NT + tid, chunks - 1));
+  const bool have_sample = tid < s.sampleN;
+  const int sample_i = min(tid, s.sampleN - 1);
+  const typename SRC::One sample =
+      src.load_one(min(s.N - 1, s.I + (int)(((long long)sample_i * max(0, s.N - s.I - s.L)) / s.sampleN)), u, s.N);
+  PQC_LOADS_ISSUED();
   for (int i = tid; i < kNB; i += NT) hist[i] = 0u;
-  BinParams bp;
+  float2 bounds;
   if constexpr (SRC::kFromCodes) {
     const int b = u / s.Hkv, g = u % s.Hkv;
-    bp = build_lut<T, NT, LM>(q + ((size_t)b * s.Hq + (size_t)g * s.G) * kD, cent + (size_t)u * LM * s.C * (kD / LM), s.G,
-                              s.C, lut, qs, red, tile);
-    if (blockIdx.x == 0) {
+    bounds = build_lut<T, NT, LM>(q + ((size_t)b * s.Hq + (size_t)g * s.G) * kD, cent + (size_t)u * LM * s.C * (kD / LM), s.G,
+                                  s.C, lut, qs, red, tile);
+    if (blockIdx.x == 0)
       for (int e = tid; e < LM * s.C; e += NT) ws.lut[(size_t)u * LM * s.C + e] = lut[(e / s.C) * kLutRow + (e % s.C)];
-      if (tid == 0) ws.ctl[u] = bp;
-    }
   } else {
-    bp = ws.ctl[u];
+    bounds = ws.range[u];
     __syncthreads();
   }
   PQC_MARK(ws, 0, 1);
+#pragma unroll
+  for (int v = 0; v < kMaxVecA; ++v) src.fix_tail(raw[v], chunk0 + min(v * NT + tid, chunks - 1));
+  const BinParams bp =
+      sample_window<NT>(bounds.x, bounds.y, src.score_one(sample), have_sample, s.rankHi, s.rankLo, hist, scan_sm);
+  if (blockIdx.x == 0 && tid == 0) ws.ctl[u] = bp;
+  const float b_lo = bp.lo, b_c0 = bp.c0, b_c1 = bp.c1, b_ilo = bp.inv_lo, b_ic = bp.inv_c, b_ihi = bp.inv_hi;
+  PQC_MARK(ws, 0, 2);
 #pragma unroll
   for (int v = 0; v < kMaxVecA; ++v) {
     if (v * NT + tid < chunks) {
@@ -217,16 +235,16 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
 #pragma unroll
       for (int i = 0; i < P; ++i) {
         const int t = t0 + i;
-        if (t >= s.I && t < s.N - s.L) atomicAdd(&hist[score_bin(src.score(raw[v], i), bp)], 1u);
+        if (t >= s.I && t < s.N - s.L) atomicAdd(&hist[score_bin(src.score(raw[v], i), b_lo, b_c0, b_c1, b_ilo, b_ic, b_ihi)], 1u);
       }
     }
   }
   __syncthreads();
-  PQC_MARK(ws, 0, 2);
-  unsigned* gh = ws.hist + (size_t)u * kNB;
+  PQC_MARK(ws, 0, 3);
+  unsigned* gh = ws.hist + (((size_t)s.parity * units + u) * kHistCopies + (blockIdx.x % kHistCopies)) * kNB;
   for (int i = tid; i < kNB; i += NT)
     if (hist[i]) atomicAdd(&gh[i], hist[i]);
-  PQC_MARK(ws, 0, 3);
+  PQC_MARK(ws, 0, 4);
 }
 
 // ---------------------------------------------------- 2. select (+ attention)
@@ -235,33 +253,67 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
 // prefix-summed across lanes, and the wave appends to its own LDS segment: selected
 // tokens (ascending) from the front, boundary-bin candidates from the back.
 template <typename T, int G, class SRC, bool ATTN>
-__global__ __launch_bounds__(256) void select_kernel(Shape s, Workspace ws, const T* __restrict__ q,
+__global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, const T* __restrict__ q,
                                                      const T* __restrict__ kc, const T* __restrict__ vc,
                                                      const void* __restrict__ src_ptr) {
   constexpr int NT = 256, NW = 4, P = SRC::P;
   constexpr int LM = SRC::kFromCodes ? SRC::M : 1;
+  constexpr bool kMfma = ATTN && sizeof(T) == 2;
   extern __shared__ int list[];  // [tokC]
   __shared__ float lut[LM * kLutRow];
   __shared__ int scan_sm[2 * NW + 1 + 4];
   __shared__ int wcnt[2 * NW];
   __shared__ float red[ATTN ? NW * G * (kD + 2) : 1];
-  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  __shared__ float qlds[ATTN ? G * kD : 1];
+  __shared__ __attribute__((aligned(16))) unsigned char vtile[kMfma ? NW * kVTileBytes : 16];
+  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, units = s.B * s.Hkv;
+  const int b = u / s.Hkv, g = u % s.Hkv;
   PQC_MARK(ws, 1, 0);
   SRC src;
-  src.init(src_ptr, u, s.N, s.B * s.Hkv, lut);
+  src.init(src_ptr, u, s.N, units, lut);
   // this wave's chunks, loaded up front
   const int cpw = s.tokC / (NW * P);  // chunks per wave
   const int chunk0 = blockIdx.x * (s.tokC / P) + w * cpw;
   typename SRC::Raw raw[kMaxVecC];
 #pragma unroll
-  for (int v = 0; v < kMaxVecC; ++v)
-    if (v * 64 + lane < cpw) raw[v] = src.load(chunk0 + v * 64 + lane);
-  if constexpr (SRC::kFromCodes)
-    for (int e = tid; e < LM * s.C; e += NT) lut[(e / s.C) * kLutRow + (e % s.C)] = ws.lut[(size_t)u * LM * s.C + e];
-  const BinParams bp = ws.ctl[u];
-  const Threshold th = find_threshold<NT>(ws.hist + (size_t)u * kNB, s.K, scan_sm);  // syncs: lut is ready after it
-
+  for (int v = 0; v < kMaxVecC; ++v) raw[v] = src.load(chunk0 + min(v * 64 + lane, cpw - 1));
+  // table and query into registers with straight-line, clamped loads (LDS stores follow below)
+  constexpr int LUTV = SRC::kFromCodes ? (LM * kLutRow) / NT : 1;  // table entries per thread at C = 256
+  float lutreg[LUTV];
+  if constexpr (SRC::kFromCodes) {
+#pragma unroll
+    for (int x = 0; x < LUTV; ++x) lutreg[x] = ws.lut[(size_t)u * LM * s.C + min(x * NT + tid, LM * s.C - 1)];
+  }
+  constexpr int QV = ATTN ? (G * kD + NT - 1) / NT : 1;  // query elements per thread
+  float qreg[QV];
+  if constexpr (ATTN) {
+#pragma unroll
+    for (int x = 0; x < QV; ++x)
+      qreg[x] = load_as_float<T>(q + ((size_t)b * s.Hq + (size_t)g * G) * kD, min(x * NT + tid, G * kD - 1));
+  }
+  ThresholdSearch<NT> ts;
+  ts.load(ws.hist + ((size_t)s.parity * units + u) * kHistCopies * kNB);
+  const float4 bpa = reinterpret_cast<const float4*>(ws.ctl + u)[0], bpb = reinterpret_cast<const float4*>(ws.ctl + u)[1];
+  PQC_LOADS_ISSUED();
+  const float b_lo = bpa.x, b_c0 = bpa.y, b_c1 = bpa.z, b_ilo = bpa.w, b_ic = bpb.x, b_ihi = bpb.y;
+  if constexpr (SRC::kFromCodes) {
+#pragma unroll
+    for (int x = 0; x < LUTV; ++x) {
+      const int e = x * NT + tid;
+      if (e < LM * s.C) lut[(e / s.C) * kLutRow + (e % s.C)] = lutreg[x];
+    }
+  }
+  if constexpr (ATTN) {
+#pragma unroll
+    for (int x = 0; x < QV; ++x)
+      if (x * NT + tid < G * kD) qlds[x * NT + tid] = qreg[x];
+  }
+  const Threshold th = ts.resolve(s.K, scan_sm);  // syncs: lut, qlds ready
   PQC_MARK(ws, 1, 1);
+#pragma unroll
+  for (int v = 0; v < kMaxVecC; ++v) src.fix_tail(raw[v], chunk0 + min(v * 64 + lane, cpw - 1));
+  PQC_MARK(ws, 1, 6);
+
   const int segN = s.tokC / NW;
   int* seg = list + w * segN;
   int nsel = 0, ncand = 0;
@@ -279,21 +331,17 @@ __global__ __launch_bounds__(256) void select_kernel(Shape s, Workspace ws, cons
             if (t < s.I || t >= s.N - s.L) {
               selm |= 1u << i;
             } else {
-              const int bin = score_bin(src.score(raw[v], i), bp);
+              const int bin = score_bin(src.score(raw[v], i), b_lo, b_c0, b_c1, b_ilo, b_ic, b_ihi);
               selm |= (bin > th.bstar ? 1u : 0u) << i;
               candm |= (bin == th.bstar ? 1u : 0u) << i;
             }
           }
         }
       }
+      PQC_MARK(ws, 1, 7);
       const int cnt = __popc(selm) | (__popc(candm) << 16);
-      int inc = cnt;
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const int n = __shfl_up(inc, o);
-        if (lane >= o) inc += n;
-      }
-      const int tot = __shfl(inc, 63);
+      const int inc = wave_inclusive_scan(cnt);
+      const int tot = wave_last(inc);
       int ps = nsel + ((inc - cnt) & 0xffff), pc = ncand + ((inc - cnt) >> 16);
 #pragma unroll
       for (int i = 0; i < P; ++i) {
@@ -304,6 +352,7 @@ __global__ __launch_bounds__(256) void select_kernel(Shape s, Workspace ws, cons
       ncand += tot >> 16;
     }
   }
+  PQC_MARK(ws, 1, 8);
   if (lane == 0) {
     wcnt[w] = nsel;
     wcnt[NW + w] = ncand;
@@ -326,31 +375,35 @@ __global__ __launch_bounds__(256) void select_kernel(Shape s, Workspace ws, cons
     return list[i * segN + (p - csel[i])];
   };
 
-  // stage lists for the finalize kernel
+  // selected list for the finalize kernel's index output
   unsigned long long* stage = ws.stage + ((size_t)u * s.nblkC + blockIdx.x) * s.tokC;
   int* stage32 = reinterpret_cast<int*>(stage);
   for (int p = tid; p < tot_sel; p += NT) stage32[p] = sel_at(p);
-  for (int c = tid; c < tot_cand; c += NT) {
-    int i = 0;
-#pragma unroll
-    for (int x = 1; x < NW; ++x) i += (c >= ccand[x]) ? 1 : 0;
-    const int t = list[i * segN + segN - 1 - (c - ccand[i])];
-    stage[s.tokC - 1 - c] = make_composite(src.score_of_token(t, u, s.N), t);
-  }
   if (tid == 0) ws.stage_cnt[(size_t)u * s.nblkC + blockIdx.x] = make_int2(tot_sel, tot_cand);
   PQC_MARK(ws, 1, 3);
 
+  const T* kbase = kc + (size_t)u * s.N * kD;
+  const T* vbase = vc + (size_t)u * s.N * kD;
   if constexpr (ATTN) {
-    const int b = u / s.Hkv, g = u % s.Hkv;
-    float qr[G][8];
-    load_query<T, G>(q + ((size_t)b * s.Hq + (size_t)g * G) * kD, s.scale_log2e, qr);
-    AttnState<G> st;
-    st.init();
-    constexpr int R = (G >= 8 || sizeof(T) == 4) ? 2 : 4;
-    attend_rows<T, G, R>(kc + (size_t)u * s.N * kD, vc + (size_t)u * s.N * kD, s.N, sel_at, tot_sel, w * 4 * R,
-                         NW * 4 * R, qr, st);
-    PQC_MARK(ws, 1, 4);
-    stash_wave_state<T, G, NW>(st, red);
+    if constexpr (kMfma) {
+      bf16x8_t qf[4];
+      load_q_frags(reinterpret_cast<const bf16_t*>(q) + ((size_t)b * s.Hq + (size_t)g * G) * kD, G, qf);
+      MfmaState st;
+      st.init();
+      mfma_attend(reinterpret_cast<const bf16_t*>(kbase), reinterpret_cast<const bf16_t*>(vbase), s.N, sel_at, tot_sel,
+                  w * 16 * kMfmaTiles, NW * 16 * kMfmaTiles, s.scale_log2e, qf, vtile + w * kVTileBytes, st);
+      PQC_MARK(ws, 1, 4);
+      mfma_stash_wave_state<G>(st, red);
+    } else {
+      float qr[G][8];
+      load_query<T, G>(q + ((size_t)b * s.Hq + (size_t)g * G) * kD, s.scale_log2e, qr);
+      AttnState<G> st;
+      st.init();
+      constexpr int R = (G >= 8 || sizeof(T) == 4) ? 2 : 4;
+      attend_rows<T, G, R>(kbase, vbase, s.N, sel_at, tot_sel, w * 4 * R, NW * 4 * R, qr, st);
+      PQC_MARK(ws, 1, 4);
+      stash_wave_state<T, G>(st, red);
+    }
     __syncthreads();
     float* part = ws.partials + ((size_t)u * s.npart + blockIdx.x) * G * (kD + 2);
     for (int o = tid; o < G * kD; o += NT) {
@@ -363,53 +416,170 @@ __global__ __launch_bounds__(256) void select_kernel(Shape s, Workspace ws, cons
         part[h * (kD + 2) + 1] = l;
       }
     }
-    PQC_MARK(ws, 1, 5);
-#ifdef PQC_TRACE
-    if (tid == 0 && (size_t)blockIdx.y * gridDim.x + blockIdx.x < (size_t)kTraceWgs) {
-      unsigned long long* tr = ws.trace + ((size_t)1 * kTraceWgs + (size_t)blockIdx.y * gridDim.x + blockIdx.x) * kTraceSlots;
-      tr[14] = (unsigned long long)tot_sel;
-      tr[15] = (unsigned long long)tot_cand;
+  }
+  PQC_MARK(ws, 1, 5);
+  PQC_NOTE(ws, 1, 14, tot_sel);
+  PQC_NOTE(ws, 1, 15, tot_cand);
+
+  // candidates (few): composite for the generic path; the first recPerWg also as full records
+  if (tot_cand > 0) {  // workgroup-uniform
+    const int sub = lane & 15, grp = tid >> 4;  // 16 lanes per candidate
+    for (int c = grp; c < tot_cand; c += NT / 16) {
+      int i = 0;
+#pragma unroll
+      for (int x = 1; x < NW; ++x) i += (c >= ccand[x]) ? 1 : 0;
+      const int t = list[i * segN + segN - 1 - (c - ccand[i])];
+      const unsigned long long comp = make_composite(src.score_of_token(t, u, s.N), t);
+      if (sub == 0) stage[s.tokC - 1 - c] = comp;
+      if (c < s.recPerWg) {
+        unsigned char* rec = ws.cand_rec + (((size_t)u * s.nblkC + blockIdx.x) * s.recPerWg + c) * ws.rec_stride;
+        CandHeader* hd = reinterpret_cast<CandHeader*>(rec);
+        if (sub == 0) hd->composite = comp;
+        if constexpr (ATTN) {
+          RowRaw<T> kr, vr;
+          kr.load(kbase, t, sub);
+          vr.load(vbase, t, sub);
+          float kf[8];
+          kr.unpack(kf);
+#pragma unroll
+          for (int h = 0; h < G; ++h) {
+            float d = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) d = fmaf(qlds[h * kD + owned_dim<T>(sub, e)], kf[e], d);
+            d = group16_sum(d);
+            if (sub == 0) hd->logit[h] = d;
+          }
+          vr.store(rec + sizeof(CandHeader), sub);
+        }
+      }
     }
-#endif
   }
 }
 
 // ------------------------------------------------------------- 3. finalize
-// One workgroup (512 threads, so that 8 query heads fit the register file) per unit.
-// The staged "selected" lists already hold the two windows: concatenated in workgroup
-// order they read  [0..I) , tokens above the threshold bin (ascending) , [N-L..N).
+// Grid (query heads of the group, units), 256 threads.  The staged "selected" lists
+// already hold the two windows: concatenated in workgroup order they read
+//   [0..I) , tokens above the threshold bin (ascending) , [N-L..N).
+// Fast path (candidates fit their record area): everything a head needs about the
+// candidates is in the records.  Generic path: candidates are the composites staged
+// per select workgroup; admitted rows are gathered from the K/V cache.
+template <int NT>
+__device__ __forceinline__ float block_max(float v, float* sm /* [NT/64] */) {
+  v = wave_max(v);
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = sm[0];
+#pragma unroll
+  for (int i = 1; i < NT / 64; ++i) r = fmaxf(r, sm[i]);
+  __syncthreads();
+  return r;
+}
+template <int NT>
+__device__ __forceinline__ float block_sum(float v, float* sm /* [NT/64] */) {
+  v = wave_sum(v);
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = sm[0];
+#pragma unroll
+  for (int i = 1; i < NT / 64; ++i) r += sm[i];
+  __syncthreads();
+  return r;
+}
+
+constexpr int kSlotsPerThread = 8;  // candidate record slots per unit <= 256 * kSlotsPerThread
+constexpr int kAccBatch = 32;       // partial accumulators a thread keeps in flight at once
+constexpr int kVPass = 4;           // admitted candidate V rows per thread group kept in flight at once (16 rows each)
+constexpr int kIdxLists = 4;        // staged index lists a wave copies with loads issued up front
+
 template <typename T, int G, bool ATTN>
-__global__ __launch_bounds__(512) void finalize_kernel(Shape s, Workspace ws, const T* __restrict__ q,
+__global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, const T* __restrict__ q,
                                                        const T* __restrict__ kc, const T* __restrict__ vc,
                                                        int* __restrict__ out_idx, float* __restrict__ out_attn) {
-  constexpr int NT = 512, NW = 8;
-  extern __shared__ int pre[];  // [2*(nblkC+1)]: prefix of selected counts, prefix of candidate counts
+  constexpr int NT = 256, NW = 4;
+  extern __shared__ int dyn[];  // pre_sel[nblkC+1], pre_cand[nblkC+1], pm[nblkC], pl[nblkC]
   __shared__ int scan_sm[2 * NW + 1];
-  __shared__ unsigned long long comp[kCandLds];
-  __shared__ int adm[kCandLds];
+  __shared__ float fsm[NW];
+  __shared__ unsigned long long comp[kCandRec];  // compacted candidates, (select workgroup, position) order
+  __shared__ float lgr[kCandRec];                // their logits for this head (log2 domain)
+  __shared__ unsigned short slotv[kCandRec];     // their record slots
+  __shared__ float lgk[kCandRec];                // by rank: logit, then softmax weight of the admitted ones
+  __shared__ unsigned short ordv[kCandRec];      // by rank: record slot
   __shared__ unsigned rhist[256];
-  __shared__ unsigned long long thr_sm;
   __shared__ int digit_sm[2];
-  __shared__ float red[ATTN ? NW * G * (kD + 2) : 1];
-  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  __shared__ int rows_sm[NT];
+  __shared__ int overflow_sm;
+  __shared__ float red[ATTN ? NW * (kD + 2) : 1];
+  __shared__ float half_acc[ATTN ? kD : 1];
+  __shared__ float vred[ATTN ? 16 * kD : 1];
+  const int u = blockIdx.y, hq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, units = s.B * s.Hkv;
+  const int heads = gridDim.x;
+  const int b = u / s.Hkv, g = u % s.Hkv;
+  int* pre_sel = dyn;
+  int* pre_cand = dyn + (s.nblkC + 1);
+  float* pm = reinterpret_cast<float*>(dyn + 2 * (s.nblkC + 1));
+  float* pl = pm + s.nblkC;
+  const int d = tid & (kD - 1), half = tid >> 7;  // output dimension and half of the partials this thread sums
   PQC_MARK(ws, 2, 0);
-  int* pre_sel = pre;
-  int* pre_cand = pre + (s.nblkC + 1);
-  unsigned* gh = ws.hist + (size_t)u * kNB;
-  for (int i = tid; i < kNB; i += NT) gh[i] = 0u;  // all readers finished with the previous launch: ready for the next call
 
-  // prefix sums of the per-workgroup list sizes
+  // ---- everything whose address is known up front is requested first
+  const int n_slots = s.nblkC * s.recPerWg;  // <= NT * kSlotsPerThread
+  const unsigned char* recs = ws.cand_rec + (size_t)u * n_slots * ws.rec_stride;
+  unsigned long long rc[kSlotsPerThread];
+  float rl[kSlotsPerThread];
+#pragma unroll
+  for (int x = 0; x < kSlotsPerThread; ++x) {
+    const int slot = min(x * NT + tid, n_slots - 1);  // clamped: straight-line loads, extra lanes unused
+    const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)slot * ws.rec_stride);
+    rc[x] = hd->composite;
+    rl[x] = ATTN ? hd->logit[hq] : 0.0f;
+  }
+  const float* parts = ws.partials + (size_t)u * s.npart * G * (kD + 2);
   const int2* cnt = ws.stage_cnt + (size_t)u * s.nblkC;
+  const int jc = min(tid, s.nblkC - 1);
+  const int2 cnt0 = cnt[jc];  // list sizes of the first NT select workgroups
+  float pm0 = 0.0f, pl0 = 0.0f;
+  float a0[kAccBatch];  // first batch of this thread's partial accumulators: lists half, half+2, ...
+  if constexpr (ATTN) {
+    pm0 = parts[((size_t)jc * G + hq) * (kD + 2)];
+    pl0 = parts[((size_t)jc * G + hq) * (kD + 2) + 1];
+#pragma unroll
+    for (int x = 0; x < kAccBatch; ++x)
+      a0[x] = parts[((size_t)min(half + 2 * x, s.nblkC - 1) * G + hq) * (kD + 2) + 2 + d];
+  }
+  // index lists this wave will copy: list (hq*NW + w) + x*heads*NW, first 256 entries each
+  const unsigned long long* stage_u = ws.stage + (size_t)u * s.nblkC * s.tokC;
+  int ix[kIdxLists][4];
+#pragma unroll
+  for (int x = 0; x < kIdxLists; ++x) {
+    const int j = min(hq * NW + w + x * heads * NW, s.nblkC - 1);
+    const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.tokC);
+#pragma unroll
+    for (int y = 0; y < 4; ++y) ix[x][y] = src[min(y * 64 + lane, 2 * s.tokC - 1)];
+  }
+  PQC_LOADS_ISSUED();
+  if constexpr (ATTN) {
+    if (tid < s.nblkC) {
+      pm[tid] = pm0;
+      pl[tid] = pl0;
+    }
+    for (int j = NT + tid; j < s.nblkC; j += NT) {  // beyond the first NT lists (very long contexts)
+      pm[j] = parts[((size_t)j * G + hq) * (kD + 2)];
+      pl[j] = parts[((size_t)j * G + hq) * (kD + 2) + 1];
+    }
+  }
+  if (tid == 0) overflow_sm = 0;
+  // prefix sums of the per-workgroup list sizes
   int carry_s = 0, carry_c = 0;
   for (int j0 = 0; j0 < s.nblkC; j0 += NT) {
     const int j = j0 + tid;
-    const int2 c = j < s.nblkC ? cnt[j] : make_int2(0, 0);
+    const int2 c = j < s.nblkC ? (j0 == 0 ? cnt0 : cnt[j]) : make_int2(0, 0);
     int ts, tc;
     const int ps = block_exclusive_scan<NT>(c.x, &ts, scan_sm);
     const int pc = block_exclusive_scan<NT>(c.y, &tc, scan_sm);
     if (j < s.nblkC) {
       pre_sel[j] = carry_s + ps;
       pre_cand[j] = carry_c + pc;
+      if (c.y > s.recPerWg) overflow_sm = 1;
     }
     carry_s += ts;
     carry_c += tc;
@@ -423,53 +593,133 @@ __global__ __launch_bounds__(512) void finalize_kernel(Shape s, Workspace ws, co
   const int n_above = max(0, n_list - s.I - s.L);
   const int n_cand = carry_c;
   const int need = max(0, min(s.K - n_above, n_cand));
-  auto owner = [&](const int* prefix, int p) -> int {  // largest j with prefix[j] <= p
-    int lo = 0, hi = s.nblkC - 1;
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if (prefix[mid] <= p) lo = mid; else hi = mid - 1;
-    }
-    return lo;
-  };
-  const unsigned long long* stage_u = ws.stage + (size_t)u * s.nblkC * s.tokC;
+  const bool fast = overflow_sm == 0 && n_cand <= kCandRec;
   int* out = out_idx + (size_t)u * s.Ktot;
   PQC_MARK(ws, 2, 1);
 
-  // indices of the staged lists: one wave per list, coalesced; the local window moves
-  // behind the admitted candidates
-  for (int j = w; j < s.nblkC; j += NW) {
-    const int base = pre_sel[j], n = pre_sel[j + 1] - base;
-    const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.tokC);
-    for (int p = lane; p < n; p += 64) {
-      const int pos = base + p;
-      out[pos < s.I + n_above ? pos : pos + need] = src[p];
-    }
-  }
-
-  PQC_MARK(ws, 2, 2);
-  // candidates: the `need` best by (score desc, token asc) are admitted, listed in token order
-  auto cand_at = [&](int i) -> unsigned long long {
-    const int j = owner(pre_cand, i);
-    return stage_u[(size_t)j * s.tokC + s.tokC - 1 - (i - pre_cand[j])];
-  };
-  const bool in_lds = n_cand <= kCandLds;
-  if (need > 0) {
-    if (in_lds) {
-      for (int i = tid; i < n_cand; i += NT) comp[i] = cand_at(i);
-      __syncthreads();
-      for (int i = tid; i < n_cand; i += NT) {
-        const unsigned long long mine = comp[i];
-        int rank = 0;
-        for (int j = 0; j < n_cand; ++j) rank += comp[j] > mine ? 1 : 0;
-        if (rank == need - 1) thr_sm = mine;
+  if (fast) {
+    // compact the valid record headers into (select workgroup, position) order
+#pragma unroll
+    for (int x = 0; x < kSlotsPerThread; ++x) {
+      const int slot = x * NT + tid;
+      if (slot < n_slots) {
+        const int j = slot / s.recPerWg, c = slot - j * s.recPerWg;
+        if (c < pre_cand[j + 1] - pre_cand[j]) {
+          const int k = pre_cand[j] + c;
+          comp[k] = rc[x];
+          lgr[k] = rl[x] * s.scale_log2e;
+          slotv[k] = (unsigned short)slot;
+        }
       }
+    }
+    __syncthreads();
+    // rank every candidate; admitted ones are then handled in rank order
+    for (int k = tid; k < (need > 0 ? n_cand : 0); k += NT) {
+      const unsigned long long mine = comp[k];
+      int rank = 0;
+      for (int j = 0; j < n_cand; ++j) rank += comp[j] > mine ? 1 : 0;
+      if (rank < need) {
+        if (hq == 0) out[s.I + n_above + rank] = composite_token(mine);  // best first
+        lgk[rank] = lgr[k];
+        ordv[rank] = (unsigned short)k;
+      } else {
+        lgr[k] = kNegBig;  // not admitted: weight 0
+      }
+    }
+    __syncthreads();
+    if constexpr (ATTN) {
+      float mx = kNegBig;
+      for (int k = tid; k < need; k += NT) mx = fmaxf(mx, lgk[k]);
+      for (int j = tid; j < s.nblkC; j += NT) mx = fmaxf(mx, pm[j]);
+      const float mstar = block_max<NT>(mx, fsm);
+      float lsum = 0.0f;
+      for (int k = tid; k < need; k += NT) {
+        const float p = __builtin_amdgcn_exp2f(lgk[k] - mstar);
+        lgk[k] = p;
+        lsum += p;
+      }
+      for (int j = tid; j < s.nblkC; j += NT) {
+        const float wj = __builtin_amdgcn_exp2f(pm[j] - mstar);
+        pm[j] = wj;
+        lsum = fmaf(wj, pl[j], lsum);
+      }
+      const float lstar = block_sum<NT>(lsum, fsm);  // its barriers make lgk and pm visible
+      PQC_MARK(ws, 2, 2);
+      // out[d] = (sum_j w_j acc_j[d] + sum_k p_k V_k[d]) / l ; two threads per dimension
+      float acc = 0.0f;
+#pragma unroll
+      for (int x = 0; x < kAccBatch; ++x) {
+        const int j = half + 2 * x;
+        if (j < s.nblkC) acc = fmaf(pm[j], a0[x], acc);
+      }
+      for (int j0 = half + 2 * kAccBatch; j0 < s.nblkC; j0 += 2 * kAccBatch) {
+        float a[kAccBatch];
+#pragma unroll
+        for (int x = 0; x < kAccBatch; ++x) {
+          const int j = j0 + 2 * x;
+          a[x] = j < s.nblkC ? parts[((size_t)j * G + hq) * (kD + 2) + 2 + d] : 0.0f;
+        }
+#pragma unroll
+        for (int x = 0; x < kAccBatch; ++x) {
+          const int j = j0 + 2 * x;
+          if (j < s.nblkC) acc = fmaf(pm[j], a[x], acc);
+        }
+      }
+      if (need > 0) {
+        // admitted candidates in rank order, 16 rows at a time per pass (16 lanes read one V row)
+        const int sub = tid & 15, grp = tid >> 4;
+        float va[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) va[e] = 0.0f;
+        for (int k0 = 0; k0 < need; k0 += 16 * kVPass) {
+          RowRaw<T> vr[kVPass];
+#pragma unroll
+          for (int x = 0; x < kVPass; ++x) {
+            const int k = min(k0 + x * 16 + grp, need - 1);
+            vr[x].load_row(recs + (size_t)slotv[ordv[k]] * ws.rec_stride + sizeof(CandHeader), sub);
+          }
+          PQC_LOADS_ISSUED();
+#pragma unroll
+          for (int x = 0; x < kVPass; ++x) {
+            const int k = k0 + x * 16 + grp;
+            const float p = k < need ? lgk[k] : 0.0f;
+            float vf[8];
+            vr[x].unpack(vf);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) va[e] = fmaf(p, vf[e], va[e]);
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vred[grp * kD + owned_dim<T>(sub, e)] = va[e];
+        __syncthreads();
+#pragma unroll
+        for (int x = 0; x < 8; ++x) acc += vred[(half * 8 + x) * kD + d];
+      }
+      if (half == 1) half_acc[d] = acc;
       __syncthreads();
-    } else {
-      // radix select of the need-th largest composite, 8 bits per pass, through global memory
+      if (half == 0) out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + d] = (acc + half_acc[d]) / lstar;
+      PQC_MARK(ws, 2, 3);
+    }
+  } else {
+    // generic path: radix select of the need-th largest staged composite, 8 bits per pass
+    auto owner = [&](int p) -> int {  // largest j with pre_cand[j] <= p
+      int lo = 0, hi = s.nblkC - 1;
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (pre_cand[mid] <= p) lo = mid; else hi = mid - 1;
+      }
+      return lo;
+    };
+    auto cand_at = [&](int i) -> unsigned long long {
+      const int j = owner(i);
+      return stage_u[(size_t)j * s.tokC + s.tokC - 1 - (i - pre_cand[j])];
+    };
+    unsigned long long thr = ~0ull;
+    if (need > 0) {
       unsigned long long prefix = 0;
       int want = need;
       for (int shift = 56; shift >= 0; shift -= 8) {
-        if (tid < 256) rhist[tid] = 0u;
+        rhist[tid] = 0u;
         __syncthreads();
         for (int i = tid; i < n_cand; i += NT) {
           const unsigned long long c = cand_at(i);
@@ -477,12 +727,12 @@ __global__ __launch_bounds__(512) void finalize_kernel(Shape s, Workspace ws, co
         }
         __syncthreads();
         if (tid == 0) {
-          int cum = 0, d = 255;
-          for (; d > 0; --d) {
-            if (cum + (int)rhist[d] >= want) break;
-            cum += (int)rhist[d];
+          int cum = 0, dg = 255;
+          for (; dg > 0; --dg) {
+            if (cum + (int)rhist[dg] >= want) break;
+            cum += (int)rhist[dg];
           }
-          digit_sm[0] = d;
+          digit_sm[0] = dg;
           digit_sm[1] = want - cum;
         }
         __syncthreads();
@@ -490,86 +740,94 @@ __global__ __launch_bounds__(512) void finalize_kernel(Shape s, Workspace ws, co
         want = digit_sm[1];
         __syncthreads();
       }
-      if (tid == 0) thr_sm = prefix;
-      __syncthreads();
+      thr = prefix;
     }
-    const unsigned long long thr = thr_sm;
+    // admitted candidates in token order, NT candidates per round: indices out, rows attended
+    AttnState<1> st;
+    st.init();
+    float qr[1][8];
+    if constexpr (ATTN) load_query<T, 1>(q + ((size_t)b * s.Hq + (size_t)g * G + hq) * kD, s.scale_log2e, qr);
     int carry = 0;
-    for (int i0 = 0; i0 < n_cand; i0 += NT) {
+    for (int i0 = 0; i0 < (need > 0 ? n_cand : 0); i0 += NT) {
       const int i = i0 + tid;
       unsigned long long c = 0;
-      if (i < n_cand) c = in_lds ? comp[i] : cand_at(i);
+      if (i < n_cand) c = cand_at(i);
       const int flag = (i < n_cand && c >= thr) ? 1 : 0;
       int tot;
       const int pos = block_exclusive_scan<NT>(flag, &tot, scan_sm);
-      if (flag && carry + pos < need) {
-        const int t = composite_token(c);
-        out[s.I + n_above + carry + pos] = t;
-        if (need <= kCandLds) adm[carry + pos] = t;
+      if (flag) {
+        rows_sm[pos] = composite_token(c);
+        if (hq == 0) out[s.I + n_above + carry + pos] = composite_token(c);
       }
+      __syncthreads();
+      if constexpr (ATTN) {
+        auto row_at = [&](int p) -> int { return rows_sm[p]; };
+        attend_rows<T, 1, 4>(kc + (size_t)u * s.N * kD, vc + (size_t)u * s.N * kD, s.N, row_at, tot, w * 16, NW * 16, qr, st);
+      }
+      __syncthreads();
       carry += tot;
+    }
+    if constexpr (ATTN) {
+      stash_wave_state<T, 1>(st, red);
+      __syncthreads();
+      float m_own, l_own, acc;
+      combine_waves<1, NW>(red, 0, d, m_own, l_own, acc);
+      float mx = m_own;
+      for (int j = tid; j < s.nblkC; j += NT) mx = fmaxf(mx, pm[j]);
+      const float mstar = block_max<NT>(mx, fsm);
+      float lsum = 0.0f;
+      for (int j = tid; j < s.nblkC; j += NT) {
+        const float wj = __builtin_amdgcn_exp2f(pm[j] - mstar);
+        pm[j] = wj;
+        lsum = fmaf(wj, pl[j], lsum);
+      }
+      const float f_own = __builtin_amdgcn_exp2f(m_own - mstar);
+      const float lstar = block_sum<NT>(lsum, fsm) + l_own * f_own;
+      acc = half == 0 ? acc * f_own : 0.0f;
+      for (int j = half; j < s.nblkC; j += 2) acc = fmaf(pm[j], parts[((size_t)j * G + hq) * (kD + 2) + 2 + d], acc);
+      if (half == 1) half_acc[d] = acc;
+      __syncthreads();
+      if (half == 0) out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + d] = (acc + half_acc[d]) / lstar;
     }
   }
 
-  PQC_MARK(ws, 2, 3);
-  if constexpr (ATTN) {
-    __syncthreads();  // admitted list (LDS, or this workgroup's own global writes) visible to all its threads
-    const int b = u / s.Hkv, g = u % s.Hkv;
-    AttnState<G> st;
-    st.init();
-    if (need > 0) {
-      float qr[G][8];
-      load_query<T, G>(q + ((size_t)b * s.Hq + (size_t)g * G) * kD, s.scale_log2e, qr);
-      constexpr int R = 2;
-      if (need <= kCandLds) {
-        auto row_at = [&](int p) -> int { return adm[p]; };
-        attend_rows<T, G, R>(kc + (size_t)u * s.N * kD, vc + (size_t)u * s.N * kD, s.N, row_at, need, w * 4 * R, NW * 4 * R,
-                             qr, st);
-      } else {
-        auto row_at = [&](int p) -> int { return out[s.I + n_above + p]; };
-        attend_rows<T, G, R>(kc + (size_t)u * s.N * kD, vc + (size_t)u * s.N * kD, s.N, row_at, need, w * 4 * R, NW * 4 * R,
-                             qr, st);
-      }
-    }
-    PQC_MARK(ws, 2, 4);
-    stash_wave_state<T, G, NW>(st, red);
-    __syncthreads();
-    const float* parts = ws.partials + (size_t)u * s.npart * G * (kD + 2);
-    for (int o = tid; o < G * kD; o += NT) {
-      const int h = o / kD, d = o % kD;
-      float m, l, acc;
-      combine_waves<G, NW>(red, h, d, m, l, acc);
-      for (int j0 = 0; j0 < s.nblkC; j0 += 8) {
-        float mj[8], lj[8], aj[8];
+  // indices of the staged lists, shared among the unit's head workgroups: one wave per list,
+  // coalesced; the local window moves behind the admitted candidates.  The first 256 entries
+  // of the first kIdxLists lists of a wave were loaded up front.
+  {
+    int x = 0;
+    for (int j = hq * NW + w; j < s.nblkC; j += heads * NW, ++x) {
+      const int base = pre_sel[j], n = pre_sel[j + 1] - base;
+      const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.tokC);
+      for (int p0 = 0; p0 < n; p0 += 256) {
+        int v[4];
+        if (x < kIdxLists && p0 == 0) {
 #pragma unroll
-        for (int x = 0; x < 8; ++x) {
-          const bool ok = j0 + x < s.nblkC;
-          const float* pj = parts + ((size_t)(ok ? j0 + x : j0) * G + h) * (kD + 2);
-          mj[x] = ok ? pj[0] : kNegBig;
-          lj[x] = ok ? pj[1] : 0.0f;
-          aj[x] = ok ? pj[2 + d] : 0.0f;
+          for (int y = 0; y < 4; ++y) v[y] = x == 0 ? ix[0][y] : x == 1 ? ix[1][y] : x == 2 ? ix[2][y] : ix[3][y];
+        } else {
+#pragma unroll
+          for (int y = 0; y < 4; ++y)
+            if (p0 + y * 64 + lane < n) v[y] = src[p0 + y * 64 + lane];
         }
 #pragma unroll
-        for (int x = 0; x < 8; ++x) {
-          const float mn = fmaxf(m, mj[x]);
-          const float fa = __builtin_amdgcn_exp2f(m - mn), fb = __builtin_amdgcn_exp2f(mj[x] - mn);
-          l = l * fa + lj[x] * fb;
-          acc = acc * fa + aj[x] * fb;
-          m = mn;
+        for (int y = 0; y < 4; ++y) {
+          const int pos = base + p0 + y * 64 + lane;
+          if (p0 + y * 64 + lane < n) out[pos < s.I + n_above ? pos : pos + need] = v[y];
         }
       }
-      out_attn[((size_t)b * s.Hq + (size_t)g * G + h) * kD + d] = acc / l;
     }
-    PQC_MARK(ws, 2, 5);
-#ifdef PQC_TRACE
-    if (tid == 0 && (size_t)blockIdx.y * gridDim.x + blockIdx.x < (size_t)kTraceWgs) {
-      unsigned long long* tr = ws.trace + ((size_t)2 * kTraceWgs + (size_t)blockIdx.y * gridDim.x + blockIdx.x) * kTraceSlots;
-      tr[13] = (unsigned long long)n_above;
-      tr[14] = (unsigned long long)n_cand;
-      tr[15] = (unsigned long long)need;
-    }
-#endif
   }
+  PQC_MARK(ws, 2, 4);
+
+  // leave the other parity's histogram zeroed for the next call
+  if (hq == 0) {
+    unsigned* gh = ws.hist + ((size_t)(s.parity ^ 1) * units + u) * kHistCopies * kNB;
+    for (int i = tid; i < kHistCopies * kNB; i += NT) gh[i] = 0u;
+  }
+  PQC_MARK(ws, 2, 5);
+  PQC_NOTE(ws, 2, 13, n_above);
+  PQC_NOTE(ws, 2, 14, n_cand);
+  PQC_NOTE(ws, 2, 15, need);
 }
 
 // ---------------------------------------------- stand-alone attention over a list
@@ -579,21 +837,34 @@ __global__ __launch_bounds__(256) void attn_list_kernel(Shape s, Workspace ws, c
                                                         const T* __restrict__ kc, const T* __restrict__ vc,
                                                         const int* __restrict__ idx) {
   constexpr int NT = 256, NW = 4;
+  constexpr bool kMfma = sizeof(T) == 2;
   __shared__ float red[NW * G * (kD + 2)];
+  __shared__ __attribute__((aligned(16))) unsigned char vtile[kMfma ? NW * kVTileBytes : 16];
   const int u = blockIdx.y, tid = threadIdx.x, w = tid >> 6;
   const int b = u / s.Hkv, g = u % s.Hkv;
   const int p0 = blockIdx.x * s.rowsP;
   const int count = min(s.rowsP, s.Ktot - p0);
   const int* lst = idx + (size_t)u * s.Ktot + p0;
-  float qr[G][8];
-  load_query<T, G>(q + ((size_t)b * s.Hq + (size_t)g * G) * kD, s.scale_log2e, qr);
-  AttnState<G> st;
-  st.init();
-  constexpr int R = (G >= 8 || sizeof(T) == 4) ? 2 : 4;
   auto row_at = [&](int p) -> int { return lst[p]; };
-  attend_rows<T, G, R>(kc + (size_t)u * s.N * kD, vc + (size_t)u * s.N * kD, s.N, row_at, count, w * 4 * R, NW * 4 * R,
-                       qr, st);
-  stash_wave_state<T, G, NW>(st, red);
+  const T* kbase = kc + (size_t)u * s.N * kD;
+  const T* vbase = vc + (size_t)u * s.N * kD;
+  if constexpr (kMfma) {
+    bf16x8_t qf[4];
+    load_q_frags(reinterpret_cast<const bf16_t*>(q) + ((size_t)b * s.Hq + (size_t)g * G) * kD, G, qf);
+    MfmaState st;
+    st.init();
+    mfma_attend(reinterpret_cast<const bf16_t*>(kbase), reinterpret_cast<const bf16_t*>(vbase), s.N, row_at, count,
+                w * 16 * kMfmaTiles, NW * 16 * kMfmaTiles, s.scale_log2e, qf, vtile + w * kVTileBytes, st);
+    mfma_stash_wave_state<G>(st, red);
+  } else {
+    float qr[G][8];
+    load_query<T, G>(q + ((size_t)b * s.Hq + (size_t)g * G) * kD, s.scale_log2e, qr);
+    AttnState<G> st;
+    st.init();
+    constexpr int R = G >= 8 ? 2 : 4;
+    attend_rows<T, G, R>(kbase, vbase, s.N, row_at, count, w * 4 * R, NW * 4 * R, qr, st);
+    stash_wave_state<T, G>(st, red);
+  }
   __syncthreads();
   float* part = ws.partials + ((size_t)u * s.npart + blockIdx.x) * G * (kD + 2);
   for (int o = tid; o < G * kD; o += NT) {
