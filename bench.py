@@ -34,6 +34,8 @@ def main() -> int:
     ap.add_argument("--profile-steps", type=int, default=48, help="steps timed per kernel with HIP events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run one plain device copy of this size (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -92,6 +94,14 @@ def main() -> int:
     kern_us = kern / max(args.profile_steps, 1) * 1e3
     torch.cuda.synchronize()
 
+    if args.copy_calibration_mib:
+        src = torch.empty(args.copy_calibration_mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)  # one elementwise copy kernel: reads and writes exactly this many bytes
+        torch.cuda.synchronize()
+        del src, dst
+
     units = w.batch * w.n_kv_heads
     path_bytes = w.algorithmic_bytes()
     # dominant kernel (select + attention): codes, the K retrieved K/V rows, queries, table
@@ -100,21 +110,27 @@ def main() -> int:
     sel_gbps = sel_bytes / (kern_us[1] * 1e-6) / 1e9 if kern_us[1] > 0 else 0.0
     path_gbps = path_bytes / (us * 1e-6) / 1e9
 
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"select_kernel_{w.name}_traffic.json")
+    if os.path.exists(tpath):  # HBM bytes per launch measured with rocprofv3 --pmc (see the file for the commands)
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+
     result = {
-        "metric": "decode us per layer (PQ score + top-k + sparse attention) at 128K context",
+        "metric": "decode \u00b5s per layer (PQ score+top-k+sparse attn) at 128K ctx",
         "value": round(us, 3), "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "n_tokens": w.n_tokens, "pq_m": w.pq_m, "pq_centroids": w.pq_centroids,
                    "topk": w.topk, "n_init": w.n_init, "n_local": w.n_local, "kv_dtype": w.dtype,
-                   "kmeans_iters": w.kmeans_iters, "input_sets": len(sets)},
+                   "kmeans_iters": w.kmeans_iters, "input_sets": len(sets), "accumulate": "f32"},
         "achieved_hbm_gbps": round(path_gbps, 1), "hbm_frac": round(path_gbps / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": path_bytes, "host_wall_ms_per_step": round(wall_ms / args.steps, 6),
         "kernel_us": {"hist": round(float(kern_us[0]), 3), "select_attn": round(float(kern_us[1]), 3),
                       "finalize": round(float(kern_us[2]), 3)},
         "roofline": {"kernel": "select_kernel", "bound": "hbm", "achieved": round(sel_gbps, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(sel_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(sel_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "bytes_per_launch": sel_bytes, "avg_us": round(float(kern_us[1]), 3)},
     }
 

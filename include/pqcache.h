@@ -116,9 +116,10 @@ int pqc_last_hip_error(const pqc_ctx* ctx);
  *   k_cache    [B][Hkv][N][D]        kv_dtype
  *   v_cache    [B][Hkv][N][D]        kv_dtype
  *   out_idx    [B][Hkv][I+K+L]       int32      attended tokens: 0..I-1, then the K
- *                                               retrieved tokens in ascending order
- *                                               of (admission class, token index) --
- *                                               compare as a set --, then N-L..N-1
+ *                                               retrieved tokens (those above the
+ *                                               threshold ascending, then the ones
+ *                                               admitted at the threshold best first:
+ *                                               compare as a set), then N-L..N-1
  *   out_attn   [B][Hq][D]            f32        attention output
  *
  * Codes of tokens inside the initial and local windows are ignored.
