@@ -81,6 +81,7 @@ def main() -> int:
     for i in range(args.steps):
         step(i)
     ev1.record()
+    issue_ms = (time.perf_counter() - t0) * 1e3  # host time to enqueue the steps (the GPU must not wait for it)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ms_per_step = ev0.elapsed_time(ev1) / args.steps
@@ -127,6 +128,7 @@ def main() -> int:
                    "kmeans_iters": w.kmeans_iters, "input_sets": len(sets), "accumulate": "f32"},
         "achieved_hbm_gbps": round(path_gbps, 1), "hbm_frac": round(path_gbps / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": path_bytes, "host_wall_ms_per_step": round(wall_ms / args.steps, 6),
+        "host_issue_ms_per_step": round(issue_ms / args.steps, 6),
         "kernel_us": {"hist": round(float(kern_us[0]), 3), "select_attn": round(float(kern_us[1]), 3),
                       "finalize": round(float(kern_us[2]), 3)},
         "roofline": {"kernel": "select_kernel", "bound": "hbm", "achieved": round(sel_gbps, 1), "peak": HBM_PEAK_GBPS,

@@ -79,12 +79,8 @@ int make_plan(const pqc_config* c, Plan* p) {
   s.rowsP = env_int("PQC_ROWS_P", 256);
   s.nblkP = (s.Ktot + s.rowsP - 1) / s.rowsP;
   s.npart = s.nblkC > s.nblkP ? s.nblkC : s.nblkP;
+  if (s.npart < 2 * kAccBatch) s.npart = 2 * kAccBatch;  // finalize_kernel reads this many slots unconditionally
   s.parity = 0;
-  // candidate records: a fixed number of slots per select workgroup, <= 2048 per unit
-  int rec = 16;
-  while (rec > 1 && (long long)rec * s.nblkC > 256 * kSlotsPerThread) rec /= 2;
-  if ((long long)rec * s.nblkC > 256 * kSlotsPerThread) return PQC_EUNSUPPORTED;
-  s.recPerWg = rec;
   p->rec_stride = (int)sizeof(CandHeader) + kD * (c->kv_dtype == PQC_F32 ? 4 : 2);
   // sample ranks that bracket the K-th largest score by 5 standard errors (+2)
   const int nmid = s.N - s.I - s.L;
@@ -102,8 +98,8 @@ int make_plan(const pqc_config* c, Plan* p) {
   p->off_ctl = off;   off = align_up(off + sizeof(BinParams) * units);
   p->off_lut = off;   off = align_up(off + sizeof(float) * units * s.M * s.C);
   p->off_range = off; off = align_up(off + sizeof(float2) * units);
-  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * 2 * units * kHistCopies * kNB);
-  p->off_crec = off;  off = align_up(off + (size_t)p->rec_stride * s.recPerWg * s.nblkC * units);
+  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * 2 * units * (kHistCopies * kNB + 1));  // + record counters
+  p->off_crec = off;  off = align_up(off + (size_t)p->rec_stride * kCandRec * units);
   p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * s.nblkC * s.tokC);
   p->off_cnt = off;   off = align_up(off + sizeof(int2) * units * s.nblkC);
   p->off_part = off;  off = align_up(off + sizeof(float) * units * s.npart * s.G * (kD + 2));
@@ -143,7 +139,7 @@ int check_launch(pqc_ctx* ctx) {
 int ensure_clean_hist(pqc_ctx* ctx, hipStream_t st) {
   if (ctx->hist_clean) return PQC_OK;
   const Shape& s = ctx->plan.s;
-  const size_t na = (size_t)2 * s.B * s.Hkv * kHistCopies * kNB;
+  const size_t na = (size_t)2 * s.B * s.Hkv * (kHistCopies * kNB + 1);  // histograms and the record counters behind them
   hipLaunchKernelGGL(reset_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, st, ctx->ws.hist, na);
   const int rc = check_launch(ctx);
   if (rc == PQC_OK) ctx->plan.s.parity = 0;
@@ -167,7 +163,7 @@ void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uin
   hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(int), st,
                      s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));
   if (ev) (void)hipEventRecord(ev[2], st);
-  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
+  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
                      ctx->ws, qt, kt, vt, out_idx, out_attn);
   if (ev) (void)hipEventRecord(ev[3], st);
 }
@@ -279,6 +275,7 @@ int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t wor
   ctx->ws.ctl = reinterpret_cast<BinParams*>(base + p.off_ctl);
   ctx->ws.lut = reinterpret_cast<float*>(base + p.off_lut);
   ctx->ws.hist = reinterpret_cast<unsigned*>(base + p.off_hist);
+  ctx->ws.cand_count = ctx->ws.hist + (size_t)2 * p.s.B * p.s.Hkv * kHistCopies * kNB;
   ctx->ws.range = reinterpret_cast<float2*>(base + p.off_range);
   ctx->ws.cand_rec = reinterpret_cast<unsigned char*>(base + p.off_crec);
   ctx->ws.rec_stride = p.rec_stride;
@@ -394,7 +391,7 @@ int pqc_topk(pqc_ctx* ctx, const float* scores, int32_t* out_idx, void* stream) 
                      static_cast<const void*>(scores));
   hipLaunchKernelGGL((select_kernel<float, 1, ScoreChunks, false>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(int), st,
                      s, ctx->ws, nof, nof, nof, static_cast<const void*>(scores));
-  hipLaunchKernelGGL((finalize_kernel<float, 1, false>), dim3(1, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
+  hipLaunchKernelGGL((finalize_kernel<float, 1, false>), dim3(1 + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
                      ctx->ws, nof, nof, nof, out_idx, static_cast<float*>(nullptr));
   rc = check_launch(ctx);
   if (rc == PQC_OK) {

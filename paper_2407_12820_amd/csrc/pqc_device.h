@@ -14,7 +14,7 @@ constexpr int kNB = 2048;        // score bins of the one-pass threshold search
 constexpr int kHistCopies = 4;   // histogram replicas per unit (spreads contended atomics)
 constexpr int kD = 128;          // head dimension
 constexpr int kLutRow = 256;     // LDS stride of one partition's table (max centroids)
-constexpr int kCandRec = 1024;   // boundary-bin candidates the finalize kernel ranks inside LDS
+constexpr int kCandRec = 1024;   // boundary-bin candidate records per unit (ranked inside LDS by the finalize kernel)
 constexpr float kNegBig = -1.0e30f;
 
 struct bf16_t {
@@ -35,7 +35,6 @@ struct Shape {
   int parity;       // which of the two histogram sets this call uses
   int sampleN;      // tokens sampled per unit to place the fine bins (<= 1024)
   int rankHi, rankLo;  // sample ranks (from the top) that bracket the K-th largest score
-  int recPerWg;     // candidate record slots per select workgroup
   float scale_log2e;
 };
 
@@ -54,7 +53,8 @@ struct Workspace {
   float* lut;                  // [units][M][C]
   float2* range;               // [units]                       (min, max) score, stand-alone top-k only
   unsigned* hist;              // [2][units][kHistCopies][kNB]   zero between uses
-  unsigned char* cand_rec;     // [units][nblkC][recPerWg] records of rec_stride bytes
+  unsigned* cand_count;        // [2][units]   records handed out so far (directly behind hist, zeroed with it)
+  unsigned char* cand_rec;     // [units][kCandRec] records of rec_stride bytes, in order of arrival
   unsigned long long* stage;   // [units][nblkC][tokC] selected ids (front, int32) / candidate composites (back, u64)
   int2* stage_cnt;             // [units][nblkC]     (selected, candidates)
   float* partials;             // [units][npart][G][kD+2]

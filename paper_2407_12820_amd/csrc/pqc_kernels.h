@@ -7,10 +7,10 @@
 //                    above the bin (and the two windows) are listed in ascending order
 //                    without atomics and attended at once; tokens inside the bin
 //                    ("candidates") are recorded with their logits and V row
-//   finalize_kernel  one workgroup per query head: ranks the candidates, folds the
-//                    admitted ones and all partial softmax states into the output,
-//                    writes the indices, and zeroes the other parity's histogram and
-//                    counters for the next call
+//   finalize_kernel  one workgroup per query head ranks the candidates and folds the
+//                    admitted ones and all partial softmax states into the output;
+//                    copy workgroups beside them write the indices and zero the other
+//                    parity's histogram and counter for the next call
 //
 // Codes are read 16 bytes at a time (P = 16/M tokens).  A unit's codes start at byte
 // u*N*M, which need not be 16-byte aligned: chunks are laid over the aligned-down
@@ -368,6 +368,10 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
     ccand[i + 1] = ccand[i] + wcnt[NW + i];
   }
   const int tot_sel = csel[NW], tot_cand = ccand[NW];
+  // record slots for this workgroup's candidates: requested now, needed only after the
+  // attention below, which hides the round trip of the returning atomic
+  int rec_base = 0;
+  if (tid == 0 && tot_cand > 0) rec_base = (int)atomicAdd(&ws.cand_count[(size_t)s.parity * units + u], (unsigned)tot_cand);
   auto sel_at = [&](int p) -> int {
     int i = 0;
 #pragma unroll
@@ -384,13 +388,27 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
 
   const T* kbase = kc + (size_t)u * s.N * kD;
   const T* vbase = vc + (size_t)u * s.N * kD;
+  // Rows this workgroup attends: its own tokens above the threshold bin, and, instead of the
+  // window tokens it happens to hold (the list's first nI and last nL entries), every
+  // nblkC-th token of the two windows, so that the window rows are spread over the unit's
+  // workgroups.
+  const int tok_lo = max(0, (int)blockIdx.x * s.tokC - src.lead), tok_hi = min(s.N, ((int)blockIdx.x + 1) * s.tokC - src.lead);
+  const int nI = max(0, min(s.I, tok_hi) - tok_lo), nL = max(0, tok_hi - max(s.N - s.L, tok_lo));
+  const int n_own = tot_sel - nI - nL;
+  const int n_win = (int)blockIdx.x < s.I + s.L ? (s.I + s.L - (int)blockIdx.x + s.nblkC - 1) / s.nblkC : 0;
+  const int n_att = n_own + n_win;
+  auto att_at = [&](int p) -> int {
+    if (p < n_own) return sel_at(p + nI);
+    const int wt = (int)blockIdx.x + (p - n_own) * s.nblkC;
+    return wt < s.I ? wt : s.N - s.L + (wt - s.I);
+  };
   if constexpr (ATTN) {
     if constexpr (kMfma) {
       bf16x8_t qf[4];
       load_q_frags(reinterpret_cast<const bf16_t*>(q) + ((size_t)b * s.Hq + (size_t)g * G) * kD, G, qf);
       MfmaState st;
       st.init();
-      mfma_attend(reinterpret_cast<const bf16_t*>(kbase), reinterpret_cast<const bf16_t*>(vbase), s.N, sel_at, tot_sel,
+      mfma_attend(reinterpret_cast<const bf16_t*>(kbase), reinterpret_cast<const bf16_t*>(vbase), s.N, att_at, n_att,
                   w * 16 * kMfmaTiles, NW * 16 * kMfmaTiles, s.scale_log2e, qf, vtile + w * kVTileBytes, st);
       PQC_MARK(ws, 1, 4);
       mfma_stash_wave_state<G>(st, red);
@@ -400,7 +418,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
       AttnState<G> st;
       st.init();
       constexpr int R = (G >= 8 || sizeof(T) == 4) ? 2 : 4;
-      attend_rows<T, G, R>(kbase, vbase, s.N, sel_at, tot_sel, w * 4 * R, NW * 4 * R, qr, st);
+      attend_rows<T, G, R>(kbase, vbase, s.N, att_at, n_att, w * 4 * R, NW * 4 * R, qr, st);
       PQC_MARK(ws, 1, 4);
       stash_wave_state<T, G>(st, red);
     }
@@ -421,8 +439,11 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   PQC_NOTE(ws, 1, 14, tot_sel);
   PQC_NOTE(ws, 1, 15, tot_cand);
 
-  // candidates (few): composite for the generic path; the first recPerWg also as full records
+  // candidates (few): composite for the generic path, and a full record while slots last
   if (tot_cand > 0) {  // workgroup-uniform
+    if (tid == 0) scan_sm[0] = rec_base;
+    __syncthreads();
+    const int base = scan_sm[0];
     const int sub = lane & 15, grp = tid >> 4;  // 16 lanes per candidate
     for (int c = grp; c < tot_cand; c += NT / 16) {
       int i = 0;
@@ -431,8 +452,8 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
       const int t = list[i * segN + segN - 1 - (c - ccand[i])];
       const unsigned long long comp = make_composite(src.score_of_token(t, u, s.N), t);
       if (sub == 0) stage[s.tokC - 1 - c] = comp;
-      if (c < s.recPerWg) {
-        unsigned char* rec = ws.cand_rec + (((size_t)u * s.nblkC + blockIdx.x) * s.recPerWg + c) * ws.rec_stride;
+      if (base + c < kCandRec) {
+        unsigned char* rec = ws.cand_rec + ((size_t)u * kCandRec + base + c) * ws.rec_stride;
         CandHeader* hd = reinterpret_cast<CandHeader*>(rec);
         if (sub == 0) hd->composite = comp;
         if constexpr (ATTN) {
@@ -457,12 +478,19 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
 }
 
 // ------------------------------------------------------------- 3. finalize
-// Grid (query heads of the group, units), 256 threads.  The staged "selected" lists
-// already hold the two windows: concatenated in workgroup order they read
+// Grid (heads + kCopyWgs, units), 256 threads; heads = the group's query heads (1 for
+// the stand-alone top-k).
+//   blockIdx.x <  heads  ranks the candidates and folds the admitted ones and all partial
+//                        softmax states into this head's output; head 0 also writes the
+//                        admitted candidates' indices (best first)
+//   blockIdx.x >= heads  copy workgroups: concatenate the staged lists into out_idx; the
+//                        first one also zeroes the other parity's histogram and counter
+// The staged "selected" lists already hold the two windows: in workgroup order they read
 //   [0..I) , tokens above the threshold bin (ascending) , [N-L..N).
-// Fast path (candidates fit their record area): everything a head needs about the
-// candidates is in the records.  Generic path: candidates are the composites staged
-// per select workgroup; admitted rows are gathered from the K/V cache.
+// Fast path (at most kCandRec candidates): all a head needs is in the candidate records,
+// which sit densely in order of arrival.  That order differs from run to run, so every
+// sum over candidates is taken in rank order.  Generic path: candidates are the
+// composites staged per select workgroup; admitted rows are gathered from the K/V cache.
 template <int NT>
 __device__ __forceinline__ float block_max(float v, float* sm /* [NT/64] */) {
   v = wave_max(v);
@@ -486,75 +514,149 @@ __device__ __forceinline__ float block_sum(float v, float* sm /* [NT/64] */) {
   return r;
 }
 
-constexpr int kSlotsPerThread = 8;  // candidate record slots per unit <= 256 * kSlotsPerThread
-constexpr int kAccBatch = 32;       // partial accumulators a thread keeps in flight at once
-constexpr int kVPass = 4;           // admitted candidate V rows per thread group kept in flight at once (16 rows each)
-constexpr int kIdxLists = 4;        // staged index lists a wave copies with loads issued up front
+constexpr int kHdrPerThread = kCandRec / 256;  // candidate record headers per thread
+constexpr int kAccBatch = 32;                  // partial accumulators a thread keeps in flight at once
+constexpr int kVPass = 4;                      // dependent V-row passes in flight (16 rows each), many-candidate case
+constexpr int kIdxLists = 4;                   // staged index lists a wave copies with loads issued up front
+constexpr int kCopyWgs = 4;                    // copy workgroups per unit
+constexpr int kRankChunk = 64;                 // admitted rows summed per pass through LDS
 
 template <typename T, int G, bool ATTN>
 __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, const T* __restrict__ q,
                                                        const T* __restrict__ kc, const T* __restrict__ vc,
                                                        int* __restrict__ out_idx, float* __restrict__ out_attn) {
   constexpr int NT = 256, NW = 4;
+  constexpr int heads = ATTN ? G : 1;
+  constexpr int SP = ATTN ? (sizeof(T) == 2 ? 8 : 4) : 1;  // passes of 16 record V rows requested up front
+  constexpr int kSpecRows = ATTN ? 16 * SP : 0;
   extern __shared__ int dyn[];  // pre_sel[nblkC+1], pre_cand[nblkC+1], pm[nblkC], pl[nblkC]
   __shared__ int scan_sm[2 * NW + 1];
   __shared__ float fsm[NW];
-  __shared__ unsigned long long comp[kCandRec];  // compacted candidates, (select workgroup, position) order
-  __shared__ float lgr[kCandRec];                // their logits for this head (log2 domain)
-  __shared__ unsigned short slotv[kCandRec];     // their record slots
+  __shared__ int ism[2 * NW];
+  __shared__ unsigned long long comp[kCandRec];  // candidate composites, in record order
   __shared__ float lgk[kCandRec];                // by rank: logit, then softmax weight of the admitted ones
-  __shared__ unsigned short ordv[kCandRec];      // by rank: record slot
+  __shared__ unsigned short ordv[kCandRec];      // by rank: record
+  __shared__ unsigned short rankv[kCandRec];     // by record: rank if admitted, 0xffff otherwise
   __shared__ unsigned rhist[256];
   __shared__ int digit_sm[2];
   __shared__ int rows_sm[NT];
-  __shared__ int overflow_sm;
   __shared__ float red[ATTN ? NW * (kD + 2) : 1];
   __shared__ float half_acc[ATTN ? kD : 1];
-  __shared__ float vred[ATTN ? 16 * kD : 1];
-  const int u = blockIdx.y, hq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, units = s.B * s.Hkv;
-  const int heads = gridDim.x;
+  __shared__ float vl[ATTN ? kRankChunk * kD : 1];
+  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, units = s.B * s.Hkv;
   const int b = u / s.Hkv, g = u % s.Hkv;
   int* pre_sel = dyn;
   int* pre_cand = dyn + (s.nblkC + 1);
   float* pm = reinterpret_cast<float*>(dyn + 2 * (s.nblkC + 1));
   float* pl = pm + s.nblkC;
-  const int d = tid & (kD - 1), half = tid >> 7;  // output dimension and half of the partials this thread sums
+  const int2* cnt = ws.stage_cnt + (size_t)u * s.nblkC;
+  const unsigned long long* stage_u = ws.stage + (size_t)u * s.nblkC * s.tokC;
+  int* out = out_idx + (size_t)u * s.Ktot;
   PQC_MARK(ws, 2, 0);
 
-  // ---- everything whose address is known up front is requested first
-  const int n_slots = s.nblkC * s.recPerWg;  // <= NT * kSlotsPerThread
-  const unsigned char* recs = ws.cand_rec + (size_t)u * n_slots * ws.rec_stride;
-  unsigned long long rc[kSlotsPerThread];
-  float rl[kSlotsPerThread];
+  // exclusive prefix sums of the per-workgroup list sizes (into LDS); returns the totals
+  auto scan_counts = [&](const int2 cnt0, int& n_list, int& n_cand) {
+    int carry_s = 0, carry_c = 0;
+    for (int j0 = 0; j0 < s.nblkC; j0 += NT) {
+      const int j = j0 + tid;
+      const int2 c = j < s.nblkC ? (j0 == 0 ? cnt0 : cnt[j]) : make_int2(0, 0);
+      int ts, tc;
+      const int ps = block_exclusive_scan<NT>(c.x, &ts, scan_sm);
+      const int pc = block_exclusive_scan<NT>(c.y, &tc, scan_sm);
+      if (j < s.nblkC) {
+        pre_sel[j] = carry_s + ps;
+        pre_cand[j] = carry_c + pc;
+      }
+      carry_s += ts;
+      carry_c += tc;
+    }
+    if (tid == 0) {
+      pre_sel[s.nblkC] = carry_s;
+      pre_cand[s.nblkC] = carry_c;
+    }
+    __syncthreads();
+    n_list = carry_s;
+    n_cand = carry_c;
+  };
+
+  if (blockIdx.x >= heads) {
+    // ---------------------------------------------------------------- copy workgroup
+    // one wave per list, coalesced; the local window moves behind the admitted candidates
+    const int cw = blockIdx.x - heads, ncw = gridDim.x - heads;
+    const int2 cnt0 = cnt[min(tid, s.nblkC - 1)];
+    int ix[kIdxLists][4];  // first 256 entries of this wave's first kIdxLists lists
 #pragma unroll
-  for (int x = 0; x < kSlotsPerThread; ++x) {
-    const int slot = min(x * NT + tid, n_slots - 1);  // clamped: straight-line loads, extra lanes unused
-    const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)slot * ws.rec_stride);
+    for (int x = 0; x < kIdxLists; ++x) {
+      const int j = min(cw * NW + w + x * ncw * NW, s.nblkC - 1);
+      const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.tokC);
+#pragma unroll
+      for (int y = 0; y < 4; ++y) ix[x][y] = src[min(y * 64 + lane, 2 * s.tokC - 1)];
+    }
+    PQC_LOADS_ISSUED();
+    int n_list, n_cand;
+    scan_counts(cnt0, n_list, n_cand);
+    const int n_above = max(0, n_list - s.I - s.L);
+    const int need = max(0, min(s.K - n_above, n_cand));
+    PQC_MARK(ws, 2, 1);
+    int x = 0;
+    for (int j = cw * NW + w; j < s.nblkC; j += ncw * NW, ++x) {
+      const int base = pre_sel[j], n = pre_sel[j + 1] - base;
+      const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.tokC);
+      for (int p0 = 0; p0 < n; p0 += 256) {
+        int v[4];
+        if (x < kIdxLists && p0 == 0) {
+#pragma unroll
+          for (int y = 0; y < 4; ++y) v[y] = x == 0 ? ix[0][y] : x == 1 ? ix[1][y] : x == 2 ? ix[2][y] : ix[3][y];
+        } else {
+#pragma unroll
+          for (int y = 0; y < 4; ++y)
+            if (p0 + y * 64 + lane < n) v[y] = src[p0 + y * 64 + lane];
+        }
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+          const int pos = base + p0 + y * 64 + lane;
+          if (p0 + y * 64 + lane < n) out[pos < s.I + n_above ? pos : pos + need] = v[y];
+        }
+      }
+    }
+    PQC_MARK(ws, 2, 4);
+    if (cw == 0) {  // leave the other parity's histogram and record counter zeroed for the next call
+      unsigned* gh = ws.hist + ((size_t)(s.parity ^ 1) * units + u) * kHistCopies * kNB;
+      for (int i = tid; i < kHistCopies * kNB; i += NT) gh[i] = 0u;
+      if (tid == 0) ws.cand_count[(size_t)(s.parity ^ 1) * units + u] = 0u;
+    }
+    PQC_MARK(ws, 2, 5);
+    return;
+  }
+
+  // ------------------------------------------------------------------ head workgroup
+  const int hq = blockIdx.x;
+  const int d = tid & (kD - 1), half = tid >> 7;  // output dimension and half of the partials this thread sums
+  const int sub = tid & 15, grp = tid >> 4;       // 16 lanes per candidate V row
+  // ---- everything whose address is known up front is requested first
+  const unsigned char* recs = ws.cand_rec + (size_t)u * kCandRec * ws.rec_stride;
+  unsigned long long rc[kHdrPerThread];
+  float rl[kHdrPerThread];
+#pragma unroll
+  for (int x = 0; x < kHdrPerThread; ++x) {
+    const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)(x * NT + tid) * ws.rec_stride);
     rc[x] = hd->composite;
     rl[x] = ATTN ? hd->logit[hq] : 0.0f;
   }
   const float* parts = ws.partials + (size_t)u * s.npart * G * (kD + 2);
-  const int2* cnt = ws.stage_cnt + (size_t)u * s.nblkC;
   const int jc = min(tid, s.nblkC - 1);
   const int2 cnt0 = cnt[jc];  // list sizes of the first NT select workgroups
   float pm0 = 0.0f, pl0 = 0.0f;
   float a0[kAccBatch];  // first batch of this thread's partial accumulators: lists half, half+2, ...
+  RowRaw<T> vspec[SP];  // V rows of the first kSpecRows records
   if constexpr (ATTN) {
     pm0 = parts[((size_t)jc * G + hq) * (kD + 2)];
     pl0 = parts[((size_t)jc * G + hq) * (kD + 2) + 1];
+    const float* a0p = parts + ((size_t)half * G + hq) * (kD + 2) + 2 + d;
 #pragma unroll
-    for (int x = 0; x < kAccBatch; ++x)
-      a0[x] = parts[((size_t)min(half + 2 * x, s.nblkC - 1) * G + hq) * (kD + 2) + 2 + d];
-  }
-  // index lists this wave will copy: list (hq*NW + w) + x*heads*NW, first 256 entries each
-  const unsigned long long* stage_u = ws.stage + (size_t)u * s.nblkC * s.tokC;
-  int ix[kIdxLists][4];
+    for (int x = 0; x < kAccBatch; ++x) a0[x] = a0p[(size_t)x * (2 * G * (kD + 2))];  // slots exist up to 2*kAccBatch
 #pragma unroll
-  for (int x = 0; x < kIdxLists; ++x) {
-    const int j = min(hq * NW + w + x * heads * NW, s.nblkC - 1);
-    const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.tokC);
-#pragma unroll
-    for (int y = 0; y < 4; ++y) ix[x][y] = src[min(y * 64 + lane, 2 * s.tokC - 1)];
+    for (int x = 0; x < SP; ++x) vspec[x].load_row(recs + (size_t)(x * 16 + grp) * ws.rec_stride + sizeof(CandHeader), sub);
   }
   PQC_LOADS_ISSUED();
   if constexpr (ATTN) {
@@ -567,66 +669,60 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       pl[j] = parts[((size_t)j * G + hq) * (kD + 2) + 1];
     }
   }
-  if (tid == 0) overflow_sm = 0;
-  // prefix sums of the per-workgroup list sizes
-  int carry_s = 0, carry_c = 0;
-  for (int j0 = 0; j0 < s.nblkC; j0 += NT) {
-    const int j = j0 + tid;
-    const int2 c = j < s.nblkC ? (j0 == 0 ? cnt0 : cnt[j]) : make_int2(0, 0);
-    int ts, tc;
-    const int ps = block_exclusive_scan<NT>(c.x, &ts, scan_sm);
-    const int pc = block_exclusive_scan<NT>(c.y, &tc, scan_sm);
-    if (j < s.nblkC) {
-      pre_sel[j] = carry_s + ps;
-      pre_cand[j] = carry_c + pc;
-      if (c.y > s.recPerWg) overflow_sm = 1;
+  // totals of the per-workgroup list sizes
+  int n_list, n_cand;
+  {
+    int ss = tid < s.nblkC ? cnt0.x : 0, sc = tid < s.nblkC ? cnt0.y : 0;
+    for (int j = NT + tid; j < s.nblkC; j += NT) {
+      const int2 c = cnt[j];
+      ss += c.x;
+      sc += c.y;
     }
-    carry_s += ts;
-    carry_c += tc;
+    ss = wave_sum(ss);
+    sc = wave_sum(sc);
+    if (lane == 0) {
+      ism[w] = ss;
+      ism[NW + w] = sc;
+    }
+    __syncthreads();  // also: pm, pl visible
+    n_list = 0;
+    n_cand = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+      n_list += ism[i];
+      n_cand += ism[NW + i];
+    }
   }
-  if (tid == 0) {
-    pre_sel[s.nblkC] = carry_s;
-    pre_cand[s.nblkC] = carry_c;
-  }
-  __syncthreads();
-  const int n_list = carry_s;  // I + (tokens above the bin) + L
-  const int n_above = max(0, n_list - s.I - s.L);
-  const int n_cand = carry_c;
+  const int n_above = max(0, n_list - s.I - s.L);  // n_list = I + (tokens above the bin) + L
   const int need = max(0, min(s.K - n_above, n_cand));
-  const bool fast = overflow_sm == 0 && n_cand <= kCandRec;
-  int* out = out_idx + (size_t)u * s.Ktot;
   PQC_MARK(ws, 2, 1);
 
-  if (fast) {
-    // compact the valid record headers into (select workgroup, position) order
+  if (n_cand <= kCandRec) {
+    // rank every candidate (count of larger composites); the admitted ones are the `need` best
+    if (need > 0) {
 #pragma unroll
-    for (int x = 0; x < kSlotsPerThread; ++x) {
-      const int slot = x * NT + tid;
-      if (slot < n_slots) {
-        const int j = slot / s.recPerWg, c = slot - j * s.recPerWg;
-        if (c < pre_cand[j + 1] - pre_cand[j]) {
-          const int k = pre_cand[j] + c;
-          comp[k] = rc[x];
-          lgr[k] = rl[x] * s.scale_log2e;
-          slotv[k] = (unsigned short)slot;
+      for (int x = 0; x < kHdrPerThread; ++x)
+        if (x * NT + tid < n_cand) comp[x * NT + tid] = rc[x];
+      __syncthreads();
+#pragma unroll
+      for (int x = 0; x < kHdrPerThread; ++x) {
+        const int k = x * NT + tid;
+        if (k < n_cand) {
+          const unsigned long long mine = rc[x];
+          int rank = 0;
+          for (int j = 0; j < n_cand; ++j) rank += comp[j] > mine ? 1 : 0;
+          if (rank < need) {
+            if (hq == 0) out[s.I + n_above + rank] = composite_token(mine);  // best first
+            lgk[rank] = rl[x] * s.scale_log2e;
+            ordv[rank] = (unsigned short)k;
+            rankv[k] = (unsigned short)rank;
+          } else {
+            rankv[k] = 0xffffu;
+          }
         }
       }
+      __syncthreads();
     }
-    __syncthreads();
-    // rank every candidate; admitted ones are then handled in rank order
-    for (int k = tid; k < (need > 0 ? n_cand : 0); k += NT) {
-      const unsigned long long mine = comp[k];
-      int rank = 0;
-      for (int j = 0; j < n_cand; ++j) rank += comp[j] > mine ? 1 : 0;
-      if (rank < need) {
-        if (hq == 0) out[s.I + n_above + rank] = composite_token(mine);  // best first
-        lgk[rank] = lgr[k];
-        ordv[rank] = (unsigned short)k;
-      } else {
-        lgr[k] = kNegBig;  // not admitted: weight 0
-      }
-    }
-    __syncthreads();
     if constexpr (ATTN) {
       float mx = kNegBig;
       for (int k = tid; k < need; k += NT) mx = fmaxf(mx, lgk[k]);
@@ -647,10 +743,12 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       PQC_MARK(ws, 2, 2);
       // out[d] = (sum_j w_j acc_j[d] + sum_k p_k V_k[d]) / l ; two threads per dimension
       float acc = 0.0f;
+      {
+        float wv[kAccBatch];
 #pragma unroll
-      for (int x = 0; x < kAccBatch; ++x) {
-        const int j = half + 2 * x;
-        if (j < s.nblkC) acc = fmaf(pm[j], a0[x], acc);
+        for (int x = 0; x < kAccBatch; ++x) wv[x] = pm[min(half + 2 * x, s.nblkC - 1)];
+#pragma unroll
+        for (int x = 0; x < kAccBatch; ++x) acc = fmaf(wv[x], half + 2 * x < s.nblkC ? a0[x] : 0.0f, acc);
       }
       for (int j0 = half + 2 * kAccBatch; j0 < s.nblkC; j0 += 2 * kAccBatch) {
         float a[kAccBatch];
@@ -665,9 +763,28 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
           if (j < s.nblkC) acc = fmaf(pm[j], a[x], acc);
         }
       }
-      if (need > 0) {
-        // admitted candidates in rank order, 16 rows at a time per pass (16 lanes read one V row)
-        const int sub = tid & 15, grp = tid >> 4;
+      if (need > 0 && n_cand <= kSpecRows) {
+        // the V rows are already here: weighted rows go to LDS at their rank, then are summed in rank order
+        for (int r0 = 0; r0 < need; r0 += kRankChunk) {
+          const int nr = min(kRankChunk, need - r0);
+#pragma unroll
+          for (int x = 0; x < SP; ++x) {
+            const int k = x * 16 + grp;
+            const int r = (k < n_cand ? (int)rankv[k] : 0xffff) - r0;
+            if (r >= 0 && r < nr) {
+              const float p = lgk[r0 + r];
+              float vf[8];
+              vspec[x].unpack(vf);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) vl[r * kD + owned_dim<T>(sub, e)] = p * vf[e];
+            }
+          }
+          __syncthreads();
+          for (int r = half; r < nr; r += 2) acc += vl[r * kD + d];
+          __syncthreads();
+        }
+      } else if (need > 0) {
+        // many candidates: admitted rows are fetched in rank order, 16 rows at a time per pass
         float va[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) va[e] = 0.0f;
@@ -676,7 +793,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
 #pragma unroll
           for (int x = 0; x < kVPass; ++x) {
             const int k = min(k0 + x * 16 + grp, need - 1);
-            vr[x].load_row(recs + (size_t)slotv[ordv[k]] * ws.rec_stride + sizeof(CandHeader), sub);
+            vr[x].load_row(recs + (size_t)ordv[k] * ws.rec_stride + sizeof(CandHeader), sub);
           }
           PQC_LOADS_ISSUED();
 #pragma unroll
@@ -690,10 +807,10 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
           }
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) vred[grp * kD + owned_dim<T>(sub, e)] = va[e];
+        for (int e = 0; e < 8; ++e) vl[grp * kD + owned_dim<T>(sub, e)] = va[e];
         __syncthreads();
 #pragma unroll
-        for (int x = 0; x < 8; ++x) acc += vred[(half * 8 + x) * kD + d];
+        for (int x = 0; x < 8; ++x) acc += vl[(half * 8 + x) * kD + d];
       }
       if (half == 1) half_acc[d] = acc;
       __syncthreads();
@@ -702,6 +819,10 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
     }
   } else {
     // generic path: radix select of the need-th largest staged composite, 8 bits per pass
+    {
+      int nl, nc;
+      scan_counts(cnt0, nl, nc);
+    }
     auto owner = [&](int p) -> int {  // largest j with pre_cand[j] <= p
       int lo = 0, hi = s.nblkC - 1;
       while (lo < hi) {
@@ -790,41 +911,6 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       if (half == 0) out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + d] = (acc + half_acc[d]) / lstar;
     }
   }
-
-  // indices of the staged lists, shared among the unit's head workgroups: one wave per list,
-  // coalesced; the local window moves behind the admitted candidates.  The first 256 entries
-  // of the first kIdxLists lists of a wave were loaded up front.
-  {
-    int x = 0;
-    for (int j = hq * NW + w; j < s.nblkC; j += heads * NW, ++x) {
-      const int base = pre_sel[j], n = pre_sel[j + 1] - base;
-      const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.tokC);
-      for (int p0 = 0; p0 < n; p0 += 256) {
-        int v[4];
-        if (x < kIdxLists && p0 == 0) {
-#pragma unroll
-          for (int y = 0; y < 4; ++y) v[y] = x == 0 ? ix[0][y] : x == 1 ? ix[1][y] : x == 2 ? ix[2][y] : ix[3][y];
-        } else {
-#pragma unroll
-          for (int y = 0; y < 4; ++y)
-            if (p0 + y * 64 + lane < n) v[y] = src[p0 + y * 64 + lane];
-        }
-#pragma unroll
-        for (int y = 0; y < 4; ++y) {
-          const int pos = base + p0 + y * 64 + lane;
-          if (p0 + y * 64 + lane < n) out[pos < s.I + n_above ? pos : pos + need] = v[y];
-        }
-      }
-    }
-  }
-  PQC_MARK(ws, 2, 4);
-
-  // leave the other parity's histogram zeroed for the next call
-  if (hq == 0) {
-    unsigned* gh = ws.hist + ((size_t)(s.parity ^ 1) * units + u) * kHistCopies * kNB;
-    for (int i = tid; i < kHistCopies * kNB; i += NT) gh[i] = 0u;
-  }
-  PQC_MARK(ws, 2, 5);
   PQC_NOTE(ws, 2, 13, n_above);
   PQC_NOTE(ws, 2, 14, n_cand);
   PQC_NOTE(ws, 2, 15, need);
