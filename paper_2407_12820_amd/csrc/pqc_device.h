@@ -7,6 +7,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace pqc {
 
@@ -113,32 +114,31 @@ __device__ __forceinline__ int composite_token(unsigned long long c) {
   return (int)(0xffffffffu - (unsigned)(c & 0xffffffffull));
 }
 
-// Monotone map score -> bin.  Three linear pieces: kTailBins coarse bins below c0,
-// kFineBins fine bins over [c0, c1], kTailBins coarse bins above c1.  The piece is
-// chosen by exact comparisons and each piece is clamped to its own bin range, so the
-// map is non-decreasing in s whatever the parameters are (inside a piece: subtraction,
+// Monotone map score -> bin.  Bin 0 takes every score below c0, kFineBins fine bins
+// cover [c0, c1], kHighBins coarse bins lie above c1.  The piece is chosen by exact
+// comparisons and each piece is clamped to its own bin range, so the map is
+// non-decreasing in s whatever the parameters are (inside a piece: subtraction,
 // multiplication by a non-negative constant and truncation all preserve order).  Only
 // the number of boundary-bin candidates depends on how well [c0, c1] brackets the K-th
-// largest score; the selection itself never does.
-constexpr int kTailBins = 256;
-constexpr int kFineBins = kNB - 2 * kTailBins;
+// largest score; the selection itself never does.  (Should the K-th largest score lie
+// below c0, every token of bin 0 becomes a candidate: slow, still exact.)
+constexpr int kHighBins = 256;
+constexpr int kFineBins = kNB - 1 - kHighBins;
 struct BinParams {
-  float lo, c0, c1, inv_lo, inv_c, inv_hi, hi, pad;
+  float lo, c0, c1, inv_c, inv_hi, hi, pad0, pad1;
 };
-// The layout as six scalars held in registers (selecting among the fields of a struct in
-// memory makes the compiler index it like an array, which lands it in scratch or LDS).
-struct Bins {
-  float lo, c0, c1, inv_lo, inv_c, inv_hi;
-};
-__device__ __forceinline__ int score_bin(float s, float lo, float c0, float c1, float inv_lo, float inv_c, float inv_hi) {
-  const int b_lo = min(kTailBins - 1, __float2int_rz((s - lo) * inv_lo));
-  const int b_c = kTailBins + min(kFineBins - 1, __float2int_rz((s - c0) * inv_c));
-  const int b_hi = kTailBins + kFineBins + min(kTailBins - 1, __float2int_rz((s - c1) * inv_hi));
-  int b = s < c0 ? b_lo : b_c;
-  b = s > c1 ? b_hi : b;
-  return max(0, b);
+// The layout travels as scalars held in registers (selecting among the fields of a struct
+// in memory makes the compiler index it like an array, which lands it in scratch or LDS).
+__device__ __forceinline__ int fine_index(float s, float c0, float inv_c) {
+  return min(kFineBins - 1, __float2int_rz((s - c0) * inv_c));
 }
-#define PQC_BIN(s, bp) score_bin((s), (bp).lo, (bp).c0, (bp).c1, (bp).inv_lo, (bp).inv_c, (bp).inv_hi)
+__device__ __forceinline__ int score_bin(float s, float c0, float c1, float inv_c, float inv_hi) {
+  const int b_c = 1 + fine_index(s, c0, inv_c);
+  const int b_hi = 1 + kFineBins + min(kHighBins - 1, __float2int_rz((s - c1) * inv_hi));
+  int b = s < c0 ? 0 : b_c;
+  b = s > c1 ? b_hi : b;
+  return b;
+}
 // Bin layout from bounds lo <= score <= hi and a window [q_lo, q_hi] expected to hold
 // the K-th largest score.
 __device__ __forceinline__ BinParams make_bins(float lo, float hi, float q_lo, float q_hi) {
@@ -151,11 +151,11 @@ __device__ __forceinline__ BinParams make_bins(float lo, float hi, float q_lo, f
     bp.c0 = lo;
     bp.c1 = hi;
   }
-  const float wl = bp.c0 - lo, wc = bp.c1 - bp.c0, wh = hi - bp.c1;
-  bp.inv_lo = (wl > 1e-30f && wl < 3e38f) ? (float)kTailBins / wl : 0.0f;
+  const float wc = bp.c1 - bp.c0, wh = hi - bp.c1;
   bp.inv_c = (wc > 1e-30f && wc < 3e38f) ? (float)kFineBins / wc : 0.0f;
-  bp.inv_hi = (wh > 1e-30f && wh < 3e38f) ? (float)kTailBins / wh : 0.0f;
-  bp.pad = 0.0f;
+  bp.inv_hi = (wh > 1e-30f && wh < 3e38f) ? (float)kHighBins / wh : 0.0f;
+  bp.pad0 = 0.0f;
+  bp.pad1 = 0.0f;
   return bp;
 }
 
@@ -251,11 +251,11 @@ __device__ __forceinline__ float load_as_float<bf16_t>(const bf16_t* p, int i) {
 // Centroids travel global -> registers (coalesced, all loads in flight at once) -> a
 // padded LDS tile of kLutTileFloats floats -> one thread per table entry runs the chain.
 constexpr int kLutTileFloats = 8192;
-template <typename T, int NT, int M>
+template <typename T, int NT, int M, class MarkFn>
 __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] of this unit */,
                                                const float* __restrict__ cent /* [M][C][Dm] */, int G, int C,
                                                float* lut, float* qs, float* red /* [4*8] */,
-                                               float* tile /* [kLutTileFloats + kLutTileFloats/Dm] */) {
+                                               float* tile /* [kLutTileFloats + kLutTileFloats/Dm] */, MarkFn mark) {
   constexpr int Dm = kD / M;
   constexpr int VPG = kLutTileFloats / (4 * NT);      // float4 per thread per tile
   constexpr int NG = (256 * kD) / kLutTileFloats;      // tiles at the largest C
@@ -288,6 +288,7 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
     }
     if (tid < kD) qs[tid] = a;
   }
+  mark(8);
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
     if (g * kLutTileFloats < total) {  // uniform
@@ -321,9 +322,11 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
         for (int x = 0; x < Dm; ++x) p = __fmaf_rn(qj[x], cr[x], p);
         lut[j * kLutRow + c] = p;
       }
+      mark(9 + g);
     }
   }
   __syncthreads();
+  mark(13);
   // per table: min and max (one wave per table)
   const int lane = tid & 63, w = tid >> 6;
   for (int j = w; j < M; j += NT / 64) {

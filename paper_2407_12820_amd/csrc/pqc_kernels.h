@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256) void lut_kernel(Shape s, const T* __restrict__
   __shared__ float tile[kLutTileFloats + kLutTileFloats / (kD / M)];
   const int u = blockIdx.y, b = u / s.Hkv, g = u % s.Hkv;
   build_lut<T, 256, M>(q + ((size_t)b * s.Hq + (size_t)g * s.G) * kD, cent + (size_t)u * M * s.C * (kD / M), s.G, s.C, lut,
-                       qs, red, tile);
+                       qs, red, tile, [](int) {});
   for (int e = threadIdx.x; e < M * s.C; e += 256) table[(size_t)u * M * s.C + e] = lut[(e / s.C) * kLutRow + (e % s.C)];
 }
 
@@ -194,12 +194,27 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   __shared__ float tile[SRC::kFromCodes ? kLutTileFloats + kLutTileFloats / (kD / LM) : 1];
   __shared__ unsigned hist[kNB];
   __shared__ int scan_sm[2 * (NT / 64) + 1 + 2];
-  const int u = blockIdx.y, tid = threadIdx.x, units = s.B * s.Hkv;
+  const int tid = threadIdx.x, units = s.B * s.Hkv;
+  // Workgroups are handed to the 8 XCDs round-robin in launch order (x fastest).  The
+  // workgroups of a unit all read that unit's centroids, so eight units at a time are
+  // interleaved: the workgroups of one unit then share an XCD and its L2.
+  int u = blockIdx.y, bx = blockIdx.x;
+  {
+    const int nx = gridDim.x, lin = blockIdx.y * nx + blockIdx.x;
+    if (lin < (units & ~7) * nx) {
+      const int i = lin % (8 * nx);
+      u = (lin / (8 * nx)) * 8 + (i & 7);
+      bx = i >> 3;
+    }
+  }
   PQC_MARK(ws, 0, 0);
+#ifdef PQC_TRACE
+  PQC_NOTE(ws, 0, 15, (__builtin_amdgcn_s_getreg(20 | (3 << 11)) & 15) | (u << 8));  // XCC_ID[3:0], unit
+#endif
   SRC src;
   src.init(src_ptr, u, s.N, units, lut);
   // this workgroup's chunks and this thread's sample: issue the loads before anything else
-  const int chunks = s.tokA / P, chunk0 = blockIdx.x * chunks;
+  const int chunks = s.tokA / P, chunk0 = bx * chunks;
   typename SRC::Raw raw[kMaxVecA];
 #pragma unroll
   for (int v = 0; v < kMaxVecA; ++v) raw[v] = src.load(chunk0 + min(v * NT + tid, chunks - 1));
@@ -213,8 +228,8 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   if constexpr (SRC::kFromCodes) {
     const int b = u / s.Hkv, g = u % s.Hkv;
     bounds = build_lut<T, NT, LM>(q + ((size_t)b * s.Hq + (size_t)g * s.G) * kD, cent + (size_t)u * LM * s.C * (kD / LM), s.G,
-                                  s.C, lut, qs, red, tile);
-    if (blockIdx.x == 0)
+                                  s.C, lut, qs, red, tile, [&](int slot) { PQC_MARK(ws, 0, slot); });
+    if (bx == 0)
       for (int e = tid; e < LM * s.C; e += NT) ws.lut[(size_t)u * LM * s.C + e] = lut[(e / s.C) * kLutRow + (e % s.C)];
   } else {
     bounds = ws.range[u];
@@ -225,9 +240,12 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   for (int v = 0; v < kMaxVecA; ++v) src.fix_tail(raw[v], chunk0 + min(v * NT + tid, chunks - 1));
   const BinParams bp =
       sample_window<NT>(bounds.x, bounds.y, src.score_one(sample), have_sample, s.rankHi, s.rankLo, hist, scan_sm);
-  if (blockIdx.x == 0 && tid == 0) ws.ctl[u] = bp;
-  const float b_lo = bp.lo, b_c0 = bp.c0, b_c1 = bp.c1, b_ilo = bp.inv_lo, b_ic = bp.inv_c, b_ihi = bp.inv_hi;
+  if (bx == 0 && tid == 0) ws.ctl[u] = bp;
+  const float b_c0 = bp.c0, b_c1 = bp.c1, b_ic = bp.inv_c, b_ihi = bp.inv_hi;
   PQC_MARK(ws, 0, 2);
+  // most tokens score below the window: they are counted in a register (bin 0), the rest
+  // go to their LDS bin (an LDS atomic costs in proportion to the lanes that take part)
+  int n_low = 0;
 #pragma unroll
   for (int v = 0; v < kMaxVecA; ++v) {
     if (v * NT + tid < chunks) {
@@ -235,13 +253,18 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
 #pragma unroll
       for (int i = 0; i < P; ++i) {
         const int t = t0 + i;
-        if (t >= s.I && t < s.N - s.L) atomicAdd(&hist[score_bin(src.score(raw[v], i), b_lo, b_c0, b_c1, b_ilo, b_ic, b_ihi)], 1u);
+        const float sc = src.score(raw[v], i);
+        const bool mid = t >= s.I && t < s.N - s.L;
+        if (mid && !(sc < b_c0)) atomicAdd(&hist[score_bin(sc, b_c0, b_c1, b_ic, b_ihi)], 1u);
+        n_low += (mid && sc < b_c0) ? 1 : 0;
       }
     }
   }
+  n_low = wave_last(wave_inclusive_scan(n_low));
+  if ((tid & 63) == 0 && n_low) atomicAdd(&hist[0], (unsigned)n_low);
   __syncthreads();
   PQC_MARK(ws, 0, 3);
-  unsigned* gh = ws.hist + (((size_t)s.parity * units + u) * kHistCopies + (blockIdx.x % kHistCopies)) * kNB;
+  unsigned* gh = ws.hist + (((size_t)s.parity * units + u) * kHistCopies + (bx % kHistCopies)) * kNB;
   for (int i = tid; i < kNB; i += NT)
     if (hist[i]) atomicAdd(&gh[i], hist[i]);
   PQC_MARK(ws, 0, 4);
@@ -295,7 +318,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   ts.load(ws.hist + ((size_t)s.parity * units + u) * kHistCopies * kNB);
   const float4 bpa = reinterpret_cast<const float4*>(ws.ctl + u)[0], bpb = reinterpret_cast<const float4*>(ws.ctl + u)[1];
   PQC_LOADS_ISSUED();
-  const float b_lo = bpa.x, b_c0 = bpa.y, b_c1 = bpa.z, b_ilo = bpa.w, b_ic = bpb.x, b_ihi = bpb.y;
+  const float b_c0 = bpa.y, b_c1 = bpa.z, b_ic = bpa.w, b_ihi = bpb.x;
   if constexpr (SRC::kFromCodes) {
 #pragma unroll
     for (int x = 0; x < LUTV; ++x) {
@@ -317,41 +340,58 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   const int segN = s.tokC / NW;
   int* seg = list + w * segN;
   int nsel = 0, ncand = 0;
+  // A token is selected when its bin lies above the threshold bin and is a candidate when
+  // it falls into it.  With the threshold inside the fine window (the usual case) both
+  // follow from the fine index alone; the decisions are the same as comparing score_bin().
+  auto classify = [&](auto fine_case) {
+    constexpr bool kFine = decltype(fine_case)::value;
+    const int kb = th.bstar - 1;  // fine index of the threshold bin
 #pragma unroll
-  for (int v = 0; v < kMaxVecC; ++v) {
-    if (v * 64 < cpw) {  // wave-uniform
-      const bool live = v * 64 + lane < cpw;
-      const int t0 = (chunk0 + v * 64 + lane) * P - src.lead;
-      unsigned selm = 0u, candm = 0u;
-      if (live) {
+    for (int v = 0; v < kMaxVecC; ++v) {
+      if (v * 64 < cpw) {  // wave-uniform
+        const bool live = v * 64 + lane < cpw;
+        const int t0 = (chunk0 + v * 64 + lane) * P - src.lead;
+        unsigned selm = 0u, candm = 0u;
+        if (live) {
 #pragma unroll
-        for (int i = 0; i < P; ++i) {
-          const int t = t0 + i;
-          if (t >= 0 && t < s.N) {
-            if (t < s.I || t >= s.N - s.L) {
-              selm |= 1u << i;
+          for (int i = 0; i < P; ++i) {
+            const int t = t0 + i;
+            const float sc = src.score(raw[v], i);
+            bool sel, cand;
+            if constexpr (kFine) {
+              const int k = fine_index(sc, b_c0, b_ic);
+              const bool inw = !(sc < b_c0) && !(sc > b_c1);
+              sel = sc > b_c1 || (inw && k > kb);
+              cand = inw && k == kb;
             } else {
-              const int bin = score_bin(src.score(raw[v], i), b_lo, b_c0, b_c1, b_ilo, b_ic, b_ihi);
-              selm |= (bin > th.bstar ? 1u : 0u) << i;
-              candm |= (bin == th.bstar ? 1u : 0u) << i;
+              const int bin = score_bin(sc, b_c0, b_c1, b_ic, b_ihi);
+              sel = bin > th.bstar;
+              cand = bin == th.bstar;
             }
+            const bool window = t < s.I || t >= s.N - s.L;
+            const bool real = t >= 0 && t < s.N;
+            selm |= ((real && (window || sel)) ? 1u : 0u) << i;
+            candm |= ((real && !window && cand) ? 1u : 0u) << i;
           }
         }
-      }
-      PQC_MARK(ws, 1, 7);
-      const int cnt = __popc(selm) | (__popc(candm) << 16);
-      const int inc = wave_inclusive_scan(cnt);
-      const int tot = wave_last(inc);
-      int ps = nsel + ((inc - cnt) & 0xffff), pc = ncand + ((inc - cnt) >> 16);
+        const int cnt = __popc(selm) | (__popc(candm) << 16);
+        const int inc = wave_inclusive_scan(cnt);
+        const int tot = wave_last(inc);
+        int ps = nsel + ((inc - cnt) & 0xffff), pc = ncand + ((inc - cnt) >> 16);
 #pragma unroll
-      for (int i = 0; i < P; ++i) {
-        if (selm & (1u << i)) seg[ps++] = t0 + i;
-        if (candm & (1u << i)) seg[segN - 1 - (pc++)] = t0 + i;
+        for (int i = 0; i < P; ++i) {
+          if (selm & (1u << i)) seg[ps++] = t0 + i;
+          if (candm & (1u << i)) seg[segN - 1 - (pc++)] = t0 + i;
+        }
+        nsel += tot & 0xffff;
+        ncand += tot >> 16;
       }
-      nsel += tot & 0xffff;
-      ncand += tot >> 16;
     }
-  }
+  };
+  if (th.bstar >= 1 && th.bstar <= kFineBins)  // workgroup-uniform
+    classify(std::true_type{});
+  else
+    classify(std::false_type{});
   PQC_MARK(ws, 1, 8);
   if (lane == 0) {
     wcnt[w] = nsel;
