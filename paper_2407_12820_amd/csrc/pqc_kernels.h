@@ -675,13 +675,12 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
   const int sub = tid & 15, grp = tid >> 4;       // 16 lanes per candidate V row
   // ---- everything whose address is known up front is requested first
   const unsigned char* recs = ws.cand_rec + (size_t)u * kCandRec * ws.rec_stride;
-  unsigned long long rc[kHdrPerThread];
+  unsigned long long rc[kHdrPerThread];  // record x*NT + tid; the first NT are requested up front
   float rl[kHdrPerThread];
-#pragma unroll
-  for (int x = 0; x < kHdrPerThread; ++x) {
-    const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)(x * NT + tid) * ws.rec_stride);
-    rc[x] = hd->composite;
-    rl[x] = ATTN ? hd->logit[hq] : 0.0f;
+  {
+    const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)tid * ws.rec_stride);
+    rc[0] = hd->composite;
+    rl[0] = ATTN ? hd->logit[hq] : 0.0f;
   }
   const float* parts = ws.partials + (size_t)u * s.npart * G * (kD + 2);
   const int jc = min(tid, s.nblkC - 1);
@@ -740,6 +739,16 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
   if (n_cand <= kCandRec) {
     // rank every candidate (count of larger composites); the admitted ones are the `need` best
     if (need > 0) {
+#pragma unroll
+      for (int x = 1; x < kHdrPerThread; ++x) {
+        rc[x] = 0ull;
+        rl[x] = 0.0f;
+        if (x * NT + tid < n_cand) {  // rare: more than NT candidates
+          const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)(x * NT + tid) * ws.rec_stride);
+          rc[x] = hd->composite;
+          rl[x] = ATTN ? hd->logit[hq] : 0.0f;
+        }
+      }
 #pragma unroll
       for (int x = 0; x < kHdrPerThread; ++x)
         if (x * NT + tid < n_cand) comp[x * NT + tid] = rc[x];
