@@ -20,7 +20,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
   Shape s;
-  size_t off_ctl, off_lut, off_range, off_hist, off_crec, off_stage, off_cnt, off_part, off_trace, total;
+  size_t off_ctl, off_lut, off_range, off_hist, off_bins, off_crec, off_stage, off_cnt, off_part, off_trace, total;
   int rec_stride;
 };
 
@@ -71,11 +71,12 @@ int make_plan(const pqc_config* c, Plan* p) {
   // select kernel: 256-thread workgroups, two resident per compute unit
   int tokC = env_int("PQC_TOK_C", 0);
   if (!tokC) {
-    tokC = 1024;
-    while (tokC < 4096 && units * ((s.N + lead + tokC - 1) / tokC) > 512) tokC *= 2;
+    tokC = 512;
+    while (tokC < 8192 && units * ((s.N + tokC - 1) / tokC) > 512) tokC *= 2;
   }
-  if (tokC % 256 || tokC > 4096) return PQC_EINVAL;
-  s.tokC = tokC; s.nblkC = (s.N + lead + tokC - 1) / tokC;
+  if (tokC != 512 && tokC != 1024 && tokC != 2048 && tokC != 4096 && tokC != 8192) return PQC_EINVAL;
+  s.tokC = tokC; s.nblkC = (s.N + tokC - 1) / tokC;
+  s.binStride = s.nblkC * s.tokC;
   s.rowsP = env_int("PQC_ROWS_P", 256);
   s.nblkP = (s.Ktot + s.rowsP - 1) / s.rowsP;
   s.npart = s.nblkC > s.nblkP ? s.nblkC : s.nblkP;
@@ -99,6 +100,7 @@ int make_plan(const pqc_config* c, Plan* p) {
   p->off_lut = off;   off = align_up(off + sizeof(float) * units * s.M * s.C);
   p->off_range = off; off = align_up(off + sizeof(float2) * units);
   p->off_hist = off;  off = align_up(off + sizeof(unsigned) * 2 * units * (kHistCopies * kNB + 1));  // + record counters
+  p->off_bins = off;  off = align_up(off + sizeof(unsigned short) * units * s.binStride);
   p->off_crec = off;  off = align_up(off + (size_t)p->rec_stride * kCandRec * units);
   p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * s.nblkC * s.tokC);
   p->off_cnt = off;   off = align_up(off + sizeof(int2) * units * s.nblkC);
@@ -160,7 +162,7 @@ void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uin
   hipLaunchKernelGGL((hist_kernel<T, CodeChunks<M>>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, qt, cent,
                      static_cast<const void*>(codes));
   if (ev) (void)hipEventRecord(ev[1], st);
-  hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(int), st,
+  hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(unsigned short), st,
                      s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));
   if (ev) (void)hipEventRecord(ev[2], st);
   hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
@@ -277,6 +279,7 @@ int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t wor
   ctx->ws.hist = reinterpret_cast<unsigned*>(base + p.off_hist);
   ctx->ws.cand_count = ctx->ws.hist + (size_t)2 * p.s.B * p.s.Hkv * kHistCopies * kNB;
   ctx->ws.range = reinterpret_cast<float2*>(base + p.off_range);
+  ctx->ws.bins = reinterpret_cast<unsigned short*>(base + p.off_bins);
   ctx->ws.cand_rec = reinterpret_cast<unsigned char*>(base + p.off_crec);
   ctx->ws.rec_stride = p.rec_stride;
   ctx->ws.stage = reinterpret_cast<unsigned long long*>(base + p.off_stage);
@@ -389,7 +392,7 @@ int pqc_topk(pqc_ctx* ctx, const float* scores, int32_t* out_idx, void* stream) 
   hipLaunchKernelGGL(score_range_kernel, dim3(1, units), dim3(1024), 0, st, s, scores, ctx->ws.range);
   hipLaunchKernelGGL((hist_kernel<float, ScoreChunks>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, nof, nof,
                      static_cast<const void*>(scores));
-  hipLaunchKernelGGL((select_kernel<float, 1, ScoreChunks, false>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(int), st,
+  hipLaunchKernelGGL((select_kernel<float, 1, ScoreChunks, false>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(unsigned short), st,
                      s, ctx->ws, nof, nof, nof, static_cast<const void*>(scores));
   hipLaunchKernelGGL((finalize_kernel<float, 1, false>), dim3(1 + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
                      ctx->ws, nof, nof, nof, out_idx, static_cast<float*>(nullptr));

@@ -34,6 +34,7 @@ struct Shape {
   int rowsP, nblkP; // list-attention kernel: rows per workgroup, workgroups per unit
   int npart;        // partial slots per unit
   int parity;       // which of the two histogram sets this call uses
+  int binStride;    // stored bins per unit (nblkC * tokC)
   int sampleN;      // tokens sampled per unit to place the fine bins (<= 1024)
   int rankHi, rankLo;  // sample ranks (from the top) that bracket the K-th largest score
   float scale_log2e;
@@ -55,6 +56,7 @@ struct Workspace {
   float2* range;               // [units]                       (min, max) score, stand-alone top-k only
   unsigned* hist;              // [2][units][kHistCopies][kNB]   zero between uses
   unsigned* cand_count;        // [2][units]   records handed out so far (directly behind hist, zeroed with it)
+  unsigned short* bins;        // [units][binStride]  per token: bin + 1, or kBinWindow inside the two windows
   unsigned char* cand_rec;     // [units][kCandRec] records of rec_stride bytes, in order of arrival
   unsigned long long* stage;   // [units][nblkC][tokC] selected ids (front, int32) / candidate composites (back, u64)
   int2* stage_cnt;             // [units][nblkC]     (selected, candidates)
@@ -123,6 +125,7 @@ __device__ __forceinline__ int composite_token(unsigned long long c) {
 // largest score; the selection itself never does.  (Should the K-th largest score lie
 // below c0, every token of bin 0 becomes a candidate: slow, still exact.)
 constexpr int kHighBins = 256;
+constexpr unsigned kBinWindow = 0xffffu;  // stored bin of a window token: above every threshold
 constexpr int kFineBins = kNB - 1 - kHighBins;
 struct BinParams {
   float lo, c0, c1, inv_c, inv_hi, hi, pad0, pad1;
@@ -746,9 +749,9 @@ __device__ __forceinline__ void combine_waves(const float* red, int h, int d, fl
 // a transposed read land in different banks).  P is split into two bf16 terms
 // (p = hi + lo, error 2^-17) because one bf16 term alone would cost 2^-9 of the result.
 //
-// Softmax: a wave first computes the logits of a chunk of up to kMfmaTiles tiles,
+// Softmax: a wave first computes the logits of a stage of up to kMfmaTiles tiles,
 // takes its maximum per head, rescales O once if the maximum grew, then accumulates.
-constexpr int kMfmaTiles = 4;          // tiles (of 16 rows) per chunk and wave
+constexpr int kMfmaTiles = 2;          // tiles (of 16 rows) per stage and wave
 constexpr int kVTileStride = 264;      // bytes per V row in the LDS transpose tile
 constexpr int kVTileBytes = 16 * kVTileStride;
 
@@ -779,115 +782,156 @@ __device__ __forceinline__ unsigned bf16_round_bits(float f) {  // round to near
   return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
+// One stage = kMfmaTiles tiles.  Two stages are kept in registers: while one is being
+// consumed the loads of the next are in flight, so a wave never sits without outstanding
+// memory requests until its rows run out.  Loads are unconditional (positions past the
+// end of the list re-read its last row, which the caches hold); masking happens on the
+// logits.
+struct MfmaStage {
+  uint4 kr[kMfmaTiles][4], vr[kMfmaTiles][4];
+};
+
+template <class ListFn>
+__device__ __forceinline__ void mfma_issue(const bf16_t* __restrict__ kbase, const bf16_t* __restrict__ vbase, int N,
+                                           ListFn list, int count, int base, MfmaStage& g) {
+  const int lane = threadIdx.x & 63, col = lane & 15, quad = lane >> 4;
+#pragma unroll
+  for (int tl = 0; tl < kMfmaTiles; ++tl) {
+    int t = list(min(base + tl * 16 + col, count - 1));
+    t = max(0, min(N - 1, t));
+    const uint4* kp = reinterpret_cast<const uint4*>(kbase + (size_t)t * kD + 8 * quad);
+    const uint4* vp = reinterpret_cast<const uint4*>(vbase + (size_t)t * kD + 8 * quad);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      g.kr[tl][kk] = kp[4 * kk];  // dims 32*kk + 8*quad .. +7
+      g.vr[tl][kk] = vp[4 * kk];
+    }
+  }
+}
+
+__device__ __forceinline__ void mfma_consume(const MfmaStage& g, int count, int base, float scale_log2e,
+                                             const bf16x8_t (&qf)[4], unsigned char* vt, MfmaState& st) {
+  const int lane = threadIdx.x & 63, col = lane & 15, quad = lane >> 4;
+#ifdef PQC_EXP_NO_COMPUTE
+  {
+    unsigned x = 0;
+#pragma unroll
+    for (int tl = 0; tl < kMfmaTiles; ++tl)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) x += g.kr[tl][kk].x ^ g.kr[tl][kk].w ^ g.vr[tl][kk].y ^ g.vr[tl][kk].z;
+    st.l += __uint_as_float(x & 0xff);
+    st.m = 0.0f;
+    return;
+  }
+#endif
+  // logits of the stage
+  f32x4_t s[kMfmaTiles];
+  float mx = kNegBig;
+#pragma unroll
+  for (int tl = 0; tl < kMfmaTiles; ++tl) {
+    s[tl] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    if (base + tl * 16 < count) {  // wave-uniform
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        bf16x8_t a;
+        __builtin_memcpy(&a, &g.kr[tl][kk], 16);
+        s[tl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[kk], s[tl], 0, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool ok = base + tl * 16 + 4 * quad + i < count;
+        s[tl][i] = ok ? s[tl][i] * scale_log2e : kNegBig;
+        mx = fmaxf(mx, s[tl][i]);
+      }
+    }
+  }
+  // the stage's maximum per head (over the four quads: row_ror 16 and 32 of the wave), and the
+  // one-off rescale of O
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float mnew = fmaxf(st.m, mx);
+  const float corr = __builtin_amdgcn_exp2f(st.m - mnew);
+  st.l *= corr;
+  st.m = mnew;
+  if (__any(corr != 1.0f)) {
+    float cr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) cr[i] = __shfl(corr, 4 * quad + i);  // corr of head 4*quad+i lives in lane col == that head
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) st.o[j][i] *= cr[i];
+  }
+  // accumulate
+#pragma unroll
+  for (int tl = 0; tl < kMfmaTiles; ++tl) {
+    if (base + tl * 16 < count) {
+      // V tile -> LDS, row `col`, bytes 64*kk + 16*quad (two 8-byte stores: rows are 8-byte aligned)
+      unsigned char* vrow = vt + col * kVTileStride + 16 * quad;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        *reinterpret_cast<uint2*>(vrow + 64 * kk) = make_uint2(g.vr[tl][kk].x, g.vr[tl][kk].y);
+        *reinterpret_cast<uint2*>(vrow + 64 * kk + 8) = make_uint2(g.vr[tl][kk].z, g.vr[tl][kk].w);
+      }
+      // P = exp2(S - m), as hi + lo bf16 terms (masked rows hold kNegBig: P = 0)
+      unsigned hi[4], lo[4];
+      float psum = 0.0f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float p = __builtin_amdgcn_exp2f(s[tl][i] - mnew);
+        psum += p;
+        hi[i] = bf16_round_bits(p);
+        lo[i] = bf16_round_bits(p - __uint_as_float(hi[i] << 16));
+      }
+      st.l += psum;
+      s16x4_t pa_hi, pa_lo;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        pa_hi[i] = (short)hi[i];
+        pa_lo[i] = (short)lo[i];
+      }
+      // the wave's LDS stores must land before its lanes read each other's rows
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      const unsigned short* vt16 = reinterpret_cast<const unsigned short*>(vt);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        s16x4_t vb;  // B[k = token 4*quad+e][n = dim 16*j + col]
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vb[e] = (short)vt16[(4 * quad + e) * (kVTileStride / 2) + 16 * j + col];
+        st.o[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa_hi, vb, st.o[j], 0, 0, 0);
+        st.o[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa_lo, vb, st.o[j], 0, 0, 0);
+      }
+      // tile fully read before the next tile overwrites it
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+  }
+}
+
+// Rows list(first), list(first+1), ... in stages of 16*kMfmaTiles positions, `stride` apart.
 template <class ListFn>
 __device__ __forceinline__ void mfma_attend(const bf16_t* __restrict__ kbase, const bf16_t* __restrict__ vbase, int N,
                                             ListFn list, int count, int first, int stride, float scale_log2e,
                                             const bf16x8_t (&qf)[4], unsigned char* vt /* wave-private LDS [kVTileBytes] */,
                                             MfmaState& st) {
-  const int lane = threadIdx.x & 63, col = lane & 15, quad = lane >> 4;
-  // chunk = kMfmaTiles tiles of 16 consecutive list positions, starting at `base`
-  for (int base = first; base < count; base += stride) {
-    uint4 kr[kMfmaTiles][4], vr[kMfmaTiles][4];
-#pragma unroll
-    for (int tl = 0; tl < kMfmaTiles; ++tl) {
-      const int p = base + tl * 16 + col;
-      if (base + tl * 16 < count) {  // wave-uniform
-        int t = list(min(p, count - 1));
-        t = max(0, min(N - 1, t));
-        const uint4* kp = reinterpret_cast<const uint4*>(kbase + (size_t)t * kD + 8 * quad);
-        const uint4* vp = reinterpret_cast<const uint4*>(vbase + (size_t)t * kD + 8 * quad);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          kr[tl][kk] = kp[4 * kk];  // dims 32*kk + 8*quad .. +7
-          vr[tl][kk] = vp[4 * kk];
-        }
-      }
-    }
+  if (first >= count) return;  // wave-uniform
+  MfmaStage ga, gb;
+  int base = first;
+  mfma_issue(kbase, vbase, N, list, count, base, ga);
+  for (;;) {
+    mfma_issue(kbase, vbase, N, list, count, base + stride, gb);
     PQC_LOADS_ISSUED();
-    // logits of the chunk
-    f32x4_t s[kMfmaTiles];
-    float mx = kNegBig;
-#pragma unroll
-    for (int tl = 0; tl < kMfmaTiles; ++tl) {
-      s[tl] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-      if (base + tl * 16 < count) {
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          bf16x8_t a;
-          __builtin_memcpy(&a, &kr[tl][kk], 16);
-          s[tl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[kk], s[tl], 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const bool ok = base + tl * 16 + 4 * quad + i < count;
-          s[tl][i] = ok ? s[tl][i] * scale_log2e : kNegBig;
-          mx = fmaxf(mx, s[tl][i]);
-        }
-      }
-    }
-    // the chunk's maximum per head (over the four quads), and the one-off rescale of O
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float mnew = fmaxf(st.m, mx);
-    const float corr = __builtin_amdgcn_exp2f(st.m - mnew);
-    st.l *= corr;
-    st.m = mnew;
-    if (__any(corr != 1.0f)) {
-      float cr[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) cr[i] = __shfl(corr, 4 * quad + i);  // corr of head 4*quad+i lives in lane col == that head
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) st.o[j][i] *= cr[i];
-    }
-    // accumulate
-#pragma unroll
-    for (int tl = 0; tl < kMfmaTiles; ++tl) {
-      if (base + tl * 16 < count) {
-        // V tile -> LDS, row `col`, bytes 64*kk + 16*quad (two 8-byte stores: rows are 8-byte aligned)
-        unsigned char* vrow = vt + col * kVTileStride + 16 * quad;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          *reinterpret_cast<uint2*>(vrow + 64 * kk) = make_uint2(vr[tl][kk].x, vr[tl][kk].y);
-          *reinterpret_cast<uint2*>(vrow + 64 * kk + 8) = make_uint2(vr[tl][kk].z, vr[tl][kk].w);
-        }
-        // P = exp2(S - m), as hi + lo bf16 terms (masked rows hold kNegBig: P = 0)
-        unsigned hi[4], lo[4];
-        float psum = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float p = __builtin_amdgcn_exp2f(s[tl][i] - mnew);
-          psum += p;
-          hi[i] = bf16_round_bits(p);
-          lo[i] = bf16_round_bits(p - __uint_as_float(hi[i] << 16));
-        }
-        st.l += psum;
-        s16x4_t pa_hi, pa_lo;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          pa_hi[i] = (short)hi[i];
-          pa_lo[i] = (short)lo[i];
-        }
-        // the wave's LDS stores must land before its lanes read each other's rows
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const unsigned short* vt16 = reinterpret_cast<const unsigned short*>(vt);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          s16x4_t vb;  // B[k = token 4*quad+e][n = dim 16*j + col]
-#pragma unroll
-          for (int e = 0; e < 4; ++e) vb[e] = (short)vt16[(4 * quad + e) * (kVTileStride / 2) + 16 * j + col];
-          st.o[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa_hi, vb, st.o[j], 0, 0, 0);
-          st.o[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa_lo, vb, st.o[j], 0, 0, 0);
-        }
-        // tile fully read before the next tile overwrites it
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      }
-    }
+    mfma_consume(ga, count, base, scale_log2e, qf, vt, st);
+    base += stride;
+    if (base >= count) break;
+    mfma_issue(kbase, vbase, N, list, count, base + stride, ga);
+    PQC_LOADS_ISSUED();
+    mfma_consume(gb, count, base, scale_log2e, qf, vt, st);
+    base += stride;
+    if (base >= count) break;
   }
 }
 

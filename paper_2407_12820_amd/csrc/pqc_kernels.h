@@ -22,7 +22,6 @@
 namespace pqc {
 
 constexpr int kMaxVecA = 4;   // 16-byte code chunks per thread, histogram kernel
-constexpr int kMaxVecC = 8;   // 16-byte code chunks per lane, select kernel (tokC <= 4096)
 
 // ------------------------------------------------------------------ sources
 // Where a kernel takes its scores from: PQ codes through the LDS table (the decode
@@ -246,17 +245,41 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   // most tokens score below the window: they are counted in a register (bin 0), the rest
   // go to their LDS bin (an LDS atomic costs in proportion to the lanes that take part)
   int n_low = 0;
+  unsigned short* bins_u = ws.bins + (size_t)u * s.binStride;
 #pragma unroll
   for (int v = 0; v < kMaxVecA; ++v) {
     if (v * NT + tid < chunks) {
       const int t0 = (chunk0 + v * NT + tid) * P - src.lead;
+      unsigned st[P];  // what the select kernel will read back: bin + 1, or the window mark
 #pragma unroll
       for (int i = 0; i < P; ++i) {
         const int t = t0 + i;
         const float sc = src.score(raw[v], i);
         const bool mid = t >= s.I && t < s.N - s.L;
-        if (mid && !(sc < b_c0)) atomicAdd(&hist[score_bin(sc, b_c0, b_c1, b_ic, b_ihi)], 1u);
+        const int bin = score_bin(sc, b_c0, b_c1, b_ic, b_ihi);
+        if (mid && !(sc < b_c0)) atomicAdd(&hist[bin], 1u);
         n_low += (mid && sc < b_c0) ? 1 : 0;
+        st[i] = mid ? (unsigned)bin + 1u : kBinWindow;
+      }
+      if (src.lead == 0 && t0 + P <= s.N) {  // the usual case: aligned, all P tokens exist
+        if constexpr (P == 1) {
+          bins_u[t0] = (unsigned short)st[0];
+        } else {
+          unsigned pw[P / 2];
+#pragma unroll
+          for (int i = 0; i < P / 2; ++i) pw[i] = st[2 * i] | (st[2 * i + 1] << 16);
+          if constexpr (P == 2) *reinterpret_cast<unsigned*>(bins_u + t0) = pw[0];
+          if constexpr (P == 4) *reinterpret_cast<uint2*>(bins_u + t0) = make_uint2(pw[0], pw[1]);
+          if constexpr (P >= 8) {
+#pragma unroll
+            for (int i = 0; i < P / 8; ++i)
+              reinterpret_cast<uint4*>(bins_u + t0)[i] = make_uint4(pw[4 * i], pw[4 * i + 1], pw[4 * i + 2], pw[4 * i + 3]);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < P; ++i)
+          if (t0 + i >= 0 && t0 + i < s.N) bins_u[t0 + i] = (unsigned short)st[i];
       }
     }
   }
@@ -271,19 +294,21 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
 }
 
 // ---------------------------------------------------- 2. select (+ attention)
-// One workgroup owns virtual tokens [blockIdx.x*tokC, +tokC) of its unit; its 4 waves
-// each own a contiguous quarter.  Per wave, lanes hold consecutive chunks, counts are
-// prefix-summed across lanes, and the wave appends to its own LDS segment: selected
-// tokens (ascending) from the front, boundary-bin candidates from the back.
+// One workgroup owns tokens [blockIdx.x*tokC, +tokC) of its unit; its 4 waves each own
+// a contiguous quarter.  The histogram kernel left every token's bin behind, so a token
+// is classified by comparing that number with the threshold bin.  Per wave, lanes hold
+// 8 consecutive tokens, counts are prefix-summed across lanes, and the wave appends to
+// its own LDS segment: selected tokens (ascending) from the front, boundary-bin
+// candidates from the back.  SRC is only used to score the few candidates exactly.
+constexpr int kMaxVecC = 4;  // 8-token groups per lane (tokC <= 8192)
+
 template <typename T, int G, class SRC, bool ATTN>
 __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, const T* __restrict__ q,
                                                      const T* __restrict__ kc, const T* __restrict__ vc,
                                                      const void* __restrict__ src_ptr) {
-  constexpr int NT = 256, NW = 4, P = SRC::P;
-  constexpr int LM = SRC::kFromCodes ? SRC::M : 1;
+  constexpr int NT = 256, NW = 4;
   constexpr bool kMfma = ATTN && sizeof(T) == 2;
-  extern __shared__ int list[];  // [tokC]
-  __shared__ float lut[LM * kLutRow];
+  extern __shared__ unsigned short list[];  // [tokC] token offsets from the workgroup's first token
   __shared__ int scan_sm[2 * NW + 1 + 4];
   __shared__ int wcnt[2 * NW];
   __shared__ float red[ATTN ? NW * G * (kD + 2) : 1];
@@ -292,21 +317,15 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, units = s.B * s.Hkv;
   const int b = u / s.Hkv, g = u % s.Hkv;
   PQC_MARK(ws, 1, 0);
-  SRC src;
-  src.init(src_ptr, u, s.N, units, lut);
-  // this wave's chunks, loaded up front
-  const int cpw = s.tokC / (NW * P);  // chunks per wave
-  const int chunk0 = blockIdx.x * (s.tokC / P) + w * cpw;
-  typename SRC::Raw raw[kMaxVecC];
+  // this wave's stored bins, the query and the histogram: all requested up front
+  const int tpw = s.tokC / NW;           // tokens per wave, in groups of 8 per lane
+  const int gpw = (tpw + 511) / 512;     // groups per lane: 1, 2 or 4 (the last lanes idle when tpw < 512)
+  const int wave_t0 = blockIdx.x * s.tokC + w * tpw;
+  const unsigned short* bins_u = ws.bins + (size_t)u * s.binStride;
+  uint4 raw[kMaxVecC];
 #pragma unroll
-  for (int v = 0; v < kMaxVecC; ++v) raw[v] = src.load(chunk0 + min(v * 64 + lane, cpw - 1));
-  // table and query into registers with straight-line, clamped loads (LDS stores follow below)
-  constexpr int LUTV = SRC::kFromCodes ? (LM * kLutRow) / NT : 1;  // table entries per thread at C = 256
-  float lutreg[LUTV];
-  if constexpr (SRC::kFromCodes) {
-#pragma unroll
-    for (int x = 0; x < LUTV; ++x) lutreg[x] = ws.lut[(size_t)u * LM * s.C + min(x * NT + tid, LM * s.C - 1)];
-  }
+  for (int v = 0; v < kMaxVecC; ++v)
+    raw[v] = *reinterpret_cast<const uint4*>(bins_u + wave_t0 + min((v * 64 + lane) * 8, tpw - 8));
   constexpr int QV = ATTN ? (G * kD + NT - 1) / NT : 1;  // query elements per thread
   float qreg[QV];
   if constexpr (ATTN) {
@@ -316,82 +335,48 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   }
   ThresholdSearch<NT> ts;
   ts.load(ws.hist + ((size_t)s.parity * units + u) * kHistCopies * kNB);
-  const float4 bpa = reinterpret_cast<const float4*>(ws.ctl + u)[0], bpb = reinterpret_cast<const float4*>(ws.ctl + u)[1];
   PQC_LOADS_ISSUED();
-  const float b_c0 = bpa.y, b_c1 = bpa.z, b_ic = bpa.w, b_ihi = bpb.x;
-  if constexpr (SRC::kFromCodes) {
-#pragma unroll
-    for (int x = 0; x < LUTV; ++x) {
-      const int e = x * NT + tid;
-      if (e < LM * s.C) lut[(e / s.C) * kLutRow + (e % s.C)] = lutreg[x];
-    }
-  }
   if constexpr (ATTN) {
 #pragma unroll
     for (int x = 0; x < QV; ++x)
       if (x * NT + tid < G * kD) qlds[x * NT + tid] = qreg[x];
   }
-  const Threshold th = ts.resolve(s.K, scan_sm);  // syncs: lut, qlds ready
+  const Threshold th = ts.resolve(s.K, scan_sm);  // syncs: qlds ready
   PQC_MARK(ws, 1, 1);
-#pragma unroll
-  for (int v = 0; v < kMaxVecC; ++v) src.fix_tail(raw[v], chunk0 + min(v * 64 + lane, cpw - 1));
-  PQC_MARK(ws, 1, 6);
 
   const int segN = s.tokC / NW;
-  int* seg = list + w * segN;
+  unsigned short* seg = list + w * segN;
+  const int wg_t0 = blockIdx.x * s.tokC;
   int nsel = 0, ncand = 0;
-  // A token is selected when its bin lies above the threshold bin and is a candidate when
-  // it falls into it.  With the threshold inside the fine window (the usual case) both
-  // follow from the fine index alone; the decisions are the same as comparing score_bin().
-  auto classify = [&](auto fine_case) {
-    constexpr bool kFine = decltype(fine_case)::value;
-    const int kb = th.bstar - 1;  // fine index of the threshold bin
+  const unsigned thr = (unsigned)th.bstar + 1u;  // in stored form
 #pragma unroll
-    for (int v = 0; v < kMaxVecC; ++v) {
-      if (v * 64 < cpw) {  // wave-uniform
-        const bool live = v * 64 + lane < cpw;
-        const int t0 = (chunk0 + v * 64 + lane) * P - src.lead;
-        unsigned selm = 0u, candm = 0u;
-        if (live) {
+  for (int v = 0; v < kMaxVecC; ++v) {
+    if (v < gpw) {  // uniform
+      const int t0 = wave_t0 + (v * 64 + lane) * 8;
+      const unsigned wv[4] = {raw[v].x, raw[v].y, raw[v].z, raw[v].w};
+      unsigned selm = 0u, candm = 0u;
 #pragma unroll
-          for (int i = 0; i < P; ++i) {
-            const int t = t0 + i;
-            const float sc = src.score(raw[v], i);
-            bool sel, cand;
-            if constexpr (kFine) {
-              const int k = fine_index(sc, b_c0, b_ic);
-              const bool inw = !(sc < b_c0) && !(sc > b_c1);
-              sel = sc > b_c1 || (inw && k > kb);
-              cand = inw && k == kb;
-            } else {
-              const int bin = score_bin(sc, b_c0, b_c1, b_ic, b_ihi);
-              sel = bin > th.bstar;
-              cand = bin == th.bstar;
-            }
-            const bool window = t < s.I || t >= s.N - s.L;
-            const bool real = t >= 0 && t < s.N;
-            selm |= ((real && (window || sel)) ? 1u : 0u) << i;
-            candm |= ((real && !window && cand) ? 1u : 0u) << i;
-          }
-        }
-        const int cnt = __popc(selm) | (__popc(candm) << 16);
-        const int inc = wave_inclusive_scan(cnt);
-        const int tot = wave_last(inc);
-        int ps = nsel + ((inc - cnt) & 0xffff), pc = ncand + ((inc - cnt) >> 16);
-#pragma unroll
-        for (int i = 0; i < P; ++i) {
-          if (selm & (1u << i)) seg[ps++] = t0 + i;
-          if (candm & (1u << i)) seg[segN - 1 - (pc++)] = t0 + i;
-        }
-        nsel += tot & 0xffff;
-        ncand += tot >> 16;
+      for (int i = 0; i < 8; ++i) {
+        const unsigned st = (wv[i >> 1] >> (16 * (i & 1))) & 0xffffu;
+        selm |= (st > thr ? 1u : 0u) << i;
+        candm |= (st == thr ? 1u : 0u) << i;
       }
+      const int nreal = (v * 64 + lane) * 8 < tpw ? min(8, max(0, s.N - t0)) : 0;  // tokens of this group that exist
+      selm &= (1u << nreal) - 1u;
+      candm &= (1u << nreal) - 1u;
+      const int cnt = __popc(selm) | (__popc(candm) << 16);
+      const int inc = wave_inclusive_scan(cnt);
+      const int tot = wave_last(inc);
+      int ps = nsel + ((inc - cnt) & 0xffff), pc = ncand + ((inc - cnt) >> 16);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (selm & (1u << i)) seg[ps++] = (unsigned short)(t0 + i - wg_t0);
+        if (candm & (1u << i)) seg[segN - 1 - (pc++)] = (unsigned short)(t0 + i - wg_t0);
+      }
+      nsel += tot & 0xffff;
+      ncand += tot >> 16;
     }
-  };
-  if (th.bstar >= 1 && th.bstar <= kFineBins)  // workgroup-uniform
-    classify(std::true_type{});
-  else
-    classify(std::false_type{});
+  }
   PQC_MARK(ws, 1, 8);
   if (lane == 0) {
     wcnt[w] = nsel;
@@ -416,7 +401,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
     int i = 0;
 #pragma unroll
     for (int x = 1; x < NW; ++x) i += (p >= csel[x]) ? 1 : 0;
-    return list[i * segN + (p - csel[i])];
+    return wg_t0 + list[i * segN + (p - csel[i])];
   };
 
   // selected list for the finalize kernel's index output
@@ -432,7 +417,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   // window tokens it happens to hold (the list's first nI and last nL entries), every
   // nblkC-th token of the two windows, so that the window rows are spread over the unit's
   // workgroups.
-  const int tok_lo = max(0, (int)blockIdx.x * s.tokC - src.lead), tok_hi = min(s.N, ((int)blockIdx.x + 1) * s.tokC - src.lead);
+  const int tok_lo = (int)blockIdx.x * s.tokC, tok_hi = min(s.N, ((int)blockIdx.x + 1) * s.tokC);
   const int nI = max(0, min(s.I, tok_hi) - tok_lo), nL = max(0, tok_hi - max(s.N - s.L, tok_lo));
   const int n_own = tot_sel - nI - nL;
   const int n_win = (int)blockIdx.x < s.I + s.L ? (s.I + s.L - (int)blockIdx.x + s.nblkC - 1) / s.nblkC : 0;
@@ -480,6 +465,18 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   PQC_NOTE(ws, 1, 15, tot_cand);
 
   // candidates (few): composite for the generic path, and a full record while slots last
+  auto cand_score = [&](int t) -> float {  // exact score, same evaluation order as everywhere
+    if constexpr (SRC::kFromCodes) {
+      const uint8_t* cp = static_cast<const uint8_t*>(src_ptr) + ((size_t)u * s.N + t) * SRC::M;
+      const float* tb = ws.lut + (size_t)u * SRC::M * s.C;
+      float sc = tb[cp[0]];
+#pragma unroll
+      for (int j = 1; j < SRC::M; ++j) sc = __fadd_rn(sc, tb[j * s.C + cp[j]]);
+      return sc;
+    } else {
+      return static_cast<const float*>(src_ptr)[(size_t)u * s.N + t];
+    }
+  };
   if (tot_cand > 0) {  // workgroup-uniform
     if (tid == 0) scan_sm[0] = rec_base;
     __syncthreads();
@@ -489,8 +486,8 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
       int i = 0;
 #pragma unroll
       for (int x = 1; x < NW; ++x) i += (c >= ccand[x]) ? 1 : 0;
-      const int t = list[i * segN + segN - 1 - (c - ccand[i])];
-      const unsigned long long comp = make_composite(src.score_of_token(t, u, s.N), t);
+      const int t = wg_t0 + list[i * segN + segN - 1 - (c - ccand[i])];
+      const unsigned long long comp = make_composite(cand_score(t), t);
       if (sub == 0) stage[s.tokC - 1 - c] = comp;
       if (base + c < kCandRec) {
         unsigned char* rec = ws.cand_rec + ((size_t)u * kCandRec + base + c) * ws.rec_stride;
