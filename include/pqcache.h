@@ -128,14 +128,16 @@ int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_
                const void* k_cache, const void* v_cache, int32_t* out_idx, float* out_attn,
                void* stream);
 
-/* Profiling aid: pqc_decode with HIP events recorded on `stream` around each of its
- * kernels.  Unlike every other entry point it creates and destroys events and
- * SYNCHRONISES the stream before returning.  kernel_ms is HOST memory for
- * PQC_DECODE_KERNELS floats, in launch order: histogram, select+attention, finalize. */
+/* Profiling aid: the kernels of pqc_decode one at a time.  phase 0 = histogram, 1 =
+ * select + attention, 2 = finalize; calling phases 0, 1, 2 in this order with the same
+ * arguments is exactly one pqc_decode (same kernels, same results).  It lets a harness
+ * launch one phase for several contexts back to back between two events, which times
+ * a kernel without an event in front of every launch.  Any other order on one context
+ * gives undefined results (never a fault).  Returns PQC_EINVAL for another phase. */
 #define PQC_DECODE_KERNELS 3
-int pqc_decode_profile(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes,
-                       const void* k_cache, const void* v_cache, int32_t* out_idx, float* out_attn,
-                       void* stream, float* kernel_ms);
+int pqc_decode_phase(pqc_ctx* ctx, int phase, const void* q, const float* centroids, const uint8_t* codes,
+                     const void* k_cache, const void* v_cache, int32_t* out_idx, float* out_attn,
+                     void* stream);
 
 /* ---- the same path, one stage at a time (unit tests, per-kernel profiling) ---- */
 

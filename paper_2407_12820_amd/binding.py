@@ -53,8 +53,8 @@ def load() -> C.CDLL:
     lib.pqc_last_hip_error.argtypes = [vp]
     lib.pqc_decode.restype = C.c_int
     lib.pqc_decode.argtypes = [vp] * 9
-    lib.pqc_decode_profile.restype = C.c_int
-    lib.pqc_decode_profile.argtypes = [vp] * 9 + [C.POINTER(C.c_float)]
+    lib.pqc_decode_phase.restype = C.c_int
+    lib.pqc_decode_phase.argtypes = [vp, C.c_int] + [vp] * 8
     lib.pqc_lut.restype = C.c_int
     lib.pqc_lut.argtypes = [vp] * 5
     lib.pqc_scan.restype = C.c_int
@@ -168,18 +168,25 @@ class PQCache:
         self._check(rc, "pqc_decode")
         return out_idx, out_attn
 
-    def decode_profile(self, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream=None):
-        """pqc_decode with per-kernel HIP-event timing -> list of milliseconds (synchronises the stream)."""
+    def marshal_decode_args(self, q, centroids, codes, k_cache, v_cache, out_idx, out_attn):
+        """Checks the seven tensors of a decode call once and returns their device addresses, for
+        callers that repeat the same call and want the per-call Python cost out of the way."""
         sh = self.shapes
-        ms = (C.c_float * 3)()
-        rc = self.lib.pqc_decode_profile(self.handle, self._ptr(q, self.kv_torch, sh["q"]),
-                                         self._ptr(centroids, torch.float32, sh["centroids"]),
-                                         self._ptr(codes, torch.uint8, sh["codes"]),
-                                         self._ptr(k_cache, self.kv_torch, sh["kv"]), self._ptr(v_cache, self.kv_torch, sh["kv"]),
-                                         self._ptr(out_idx, torch.int32, sh["idx"]), self._ptr(out_attn, torch.float32, sh["out"]),
-                                         self._stream(stream), ms)
-        self._check(rc, "pqc_decode_profile")
-        return list(ms)
+        return (self._ptr(q, self.kv_torch, sh["q"]), self._ptr(centroids, torch.float32, sh["centroids"]),
+                self._ptr(codes, torch.uint8, sh["codes"]), self._ptr(k_cache, self.kv_torch, sh["kv"]),
+                self._ptr(v_cache, self.kv_torch, sh["kv"]), self._ptr(out_idx, torch.int32, sh["idx"]),
+                self._ptr(out_attn, torch.float32, sh["out"]))
+
+    def decode_marshalled(self, args, stream_handle: int) -> None:
+        self._check(self.lib.pqc_decode(self.handle, *args, stream_handle), "pqc_decode")
+
+    def decode_phase_marshalled(self, phase: int, args, stream_handle: int) -> None:
+        """One kernel of pqc_decode (0 histogram, 1 select + attention, 2 finalize); see the header."""
+        self._check(self.lib.pqc_decode_phase(self.handle, phase, *args, stream_handle), "pqc_decode_phase")
+
+    def decode_phase(self, phase, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream=None):
+        self.decode_phase_marshalled(int(phase), self.marshal_decode_args(q, centroids, codes, k_cache, v_cache, out_idx, out_attn),
+                                     self._stream(stream))
 
     def lut(self, q, centroids, table=None, stream=None):
         sh = self.shapes

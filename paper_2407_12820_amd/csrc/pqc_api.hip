@@ -149,46 +149,45 @@ int ensure_clean_hist(pqc_ctx* ctx, hipStream_t st) {
 }
 
 // ---- template dispatch -------------------------------------------------------
-// ev: nullptr, or PQC_DECODE_KERNELS+1 events recorded before, between and after the launches
+// phases: bit k set = launch kernel k of the decode path (0 histogram, 1 select + attention, 2 finalize)
 template <typename T, int G, int M>
 void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const void* k,
-                       const void* v, int32_t* out_idx, float* out_attn, hipStream_t st, hipEvent_t* ev) {
+                       const void* v, int32_t* out_idx, float* out_attn, hipStream_t st, unsigned phases) {
   const Shape& s = ctx->plan.s;
   const unsigned units = (unsigned)(s.B * s.Hkv);
   const T* qt = static_cast<const T*>(q);
   const T* kt = static_cast<const T*>(k);
   const T* vt = static_cast<const T*>(v);
-  if (ev) (void)hipEventRecord(ev[0], st);
-  hipLaunchKernelGGL((hist_kernel<T, CodeChunks<M>>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, qt, cent,
-                     static_cast<const void*>(codes));
-  if (ev) (void)hipEventRecord(ev[1], st);
-  hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(unsigned short), st,
-                     s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));
-  if (ev) (void)hipEventRecord(ev[2], st);
-  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
-                     ctx->ws, qt, kt, vt, out_idx, out_attn);
-  if (ev) (void)hipEventRecord(ev[3], st);
+  if (phases & 1u)
+    hipLaunchKernelGGL((hist_kernel<T, CodeChunks<M>>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, qt, cent,
+                       static_cast<const void*>(codes));
+  if (phases & 2u)
+    hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC, units), dim3(256),
+                       s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));
+  if (phases & 4u)
+    hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st,
+                       s, ctx->ws, qt, kt, vt, out_idx, out_attn);
 }
 
 template <typename T, int G>
 void launch_decode_tg(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const void* k, const void* v,
-                      int32_t* out_idx, float* out_attn, hipStream_t st, hipEvent_t* ev) {
+                      int32_t* out_idx, float* out_attn, hipStream_t st, unsigned phases) {
   switch (ctx->plan.s.M) {
-    case 1: launch_decode_tgm<T, G, 1>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
-    case 2: launch_decode_tgm<T, G, 2>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
-    case 4: launch_decode_tgm<T, G, 4>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
-    default: launch_decode_tgm<T, G, 8>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
+    case 1: launch_decode_tgm<T, G, 1>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, phases); break;
+    case 2: launch_decode_tgm<T, G, 2>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, phases); break;
+    case 4: launch_decode_tgm<T, G, 4>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, phases); break;
+    default: launch_decode_tgm<T, G, 8>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, phases); break;
   }
 }
 
 template <typename T>
 void launch_decode_t(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const void* k, const void* v,
-                     int32_t* out_idx, float* out_attn, hipStream_t st, hipEvent_t* ev) {
+                     int32_t* out_idx, float* out_attn, hipStream_t st, unsigned phases) {
   switch (ctx->plan.s.G) {
-    case 1: launch_decode_tg<T, 1>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
-    case 2: launch_decode_tg<T, 2>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
-    case 4: launch_decode_tg<T, 4>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
-    default: launch_decode_tg<T, 8>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, ev); break;
+    case 1: launch_decode_tg<T, 1>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, phases); break;
+    case 2: launch_decode_tg<T, 2>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, phases); break;
+    case 4: launch_decode_tg<T, 4>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, phases); break;
+    default: launch_decode_tg<T, 8>(ctx, q, cent, codes, k, v, out_idx, out_attn, st, phases); break;
   }
 }
 
@@ -299,21 +298,24 @@ void pqc_destroy(pqc_ctx* ctx) { delete ctx; }
 int pqc_last_hip_error(const pqc_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
 
 static int decode_impl(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes, const void* k_cache,
-                       const void* v_cache, int32_t* out_idx, float* out_attn, void* stream, hipEvent_t* ev) {
+                       const void* v_cache, int32_t* out_idx, float* out_attn, void* stream, unsigned phases) {
   if (!ctx || !q || !centroids || !codes || !k_cache || !v_cache || !out_idx || !out_attn) return PQC_EINVAL;
   if (!aligned16(q) || !aligned16(centroids) || !aligned16(codes) || !aligned16(k_cache) || !aligned16(v_cache) ||
       !aligned16(out_idx) || !aligned16(out_attn))
     return PQC_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  int rc = ensure_clean_hist(ctx, st);
-  if (rc != PQC_OK) return rc;
-  ctx->hist_clean = false;
+  int rc = PQC_OK;
+  if (phases & 1u) {
+    rc = ensure_clean_hist(ctx, st);
+    if (rc != PQC_OK) return rc;
+    ctx->hist_clean = false;
+  }
   if (ctx->cfg.kv_dtype == PQC_F32)
-    launch_decode_t<float>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st, ev);
+    launch_decode_t<float>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st, phases);
   else
-    launch_decode_t<bf16_t>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st, ev);
+    launch_decode_t<bf16_t>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st, phases);
   rc = check_launch(ctx);
-  if (rc == PQC_OK) {
+  if (rc == PQC_OK && (phases & 4u)) {
     ctx->hist_clean = true;  // finalize_kernel zeroed the other parity's set, which the next call uses
     ctx->plan.s.parity ^= 1;
   }
@@ -322,36 +324,13 @@ static int decode_impl(pqc_ctx* ctx, const void* q, const float* centroids, cons
 
 int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes, const void* k_cache,
                const void* v_cache, int32_t* out_idx, float* out_attn, void* stream) {
-  return decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, nullptr);
+  return decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 7u);
 }
 
-int pqc_decode_profile(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes, const void* k_cache,
-                       const void* v_cache, int32_t* out_idx, float* out_attn, void* stream, float* kernel_ms) {
-  if (!ctx || !kernel_ms) return PQC_EINVAL;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  int rc = ensure_clean_hist(ctx, st);  // keep the one-off reset out of the timed span
-  if (rc != PQC_OK) return rc;
-  hipEvent_t ev[PQC_DECODE_KERNELS + 1];
-  int made = 0;
-  for (; made <= PQC_DECODE_KERNELS; ++made)
-    if (hipEventCreate(&ev[made]) != hipSuccess) break;
-  if (made <= PQC_DECODE_KERNELS) {
-    ctx->last_hip = (int)hipGetLastError();
-    rc = PQC_EHIP;
-  } else {
-    rc = decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, ev);
-    if (rc == PQC_OK && hipStreamSynchronize(st) != hipSuccess) {
-      ctx->last_hip = (int)hipGetLastError();
-      rc = PQC_EHIP;
-    }
-    for (int i = 0; rc == PQC_OK && i < PQC_DECODE_KERNELS; ++i)
-      if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) {
-        ctx->last_hip = (int)hipGetLastError();
-        rc = PQC_EHIP;
-      }
-  }
-  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
-  return rc;
+int pqc_decode_phase(pqc_ctx* ctx, int phase, const void* q, const float* centroids, const uint8_t* codes,
+                     const void* k_cache, const void* v_cache, int32_t* out_idx, float* out_attn, void* stream) {
+  if (phase < 0 || phase >= PQC_DECODE_KERNELS) return PQC_EINVAL;
+  return decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 1u << phase);
 }
 
 int pqc_lut(pqc_ctx* ctx, const void* q, const float* centroids, float* table, void* stream) {

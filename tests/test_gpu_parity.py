@@ -143,6 +143,14 @@ def _small(**kw):
     dict(pq_m=4, pq_centroids=7, n_q_heads=16, n_kv_heads=2, topk=999, n_tokens=4097),
     dict(dtype="f32", n_q_heads=8, n_kv_heads=1, topk=511, n_tokens=2500),
     dict(batch=3, n_tokens=2049, topk=100),
+    # tie classes of different sizes at the threshold: about 90, 190, 380 and 1500 equal scores
+    dict(pq_m=1, pq_centroids=32, topk=500),
+    dict(pq_m=1, pq_centroids=16, topk=700),
+    dict(pq_m=1, pq_centroids=8, topk=700),
+    dict(dtype="f32", pq_m=1, pq_centroids=32, topk=500, n_q_heads=2, n_kv_heads=2),
+    dict(dtype="f32", pq_m=1, pq_centroids=4, topk=900, n_q_heads=2, n_kv_heads=1),
+    # more select workgroups per unit than the finalize kernel has threads
+    dict(n_tokens=140001, topk=9000, n_q_heads=2, n_kv_heads=1, pq_centroids=64),
 ], ids=lambda kw: ",".join(f"{k}={v}" for k, v in kw.items()))
 def test_edge_shapes(pqc, kw):
     w = _small(**kw)
@@ -177,6 +185,24 @@ def test_context_reuse_and_two_contexts(pqc):
     np.testing.assert_array_equal(np.sort(ig, -1), np.sort(oracle.select(s32, wa.topk, wa.n_init, wa.n_local), -1))
     idx, out = run_decode(pqc, pa2, ctx=ca)
     full_check(pa2, idx, out)
+
+
+def test_decode_phase_by_phase_equals_decode(pqc):
+    # the profiling entry point launches the same three kernels one at a time
+    w = _small(n_tokens=9000, topk=1200, pq_m=4)
+    p = build_problem(w, seed=9)
+    dev, ctx = upload(pqc, p), pqc.PQCache(w, DEV)
+    a = run_decode(pqc, p, ctx, dev)
+    idx, out = ctx.empty_outputs()
+    for _ in range(2):  # twice: the histogram parity flips after each complete pass
+        idx.zero_()
+        out.zero_()
+        for phase in range(3):
+            ctx.decode_phase(phase, dev["q"], dev["centroids"], dev["codes"], dev["k"], dev["v"], idx, out)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(a[0], idx.cpu().numpy())
+        np.testing.assert_array_equal(a[1].view(np.uint32), out.cpu().numpy().view(np.uint32))
+    full_check(p, a[0], a[1])
 
 
 def test_decode_is_deterministic(pqc):
