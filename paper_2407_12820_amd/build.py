@@ -15,7 +15,10 @@ LIB = os.path.join(HERE, "libpqcache.so")
 OBJ = os.path.join(HERE, "_build")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # keep returning atomics as written: the wave-level rewrite reads the result back at once,
+         # which puts the atomic's round trip on the critical path of select_kernel
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]
 
 
 def sources():

@@ -395,7 +395,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   const int tot_sel = csel[NW], tot_cand = ccand[NW];
   // record slots for this workgroup's candidates: requested now, needed only after the
   // attention below, which hides the round trip of the returning atomic
-  int rec_base = 0;
+  int rec_base;  // set and read by thread 0 only; no initialiser, or the merge with it would wait for the atomic here
   if (tid == 0 && tot_cand > 0) rec_base = (int)atomicAdd(&ws.cand_count[(size_t)s.parity * units + u], (unsigned)tot_cand);
   auto sel_at = [&](int p) -> int {
     int i = 0;
@@ -407,8 +407,6 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   // selected list for the finalize kernel's index output
   unsigned long long* stage = ws.stage + ((size_t)u * s.nblkC + blockIdx.x) * s.tokC;
   int* stage32 = reinterpret_cast<int*>(stage);
-  for (int p = tid; p < tot_sel; p += NT) stage32[p] = sel_at(p);
-  if (tid == 0) ws.stage_cnt[(size_t)u * s.nblkC + blockIdx.x] = make_int2(tot_sel, tot_cand);
   PQC_MARK(ws, 1, 3);
 
   const T* kbase = kc + (size_t)u * s.N * kD;
@@ -460,6 +458,10 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
       }
     }
   }
+  // (written after the attention: stores issued while the K/V loads of the co-resident workgroup
+  // fill the memory pipeline would only delay this workgroup's own first loads)
+  for (int p = tid; p < tot_sel; p += NT) stage32[p] = sel_at(p);
+  if (tid == 0) ws.stage_cnt[(size_t)u * s.nblkC + blockIdx.x] = make_int2(tot_sel, tot_cand);
   PQC_MARK(ws, 1, 5);
   PQC_NOTE(ws, 1, 14, tot_sel);
   PQC_NOTE(ws, 1, 15, tot_cand);
@@ -478,7 +480,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
     }
   };
   if (tot_cand > 0) {  // workgroup-uniform
-    if (tid == 0) scan_sm[0] = rec_base;
+    if (tid == 0 && tot_cand > 0) scan_sm[0] = rec_base;
     __syncthreads();
     const int base = scan_sm[0];
     const int sub = lane & 15, grp = tid >> 4;  // 16 lanes per candidate
