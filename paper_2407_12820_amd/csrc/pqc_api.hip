@@ -159,8 +159,8 @@ void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uin
   const T* kt = static_cast<const T*>(k);
   const T* vt = static_cast<const T*>(v);
   if (phases & 1u)
-    hipLaunchKernelGGL((hist_kernel<T, CodeChunks<M>>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, qt, cent,
-                       static_cast<const void*>(codes));
+    hipLaunchKernelGGL((hist_kernel<T, CodeChunks<M>>), dim3(s.nblkA, units), dim3(1024),
+                       sizeof(float) * lut_tile_floats(1024, M, s.C), st, s, ctx->ws, qt, cent, static_cast<const void*>(codes));
   if (phases & 2u)
     hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC, units), dim3(256),
                        s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));

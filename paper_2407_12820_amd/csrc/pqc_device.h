@@ -252,29 +252,31 @@ __device__ __forceinline__ float load_as_float<bf16_t>(const bf16_t* p, int i) {
 }
 
 // Centroids travel global -> registers (coalesced, all loads in flight at once) -> a
-// padded LDS tile of kLutTileFloats floats -> one thread per table entry runs the chain.
+// padded LDS tile -> one thread per table entry runs the chain.  With 1024 threads the
+// tile holds the whole table (C*(kD+M) floats, up to 136 KB of the CU's 160 KB) and there
+// is a single pass; with fewer threads the table goes through a tile of kLutTileFloats
+// floats piece by piece.
 constexpr int kLutTileFloats = 8192;
+__host__ __device__ constexpr int lut_tile_floats(int nt, int M, int C) {
+  return nt >= 1024 ? C * (kD + M) : kLutTileFloats + kLutTileFloats / (kD / M);
+}
 template <typename T, int NT, int M, class MarkFn>
 __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] of this unit */,
                                                const float* __restrict__ cent /* [M][C][Dm] */, int G, int C,
                                                float* lut, float* qs, float* red /* [4*8] */,
-                                               float* tile /* [kLutTileFloats + kLutTileFloats/Dm] */, MarkFn mark) {
+                                               float* tile /* [lut_tile_floats(NT, M, C)] */, MarkFn mark) {
   constexpr int Dm = kD / M;
-  constexpr int VPG = kLutTileFloats / (4 * NT);      // float4 per thread per tile
-  constexpr int NG = (256 * kD) / kLutTileFloats;      // tiles at the largest C
-  constexpr bool kPrefetchAll = (VPG * NG <= 8);       // keep every tile's loads in flight
+  constexpr bool kWhole = NT >= 1024;
+  constexpr int VW = kWhole ? (256 * kD) / (4 * NT) : 1;  // float4 per thread for the largest table
+  constexpr int VPG = kLutTileFloats / (4 * NT);      // float4 per thread per tile (piecewise mode)
+  constexpr int NG = (256 * kD) / kLutTileFloats;      // tiles at the largest C (piecewise mode)
   const int tid = threadIdx.x;
   const int total = M * C * Dm;                        // floats, a multiple of 4
   const float4* cent4 = reinterpret_cast<const float4*>(cent);
-  float4 v[kPrefetchAll ? NG : 1][VPG];
-  if constexpr (kPrefetchAll) {
+  float4 vw[VW];
+  if constexpr (kWhole) {
 #pragma unroll
-    for (int g = 0; g < NG; ++g)
-#pragma unroll
-      for (int x = 0; x < VPG; ++x) {
-        const int f = g * (kLutTileFloats / 4) + x * NT + tid;
-        v[g][x] = cent4[min(f, total / 4 - 1)];
-      }
+    for (int x = 0; x < VW; ++x) vw[x] = cent4[min(x * NT + tid, total / 4 - 1)];
   }
   {
     // the group's query heads: all loads first (clamped, straight-line), then the sum in head order
@@ -292,40 +294,60 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
     if (tid < kD) qs[tid] = a;
   }
   mark(8);
+  if constexpr (kWhole) {
 #pragma unroll
-  for (int g = 0; g < NG; ++g) {
-    if (g * kLutTileFloats < total) {  // uniform
-      if constexpr (!kPrefetchAll) {
+    for (int x = 0; x < VW; ++x) {
+      const int fl = (x * NT + tid) * 4;  // float index inside the table
+      if (fl < total) {
+        const int row = fl / Dm, col = fl % Dm;  // Dm is a multiple of 4: one row per float4
+        float* dst = tile + row * (Dm + 1) + col;
+        dst[0] = vw[x].x; dst[1] = vw[x].y; dst[2] = vw[x].z; dst[3] = vw[x].w;
+      }
+    }
+    __syncthreads();  // tile and qs visible
+    for (int e = tid; e < M * C; e += NT) {
+      const int j = e / C, c = e - j * C;
+      const float* qj = qs + j * Dm;
+      const float* cr = tile + e * (Dm + 1);
+      float p = 0.0f;
+#pragma unroll
+      for (int x = 0; x < Dm; ++x) p = __fmaf_rn(qj[x], cr[x], p);
+      lut[j * kLutRow + c] = p;
+    }
+    mark(9);
+  } else {
+    float4 v[VPG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      if (g * kLutTileFloats < total) {  // uniform
 #pragma unroll
         for (int x = 0; x < VPG; ++x) {
           const int f = g * (kLutTileFloats / 4) + x * NT + tid;
-          v[0][x] = cent4[min(f, total / 4 - 1)];
+          v[x] = cent4[min(f, total / 4 - 1)];
+        }
+        if (g > 0) __syncthreads();  // previous tile fully consumed
+#pragma unroll
+        for (int x = 0; x < VPG; ++x) {
+          const int fl = (x * NT + tid) * 4;  // float index inside the tile
+          if (g * kLutTileFloats + fl < total) {
+            const int row = fl / Dm, col = fl % Dm;
+            float* dst = tile + row * (Dm + 1) + col;
+            dst[0] = v[x].x; dst[1] = v[x].y; dst[2] = v[x].z; dst[3] = v[x].w;
+          }
+        }
+        __syncthreads();  // tile (and, first time round, qs) visible
+        const int rows = min(kLutTileFloats, total - g * kLutTileFloats) / Dm;
+        for (int r = tid; r < rows; r += NT) {
+          const int e = g * (kLutTileFloats / Dm) + r;
+          const int j = e / C, c = e - j * C;
+          const float* qj = qs + j * Dm;
+          const float* cr = tile + r * (Dm + 1);
+          float p = 0.0f;
+#pragma unroll
+          for (int x = 0; x < Dm; ++x) p = __fmaf_rn(qj[x], cr[x], p);
+          lut[j * kLutRow + c] = p;
         }
       }
-      if (g > 0) __syncthreads();  // previous tile fully consumed
-#pragma unroll
-      for (int x = 0; x < VPG; ++x) {
-        const int fl = (x * NT + tid) * 4;  // float index inside the tile
-        if (g * kLutTileFloats + fl < total) {
-          const float4 cv = v[kPrefetchAll ? g : 0][x];
-          const int row = fl / Dm, col = fl % Dm;  // Dm is a multiple of 4: one row per float4
-          float* dst = tile + row * (Dm + 1) + col;
-          dst[0] = cv.x; dst[1] = cv.y; dst[2] = cv.z; dst[3] = cv.w;
-        }
-      }
-      __syncthreads();  // tile (and, first time round, qs) visible
-      const int rows = min(kLutTileFloats, total - g * kLutTileFloats) / Dm;
-      for (int r = tid; r < rows; r += NT) {
-        const int e = g * (kLutTileFloats / Dm) + r;
-        const int j = e / C, c = e - j * C;
-        const float* qj = qs + j * Dm;
-        const float* cr = tile + r * (Dm + 1);
-        float p = 0.0f;
-#pragma unroll
-        for (int x = 0; x < Dm; ++x) p = __fmaf_rn(qj[x], cr[x], p);
-        lut[j * kLutRow + c] = p;
-      }
-      mark(9 + g);
     }
   }
   __syncthreads();

@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void lut_kernel(Shape s, const T* __restrict__
   __shared__ float lut[M * kLutRow];
   __shared__ float qs[kD];
   __shared__ float red[32];
-  __shared__ float tile[kLutTileFloats + kLutTileFloats / (kD / M)];
+  __shared__ float tile[lut_tile_floats(256, M, 256)];
   const int u = blockIdx.y, b = u / s.Hkv, g = u % s.Hkv;
   build_lut<T, 256, M>(q + ((size_t)b * s.Hq + (size_t)g * s.G) * kD, cent + (size_t)u * M * s.C * (kD / M), s.G, s.C, lut,
                        qs, red, tile, [](int) {});
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   __shared__ float lut[LM * kLutRow];
   __shared__ float qs[kD];
   __shared__ float red[32];
-  __shared__ float tile[SRC::kFromCodes ? kLutTileFloats + kLutTileFloats / (kD / LM) : 1];
+  extern __shared__ float tile[];  // lut_tile_floats(NT, LM, C) floats when the source is codes
   __shared__ unsigned hist[kNB];
   __shared__ int scan_sm[2 * (NT / 64) + 1 + 2];
   const int tid = threadIdx.x, units = s.B * s.Hkv;
@@ -567,7 +567,6 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
   constexpr int NT = 256, NW = 4;
   constexpr int heads = ATTN ? G : 1;
   constexpr int SP = ATTN ? (sizeof(T) == 2 ? 8 : 4) : 1;  // passes of 16 record V rows requested up front
-  constexpr int kSpecRows = ATTN ? 16 * SP : 0;
   extern __shared__ int dyn[];  // pre_sel[nblkC+1], pre_cand[nblkC+1], pm[nblkC], pl[nblkC]
   __shared__ int scan_sm[2 * NW + 1];
   __shared__ float fsm[NW];
@@ -686,15 +685,19 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
   const int2 cnt0 = cnt[jc];  // list sizes of the first NT select workgroups
   float pm0 = 0.0f, pl0 = 0.0f;
   float a0[kAccBatch];  // first batch of this thread's partial accumulators: lists half, half+2, ...
-  RowRaw<T> vspec[SP];  // V rows of the first kSpecRows records
+  RowRaw<T> vspec[SP];  // V rows of the first 16*sp records
+  // with many head workgroups in flight the unused part of this guess is real traffic: guess less
+  const int sp = (int)gridDim.y * heads <= 64 ? SP : SP / 2;
   if constexpr (ATTN) {
     pm0 = parts[((size_t)jc * G + hq) * (kD + 2)];
     pl0 = parts[((size_t)jc * G + hq) * (kD + 2) + 1];
     const float* a0p = parts + ((size_t)half * G + hq) * (kD + 2) + 2 + d;
 #pragma unroll
-    for (int x = 0; x < kAccBatch; ++x) a0[x] = a0p[(size_t)x * (2 * G * (kD + 2))];  // slots exist up to 2*kAccBatch
+    for (int x = 0; x < kAccBatch; ++x)  // lists that do not exist re-read the first one (a cache hit, no extra traffic)
+      a0[x] = a0p[half + 2 * x < s.nblkC ? (size_t)x * (2 * G * (kD + 2)) : (size_t)0];
 #pragma unroll
-    for (int x = 0; x < SP; ++x) vspec[x].load_row(recs + (size_t)(x * 16 + grp) * ws.rec_stride + sizeof(CandHeader), sub);
+    for (int x = 0; x < SP; ++x)
+      if (x < sp) vspec[x].load_row(recs + (size_t)(x * 16 + grp) * ws.rec_stride + sizeof(CandHeader), sub);
   }
   PQC_LOADS_ISSUED();
   if constexpr (ATTN) {
@@ -811,7 +814,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
           if (j < s.nblkC) acc = fmaf(pm[j], a[x], acc);
         }
       }
-      if (need > 0 && n_cand <= kSpecRows) {
+      if (need > 0 && n_cand <= 16 * sp) {
         // the V rows are already here: weighted rows go to LDS at their rank, then are summed in rank order
         for (int r0 = 0; r0 < need; r0 += kRankChunk) {
           const int nr = min(kRankChunk, need - r0);
