@@ -397,6 +397,42 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   // attention below, which hides the round trip of the returning atomic
   int rec_base;  // set and read by thread 0 only; no initialiser, or the merge with it would wait for the atomic here
   if (tid == 0 && tot_cand > 0) rec_base = (int)atomicAdd(&ws.cand_count[(size_t)s.parity * units + u], (unsigned)tot_cand);
+  // A candidate's exact score comes from its codes and the unit's table (same evaluation order
+  // as everywhere), or from the score array of the stand-alone top-k.
+  struct CandKey {
+    unsigned cb[SRC::kFromCodes ? SRC::M : 1];
+    float sc;
+  };
+  auto cand_token = [&](int c) -> int {
+    int i = 0;
+#pragma unroll
+    for (int x = 1; x < NW; ++x) i += (c >= ccand[x]) ? 1 : 0;
+    return wg_t0 + list[i * segN + segN - 1 - (c - ccand[i])];
+  };
+  auto cand_key_load = [&](int t) -> CandKey {
+    CandKey k;
+    k.sc = 0.0f;
+    if constexpr (SRC::kFromCodes) {
+      const uint8_t* cp = static_cast<const uint8_t*>(src_ptr) + ((size_t)u * s.N + t) * SRC::M;
+#pragma unroll
+      for (int j = 0; j < SRC::M; ++j) k.cb[j] = cp[j];
+    } else {
+      k.cb[0] = 0u;
+      k.sc = static_cast<const float*>(src_ptr)[(size_t)u * s.N + t];
+    }
+    return k;
+  };
+  auto cand_score = [&](const CandKey& k) -> float {
+    if constexpr (SRC::kFromCodes) {
+      const float* tb = ws.lut + (size_t)u * SRC::M * s.C;
+      float sc = tb[k.cb[0]];
+#pragma unroll
+      for (int j = 1; j < SRC::M; ++j) sc = __fadd_rn(sc, tb[j * s.C + k.cb[j]]);
+      return sc;
+    } else {
+      return k.sc;
+    }
+  };
   auto sel_at = [&](int p) -> int {
     int i = 0;
 #pragma unroll
@@ -411,6 +447,25 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
 
   const T* kbase = kc + (size_t)u * s.N * kD;
   const T* vbase = vc + (size_t)u * s.N * kD;
+  // The first candidates (one per 16-lane group): their codes and K/V rows are requested now, so that
+  // after the attention only the table look-up, arithmetic and the record write remain.
+  const int sub = lane & 15, grp = tid >> 4;
+  int c0_t = 0;
+  CandKey c0_key;
+  RowRaw<T> c0_k, c0_v;
+  c0_key.sc = 0.0f;
+#pragma unroll
+  for (int j = 0; j < (SRC::kFromCodes ? SRC::M : 1); ++j) c0_key.cb[j] = 0u;
+  c0_k.zero();
+  c0_v.zero();
+  if (grp < tot_cand) {
+    c0_t = cand_token(grp);
+    c0_key = cand_key_load(c0_t);
+    if constexpr (ATTN) {
+      c0_k.load(kbase, c0_t, sub);
+      c0_v.load(vbase, c0_t, sub);
+    }
+  }
   // Rows this workgroup attends: its own tokens above the threshold bin, and, instead of the
   // window tokens it happens to hold (the list's first nI and last nL entries), every
   // nblkC-th token of the two windows, so that the window rows are spread over the unit's
@@ -467,38 +522,29 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   PQC_NOTE(ws, 1, 15, tot_cand);
 
   // candidates (few): composite for the generic path, and a full record while slots last
-  auto cand_score = [&](int t) -> float {  // exact score, same evaluation order as everywhere
-    if constexpr (SRC::kFromCodes) {
-      const uint8_t* cp = static_cast<const uint8_t*>(src_ptr) + ((size_t)u * s.N + t) * SRC::M;
-      const float* tb = ws.lut + (size_t)u * SRC::M * s.C;
-      float sc = tb[cp[0]];
-#pragma unroll
-      for (int j = 1; j < SRC::M; ++j) sc = __fadd_rn(sc, tb[j * s.C + cp[j]]);
-      return sc;
-    } else {
-      return static_cast<const float*>(src_ptr)[(size_t)u * s.N + t];
-    }
-  };
   if (tot_cand > 0) {  // workgroup-uniform
-    if (tid == 0 && tot_cand > 0) scan_sm[0] = rec_base;
+    if (tid == 0) scan_sm[0] = rec_base;
     __syncthreads();
     const int base = scan_sm[0];
-    const int sub = lane & 15, grp = tid >> 4;  // 16 lanes per candidate
     for (int c = grp; c < tot_cand; c += NT / 16) {
-      int i = 0;
-#pragma unroll
-      for (int x = 1; x < NW; ++x) i += (c >= ccand[x]) ? 1 : 0;
-      const int t = wg_t0 + list[i * segN + segN - 1 - (c - ccand[i])];
-      const unsigned long long comp = make_composite(cand_score(t), t);
+      int t = c0_t;
+      CandKey key = c0_key;
+      RowRaw<T> kr = c0_k, vr = c0_v;
+      if (c >= NT / 16) {  // beyond the candidates whose loads went out before the attention
+        t = cand_token(c);
+        key = cand_key_load(t);
+        if constexpr (ATTN) {
+          kr.load(kbase, t, sub);
+          vr.load(vbase, t, sub);
+        }
+      }
+      const unsigned long long comp = make_composite(cand_score(key), t);
       if (sub == 0) stage[s.tokC - 1 - c] = comp;
       if (base + c < kCandRec) {
         unsigned char* rec = ws.cand_rec + ((size_t)u * kCandRec + base + c) * ws.rec_stride;
         CandHeader* hd = reinterpret_cast<CandHeader*>(rec);
         if (sub == 0) hd->composite = comp;
         if constexpr (ATTN) {
-          RowRaw<T> kr, vr;
-          kr.load(kbase, t, sub);
-          vr.load(vbase, t, sub);
           float kf[8];
           kr.unpack(kf);
 #pragma unroll
