@@ -26,7 +26,7 @@ def lib() -> C.CDLL:
         _LIB = C.CDLL(path)
         for name in ("pqo_kmeans", "pqo_pq_build", "pqo_nearest_codes", "pqo_scores",
                      "pqo_exact_scores", "pqo_select", "pqo_attention", "pqo_decode",
-                     "pqo_block_counts", "pqo_threads"):
+                     "pqo_block_counts", "pqo_block_topk", "pqo_threads"):
             getattr(_LIB, name).restype = C.c_int
     return _LIB
 
@@ -170,4 +170,13 @@ def block_counts(idx: np.ndarray, n_tokens: int, block: int) -> np.ndarray:
     out = np.empty((B, Hkv, nb), np.int32)
     _chk(lib().pqo_block_counts(_p(idx), B, Hkv, C.c_int64(n_tokens), C.c_int64(n_idx), block, _p(out)),
          "block_counts")
+    return out
+
+
+def block_topk(counts: np.ndarray, k_cache: int) -> np.ndarray:
+    """The k_cache blocks with the most selected tokens, best first (ties: lower block index)."""
+    counts = np.ascontiguousarray(counts, dtype=np.int32)
+    B, Hkv, nb = counts.shape
+    out = np.empty((B, Hkv, k_cache), np.int32)
+    _chk(lib().pqo_block_topk(_p(counts), B, Hkv, C.c_int64(nb), C.c_int64(k_cache), _p(out)), "block_topk")
     return out

@@ -386,3 +386,27 @@ int pqo_block_counts(const int32_t* idx, int B, int Hkv, int64_t N, int64_t n_id
     }
   return 0;
 }
+
+/* The blocks to refresh the cache with (Section 3.4): the k_cache blocks that hold the
+ * most selected tokens.  The paper does not say how equal counts are ordered: a lower
+ * block index ranks first here.  Plain selection sort of the best k_cache blocks.
+ *   counts [B][Hkv][nb]  ->  blocks [B][Hkv][k_cache] int32, best first
+ */
+int pqo_block_topk(const int32_t* counts, int B, int Hkv, int64_t nb, int64_t k_cache, int32_t* blocks) {
+  if (k_cache < 0 || k_cache > nb) return -1;
+  unsigned char* used = (unsigned char*)malloc((size_t)(nb > 0 ? nb : 1));
+  if (!used) return -3;
+  for (int64_t u = 0; u < (int64_t)B * Hkv; ++u) {
+    const int32_t* c = counts + u * nb;
+    memset(used, 0, (size_t)nb);
+    for (int64_t r = 0; r < k_cache; ++r) {
+      int64_t best = -1;
+      for (int64_t j = 0; j < nb; ++j)
+        if (!used[j] && (best < 0 || c[j] > c[best])) best = j; /* strict >: the lowest index wins a tie */
+      used[best] = 1;
+      blocks[u * k_cache + r] = (int32_t)best;
+    }
+  }
+  free(used);
+  return 0;
+}

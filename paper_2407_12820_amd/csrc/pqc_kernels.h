@@ -1062,24 +1062,43 @@ __global__ __launch_bounds__(256) void attn_list_kernel(Shape s, Workspace ws, c
   }
 }
 
+// Folds the partial softmax states of a unit into the outputs: grid (G, units), one
+// workgroup per query head, two threads per output dimension.
 template <int G>
 __global__ __launch_bounds__(256) void merge_kernel(Shape s, Workspace ws, int nparts, float* __restrict__ out_attn) {
-  const int u = blockIdx.y, b = u / s.Hkv, g = u % s.Hkv;
-  const float* parts = ws.partials + (size_t)u * s.npart * G * (kD + 2);
-  for (int o = threadIdx.x; o < G * kD; o += 256) {
-    const int h = o / kD, d = o % kD;
-    float m = kNegBig, l = 0.0f, acc = 0.0f;
-    for (int j = 0; j < nparts; ++j) {
-      const float* pj = parts + ((size_t)j * G + h) * (kD + 2);
-      const float mj = pj[0], lj = pj[1], aj = pj[2 + d];
-      const float mn = fmaxf(m, mj);
-      const float fa = __builtin_amdgcn_exp2f(m - mn), fb = __builtin_amdgcn_exp2f(mj - mn);
-      l = l * fa + lj * fb;
-      acc = acc * fa + aj * fb;
-      m = mn;
-    }
-    out_attn[((size_t)b * s.Hq + (size_t)g * G + h) * kD + d] = acc / l;
+  constexpr int NT = 256, NW = 4, kBatch = 16;
+  extern __shared__ float wsm[];  // [nparts] weights
+  __shared__ float fsm[NW];
+  __shared__ float half_acc[kD];
+  const int u = blockIdx.y, hq = blockIdx.x, b = u / s.Hkv, g = u % s.Hkv, tid = threadIdx.x;
+  const int d = tid & (kD - 1), half = tid >> 7;
+  const float* parts = ws.partials + ((size_t)u * s.npart * G + hq) * (kD + 2);
+  const size_t stride = (size_t)G * (kD + 2);
+  float mx = kNegBig;
+  for (int j = tid; j < nparts; j += NT) {
+    const float m = parts[j * stride];
+    wsm[j] = m;
+    mx = fmaxf(mx, m);
   }
+  const float mstar = block_max<NT>(mx, fsm);  // its barriers make wsm visible
+  float lsum = 0.0f;
+  for (int j = tid; j < nparts; j += NT) {
+    const float wj = __builtin_amdgcn_exp2f(wsm[j] - mstar);
+    wsm[j] = wj;
+    lsum = fmaf(wj, parts[j * stride + 1], lsum);
+  }
+  const float lstar = block_sum<NT>(lsum, fsm);
+  float acc = 0.0f;
+  for (int j0 = half; j0 < nparts; j0 += 2 * kBatch) {
+    float a[kBatch];
+#pragma unroll
+    for (int x = 0; x < kBatch; ++x) a[x] = parts[(size_t)min(j0 + 2 * x, nparts - 1) * stride + 2 + d];
+#pragma unroll
+    for (int x = 0; x < kBatch; ++x) acc = fmaf(j0 + 2 * x < nparts ? wsm[j0 + 2 * x] : 0.0f, a[x], acc);
+  }
+  if (half == 1) half_acc[d] = acc;
+  __syncthreads();
+  if (half == 0) out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + d] = (acc + half_acc[d]) / lstar;
 }
 
 }  // namespace pqc

@@ -371,3 +371,26 @@ def test_planted_tokens_are_retrieved_and_recall_beats_chance():
 def test_block_counts():
     idx = np.array([[[0, 1, 130, 255, 256, 700]]], np.int32)
     assert oracle.block_counts(idx, 1000, 128)[0, 0].tolist() == [2, 2, 1, 0, 0, 1, 0, 0]
+
+
+def test_block_topk_hand_example_and_stable_sort():
+    # hand example: counts 2 2 1 0 0 1 0 0 -> best four blocks 0, 1 (two each), then 2, 5 (one each)
+    c = np.array([[[2, 2, 1, 0, 0, 1, 0, 0]]], np.int32)
+    assert oracle.block_topk(c, 4)[0, 0].tolist() == [0, 1, 2, 5]
+    assert oracle.block_topk(c, 0).shape == (1, 1, 0)
+    assert oracle.block_topk(c, 8)[0, 0].tolist() == [0, 1, 2, 5, 3, 4, 6, 7]
+    # against a library routine: a stable argsort of the negated counts is the same order
+    rng = np.random.default_rng(5)
+    c = rng.integers(0, 6, size=(2, 3, 57)).astype(np.int32)
+    want = np.argsort(-c, axis=-1, kind="stable")[..., :20]
+    np.testing.assert_array_equal(oracle.block_topk(c, 20), want)
+
+
+def test_block_counts_against_bincount():
+    rng = np.random.default_rng(6)
+    idx = np.stack([rng.choice(5000, size=700, replace=False) for _ in range(6)]).reshape(2, 3, 700).astype(np.int32)
+    got = oracle.block_counts(idx, 5000, 128)
+    for b in range(2):
+        for g in range(3):
+            np.testing.assert_array_equal(got[b, g], np.bincount(idx[b, g] // 128, minlength=40))
+    assert got.sum() == idx.size
