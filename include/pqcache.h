@@ -198,6 +198,23 @@ int pqc_pq_assign(const pqc_config* cfg, const void* keys, const float* centroid
 int pqc_pq_encode_token(const pqc_config* cfg, const void* key, const float* centroids,
                         uint8_t* codes, int32_t position, void* stream);
 
+/* Block statistics for a block-level cache of hot K/V blocks (Section 3.4: after each
+ * retrieval the cache is refreshed with the k_cache blocks that contain the most
+ * retrieved tokens).  A block is block_tokens consecutive tokens, 1 <= block_tokens <= 2047;
+ * nb = ceil(N / block_tokens) with N from cfg.
+ *   idx     [B][Hkv][n_idx]  int32   listed tokens (e.g. out_idx of pqc_decode, or its
+ *                                    retrieved part); entries outside [0, N) are skipped;
+ *                                    the entries of one unit must be distinct
+ *   counts  [B][Hkv][nb]     int32   listed tokens per block (fully overwritten)
+ *   blocks  [B][Hkv][k_cache] int32  the k_cache blocks with the largest counts, a lower
+ *                                    block index winning among equal counts: first the
+ *                                    blocks above the cut in ascending order, then those
+ *                                    admitted at the cut in ascending order; may be NULL
+ *                                    when k_cache == 0.  0 <= k_cache <= nb.
+ * Needs no context and no workspace.  PQC_EINVAL on null pointers or sizes out of range. */
+int pqc_block_stats(const pqc_config* cfg, const int32_t* idx, int64_t n_idx, int32_t block_tokens,
+                    int32_t k_cache, int32_t* counts, int32_t* blocks, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -71,6 +71,8 @@ def load() -> C.CDLL:
     lib.pqc_pq_assign.argtypes = [cp, vp, vp, vp, vp]
     lib.pqc_pq_encode_token.restype = C.c_int
     lib.pqc_pq_encode_token.argtypes = [cp, vp, vp, vp, C.c_int32, vp]
+    lib.pqc_block_stats.restype = C.c_int
+    lib.pqc_block_stats.argtypes = [cp, vp, C.c_int64, C.c_int32, C.c_int32, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -285,6 +287,23 @@ def pq_encode_token(w: Workload, key: torch.Tensor, centroids: torch.Tensor, cod
                                  _need(codes, torch.uint8, (w.batch, w.n_kv_heads, w.n_tokens, w.pq_m), "codes"), position, st)
     if rc != 0:
         raise PQCacheError(rc, "pqc_pq_encode_token")
+
+
+def block_stats(w: Workload, idx: torch.Tensor, block_tokens: int, k_cache: int, stream=None):
+    """Listed tokens per block and the k_cache fullest blocks -> (counts [B][Hkv][nb], blocks [B][Hkv][k_cache])."""
+    lib = load()
+    cfg = make_config(w)
+    if idx.dtype != torch.int32 or idx.dim() != 3 or tuple(idx.shape[:2]) != (w.batch, w.n_kv_heads) or not idx.is_contiguous():
+        raise ValueError("idx must be a contiguous int32 tensor [B][Hkv][n_idx]")
+    nb = (w.n_tokens + block_tokens - 1) // block_tokens
+    counts = torch.empty((w.batch, w.n_kv_heads, nb), dtype=torch.int32, device=idx.device)
+    blocks = torch.empty((w.batch, w.n_kv_heads, k_cache), dtype=torch.int32, device=idx.device)
+    st = (stream if stream is not None else torch.cuda.current_stream(idx.device)).cuda_stream
+    rc = lib.pqc_block_stats(C.byref(cfg), idx.data_ptr(), idx.shape[2], block_tokens, k_cache, counts.data_ptr(),
+                             blocks.data_ptr() if k_cache > 0 else None, st)
+    if rc != 0:
+        raise PQCacheError(rc, "pqc_block_stats")
+    return counts, blocks
 
 
 def to_device(a, dtype: str, device="cuda:0") -> torch.Tensor:

@@ -507,4 +507,17 @@ int pqc_pq_encode_token(const pqc_config* cfg, const void* key, const float* cen
   return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
 }
 
+int pqc_block_stats(const pqc_config* cfg, const int32_t* idx, int64_t n_idx, int32_t block_tokens, int32_t k_cache,
+                    int32_t* counts, int32_t* blocks, void* stream) {
+  Plan p;
+  int rc = make_plan(cfg, &p);
+  if (rc != PQC_OK) return rc;
+  if (!idx || !counts || n_idx < 0 || block_tokens < 1 || block_tokens >= kCountBins) return PQC_EINVAL;
+  const int nb = (p.s.N + block_tokens - 1) / block_tokens;
+  if (k_cache < 0 || k_cache > nb || (k_cache > 0 && !blocks)) return PQC_EINVAL;
+  hipLaunchKernelGGL(block_stats_kernel, dim3((unsigned)(p.s.B * p.s.Hkv)), dim3(1024), 0, static_cast<hipStream_t>(stream),
+                     idx, (long long)n_idx, p.s.N, (int)block_tokens, nb, (int)k_cache, counts, blocks);
+  return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
+}
+
 }  // extern "C"

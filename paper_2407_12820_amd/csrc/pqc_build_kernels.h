@@ -129,4 +129,66 @@ __global__ __launch_bounds__(256) void pq_mean_kernel(BuildShape s, const unsign
   if (k) cent[i] = (float)((double)(long long)sums[i] * (1.0 / (double)(1 << kFixShift)) / (double)k);
 }
 
+// ------------------------------------------------------------ block statistics
+// Section 3.4: the block-level cache is refreshed with the k_cache blocks that hold the
+// most retrieved tokens.  One workgroup per unit: counts per block (global atomics, read
+// back through the L2 with returning atomics), a histogram of the count values (a count
+// never exceeds the block size when the listed tokens are distinct), the cut c* and the
+// number of blocks to admit at the cut, then an ordered compaction: blocks above the cut in
+// ascending order, then the lowest-numbered blocks at the cut.
+constexpr int kCountBins = 2048;
+__global__ __launch_bounds__(1024) void block_stats_kernel(const int* __restrict__ idx, long long n_idx, int N, int bt,
+                                                           int nb, int k_cache, int* __restrict__ counts,
+                                                           int* __restrict__ blocks) {
+  constexpr int NT = 1024, NW = NT / 64;
+  __shared__ unsigned hist[kCountBins];
+  __shared__ int scan_sm[2 * NW + 1];
+  __shared__ int res[2];
+  const int u = blockIdx.x, tid = threadIdx.x;
+  int* cu = counts + (size_t)u * nb;
+  for (int i = tid; i < nb; i += NT) cu[i] = 0;
+  for (int i = tid; i < kCountBins; i += NT) hist[i] = 0u;
+  if (tid == 0) {
+    res[0] = kCountBins;  // cut (no block reaches it when k_cache == 0)
+    res[1] = 0;           // blocks above the cut
+  }
+  __threadfence();
+  __syncthreads();
+  const int* lst = idx + (size_t)u * n_idx;
+  for (long long i = tid; i < n_idx; i += NT) {
+    const int t = lst[i];
+    if (t >= 0 && t < N) atomicAdd(&cu[t / bt], 1);
+  }
+  __threadfence();
+  __syncthreads();
+  for (int i = tid; i < nb; i += NT) atomicAdd(&hist[min(atomicAdd(&cu[i], 0), kCountBins - 1)], 1u);
+  __syncthreads();
+  // thread tid owns count values kCountBins-1-2*tid and kCountBins-2-2*tid (descending)
+  const int h0 = (int)hist[kCountBins - 1 - 2 * tid], h1 = (int)hist[kCountBins - 2 - 2 * tid];
+  int total;
+  int cum = block_exclusive_scan<NT>(h0 + h1, &total, scan_sm);
+  if (k_cache > 0 && cum < k_cache && cum + h0 >= k_cache) {
+    res[0] = kCountBins - 1 - 2 * tid;
+    res[1] = cum;
+  } else if (k_cache > 0 && cum + h0 < k_cache && cum + h0 + h1 >= k_cache) {
+    res[0] = kCountBins - 2 - 2 * tid;
+    res[1] = cum + h0;
+  }
+  __syncthreads();
+  const int cut = res[0], n_above = res[1], need = k_cache - n_above;
+  int* out = blocks + (size_t)u * k_cache;
+  int carry_a = 0, carry_t = 0;
+  for (int i0 = 0; i0 < (k_cache > 0 ? nb : 0); i0 += NT) {
+    const int i = i0 + tid;
+    const int c = i < nb ? min(atomicAdd(&cu[i], 0), kCountBins - 1) : -1;
+    int ta, tt;
+    const int pa = block_exclusive_scan<NT>(c > cut ? 1 : 0, &ta, scan_sm);
+    const int pt = block_exclusive_scan<NT>(c == cut ? 1 : 0, &tt, scan_sm);
+    if (c > cut) out[carry_a + pa] = i;
+    if (c == cut && carry_t + pt < need) out[n_above + carry_t + pt] = i;
+    carry_a += ta;
+    carry_t += tt;
+  }
+}
+
 }  // namespace pqc

@@ -133,3 +133,22 @@ def test_decode_after_gpu_pq_build(pqc):
     got = idx.cpu().numpy()
     found = np.mean([np.isin(planted[0, g], got[0, g]).mean() for g in range(w.n_kv_heads)])
     assert found > 0.9, f"only {found:.2f} of the planted tokens were retrieved"
+
+
+@pytest.mark.parametrize("block,k_cache", [(128, 20), (128, 0), (64, 7), (2047, 3), (1, 300), (100, 79)])
+def test_block_stats_match_oracle(pqc, block, k_cache):
+    # per-block counts of the attended tokens and the k_cache fullest blocks (Section 3.4)
+    w = wl.Workload(name="blocks", batch=2, n_q_heads=4, n_kv_heads=2, head_dim=128, n_tokens=7900, pq_m=2, pq_centroids=16,
+                    topk=900, n_init=4, n_local=64, dtype="bf16", kmeans_iters=1, recipe="plain")
+    rng = np.random.default_rng(block * 1000 + k_cache)
+    # clumped selections, so that counts differ and tie at the same time
+    idx = np.stack([np.sort(rng.choice(np.arange(0, w.n_tokens, 3) if u % 2 else w.n_tokens, size=w.n_selected, replace=False))
+                    for u in range(4)]).reshape(2, 2, -1).astype(np.int32)
+    nb = (w.n_tokens + block - 1) // block
+    k_cache = min(k_cache, nb)
+    counts, blocks = pqc.block_stats(w, torch.from_numpy(idx).to(DEV), block, k_cache)
+    torch.cuda.synchronize()
+    want_c = oracle.block_counts(idx, w.n_tokens, block)
+    np.testing.assert_array_equal(counts.cpu().numpy(), want_c)
+    want_b = oracle.block_topk(want_c, k_cache)
+    np.testing.assert_array_equal(np.sort(blocks.cpu().numpy(), -1), np.sort(want_b, -1))
