@@ -834,18 +834,6 @@ __device__ __forceinline__ void mfma_issue(const bf16_t* __restrict__ kbase, con
 __device__ __forceinline__ void mfma_consume(const MfmaStage& g, int count, int base, float scale_log2e,
                                              const bf16x8_t (&qf)[4], unsigned char* vt, MfmaState& st) {
   const int lane = threadIdx.x & 63, col = lane & 15, quad = lane >> 4;
-#ifdef PQC_EXP_NO_COMPUTE
-  {
-    unsigned x = 0;
-#pragma unroll
-    for (int tl = 0; tl < kMfmaTiles; ++tl)
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) x += g.kr[tl][kk].x ^ g.kr[tl][kk].w ^ g.vr[tl][kk].y ^ g.vr[tl][kk].z;
-    st.l += __uint_as_float(x & 0xff);
-    st.m = 0.0f;
-    return;
-  }
-#endif
   // logits of the stage
   f32x4_t s[kMfmaTiles];
   float mx = kNegBig;
