@@ -2,9 +2,10 @@
 // head g); blockIdx.x = workgroup inside the unit (query head for finalize_kernel).
 //
 // Decode path (pqc_decode), three launches, every dependency at a kernel boundary:
-//   hist_kernel      table -> scan codes -> histogram of scores over kNB bins
-//   select_kernel    threshold bin from the histogram -> scan codes again -> tokens
-//                    above the bin (and the two windows) are listed in ascending order
+//   hist_kernel      table -> scan codes -> histogram of scores over kNB bins, and every
+//                    token's bin number left behind for the next kernel
+//   select_kernel    threshold bin from the histogram -> tokens whose stored bin lies
+//                    above it (and the two windows) are listed in ascending order
 //                    without atomics and attended at once; tokens inside the bin
 //                    ("candidates") are recorded with their logits and V row
 //   finalize_kernel  one workgroup per query head ranks the candidates and folds the
