@@ -170,6 +170,25 @@ def test_all_scores_equal_takes_lowest_indices(pqc):
     full_check(p, idx, out)
 
 
+@pytest.mark.parametrize("sample_value", [-1.0, 10.0])
+def test_topk_when_the_sample_misleads(pqc, sample_value):
+    # The bin window is placed from 1024 evenly spaced tokens.  Give exactly those tokens one
+    # extreme score: the window then misses the K-th largest score altogether (it falls into the
+    # coarse bins above the window, or into the single bin below it, where every low token becomes
+    # a candidate).  Only speed may suffer: the selection must still be the oracle's.
+    w = _small(n_tokens=20068, topk=5000, n_q_heads=2, n_kv_heads=2)
+    rng = np.random.default_rng(11)
+    s32 = rng.random((1, 2, w.n_tokens), dtype=np.float32)
+    nmid = w.n_tokens - w.n_init - w.n_local
+    pos = w.n_init + (np.arange(1024, dtype=np.int64) * nmid) // 1024
+    s32[:, :, pos] = sample_value
+    ctx = pqc.PQCache(w, DEV)
+    got = ctx.topk(torch.from_numpy(s32).to(DEV))
+    torch.cuda.synchronize()
+    want = oracle.select(s32, w.topk, w.n_init, w.n_local)
+    np.testing.assert_array_equal(np.sort(got.cpu().numpy(), -1), np.sort(want, -1))
+
+
 def test_context_reuse_and_two_contexts(pqc):
     # Calls on one context leave the workspace ready for the next call; contexts do not interfere.
     wa, wb = _small(topk=123), _small(n_tokens=5000, topk=900, pq_m=4)
