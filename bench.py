@@ -158,6 +158,24 @@ def main() -> int:
                      "bytes_per_launch": sel_bytes, "avg_us": round(float(kern_us[1]), 3)},
     }
 
+    # the same step through pqc_decode_indexed (threshold from code-pair counts; two partitions only):
+    # reported beside `value`, which stays the general path whose inputs are centroids and codes alone
+    if w.pq_m == 2 and w.pq_centroids <= 64 and w.n_tokens % 8 == 0:
+        pcs = [binding.pair_counts(w, st[2]) for st in sets]
+        pptr = [ctx._pair_ptr(pc) for pc in pcs]
+        for i in range(args.warmup):
+            ctx.decode_indexed_marshalled(margs[i % len(sets)], pptr[i % len(sets)], stream_handle)
+        torch.cuda.synchronize()
+        ev0.record()
+        for i in range(args.steps):
+            ctx.decode_indexed_marshalled(margs[i % len(sets)], pptr[i % len(sets)], stream_handle)
+        ev1.record()
+        torch.cuda.synchronize()
+        us_i = ev0.elapsed_time(ev1) / args.steps * 1e3
+        result["indexed_path"] = {"entry_point": "pqc_decode_indexed", "us_per_layer": round(us_i, 3),
+                                  "hbm_frac": round(path_bytes / (us_i * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                                  "extra_input": "tokens per code pair, [units][C*C] uint32, built once per code tensor"}
+
     # PQ construction on the GPU (not part of the decode step): K-Means over all cached keys of one layer
     result["pq_build"] = {"ms_per_layer": round(float(np.median(build_ms)), 3), "kmeans_iters": w.kmeans_iters,
                           "note": "host-timed pqc_pq_build, median over the input sets"}

@@ -128,6 +128,27 @@ int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_
                const void* k_cache, const void* v_cache, int32_t* out_idx, float* out_attn,
                void* stream);
 
+/* The same step for PQ structures with two partitions of at most 64 centroids, where a
+ * token's score takes one of C*C values (one per pair of codes): the threshold of the
+ * top-k selection (Section 3.1 steps 4-5) then follows from the look-up table and from how
+ * many tokens carry each pair, without a separate pass over the tokens.  Results are those
+ * of pqc_decode (same scores, same selection, same attention).
+ *   pair_counts [B][Hkv][C*C] uint32  tokens of the unit whose codes are (c0, c1), at index
+ *                                     c0 + C*c1, over all N tokens: a statistic of `codes`
+ *                                     alone, built by pqc_pair_counts and kept in step with
+ *                                     appended codes by pqc_pair_counts_add (caller-owned)
+ * PQC_EUNSUPPORTED unless pq_m == 2, pq_centroids <= 64 and n_tokens is a multiple of 8. */
+int pqc_decode_indexed(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes,
+                       const uint32_t* pair_counts, const void* k_cache, const void* v_cache,
+                       int32_t* out_idx, float* out_attn, void* stream);
+
+/* pair_counts of a whole code tensor (fully overwritten), and the update for the one code
+ * pair written at `position` of every unit (call after pqc_pq_encode_token for a position
+ * that was not counted before).  Need no context.  pq_m == 2 and pq_centroids <= 64. */
+int pqc_pair_counts(const pqc_config* cfg, const uint8_t* codes, uint32_t* pair_counts, void* stream);
+int pqc_pair_counts_add(const pqc_config* cfg, const uint8_t* codes, int32_t position, uint32_t* pair_counts,
+                        void* stream);
+
 /* Profiling aid: the kernels of pqc_decode one at a time.  phase 0 = histogram, 1 =
  * select + attention, 2 = finalize; calling phases 0, 1, 2 in this order with the same
  * arguments is exactly one pqc_decode (same kernels, same results).  It lets a harness

@@ -71,6 +71,12 @@ def load() -> C.CDLL:
     lib.pqc_pq_assign.argtypes = [cp, vp, vp, vp, vp]
     lib.pqc_pq_encode_token.restype = C.c_int
     lib.pqc_pq_encode_token.argtypes = [cp, vp, vp, vp, C.c_int32, vp]
+    lib.pqc_decode_indexed.restype = C.c_int
+    lib.pqc_decode_indexed.argtypes = [vp] * 10
+    lib.pqc_pair_counts.restype = C.c_int
+    lib.pqc_pair_counts.argtypes = [cp, vp, vp, vp]
+    lib.pqc_pair_counts_add.restype = C.c_int
+    lib.pqc_pair_counts_add.argtypes = [cp, vp, C.c_int32, vp, vp]
     lib.pqc_block_stats.restype = C.c_int
     lib.pqc_block_stats.argtypes = [cp, vp, C.c_int64, C.c_int32, C.c_int32, vp, vp, vp]
     _lib = lib
@@ -182,6 +188,23 @@ class PQCache:
     def decode_marshalled(self, args, stream_handle: int) -> None:
         self._check(self.lib.pqc_decode(self.handle, *args, stream_handle), "pqc_decode")
 
+    def decode_indexed(self, q, centroids, codes, pair_counts, k_cache, v_cache, out_idx=None, out_attn=None, stream=None):
+        """pqc_decode_indexed: the same step with the threshold taken from code-pair counts (two partitions)."""
+        if out_idx is None or out_attn is None:
+            out_idx, out_attn = self.empty_outputs()
+        a = self.marshal_decode_args(q, centroids, codes, k_cache, v_cache, out_idx, out_attn)
+        self.decode_indexed_marshalled(a, self._pair_ptr(pair_counts), self._stream(stream))
+        return out_idx, out_attn
+
+    def _pair_ptr(self, pair_counts) -> int:
+        w = self.w
+        return self._ptr(pair_counts, torch.int32, (w.batch, w.n_kv_heads, w.pq_centroids * w.pq_centroids))
+
+    def decode_indexed_marshalled(self, args, pair_ptr: int, stream_handle: int) -> None:
+        q, cent, codes, k, v, oi, oa = args
+        self._check(self.lib.pqc_decode_indexed(self.handle, q, cent, codes, pair_ptr, k, v, oi, oa, stream_handle),
+                    "pqc_decode_indexed")
+
     def decode_phase_marshalled(self, phase: int, args, stream_handle: int) -> None:
         """One kernel of pqc_decode (0 histogram, 1 select + attention, 2 finalize); see the header."""
         self._check(self.lib.pqc_decode_phase(self.handle, phase, *args, stream_handle), "pqc_decode_phase")
@@ -287,6 +310,28 @@ def pq_encode_token(w: Workload, key: torch.Tensor, centroids: torch.Tensor, cod
                                  _need(codes, torch.uint8, (w.batch, w.n_kv_heads, w.n_tokens, w.pq_m), "codes"), position, st)
     if rc != 0:
         raise PQCacheError(rc, "pqc_pq_encode_token")
+
+
+def pair_counts(w: Workload, codes: torch.Tensor, stream=None) -> torch.Tensor:
+    """Tokens per pair of codes, [B][Hkv][C*C] (uint32 values in an int32 tensor); two partitions only."""
+    lib = load()
+    cfg = make_config(w)
+    _need(codes, torch.uint8, (w.batch, w.n_kv_heads, w.n_tokens, w.pq_m), "codes")
+    out = torch.empty((w.batch, w.n_kv_heads, w.pq_centroids * w.pq_centroids), dtype=torch.int32, device=codes.device)
+    st = (stream if stream is not None else torch.cuda.current_stream(codes.device)).cuda_stream
+    rc = lib.pqc_pair_counts(C.byref(cfg), codes.data_ptr(), out.data_ptr(), st)
+    if rc != 0:
+        raise PQCacheError(rc, "pqc_pair_counts")
+    return out
+
+
+def pair_counts_add(w: Workload, codes: torch.Tensor, position: int, counts: torch.Tensor, stream=None) -> None:
+    lib = load()
+    cfg = make_config(w)
+    st = (stream if stream is not None else torch.cuda.current_stream(codes.device)).cuda_stream
+    rc = lib.pqc_pair_counts_add(C.byref(cfg), codes.data_ptr(), position, counts.data_ptr(), st)
+    if rc != 0:
+        raise PQCacheError(rc, "pqc_pair_counts_add")
 
 
 def block_stats(w: Workload, idx: torch.Tensor, block_tokens: int, k_cache: int, stream=None):

@@ -191,6 +191,37 @@ void launch_decode_t(pqc_ctx* ctx, const void* q, const float* cent, const uint8
   }
 }
 
+// decode with the threshold taken from code-pair counts (M = 2): select + finalize, no histogram kernel
+template <typename T, int G>
+void launch_indexed_tg(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const unsigned* pair_counts,
+                       const void* k, const void* v, int32_t* out_idx, float* out_attn, hipStream_t st) {
+  const Shape& s = ctx->plan.s;
+  const unsigned units = (unsigned)(s.B * s.Hkv);
+  const T* qt = static_cast<const T*>(q);
+  const T* kt = static_cast<const T*>(k);
+  const T* vt = static_cast<const T*>(v);
+  hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<2>, true, true>), dim3(s.nblkC, units), dim3(256),
+                     s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes), cent,
+                     pair_counts);
+  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st,
+                     s, ctx->ws, qt, kt, vt, out_idx, out_attn);
+}
+
+template <typename T>
+void launch_indexed_t(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const unsigned* pair_counts,
+                      const void* k, const void* v, int32_t* out_idx, float* out_attn, hipStream_t st) {
+  switch (ctx->plan.s.G) {
+    case 1: launch_indexed_tg<T, 1>(ctx, q, cent, codes, pair_counts, k, v, out_idx, out_attn, st); break;
+    case 2: launch_indexed_tg<T, 2>(ctx, q, cent, codes, pair_counts, k, v, out_idx, out_attn, st); break;
+    case 4: launch_indexed_tg<T, 4>(ctx, q, cent, codes, pair_counts, k, v, out_idx, out_attn, st); break;
+    default: launch_indexed_tg<T, 8>(ctx, q, cent, codes, pair_counts, k, v, out_idx, out_attn, st); break;
+  }
+}
+
+bool pairs_supported(const pqc_config* c) {
+  return c->pq_m == 2 && c->pq_centroids <= kPairC && c->n_tokens % 8 == 0;
+}
+
 template <typename T, int G>
 void launch_attn_tg(pqc_ctx* ctx, const void* q, const void* k, const void* v, const int32_t* idx, float* out,
                     hipStream_t st) {
@@ -325,6 +356,57 @@ static int decode_impl(pqc_ctx* ctx, const void* q, const float* centroids, cons
 int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes, const void* k_cache,
                const void* v_cache, int32_t* out_idx, float* out_attn, void* stream) {
   return decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 7u);
+}
+
+int pqc_decode_indexed(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes,
+                       const uint32_t* pair_counts, const void* k_cache, const void* v_cache, int32_t* out_idx,
+                       float* out_attn, void* stream) {
+  if (!ctx || !q || !centroids || !codes || !pair_counts || !k_cache || !v_cache || !out_idx || !out_attn) return PQC_EINVAL;
+  if (!aligned16(q) || !aligned16(centroids) || !aligned16(codes) || !aligned16(pair_counts) || !aligned16(k_cache) ||
+      !aligned16(v_cache) || !aligned16(out_idx) || !aligned16(out_attn))
+    return PQC_EINVAL;
+  if (!pairs_supported(&ctx->cfg)) return PQC_EUNSUPPORTED;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = ensure_clean_hist(ctx, st);  // the record counters live with the histograms
+  if (rc != PQC_OK) return rc;
+  ctx->hist_clean = false;
+  if (ctx->cfg.kv_dtype == PQC_F32)
+    launch_indexed_t<float>(ctx, q, centroids, codes, pair_counts, k_cache, v_cache, out_idx, out_attn, st);
+  else
+    launch_indexed_t<bf16_t>(ctx, q, centroids, codes, pair_counts, k_cache, v_cache, out_idx, out_attn, st);
+  rc = check_launch(ctx);
+  if (rc == PQC_OK) {
+    ctx->hist_clean = true;
+    ctx->plan.s.parity ^= 1;
+  }
+  return rc;
+}
+
+int pqc_pair_counts(const pqc_config* cfg, const uint8_t* codes, uint32_t* pair_counts, void* stream) {
+  Plan p;
+  const int rc = make_plan(cfg, &p);
+  if (rc != PQC_OK) return rc;
+  if (!codes || !pair_counts) return PQC_EINVAL;
+  if (cfg->pq_m != 2 || cfg->pq_centroids > kPairC) return PQC_EUNSUPPORTED;
+  const Shape& s = p.s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const size_t n = (size_t)s.B * s.Hkv * s.C * s.C;
+  hipLaunchKernelGGL(reset_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, pair_counts, n);
+  hipLaunchKernelGGL(pair_count_kernel, dim3((unsigned)((s.N + kPairTok - 1) / kPairTok), (unsigned)(s.B * s.Hkv)), dim3(256), 0,
+                     st, codes, s.N, s.C, pair_counts);
+  return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
+}
+
+int pqc_pair_counts_add(const pqc_config* cfg, const uint8_t* codes, int32_t position, uint32_t* pair_counts, void* stream) {
+  Plan p;
+  const int rc = make_plan(cfg, &p);
+  if (rc != PQC_OK) return rc;
+  if (!codes || !pair_counts || position < 0 || position >= cfg->n_tokens) return PQC_EINVAL;
+  if (cfg->pq_m != 2 || cfg->pq_centroids > kPairC) return PQC_EUNSUPPORTED;
+  const int units = p.s.B * p.s.Hkv;
+  hipLaunchKernelGGL(pair_count_add_kernel, dim3((unsigned)((units + 63) / 64)), dim3(64), 0, static_cast<hipStream_t>(stream),
+                     codes, p.s.N, p.s.C, units, (int)position, pair_counts);
+  return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
 }
 
 int pqc_decode_phase(pqc_ctx* ctx, int phase, const void* q, const float* centroids, const uint8_t* codes,

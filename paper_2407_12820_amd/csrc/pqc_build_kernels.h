@@ -191,4 +191,36 @@ __global__ __launch_bounds__(1024) void block_stats_kernel(const int* __restrict
   }
 }
 
+// -------------------------------------------------------------- code-pair counts
+// M = 2: how many tokens of a unit carry each pair of codes (c0 + C*c1), over all N tokens.
+// A statistic of the codes alone; pqc_decode_indexed takes its threshold from it.
+constexpr int kPairTok = 8192;  // tokens per workgroup
+__global__ __launch_bounds__(256) void pair_count_kernel(const uint8_t* __restrict__ codes, int N, int C,
+                                                         unsigned* __restrict__ counts) {
+  __shared__ unsigned h[4096];
+  const int u = blockIdx.y, tid = threadIdx.x, np = C * C;
+  for (int i = tid; i < np; i += 256) h[i] = 0u;
+  __syncthreads();
+  const unsigned short* cu = reinterpret_cast<const unsigned short*>(codes) + (size_t)u * N;
+  const int t1 = min(N, ((int)blockIdx.x + 1) * kPairTok);
+  for (int t = blockIdx.x * kPairTok + tid; t < t1; t += 256) {
+    const unsigned cw = cu[t];
+    const int pr = (int)(cw & 0xffu) + C * (int)(cw >> 8);
+    if (pr < np) atomicAdd(&h[pr], 1u);
+  }
+  __syncthreads();
+  for (int i = tid; i < np; i += 256)
+    if (h[i]) atomicAdd(&counts[(size_t)u * np + i], h[i]);
+}
+
+// one appended token per unit: its pair gains a token
+__global__ void pair_count_add_kernel(const uint8_t* __restrict__ codes, int N, int C, int units, int position,
+                                      unsigned* __restrict__ counts) {
+  const int u = blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= units) return;
+  const uint8_t* cp = codes + ((size_t)u * N + position) * 2;
+  const int pr = (int)cp[0] + C * (int)cp[1];
+  if (pr < C * C) counts[(size_t)u * C * C + pr] += 1u;
+}
+
 }  // namespace pqc

@@ -541,6 +541,207 @@ struct ThresholdSearch {
   }
 };
 
+// ------------------------------------------------- threshold from code-pair counts
+// With M = 2 and C <= 64 a token's score takes one of C*C values, one per pair of codes.
+// Given how many tokens carry each pair (a statistic of the codes alone, kept with them),
+// the K-th largest score follows from the table without a pass over the tokens: weight
+// the C*C pair scores by their counts, find the uniform score bin that holds the K-th
+// largest, then resolve the few pairs inside that bin exactly.  The result is the score
+// key of the K-th largest middle token: larger keys are selected, equal keys are
+// candidates (ranked by token index later).  Scores use the same fp32 order as everywhere.
+constexpr int kPairSlots = 4096;  // C*C <= kPairSlots
+constexpr int kPairC = 64;        // largest C
+constexpr int kPairList = 256;    // pairs resolved by direct ranking; more fall back to a radix search
+struct PairLds {
+  unsigned cnt[kPairSlots];       // tokens per pair (c0 + C*c1), window tokens taken out
+  float lut[2 * kPairC];          // table[j][c] at j*kPairC + c
+  float qs[kD];
+  unsigned hist[kNB];
+  unsigned long long lst[kPairList];  // (key << 32) | count of the pairs in the threshold bin
+  int res[8];
+};
+struct PairThreshold {
+  unsigned key;  // score key of the K-th largest middle token
+  bool none;     // K == 0: nothing is retrieved
+};
+
+template <typename T, int NT>
+__device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T* __restrict__ q /* [G][kD] of the unit */,
+                                                        const float* __restrict__ cent /* [2][C][64] of the unit */,
+                                                        const unsigned* __restrict__ pair_counts /* [C*C] of the unit */,
+                                                        const uint8_t* __restrict__ codes_u /* [N][2] of the unit */,
+                                                        PairLds& L, int* scan_sm /* [2*(NT/64)+1] */) {
+  static_assert(NT == 256, "written for 256 threads");
+  constexpr int Dm = kD / 2, PPT = kPairSlots / NT, BPT = kNB / NT;
+  const int tid = threadIdx.x, C = s.C, np = C * C;
+  // ---- loads: one table entry's centroid per thread (2C threads), query, counts, window codes
+  const int e = min(tid, 2 * C - 1);
+  const float4* crow = reinterpret_cast<const float4*>(cent + (size_t)e * Dm);
+  float4 cr[Dm / 4];
+#pragma unroll
+  for (int x = 0; x < Dm / 4; ++x) cr[x] = crow[x];
+  float qv[8];
+#pragma unroll
+  for (int h = 0; h < 8; ++h) qv[h] = load_as_float<T>(q, min(h, s.G - 1) * kD + (tid & (kD - 1)));
+  unsigned pc[PPT];
+#pragma unroll
+  for (int x = 0; x < PPT; ++x) pc[x] = pair_counts[min(x * NT + tid, np - 1)];
+  const int nwin = s.I + s.L;
+  unsigned short wcode = 0;  // first window token of this thread (the usual case: I + L <= NT)
+  {
+    const int wt = min(tid, max(nwin - 1, 0));
+    const int t = wt < s.I ? wt : s.N - s.L + (wt - s.I);
+    wcode = *reinterpret_cast<const unsigned short*>(codes_u + (size_t)min(max(t, 0), s.N - 1) * 2);
+  }
+  PQC_LOADS_ISSUED();
+  {
+    float a = qv[0];
+#pragma unroll
+    for (int h = 1; h < 8; ++h) {
+      const float t = __fadd_rn(a, qv[h]);
+      a = h < s.G ? t : a;
+    }
+    if (tid < kD) L.qs[tid] = a;
+  }
+#pragma unroll
+  for (int x = 0; x < PPT; ++x)
+    if (x * NT + tid < np) L.cnt[x * NT + tid] = pc[x];
+#pragma unroll
+  for (int x = 0; x < BPT; ++x) L.hist[x * NT + tid] = 0u;
+  if (tid < 8) L.res[tid] = 0;
+  __syncthreads();
+  // ---- table entries (fixed-order chain) and the window tokens taken out of the counts
+  if (tid < 2 * C) {
+    const int j = tid / C, c = tid - j * C;
+    const float* qj = L.qs + j * Dm;
+    float p = 0.0f;
+#pragma unroll
+    for (int x = 0; x < Dm / 4; ++x) {
+      p = __fmaf_rn(qj[4 * x + 0], cr[x].x, p);
+      p = __fmaf_rn(qj[4 * x + 1], cr[x].y, p);
+      p = __fmaf_rn(qj[4 * x + 2], cr[x].z, p);
+      p = __fmaf_rn(qj[4 * x + 3], cr[x].w, p);
+    }
+    L.lut[j * kPairC + c] = p;
+  }
+  for (int wt = tid; wt < nwin; wt += NT) {
+    unsigned short cw = wcode;
+    if (wt >= NT) {
+      const int t = wt < s.I ? wt : s.N - s.L + (wt - s.I);
+      cw = *reinterpret_cast<const unsigned short*>(codes_u + (size_t)t * 2);
+    }
+    const int pr = (cw & 0xff) + C * (cw >> 8);
+    if (pr < np) atomicSub(&L.cnt[pr], 1u);
+  }
+  __syncthreads();
+  // ---- bounds (added in the same order as a score), weighted histogram over uniform bins
+  float mn0 = INFINITY, mx0 = -INFINITY, mn1 = INFINITY, mx1 = -INFINITY;
+  for (int c = 0; c < C; ++c) {
+    const float a = L.lut[c], b = L.lut[kPairC + c];
+    mn0 = fminf(mn0, a); mx0 = fmaxf(mx0, a);
+    mn1 = fminf(mn1, b); mx1 = fmaxf(mx1, b);
+  }
+  const float lo = __fadd_rn(mn0, mn1), hi = __fadd_rn(mx0, mx1), width = hi - lo;
+  const float inv = (width > 1e-30f && width < 3e38f) ? (float)kNB / width : 0.0f;
+  unsigned pkey[PPT];
+  int pbin[PPT];
+#pragma unroll
+  for (int x = 0; x < PPT; ++x) {
+    const int pr = x * NT + tid;
+    const int c1 = min(pr, np - 1) / C, c0 = min(pr, np - 1) - c1 * C;
+    const float sc = __fadd_rn(L.lut[c0], L.lut[kPairC + c1]);
+    pkey[x] = score_key(sc);
+    pbin[x] = max(0, min(kNB - 1, __float2int_rz((sc - lo) * inv)));
+    pc[x] = pr < np ? L.cnt[pr] : 0u;
+    if (pc[x]) atomicAdd(&L.hist[pbin[x]], pc[x]);
+  }
+  __syncthreads();
+  // ---- the bin that holds the K-th largest: thread tid owns bins kNB-1-(tid*BPT+e), descending
+  unsigned h[BPT];
+  int sum = 0;
+#pragma unroll
+  for (int x = 0; x < BPT; ++x) {
+    h[x] = L.hist[kNB - 1 - (tid * BPT + x)];
+    sum += (int)h[x];
+  }
+  int total;
+  int cum = block_exclusive_scan<NT>(sum, &total, scan_sm);
+  if (tid == 0) {
+    L.res[0] = -1;  // threshold bin
+    L.res[1] = 0;   // tokens in bins above it
+  }
+  __syncthreads();
+#pragma unroll
+  for (int x = 0; x < BPT; ++x) {
+    if (s.K > 0 && cum < s.K && cum + (int)h[x] >= s.K) {
+      L.res[0] = kNB - 1 - (tid * BPT + x);
+      L.res[1] = cum;
+    }
+    cum += (int)h[x];
+  }
+  __syncthreads();
+  const int bstar = L.res[0];
+  const int want = s.K - L.res[1];  // rank of the K-th largest among the tokens of bin bstar (1-based)
+  PairThreshold out;
+  out.none = bstar < 0;
+  out.key = 0xffffffffu;
+  if (bstar < 0) return out;  // uniform
+  // ---- the pairs of that bin
+#pragma unroll
+  for (int x = 0; x < PPT; ++x)
+    if (pc[x] && pbin[x] == bstar) {
+      const int slot = atomicAdd(&L.res[2], 1);
+      if (slot < kPairList) L.lst[slot] = ((unsigned long long)pkey[x] << 32) | pc[x];
+    }
+  __syncthreads();
+  const int n_in = L.res[2];
+  if (n_in <= kPairList) {
+    if (tid < n_in) {
+      const unsigned long long mine = L.lst[tid];
+      const unsigned mk = (unsigned)(mine >> 32);
+      long long above = 0, same = 0;
+      for (int j = 0; j < n_in; ++j) {
+        const unsigned long long o = L.lst[j];
+        const unsigned ok = (unsigned)(o >> 32), oc = (unsigned)o;
+        above += ok > mk ? oc : 0u;
+        same += ok == mk ? oc : 0u;
+      }
+      if (above < want && want <= above + same) L.res[3] = (int)mk;
+    }
+    __syncthreads();
+    out.key = (unsigned)L.res[3];
+  } else {
+    // many pairs share the bin (nearly equal scores): 8-bit radix search over their keys
+    unsigned prefix = 0u;
+    long long w = want;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      L.hist[tid] = 0u;  // 256 digits
+      __syncthreads();
+#pragma unroll
+      for (int x = 0; x < PPT; ++x)
+        if (pc[x] && pbin[x] == bstar && (shift == 24 || (pkey[x] >> (shift + 8)) == (prefix >> (shift + 8))))
+          atomicAdd(&L.hist[(pkey[x] >> shift) & 255u], pc[x]);
+      __syncthreads();
+      if (tid == 0) {
+        long long c2 = 0;
+        int dg = 255;
+        for (; dg > 0; --dg) {
+          if (c2 + (long long)L.hist[dg] >= w) break;
+          c2 += L.hist[dg];
+        }
+        L.res[4] = dg;
+        L.res[5] = (int)(w - c2);
+      }
+      __syncthreads();
+      prefix |= (unsigned)L.res[4] << shift;
+      w = L.res[5];
+      __syncthreads();
+    }
+    out.key = prefix;
+  }
+  return out;
+}
+
 // ------------------------------------------------------- attention, vector ALU
 // Section 2.1 restricted to listed tokens (Section 3.1 step 6).  Lane layout inside
 // a wave: sub = lane & 15 owns 8 of the 128 dimensions of a row, slot = lane >> 4

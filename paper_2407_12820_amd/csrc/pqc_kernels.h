@@ -303,13 +303,19 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
 // candidates from the back.  SRC is only used to score the few candidates exactly.
 constexpr int kMaxVecC = 4;  // 8-token groups per lane (tokC <= 8192)
 
-template <typename T, int G, class SRC, bool ATTN>
+// PAIRS (M = 2 only): there is no histogram kernel in front; the threshold comes from the
+// code-pair counts (pair_threshold) and tokens are classified by their exact score keys.
+template <typename T, int G, class SRC, bool ATTN, bool PAIRS = false>
 __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, const T* __restrict__ q,
                                                      const T* __restrict__ kc, const T* __restrict__ vc,
-                                                     const void* __restrict__ src_ptr) {
+                                                     const void* __restrict__ src_ptr,
+                                                     const float* __restrict__ cent = nullptr,
+                                                     const unsigned* __restrict__ pair_counts = nullptr) {
   constexpr int NT = 256, NW = 4;
   constexpr bool kMfma = ATTN && sizeof(T) == 2;
+  static_assert(!PAIRS || (SRC::kFromCodes && SRC::M == 2), "pair counts exist for two partitions only");
   extern __shared__ unsigned short list[];  // [tokC] token offsets from the workgroup's first token
+  __shared__ std::conditional_t<PAIRS, PairLds, int> pl;
   __shared__ int scan_sm[2 * NW + 1 + 4];
   __shared__ int wcnt[2 * NW];
   __shared__ float red[ATTN ? NW * G * (kD + 2) : 1];
@@ -322,11 +328,15 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   const int tpw = s.tokC / NW;           // tokens per wave, in groups of 8 per lane
   const int gpw = (tpw + 511) / 512;     // groups per lane: 1, 2 or 4 (the last lanes idle when tpw < 512)
   const int wave_t0 = blockIdx.x * s.tokC + w * tpw;
-  const unsigned short* bins_u = ws.bins + (size_t)u * s.binStride;
+  // 16 bytes per group of 8 tokens: their stored bins, or (PAIRS) their codes
+  const unsigned short* bins_u =
+      PAIRS ? reinterpret_cast<const unsigned short*>(static_cast<const uint8_t*>(src_ptr) + (size_t)u * s.N * 2)
+            : ws.bins + (size_t)u * s.binStride;
+  const int last_group = PAIRS ? s.N - 8 : s.binStride - 8;  // PAIRS: N is a multiple of 8
   uint4 raw[kMaxVecC];
 #pragma unroll
   for (int v = 0; v < kMaxVecC; ++v)
-    raw[v] = *reinterpret_cast<const uint4*>(bins_u + wave_t0 + min((v * 64 + lane) * 8, tpw - 8));
+    raw[v] = *reinterpret_cast<const uint4*>(bins_u + min(wave_t0 + min((v * 64 + lane) * 8, tpw - 8), last_group));
   constexpr int QV = ATTN ? (G * kD + NT - 1) / NT : 1;  // query elements per thread
   float qreg[QV];
   if constexpr (ATTN) {
@@ -334,15 +344,29 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
     for (int x = 0; x < QV; ++x)
       qreg[x] = load_as_float<T>(q + ((size_t)b * s.Hq + (size_t)g * G) * kD, min(x * NT + tid, G * kD - 1));
   }
-  ThresholdSearch<NT> ts;
-  ts.load(ws.hist + ((size_t)s.parity * units + u) * kHistCopies * kNB);
-  PQC_LOADS_ISSUED();
-  if constexpr (ATTN) {
+  Threshold th{0, 0, 0, 0};
+  PairThreshold pth{0u, true};
+  if constexpr (PAIRS) {
+    PQC_LOADS_ISSUED();
+    if constexpr (ATTN) {
 #pragma unroll
-    for (int x = 0; x < QV; ++x)
-      if (x * NT + tid < G * kD) qlds[x * NT + tid] = qreg[x];
+      for (int x = 0; x < QV; ++x)
+        if (x * NT + tid < G * kD) qlds[x * NT + tid] = qreg[x];
+    }
+    pth = pair_threshold<T, NT>(s, q + ((size_t)b * s.Hq + (size_t)g * G) * kD, cent + (size_t)u * 2 * s.C * (kD / 2),
+                                pair_counts + (size_t)u * s.C * s.C, static_cast<const uint8_t*>(src_ptr) + (size_t)u * s.N * 2,
+                                pl, scan_sm);  // syncs: qlds ready
+  } else {
+    ThresholdSearch<NT> ts;
+    ts.load(ws.hist + ((size_t)s.parity * units + u) * kHistCopies * kNB);
+    PQC_LOADS_ISSUED();
+    if constexpr (ATTN) {
+#pragma unroll
+      for (int x = 0; x < QV; ++x)
+        if (x * NT + tid < G * kD) qlds[x * NT + tid] = qreg[x];
+    }
+    th = ts.resolve(s.K, scan_sm);  // syncs: qlds ready
   }
-  const Threshold th = ts.resolve(s.K, scan_sm);  // syncs: qlds ready
   PQC_MARK(ws, 1, 1);
 
   const int segN = s.tokC / NW;
@@ -359,8 +383,17 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const unsigned st = (wv[i >> 1] >> (16 * (i & 1))) & 0xffffu;
-        selm |= (st > thr ? 1u : 0u) << i;
-        candm |= (st == thr ? 1u : 0u) << i;
+        if constexpr (PAIRS) {
+          const int t = t0 + i;
+          const bool window = t < s.I || t >= s.N - s.L;
+          const unsigned key =
+              score_key(__fadd_rn(pl.lut[min(st & 0xffu, (unsigned)kPairC - 1)], pl.lut[kPairC + min(st >> 8, (unsigned)kPairC - 1)]));
+          selm |= ((window || (!pth.none && key > pth.key)) ? 1u : 0u) << i;
+          candm |= ((!window && !pth.none && key == pth.key) ? 1u : 0u) << i;
+        } else {
+          selm |= (st > thr ? 1u : 0u) << i;
+          candm |= (st == thr ? 1u : 0u) << i;
+        }
       }
       const int nreal = (v * 64 + lane) * 8 < tpw ? min(8, max(0, s.N - t0)) : 0;  // tokens of this group that exist
       selm &= (1u << nreal) - 1u;
@@ -424,7 +457,9 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
     return k;
   };
   auto cand_score = [&](const CandKey& k) -> float {
-    if constexpr (SRC::kFromCodes) {
+    if constexpr (PAIRS) {
+      return __fadd_rn(pl.lut[min(k.cb[0], (unsigned)kPairC - 1)], pl.lut[kPairC + min(k.cb[1], (unsigned)kPairC - 1)]);
+    } else if constexpr (SRC::kFromCodes) {
       const float* tb = ws.lut + (size_t)u * SRC::M * s.C;
       float sc = tb[k.cb[0]];
 #pragma unroll

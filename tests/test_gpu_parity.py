@@ -224,6 +224,69 @@ def test_decode_phase_by_phase_equals_decode(pqc):
     full_check(p, a[0], a[1])
 
 
+@pytest.mark.parametrize("kw", [
+    dict(),                                                          # llama8b_128k scaled
+    dict(n_tokens=4096, topk=512, n_q_heads=1, n_kv_heads=1, dtype="f32", pq_centroids=64),
+    dict(topk=0),
+    dict(n_tokens=3000 - 3000 % 8, topk=2000, pq_centroids=7),       # few pairs, big tie classes
+    dict(n_tokens=72, topk=1),
+    dict(n_tokens=2048, n_local=300, n_init=9, topk=100),            # more window tokens than threads
+], ids=lambda kw: ",".join(f"{k}={v}" for k, v in kw.items()) or "scaled")
+def test_indexed_decode_equals_decode(pqc, kw):
+    # threshold from code-pair counts: same selection and attention as the general path, and as the oracle
+    if kw:
+        w = _small(**{**dict(pq_m=2, pq_centroids=16, n_tokens=3000 - 3000 % 8), **kw})
+    else:
+        w = wl.get("llama8b_128k", n_tokens=20008)
+    p = build_problem(w, seed=12)
+    dev, ctx = upload(pqc, p), pqc.PQCache(w, DEV)
+    counts = pqc.pair_counts(w, dev["codes"])
+    torch.cuda.synchronize()
+    want_counts = np.zeros((w.batch, w.n_kv_heads, w.pq_centroids ** 2), np.int64)
+    pair = p.codes[..., 0].astype(np.int64) + w.pq_centroids * p.codes[..., 1].astype(np.int64)
+    for b in range(w.batch):
+        for g in range(w.n_kv_heads):
+            want_counts[b, g] = np.bincount(pair[b, g], minlength=w.pq_centroids ** 2)
+    np.testing.assert_array_equal(counts.cpu().numpy(), want_counts)
+    for _ in range(2):
+        idx, out = ctx.decode_indexed(dev["q"], dev["centroids"], dev["codes"], counts, dev["k"], dev["v"])
+        torch.cuda.synchronize()
+        full_check(p, idx.cpu().numpy(), out.cpu().numpy())
+    a = run_decode(pqc, p, ctx, dev)
+    np.testing.assert_array_equal(np.sort(a[0], -1), np.sort(idx.cpu().numpy(), -1))
+
+
+def test_indexed_decode_zero_query_and_unsupported(pqc):
+    # all scores equal: one bin holds every pair (the radix branch of the threshold search)
+    w = _small(pq_m=2, pq_centroids=64, n_tokens=3000 - 3000 % 8, topk=1500)
+    p = build_problem(w, seed=13)
+    p = type(p)(w, np.zeros_like(p.q), p.k, p.v, p.centroids, p.codes, p.checked_units)
+    dev, ctx = upload(pqc, p), pqc.PQCache(w, DEV)
+    counts = pqc.pair_counts(w, dev["codes"])
+    idx, out = ctx.decode_indexed(dev["q"], dev["centroids"], dev["codes"], counts, dev["k"], dev["v"])
+    torch.cuda.synchronize()
+    assert np.all(np.sort(idx.cpu().numpy()[0, 0, 4:1504]) == np.arange(4, 1504))
+    full_check(p, idx.cpu().numpy(), out.cpu().numpy())
+    # four partitions: no pair counts
+    w4 = _small(pq_m=4)
+    with pytest.raises(pqc.PQCacheError):
+        pqc.pair_counts(w4, torch.zeros((1, 2, 3000, 4), dtype=torch.uint8, device=DEV))
+
+
+def test_pair_counts_follow_an_appended_code(pqc):
+    w = _small(pq_m=2, pq_centroids=16, n_tokens=1000)
+    rng = np.random.default_rng(3)
+    codes = torch.from_numpy(rng.integers(0, 16, size=(1, 2, 1000, 2), dtype=np.uint8)).to(DEV)
+    full = pqc.pair_counts(w, codes)
+    # counts of the first 999 tokens, then token 999 appended
+    codes2 = codes.clone()
+    codes2[:, :, 999, :] = 255  # outside the code range: not counted
+    part = pqc.pair_counts(w, codes2)
+    pqc.pair_counts_add(w, codes, 999, part)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(full.cpu().numpy(), part.cpu().numpy())
+
+
 def test_decode_is_deterministic(pqc):
     w = wl.get("llama8b_128k", n_tokens=20011)
     p = build_problem(w, seed=1)
