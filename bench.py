@@ -33,6 +33,7 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=8, help="distinct input sets visited round-robin")
     ap.add_argument("--profile-steps", type=int, default=24, help="rounds of the per-kernel timing (each launches every kernel once per input set)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-indexed", action="store_true", help="skip the pqc_decode_indexed measurement")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--also", default="llama70b_128k", help="second workload reported alongside (step time only); '' to skip")
     ap.add_argument("--also-layers", type=int, default=3)
@@ -160,7 +161,7 @@ def main() -> int:
 
     # the same step through pqc_decode_indexed (threshold from code-pair counts; two partitions only):
     # reported beside `value`, which stays the general path whose inputs are centroids and codes alone
-    if w.pq_m == 2 and w.pq_centroids <= 64 and w.n_tokens % 8 == 0:
+    if not args.no_indexed and w.pq_m == 2 and w.pq_centroids <= 64 and w.n_tokens % 8 == 0:
         pcs = [binding.pair_counts(w, st[2]) for st in sets]
         pptr = [ctx._pair_ptr(pc) for pc in pcs]
         for i in range(args.warmup):

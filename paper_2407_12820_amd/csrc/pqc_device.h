@@ -107,6 +107,10 @@ __device__ __forceinline__ unsigned score_key(float f) {
   return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
 }
 
+__device__ __forceinline__ float key_score(unsigned k) {  // inverse of score_key
+  return __uint_as_float(k ^ ((k >> 31) ? 0x80000000u : 0xffffffffu));
+}
+
 __device__ __forceinline__ unsigned long long make_composite(float score, int token) {
   // larger composite = ranks first: higher score, then lower token index
   return ((unsigned long long)score_key(score) << 32) | (unsigned long long)(0xffffffffu - (unsigned)token);
@@ -565,12 +569,12 @@ struct PairThreshold {
   bool none;     // K == 0: nothing is retrieved
 };
 
-template <typename T, int NT>
+template <typename T, int NT, class MarkFn>
 __device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T* __restrict__ q /* [G][kD] of the unit */,
                                                         const float* __restrict__ cent /* [2][C][64] of the unit */,
                                                         const unsigned* __restrict__ pair_counts /* [C*C] of the unit */,
                                                         const uint8_t* __restrict__ codes_u /* [N][2] of the unit */,
-                                                        PairLds& L, int* scan_sm /* [2*(NT/64)+1] */) {
+                                                        PairLds& L, int* scan_sm /* [2*(NT/64)+1] */, MarkFn mark) {
   static_assert(NT == 256, "written for 256 threads");
   constexpr int Dm = kD / 2, PPT = kPairSlots / NT, BPT = kNB / NT;
   const int tid = threadIdx.x, C = s.C, np = C * C;
@@ -583,7 +587,7 @@ __device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T*
   float qv[8];
 #pragma unroll
   for (int h = 0; h < 8; ++h) qv[h] = load_as_float<T>(q, min(h, s.G - 1) * kD + (tid & (kD - 1)));
-  unsigned pc[PPT];
+  unsigned pc[PPT];  // pair x*NT + tid
 #pragma unroll
   for (int x = 0; x < PPT; ++x) pc[x] = pair_counts[min(x * NT + tid, np - 1)];
   const int nwin = s.I + s.L;
@@ -608,8 +612,9 @@ __device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T*
     if (x * NT + tid < np) L.cnt[x * NT + tid] = pc[x];
 #pragma unroll
   for (int x = 0; x < BPT; ++x) L.hist[x * NT + tid] = 0u;
-  if (tid < 8) L.res[tid] = 0;
+  if (tid < 8) L.res[tid] = (tid == 4 || tid == 6) ? -1 : 0;  // slots 4..7: (min, max) keys of the two partitions
   __syncthreads();
+  mark(9);
   // ---- table entries (fixed-order chain) and the window tokens taken out of the counts
   if (tid < 2 * C) {
     const int j = tid / C, c = tid - j * C;
@@ -623,6 +628,9 @@ __device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T*
       p = __fmaf_rn(qj[4 * x + 3], cr[x].w, p);
     }
     L.lut[j * kPairC + c] = p;
+    const unsigned pk = score_key(p);  // per-partition minimum and maximum, through order-preserving keys
+    atomicMin(reinterpret_cast<unsigned*>(&L.res[4 + 2 * j]), pk);
+    atomicMax(reinterpret_cast<unsigned*>(&L.res[5 + 2 * j]), pk);
   }
   for (int wt = tid; wt < nwin; wt += NT) {
     unsigned short cw = wcode;
@@ -634,13 +642,10 @@ __device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T*
     if (pr < np) atomicSub(&L.cnt[pr], 1u);
   }
   __syncthreads();
+  mark(10);
   // ---- bounds (added in the same order as a score), weighted histogram over uniform bins
-  float mn0 = INFINITY, mx0 = -INFINITY, mn1 = INFINITY, mx1 = -INFINITY;
-  for (int c = 0; c < C; ++c) {
-    const float a = L.lut[c], b = L.lut[kPairC + c];
-    mn0 = fminf(mn0, a); mx0 = fmaxf(mx0, a);
-    mn1 = fminf(mn1, b); mx1 = fmaxf(mx1, b);
-  }
+  const float mn0 = key_score((unsigned)L.res[4]), mx0 = key_score((unsigned)L.res[5]);
+  const float mn1 = key_score((unsigned)L.res[6]), mx1 = key_score((unsigned)L.res[7]);
   const float lo = __fadd_rn(mn0, mn1), hi = __fadd_rn(mx0, mx1), width = hi - lo;
   const float inv = (width > 1e-30f && width < 3e38f) ? (float)kNB / width : 0.0f;
   unsigned pkey[PPT];
@@ -648,7 +653,14 @@ __device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T*
 #pragma unroll
   for (int x = 0; x < PPT; ++x) {
     const int pr = x * NT + tid;
-    const int c1 = min(pr, np - 1) / C, c0 = min(pr, np - 1) - c1 * C;
+    int c1, c0;
+    if (C == kPairC) {  // uniform; spares an integer division per pair
+      c1 = pr >> 6;
+      c0 = pr & (kPairC - 1);
+    } else {
+      c1 = min(pr, np - 1) / C;
+      c0 = min(pr, np - 1) - c1 * C;
+    }
     const float sc = __fadd_rn(L.lut[c0], L.lut[kPairC + c1]);
     pkey[x] = score_key(sc);
     pbin[x] = max(0, min(kNB - 1, __float2int_rz((sc - lo) * inv)));
@@ -656,6 +668,7 @@ __device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T*
     if (pc[x]) atomicAdd(&L.hist[pbin[x]], pc[x]);
   }
   __syncthreads();
+  mark(11);
   // ---- the bin that holds the K-th largest: thread tid owns bins kNB-1-(tid*BPT+e), descending
   unsigned h[BPT];
   int sum = 0;
@@ -686,6 +699,7 @@ __device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T*
   out.none = bstar < 0;
   out.key = 0xffffffffu;
   if (bstar < 0) return out;  // uniform
+  mark(12);
   // ---- the pairs of that bin
 #pragma unroll
   for (int x = 0; x < PPT; ++x)
@@ -700,11 +714,16 @@ __device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T*
       const unsigned long long mine = L.lst[tid];
       const unsigned mk = (unsigned)(mine >> 32);
       long long above = 0, same = 0;
-      for (int j = 0; j < n_in; ++j) {
-        const unsigned long long o = L.lst[j];
-        const unsigned ok = (unsigned)(o >> 32), oc = (unsigned)o;
-        above += ok > mk ? oc : 0u;
-        same += ok == mk ? oc : 0u;
+      for (int j0 = 0; j0 < n_in; j0 += 8) {  // eight independent LDS reads per round
+        unsigned long long o[8];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) o[x] = L.lst[min(j0 + x, n_in - 1)];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          const unsigned ok = (unsigned)(o[x] >> 32), oc = j0 + x < n_in ? (unsigned)o[x] : 0u;
+          above += ok > mk ? oc : 0u;
+          same += ok == mk ? oc : 0u;
+        }
       }
       if (above < want && want <= above + same) L.res[3] = (int)mk;
     }

@@ -355,7 +355,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
     }
     pth = pair_threshold<T, NT>(s, q + ((size_t)b * s.Hq + (size_t)g * G) * kD, cent + (size_t)u * 2 * s.C * (kD / 2),
                                 pair_counts + (size_t)u * s.C * s.C, static_cast<const uint8_t*>(src_ptr) + (size_t)u * s.N * 2,
-                                pl, scan_sm);  // syncs: qlds ready
+                                pl, scan_sm, [&](int slot) { PQC_MARK(ws, 1, slot); });  // syncs: qlds ready
   } else {
     ThresholdSearch<NT> ts;
     ts.load(ws.hist + ((size_t)s.parity * units + u) * kHistCopies * kNB);
