@@ -82,3 +82,36 @@ def test_create_checks_workspace_and_null_arguments():
     assert lib.pqc_last_hip_error(h) == 0
     lib.pqc_destroy(h)
     lib.pqc_destroy(None)
+
+
+def test_argument_checks_of_the_newer_entry_points():
+    # all of these are refused on the host, before any device call
+    lib = binding.load()
+    tiny = wl.CONFIGS["tiny_f32"]            # M = 2, C = 64, N = 4096
+    cfg = binding.make_config(tiny)
+    p = C.c_void_p(4096)
+    # block statistics: block size 1..2047, 0 <= k_cache <= number of blocks, blocks needed when k_cache > 0
+    assert lib.pqc_block_stats(C.byref(cfg), p, 10, 0, 1, p, p, None) == -1
+    assert lib.pqc_block_stats(C.byref(cfg), p, 10, 2048, 1, p, p, None) == -1
+    assert lib.pqc_block_stats(C.byref(cfg), p, 10, 128, 33, p, p, None) == -1
+    assert lib.pqc_block_stats(C.byref(cfg), p, 10, 128, 4, p, None, None) == -1
+    assert lib.pqc_block_stats(C.byref(cfg), None, 10, 128, 4, p, p, None) == -1
+    assert lib.pqc_block_stats(C.byref(cfg), p, -1, 128, 4, p, p, None) == -1
+    # code-pair counts exist for two partitions of at most 64 centroids
+    four = binding.make_config(wl.CONFIGS["batch8_32k"])
+    assert lib.pqc_pair_counts(C.byref(four), p, p, None) == -2
+    assert lib.pqc_pair_counts_add(C.byref(four), p, 0, p, None) == -2
+    assert lib.pqc_pair_counts(C.byref(cfg), None, p, None) == -1
+    assert lib.pqc_pair_counts_add(C.byref(cfg), p, 4096, p, None) == -1
+    # decode phases 0..2 only; indexed decode needs its pair counts and a supported shape
+    need = lib.pqc_workspace_bytes(C.byref(cfg))
+    h = C.c_void_p()
+    assert lib.pqc_create(C.byref(h), C.byref(cfg), C.c_void_p(4096), need) == 0
+    assert lib.pqc_decode_phase(h, 3, *([p] * 7), None) == -1
+    assert lib.pqc_decode_phase(h, -1, *([p] * 7), None) == -1
+    assert lib.pqc_decode_indexed(h, p, p, p, None, p, p, p, p, None) == -1
+    lib.pqc_destroy(h)
+    need4 = lib.pqc_workspace_bytes(C.byref(four))
+    assert lib.pqc_create(C.byref(h), C.byref(four), C.c_void_p(4096), need4) == 0
+    assert lib.pqc_decode_indexed(h, *([p] * 9), None) == -2
+    lib.pqc_destroy(h)
