@@ -68,6 +68,7 @@ int make_plan(const pqc_config* c, Plan* p) {
   }
   if (tokA % 1024 || tokA > maxA) return PQC_EINVAL;
   s.tokA = tokA; s.nblkA = (s.N + lead + tokA - 1) / tokA;
+  s.histCopies = s.nblkA <= 32 ? 1 : s.nblkA <= 64 ? 2 : kHistCopies;
   // select kernel: 256-thread workgroups, two resident per compute unit
   int tokC = env_int("PQC_TOK_C", 0);
   if (!tokC) {
@@ -77,6 +78,7 @@ int make_plan(const pqc_config* c, Plan* p) {
   if (tokC != 512 && tokC != 1024 && tokC != 2048 && tokC != 4096 && tokC != 8192) return PQC_EINVAL;
   s.tokC = tokC; s.nblkC = (s.N + tokC - 1) / tokC;
   s.binStride = s.nblkC * s.tokC;
+  s.stageStride = s.tokC + 40;
   s.rowsP = env_int("PQC_ROWS_P", 256);
   s.nblkP = (s.Ktot + s.rowsP - 1) / s.rowsP;
   s.npart = s.nblkC > s.nblkP ? s.nblkC : s.nblkP;
@@ -102,7 +104,7 @@ int make_plan(const pqc_config* c, Plan* p) {
   p->off_hist = off;  off = align_up(off + sizeof(unsigned) * 2 * units * (kHistCopies * kNB + 1));  // + record counters
   p->off_bins = off;  off = align_up(off + sizeof(unsigned short) * units * s.binStride);
   p->off_crec = off;  off = align_up(off + (size_t)p->rec_stride * kCandRec * units);
-  p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * s.nblkC * s.tokC);
+  p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * s.nblkC * s.stageStride);
   p->off_cnt = off;   off = align_up(off + sizeof(int2) * units * s.nblkC);
   p->off_part = off;  off = align_up(off + sizeof(float) * units * s.npart * s.G * (kD + 2));
 #ifdef PQC_TRACE

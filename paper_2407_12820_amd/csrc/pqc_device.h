@@ -12,7 +12,7 @@
 namespace pqc {
 
 constexpr int kNB = 2048;        // score bins of the one-pass threshold search
-constexpr int kHistCopies = 4;   // histogram replicas per unit (spreads contended atomics)
+constexpr int kHistCopies = 4;   // histogram replica slots per unit; Shape::histCopies of them are in use
 constexpr int kD = 128;          // head dimension
 constexpr int kLutRow = 256;     // LDS stride of one partition's table (max centroids)
 constexpr int kCandRec = 1024;   // boundary-bin candidate records per unit (ranked inside LDS by the finalize kernel)
@@ -35,6 +35,9 @@ struct Shape {
   int npart;        // partial slots per unit
   int parity;       // which of the two histogram sets this call uses
   int binStride;    // stored bins per unit (nblkC * tokC)
+  int stageStride;  // 8-byte words between the staging slots of consecutive select workgroups: tokC plus a pad, so that
+                    // the slots do not all start on the same memory channels
+  int histCopies;   // histogram replicas in use (1, 2 or 4): spreads the flush atomics of units with many workgroups
   int sampleN;      // tokens sampled per unit to place the fine bins (<= 1024)
   int rankHi, rankLo;  // sample ranks (from the top) that bracket the K-th largest score
   float scale_log2e;
@@ -54,11 +57,11 @@ struct Workspace {
   BinParams* ctl;              // [units]                       score -> bin map of the unit
   float* lut;                  // [units][M][C]
   float2* range;               // [units]                       (min, max) score, stand-alone top-k only
-  unsigned* hist;              // [2][units][kHistCopies][kNB]   zero between uses
+  unsigned* hist;              // [2][units][histCopies][kNB]   zero between uses (room for kHistCopies replicas)
   unsigned* cand_count;        // [2][units]   records handed out so far (directly behind hist, zeroed with it)
   unsigned short* bins;        // [units][binStride]  per token: bin + 1, or kBinWindow inside the two windows
   unsigned char* cand_rec;     // [units][kCandRec] records of rec_stride bytes, in order of arrival
-  unsigned long long* stage;   // [units][nblkC][tokC] selected ids (front, int32) / candidate composites (back, u64)
+  unsigned long long* stage;   // [units][nblkC][stageStride]: selected ids (front, int32) / candidate composites (ending at word tokC)
   int2* stage_cnt;             // [units][nblkC]     (selected, candidates)
   float* partials;             // [units][npart][G][kD+2]
   int rec_stride;
@@ -492,12 +495,12 @@ struct ThresholdSearch {
   static constexpr int PER = kNB / NT;
   static_assert(PER % 4 == 0, "bins per thread must allow 16-byte loads");
   uint4 x[kHistCopies][PER / 4];
-  __device__ __forceinline__ void load(const unsigned* __restrict__ ghist) {
+  __device__ __forceinline__ void load(const unsigned* __restrict__ ghist, int copies) {
 #pragma unroll
     for (int c = 0; c < kHistCopies; ++c) {
       const uint4* src = reinterpret_cast<const uint4*>(ghist + c * kNB + kNB - (threadIdx.x + 1) * PER);
 #pragma unroll
-      for (int v = 0; v < PER / 4; ++v) x[c][v] = src[v];
+      for (int v = 0; v < PER / 4; ++v) x[c][v] = c < copies ? src[v] : make_uint4(0u, 0u, 0u, 0u);  // uniform
     }
   }
   __device__ __forceinline__ Threshold resolve(int K, int* sm /* [2*(NT/64)+1+4] */) const {

@@ -182,7 +182,7 @@ __global__ __launch_bounds__(1024) void score_range_kernel(Shape s, const float*
 // SRC = ScoreChunks: bounds come from score_range_kernel.  Every workgroup of a unit
 // then derives the same bin layout from the same sampled tokens (workgroup 0 publishes
 // table and layout for the select kernel) and counts its own tokens.  Workgroups of a
-// unit spread their counts over kHistCopies replicas.
+// unit spread their counts over histCopies replicas.
 template <typename T, class SRC>
 __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const T* __restrict__ q,
                                                     const float* __restrict__ cent, const void* __restrict__ src_ptr) {
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   if ((tid & 63) == 0 && n_low) atomicAdd(&hist[0], (unsigned)n_low);
   __syncthreads();
   PQC_MARK(ws, 0, 3);
-  unsigned* gh = ws.hist + (((size_t)s.parity * units + u) * kHistCopies + (bx % kHistCopies)) * kNB;
+  unsigned* gh = ws.hist + (((size_t)s.parity * units + u) * s.histCopies + (bx % s.histCopies)) * kNB;
   for (int i = tid; i < kNB; i += NT)
     if (hist[i]) atomicAdd(&gh[i], hist[i]);
   PQC_MARK(ws, 0, 4);
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
                                 pl, scan_sm, [&](int slot) { PQC_MARK(ws, 1, slot); });  // syncs: qlds ready
   } else {
     ThresholdSearch<NT> ts;
-    ts.load(ws.hist + ((size_t)s.parity * units + u) * kHistCopies * kNB);
+    ts.load(ws.hist + ((size_t)s.parity * units + u) * s.histCopies * kNB, s.histCopies);
     PQC_LOADS_ISSUED();
     if constexpr (ATTN) {
 #pragma unroll
@@ -477,7 +477,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   };
 
   // selected list for the finalize kernel's index output
-  unsigned long long* stage = ws.stage + ((size_t)u * s.nblkC + blockIdx.x) * s.tokC;
+  unsigned long long* stage = ws.stage + ((size_t)u * s.nblkC + blockIdx.x) * s.stageStride;
   int* stage32 = reinterpret_cast<int*>(stage);
   PQC_MARK(ws, 1, 3);
 
@@ -670,7 +670,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
   float* pm = reinterpret_cast<float*>(dyn + 2 * (s.nblkC + 1));
   float* pl = pm + s.nblkC;
   const int2* cnt = ws.stage_cnt + (size_t)u * s.nblkC;
-  const unsigned long long* stage_u = ws.stage + (size_t)u * s.nblkC * s.tokC;
+  const unsigned long long* stage_u = ws.stage + (size_t)u * s.nblkC * s.stageStride;
   int* out = out_idx + (size_t)u * s.Ktot;
   PQC_MARK(ws, 2, 0);
 
@@ -708,7 +708,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
 #pragma unroll
     for (int x = 0; x < kIdxLists; ++x) {
       const int j = min(cw * NW + w + x * ncw * NW, s.nblkC - 1);
-      const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.tokC);
+      const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.stageStride);
 #pragma unroll
       for (int y = 0; y < 4; ++y) ix[x][y] = src[min(y * 64 + lane, 2 * s.tokC - 1)];
     }
@@ -721,7 +721,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
     int x = 0;
     for (int j = cw * NW + w; j < s.nblkC; j += ncw * NW, ++x) {
       const int base = pre_sel[j], n = pre_sel[j + 1] - base;
-      const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.tokC);
+      const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.stageStride);
       for (int p0 = 0; p0 < n; p0 += 256) {
         int v[4];
         if (x < kIdxLists && p0 == 0) {
@@ -741,8 +741,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
     }
     PQC_MARK(ws, 2, 4);
     if (cw == 0) {  // leave the other parity's histogram and record counter zeroed for the next call
-      unsigned* gh = ws.hist + ((size_t)(s.parity ^ 1) * units + u) * kHistCopies * kNB;
-      for (int i = tid; i < kHistCopies * kNB; i += NT) gh[i] = 0u;
+      unsigned* gh = ws.hist + ((size_t)(s.parity ^ 1) * units + u) * s.histCopies * kNB;
+      for (int i = tid; i < s.histCopies * kNB; i += NT) gh[i] = 0u;
       if (tid == 0) ws.cand_count[(size_t)(s.parity ^ 1) * units + u] = 0u;
     }
     PQC_MARK(ws, 2, 5);
@@ -966,7 +966,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
     };
     auto cand_at = [&](int i) -> unsigned long long {
       const int j = owner(i);
-      return stage_u[(size_t)j * s.tokC + s.tokC - 1 - (i - pre_cand[j])];
+      return stage_u[(size_t)j * s.stageStride + s.tokC - 1 - (i - pre_cand[j])];
     };
     unsigned long long thr = ~0ull;
     if (need > 0) {
