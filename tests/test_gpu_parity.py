@@ -143,6 +143,7 @@ def _small(**kw):
     dict(pq_m=4, pq_centroids=7, n_q_heads=16, n_kv_heads=2, topk=999, n_tokens=4097),
     dict(dtype="f32", n_q_heads=8, n_kv_heads=1, topk=511, n_tokens=2500),
     dict(batch=3, n_tokens=2049, topk=100),
+    dict(batch=3, n_q_heads=8, n_kv_heads=4, n_tokens=5000, topk=500),  # 12 units: 8 interleaved over the XCDs + 4
     # tie classes of different sizes at the threshold: about 90, 190, 380 and 1500 equal scores
     dict(pq_m=1, pq_centroids=32, topk=500),
     dict(pq_m=1, pq_centroids=16, topk=700),
@@ -156,6 +157,16 @@ def test_edge_shapes(pqc, kw):
     w = _small(**kw)
     print(f"[case] edge {kw}", flush=True)
     p = build_problem(w, seed=3)
+    idx, out = run_decode(pqc, p)
+    full_check(p, idx, out)
+
+
+@pytest.mark.timeout(600)
+def test_maximum_context_length(pqc):
+    # N = 2^22, the largest context the library accepts: 512 select workgroups of 8192 tokens
+    w = _small(n_tokens=1 << 22, topk=150000, n_q_heads=1, n_kv_heads=1, pq_centroids=16, kmeans_iters=1)
+    print(f"[case] maximum context {w}", flush=True)
+    p = build_problem(w, seed=14)
     idx, out = run_decode(pqc, p)
     full_check(p, idx, out)
 
