@@ -264,15 +264,19 @@ __device__ __forceinline__ float load_as_float<bf16_t>(const bf16_t* p, int i) {
 // is a single pass; with fewer threads the table goes through a tile of kLutTileFloats
 // floats piece by piece.
 constexpr int kLutTileFloats = 8192;
+// Row stride of the whole-table tile.  Long rows (one or two partitions: few entries, few busy
+// waves) are padded by four floats and read 128 bits at a time; short rows keep every thread busy
+// and measured faster with an odd stride and 32-bit accesses.
+__host__ __device__ constexpr int lut_row_stride(int M) { return M <= 2 ? kD / M + 4 : kD / M + 1; }
 __host__ __device__ constexpr int lut_tile_floats(int nt, int M, int C) {
-  return nt >= 1024 ? C * (kD + M) : kLutTileFloats + kLutTileFloats / (kD / M);
+  return nt >= 1024 ? M * C * lut_row_stride(M) : kLutTileFloats + kLutTileFloats / (kD / M);
 }
 template <typename T, int NT, int M, class MarkFn>
 __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] of this unit */,
                                                const float* __restrict__ cent /* [M][C][Dm] */, int G, int C,
                                                float* lut, float* qs, float* red /* [4*8] */,
                                                float* tile /* [lut_tile_floats(NT, M, C)] */, MarkFn mark) {
-  constexpr int Dm = kD / M;
+  constexpr int Dm = kD / M, RS = lut_row_stride(M);
   constexpr bool kWhole = NT >= 1024;
   constexpr int VW = kWhole ? (256 * kD) / (4 * NT) : 1;  // float4 per thread for the largest table
   constexpr int VPG = kLutTileFloats / (4 * NT);      // float4 per thread per tile (piecewise mode)
@@ -307,18 +311,39 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
       const int fl = (x * NT + tid) * 4;  // float index inside the table
       if (fl < total) {
         const int row = fl / Dm, col = fl % Dm;  // Dm is a multiple of 4: one row per float4
-        float* dst = tile + row * (Dm + 1) + col;
-        dst[0] = vw[x].x; dst[1] = vw[x].y; dst[2] = vw[x].z; dst[3] = vw[x].w;
+        float* dst = tile + row * RS + col;
+        if constexpr (RS % 4 == 0) {
+          *reinterpret_cast<float4*>(dst) = vw[x];
+        } else {
+          dst[0] = vw[x].x; dst[1] = vw[x].y; dst[2] = vw[x].z; dst[3] = vw[x].w;
+        }
       }
     }
     __syncthreads();  // tile and qs visible
     for (int e = tid; e < M * C; e += NT) {
       const int j = e / C, c = e - j * C;
       const float* qj = qs + j * Dm;
-      const float* cr = tile + e * (Dm + 1);
+      const float* cr = tile + e * RS;
       float p = 0.0f;
+      if constexpr (RS % 4 == 0) {
 #pragma unroll
-      for (int x = 0; x < Dm; ++x) p = __fmaf_rn(qj[x], cr[x], p);
+        for (int x = 0; x < Dm / 4; ++x) {
+          const float4 qq = reinterpret_cast<const float4*>(qj)[x], cc = reinterpret_cast<const float4*>(cr)[x];
+          p = __fmaf_rn(qq.x, cc.x, p);
+          p = __fmaf_rn(qq.y, cc.y, p);
+          p = __fmaf_rn(qq.z, cc.z, p);
+          p = __fmaf_rn(qq.w, cc.w, p);
+        }
+      } else {
+#pragma unroll
+        for (int x = 0; x < Dm / 4; ++x) {  // the query four at a time (one address per wave: a broadcast)
+          const float4 qq = reinterpret_cast<const float4*>(qj)[x];
+          p = __fmaf_rn(qq.x, cr[4 * x + 0], p);
+          p = __fmaf_rn(qq.y, cr[4 * x + 1], p);
+          p = __fmaf_rn(qq.z, cr[4 * x + 2], p);
+          p = __fmaf_rn(qq.w, cr[4 * x + 3], p);
+        }
+      }
       lut[j * kLutRow + c] = p;
     }
     mark(9);

@@ -189,9 +189,9 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   constexpr int NT = 1024, P = SRC::P;
   constexpr int LM = SRC::kFromCodes ? SRC::M : 1;
   __shared__ float lut[LM * kLutRow];
-  __shared__ float qs[kD];
+  __shared__ __attribute__((aligned(16))) float qs[kD];
   __shared__ float red[32];
-  extern __shared__ float tile[];  // lut_tile_floats(NT, LM, C) floats when the source is codes
+  extern __shared__ __attribute__((aligned(16))) float tile[];  // lut_tile_floats(NT, LM, C) floats when the source is codes
   __shared__ unsigned hist[kNB];
   __shared__ int scan_sm[2 * (NT / 64) + 1 + 2];
   const int tid = threadIdx.x, units = s.B * s.Hkv;
