@@ -82,40 +82,62 @@ __global__ void pq_zero_kernel(unsigned long long* p, size_t n) {
 }
 
 // sums[u][j][c][e] += fix(keys[u][t][j*Dm+e]) for every token t with code c; counts[u][j][c] += 1.
-// LDS accumulators for 16 KiB worth of centroids at a time; integer adds commute, so the
-// result does not depend on the order in which waves run.
-template <typename T>
+// Lanes run over the dimensions of the sub-vector: a group of min(Dm, 64) lanes takes one
+// token at a time, reads its sub-vector in one coalesced piece and adds it to the LDS
+// accumulators of the token's centroid (the lanes of a group hit distinct addresses).  LDS
+// holds 64 KiB worth of centroids at a time (all of them except for 256 centroids of 128
+// dimensions); integer adds commute, so the result does not depend on the order in which
+// waves run.
+constexpr int kAccumLdsWords = 8192;  // 64-bit accumulators in LDS
+template <typename T, int DM>
 __global__ __launch_bounds__(256) void pq_accum_kernel(BuildShape s, const T* __restrict__ keys,
                                                        const uint8_t* __restrict__ codes,
                                                        unsigned long long* __restrict__ sums,
                                                        unsigned* __restrict__ counts) {
-  __shared__ unsigned long long acc[2048];
+  constexpr int LPT = DM >= 64 ? 64 : DM;  // lanes per token
+  constexpr int EPL = DM / LPT;            // elements per lane
+  constexpr int TPW = 64 / LPT;            // tokens a wave handles at a time
+  constexpr int U = 4;                     // tokens per lane group in flight
+  __shared__ unsigned long long acc[kAccumLdsWords];
   __shared__ unsigned cnt[256];
-  const int uj = blockIdx.y, u = uj / s.M, j = uj % s.M;
+  const int uj = blockIdx.y, u = uj / s.M, j = uj % s.M, tid = threadIdx.x;
+  const int lane = tid & 63, w = tid >> 6, sub = lane % LPT, slot = lane / LPT;
   const int t0 = blockIdx.x * kAccumTok, t1 = min(t0 + kAccumTok, s.N);
-  const int cg = max(1, 2048 / s.Dm);  // centroids per pass
+  const int cg = min(s.C, kAccumLdsWords / DM);  // centroids per pass
+  const int step = 4 * TPW;                      // tokens the workgroup takes per round
   for (int c0 = 0; c0 < s.C; c0 += cg) {
     const int nc = min(cg, s.C - c0);
     __syncthreads();
-    for (int i = threadIdx.x; i < nc * s.Dm; i += 256) acc[i] = 0ull;
-    if (threadIdx.x < nc) cnt[threadIdx.x] = 0u;
+    for (int i = tid; i < nc * DM; i += 256) acc[i] = 0ull;
+    if (tid < nc) cnt[tid] = 0u;
     __syncthreads();
-    for (int t = t0 + threadIdx.x; t < t1; t += 256) {
-      const int c = (int)codes[((size_t)u * s.N + t) * s.M + j] - c0;
-      if (c >= 0 && c < nc) {
-        atomicAdd(&cnt[c], 1u);
-        for (int i = 0; i < s.Dm; ++i) {
-          const int e = (i + threadIdx.x) & (s.Dm - 1);  // stagger lanes over LDS banks (Dm is a power of two)
-          const float xv = load_as_float<T>(keys, ((size_t)u * s.N + t) * kD + j * s.Dm + e);
-          const long long fx = __float2ll_rn(xv * (float)(1 << kFixShift));
-          atomicAdd(&acc[c * s.Dm + e], (unsigned long long)fx);
+    for (int tb = t0 + w * TPW + slot; tb < t1; tb += U * step) {
+      int c[U];
+      float xv[U][EPL];
+#pragma unroll
+      for (int k = 0; k < U; ++k) {
+        const int t = min(tb + k * step, t1 - 1);  // clamped: straight-line loads, masked below
+        c[k] = (int)codes[((size_t)u * s.N + t) * s.M + j] - c0;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e)
+          xv[k][e] = load_as_float<T>(keys, ((size_t)u * s.N + t) * kD + j * DM + sub + e * LPT);
+      }
+#pragma unroll
+      for (int k = 0; k < U; ++k) {
+        if (tb + k * step < t1 && c[k] >= 0 && c[k] < nc) {
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) {
+            const long long fx = __float2ll_rn(xv[k][e] * (float)(1 << kFixShift));
+            atomicAdd(&acc[c[k] * DM + sub + e * LPT], (unsigned long long)fx);
+          }
+          if (sub == 0) atomicAdd(&cnt[c[k]], 1u);
         }
       }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < nc * s.Dm; i += 256)
-      if (acc[i]) atomicAdd(&sums[((size_t)uj * s.C + c0) * s.Dm + i], acc[i]);
-    if (threadIdx.x < nc && cnt[threadIdx.x]) atomicAdd(&counts[(size_t)uj * s.C + c0 + threadIdx.x], cnt[threadIdx.x]);
+    for (int i = tid; i < nc * DM; i += 256)
+      if (acc[i]) atomicAdd(&sums[((size_t)uj * s.C + c0) * DM + i], acc[i]);
+    if (tid < nc && cnt[tid]) atomicAdd(&counts[(size_t)uj * s.C + c0 + tid], cnt[tid]);
   }
 }
 
