@@ -193,8 +193,11 @@ size_t pqc_pq_build_workspace_bytes(const pqc_config* cfg);
  * to its nearest centroid in squared L2 distance, lowest index on ties; replace each
  * centroid by the mean of its members, an empty cluster keeps its centroid), then a
  * final assignment, so that the returned codes are the nearest centroids of the
- * returned centroids.  Distances are evaluated in fp32; centroid sums are exact
- * integer sums of the keys rounded to 2^-20, hence independent of execution order.
+ * returned centroids.  Distances are compared in fp32 (for bf16 keys through
+ * |c|^2 - 2 x.c on the matrix cores, with fp32 accumulation of exact products), so a
+ * token within fp32 rounding of two centroids may go to either; centroid sums are
+ * exact integer sums of the keys rounded to 2^-20, hence independent of execution
+ * order.
  *
  *   keys       [B][Hkv][N][D]        kv_dtype   (in)
  *   init_idx   [B][Hkv][M][C]        int32      (in)

@@ -506,6 +506,18 @@ int make_build_plan(const pqc_config* cfg, BuildPlan* bp) {
 template <typename T>
 void launch_assign(const BuildShape& s, const T* keys, int64_t unit_stride, int n_tokens, int pos0, const float* cent,
                    uint8_t* codes, hipStream_t st) {
+  if constexpr (sizeof(T) == 2) {
+    if (s.Dm >= 32) {  // bf16 keys: the matrix-core kernel
+      const dim3 mgrid((n_tokens + kAssignMfmaTok - 1) / kAssignMfmaTok, (unsigned)(s.units * s.M));
+      const bf16_t* kb = reinterpret_cast<const bf16_t*>(keys);
+      switch (s.Dm) {
+        case 32: hipLaunchKernelGGL((pq_assign_mfma_kernel<32>), mgrid, dim3(256), 0, st, s, kb, unit_stride, n_tokens, pos0, cent, codes); break;
+        case 64: hipLaunchKernelGGL((pq_assign_mfma_kernel<64>), mgrid, dim3(256), 0, st, s, kb, unit_stride, n_tokens, pos0, cent, codes); break;
+        default: hipLaunchKernelGGL((pq_assign_mfma_kernel<128>), mgrid, dim3(256), 0, st, s, kb, unit_stride, n_tokens, pos0, cent, codes); break;
+      }
+      return;
+    }
+  }
   const dim3 grid((n_tokens + kAssignTok - 1) / kAssignTok, (unsigned)(s.units * s.M));
   switch (s.Dm) {
     case 16: hipLaunchKernelGGL((pq_assign_kernel<T, 16>), grid, dim3(256), 0, st, s, keys, unit_stride, n_tokens, pos0, cent, codes); break;

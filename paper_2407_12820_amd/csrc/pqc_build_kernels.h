@@ -76,6 +76,144 @@ __global__ __launch_bounds__(256) void pq_assign_kernel(BuildShape s, const T* _
   if (live) codes[((size_t)u * s.N + code_pos0 + t) * s.M + j] = (uint8_t)arg;
 }
 
+// The same assignment on the matrix cores, for bf16 keys and sub-vectors of 32, 64 or 128
+// dimensions: this step is a dense contraction (tokens x dimensions by dimensions x
+// centroids).  The nearest centroid minimises |c|^2 - 2 x.c.  Keys are bf16 already; an fp32
+// centroid is split into three bf16 terms that add up to it exactly, so the products are
+// exact and only the fp32 accumulation rounds.  Per wave: 16-token tiles as the A operand
+// (kept in registers), 16-centroid tiles as the B operand (from LDS), D[token][centroid];
+// each lane keeps the best centroid of its column per token, the columns are merged with DPP
+// row operations at the end (equal values: lower centroid index).
+constexpr int kAssignTiles = 8;                          // 16-token tiles per wave and batch
+constexpr int kAssignBatchTok = 4 * 16 * kAssignTiles;   // tokens per workgroup and batch
+constexpr int kAssignBatches = 4;                        // batches per workgroup (the staged centroids are reused)
+constexpr int kAssignMfmaTok = kAssignBatchTok * kAssignBatches;
+template <int DM>
+__global__ __launch_bounds__(256) void pq_assign_mfma_kernel(BuildShape s, const bf16_t* __restrict__ keys,
+                                                             int64_t key_unit_stride, int n_tokens, int code_pos0,
+                                                             const float* __restrict__ cent, uint8_t* __restrict__ codes) {
+  constexpr int KK = DM / 32;            // k steps of 32 dimensions
+  constexpr int CG = 8192 / DM;          // centroids staged at a time (48 KB of bf16 terms)
+  constexpr int RS = DM + 8;             // LDS row stride in bf16 (16 bytes of padding)
+  __shared__ __attribute__((aligned(16))) unsigned short ct[3][CG * RS];  // hi, mid, lo terms
+  __shared__ float cn[CG];
+  const int uj = blockIdx.y, u = uj / s.M, j = uj % s.M, tid = threadIdx.x;
+  const int lane = tid & 63, w = tid >> 6, col = lane & 15, quad = lane >> 4;
+  const bool one_group = s.C <= CG;  // then the centroids are staged once for all batches
+  for (int batch = 0; batch < kAssignBatches; ++batch) {
+    const int tok0 = (blockIdx.x * kAssignBatches + batch) * kAssignBatchTok + w * 16 * kAssignTiles;
+    if (blockIdx.x * kAssignMfmaTok + batch * kAssignBatchTok >= n_tokens) break;  // workgroup-uniform
+    // this wave's keys: tile tt, row col, dims 32*kk + 8*quad .. +7
+    bf16x8_t a[kAssignTiles][KK];
+#pragma unroll
+    for (int tt = 0; tt < kAssignTiles; ++tt) {
+      const int t = min(tok0 + tt * 16 + col, n_tokens - 1);
+      const uint4* kp =
+          reinterpret_cast<const uint4*>(keys + (size_t)u * key_unit_stride + (size_t)t * kD + j * DM + 8 * quad);
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const uint4 raw = kp[4 * kk];
+        __builtin_memcpy(&a[tt][kk], &raw, 16);
+      }
+    }
+    float best[kAssignTiles][4];
+    int bidx[kAssignTiles][4];
+#pragma unroll
+    for (int tt = 0; tt < kAssignTiles; ++tt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        best[tt][i] = INFINITY;
+        bidx[tt][i] = 0;
+      }
+    for (int c0 = 0; c0 < s.C; c0 += CG) {
+      const int nc = min(CG, s.C - c0);
+      if (!(one_group && batch > 0)) {
+        __syncthreads();
+        // stage: split every centroid value into three bf16 terms that add up to it exactly
+        for (int i = tid; i < nc * DM; i += 256) {
+          const float v = cent[((size_t)uj * s.C + c0) * DM + i];
+          const unsigned h = bf16_round_bits(v);
+          const float r1 = v - __uint_as_float(h << 16);
+          const unsigned m = bf16_round_bits(r1);
+          const float r2 = r1 - __uint_as_float(m << 16);
+          const unsigned l = bf16_round_bits(r2);
+          const int o = (i / DM) * RS + (i % DM);
+          ct[0][o] = (unsigned short)h;
+          ct[1][o] = (unsigned short)m;
+          ct[2][o] = (unsigned short)l;
+        }
+        // squared norms: four threads per centroid, a quarter of the dimensions each
+        for (int cb = 0; cb < nc; cb += 64) {
+          const int c = cb + (tid >> 2), seg = tid & 3;
+          const float4* cr = reinterpret_cast<const float4*>(cent + ((size_t)uj * s.C + c0 + min(c, nc - 1)) * DM + seg * (DM / 4));
+          float n2 = 0.0f;
+#pragma unroll
+          for (int e = 0; e < DM / 16; ++e) {
+            const float4 v = cr[e];
+            n2 = fmaf(v.x, v.x, n2);
+            n2 = fmaf(v.y, v.y, n2);
+            n2 = fmaf(v.z, v.z, n2);
+            n2 = fmaf(v.w, v.w, n2);
+          }
+          n2 += dpp_f<0xB1>(0.0f, n2);
+          n2 += dpp_f<0x4E>(0.0f, n2);
+          if (seg == 0 && c < nc) cn[c] = n2;
+        }
+        __syncthreads();
+      }
+      for (int nt = 0; nt * 16 < nc; ++nt) {
+        const int c = nt * 16 + col;  // this lane's centroid column
+        const bool live = c < nc;
+        bf16x8_t b[3][KK];
+#pragma unroll
+        for (int term = 0; term < 3; ++term)
+#pragma unroll
+          for (int kk = 0; kk < KK; ++kk) {
+            const uint4 raw = *reinterpret_cast<const uint4*>(&ct[term][min(c, nc - 1) * RS + 32 * kk + 8 * quad]);
+            __builtin_memcpy(&b[term][kk], &raw, 16);
+          }
+        const float cnv = live ? cn[c] : INFINITY;
+#pragma unroll
+        for (int tt = 0; tt < kAssignTiles; ++tt) {
+          f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+            for (int term = 2; term >= 0; --term)  // small terms first
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt][kk], b[term][kk], acc, 0, 0, 0);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {  // token 4*quad + i of the tile against centroid c
+            const float sc = fmaf(-2.0f, acc[i], cnv);
+            if (sc < best[tt][i]) {  // strict: an earlier (lower) centroid of this lane keeps a tie
+              best[tt][i] = sc;
+              bidx[tt][i] = c0 + c;
+            }
+          }
+        }
+      }
+    }
+    // merge the 16 columns of a row of lanes; equal values: lower centroid index
+#pragma unroll
+    for (int tt = 0; tt < kAssignTiles; ++tt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float v = best[tt][i];
+        int x = bidx[tt][i];
+        auto take = [&](float ov, int ox) {
+          const bool t = ov < v || (ov == v && ox < x);
+          v = t ? ov : v;
+          x = t ? ox : x;
+        };
+        take(dpp_f<0xB1>(v, v), dpp_i<0xB1>(x, x));
+        take(dpp_f<0x4E>(v, v), dpp_i<0x4E>(x, x));
+        take(dpp_f<0x141>(v, v), dpp_i<0x141>(x, x));
+        take(dpp_f<0x140>(v, v), dpp_i<0x140>(x, x));
+        const int t = tok0 + tt * 16 + 4 * quad + i;
+        if (col == 0 && t < n_tokens) codes[((size_t)u * s.N + code_pos0 + t) * s.M + j] = (uint8_t)x;
+      }
+  }
+}
+
 __global__ void pq_zero_kernel(unsigned long long* p, size_t n) {
   size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0ull;
