@@ -235,7 +235,7 @@ __global__ __launch_bounds__(256) void pq_accum_kernel(BuildShape s, const T* __
   constexpr int LPT = DM >= 64 ? 64 : DM;  // lanes per token
   constexpr int EPL = DM / LPT;            // elements per lane
   constexpr int TPW = 64 / LPT;            // tokens a wave handles at a time
-  constexpr int U = 4;                     // tokens per lane group in flight
+  constexpr int U = 16;                    // tokens per lane group in flight
   __shared__ unsigned long long acc[kAccumLdsWords];
   __shared__ unsigned cnt[256];
   const int uj = blockIdx.y, u = uj / s.M, j = uj % s.M, tid = threadIdx.x;
