@@ -229,7 +229,7 @@ void launch_attn_tg(pqc_ctx* ctx, const void* q, const void* k, const void* v, c
                     hipStream_t st) {
   const Shape& s = ctx->plan.s;
   const unsigned units = (unsigned)(s.B * s.Hkv);
-  hipLaunchKernelGGL((attn_list_kernel<T, G>), dim3(s.nblkP, units), dim3(256), 0, st, s, ctx->ws,
+  hipLaunchKernelGGL((attn_list_kernel<T, G>), dim3(s.nblkP, units), dim3(256), sizeof(int) * s.rowsP, st, s, ctx->ws,
                      static_cast<const T*>(q), static_cast<const T*>(k), static_cast<const T*>(v), idx);
   hipLaunchKernelGGL((merge_kernel<G>), dim3(G, units), dim3(256), sizeof(float) * s.nblkP, st, s, ctx->ws, s.nblkP, out);
 }

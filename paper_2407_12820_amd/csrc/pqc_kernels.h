@@ -1063,7 +1063,11 @@ __global__ __launch_bounds__(256) void attn_list_kernel(Shape s, Workspace ws, c
   const int b = u / s.Hkv, g = u % s.Hkv;
   const int p0 = blockIdx.x * s.rowsP;
   const int count = min(s.rowsP, s.Ktot - p0);
-  const int* lst = idx + (size_t)u * s.Ktot + p0;
+  // this workgroup's slice of the list goes to LDS first: one coalesced load instead of a
+  // dependent global load in front of every stage of row loads
+  extern __shared__ int lst[];  // [rowsP]
+  for (int p = tid; p < count; p += NT) lst[p] = idx[(size_t)u * s.Ktot + p0 + p];
+  __syncthreads();
   auto row_at = [&](int p) -> int { return lst[p]; };
   const T* kbase = kc + (size_t)u * s.N * kD;
   const T* vbase = vc + (size_t)u * s.N * kD;
