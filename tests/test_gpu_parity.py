@@ -171,6 +171,38 @@ def test_maximum_context_length(pqc):
     full_check(p, idx, out)
 
 
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        g = int(rng.choice([1, 2, 4, 8]))
+        hkv = int(rng.choice([1, 2, 3]))
+        m = int(rng.choice([1, 2, 4, 8]))
+        c = int(rng.choice([2, 5, 16, 64, 200, 256]))
+        n_tok = int(rng.integers(1, 7000))
+        n_init = int(rng.integers(0, min(n_tok, 9) + 1))
+        n_local = int(rng.integers(0, min(n_tok - n_init, 100) + 1))
+        mid = n_tok - n_init - n_local
+        topk = int(rng.integers(0, mid + 1)) if rng.random() < 0.8 else int(rng.choice([0, mid]))
+        if n_init + topk + n_local == 0:
+            topk, n_tok = 1, max(n_tok, 1)
+            if mid < 1:
+                n_init, n_local = 0, 0
+        out.append(dict(batch=int(rng.choice([1, 2])), n_q_heads=g * hkv, n_kv_heads=hkv, n_tokens=n_tok, pq_m=m, pq_centroids=c,
+                        topk=topk, n_init=n_init, n_local=n_local, dtype=str(rng.choice(["bf16", "bf16", "f32"])), kmeans_iters=1))
+    return out
+
+
+@pytest.mark.parametrize("kw", _random_shapes(24, seed=2024), ids=lambda kw: "-".join(str(v) for v in kw.values()))
+def test_random_shapes(pqc, kw):
+    # a seeded sweep over the supported shape space (group sizes, partitions, centroid counts, windows, dtypes)
+    w = _small(**kw)
+    print(f"[case] random shape {kw}", flush=True)
+    p = build_problem(w, seed=21)
+    idx, out = run_decode(pqc, p)
+    full_check(p, idx, out)
+
+
 def test_all_scores_equal_takes_lowest_indices(pqc):
     # A zero query ties every token: the K lowest middle indices win, attention is a plain mean.
     w = _small(topk=1500)
