@@ -31,12 +31,18 @@ _lib = None
 
 
 def load() -> C.CDLL:
-    """Load libpqcache.so; raises if it has not been built (there is no other path)."""
+    """Load libpqcache.so, compiling it first if it has not been built; raises if that fails (there is no other path)."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(LIB_PATH):
-        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2407_12820_amd.build` "
+        # nothing built yet: compile the library now (hipcc cross-compiles gfx950 without a GPU)
+        from . import build as _build
+
+        if os.path.abspath(LIB_PATH) == os.path.abspath(_build.LIB):
+            _build.build()
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing and could not be built with `python -m paper_2407_12820_amd.build` "
                            "(the decode path has no CPU or PyTorch fallback)")
     lib = C.CDLL(LIB_PATH)
     vp, cp = C.c_void_p, C.POINTER(Config)
