@@ -115,3 +115,12 @@ def test_argument_checks_of_the_newer_entry_points():
     assert lib.pqc_create(C.byref(h), C.byref(four), C.c_void_p(4096), need4) == 0
     assert lib.pqc_decode_indexed(h, *([p] * 9), None) == -2
     lib.pqc_destroy(h)
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
+    # no CPU or PyTorch stand-in exists: a library that is not there (and is not the one the
+    # package knows how to build) must raise
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", os.path.join(ROOT, "paper_2407_12820_amd", "no_such_library.so"))
+    with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
+        binding.load()
