@@ -271,11 +271,12 @@ __host__ __device__ constexpr int lut_row_stride(int M) { return M <= 2 ? kD / M
 __host__ __device__ constexpr int lut_tile_floats(int nt, int M, int C) {
   return nt >= 1024 ? M * C * lut_row_stride(M) : kLutTileFloats + kLutTileFloats / (kD / M);
 }
-template <typename T, int NT, int M, class MarkFn>
+template <typename T, int NT, int M, class MarkFn, class IssueFn>
 __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] of this unit */,
                                                const float* __restrict__ cent /* [M][C][Dm] */, int G, int C,
                                                float* lut, float* qs, float* red /* [4*8] */,
-                                               float* tile /* [lut_tile_floats(NT, M, C)] */, MarkFn mark) {
+                                               float* tile /* [lut_tile_floats(NT, M, C)] */, MarkFn mark,
+                                               IssueFn issue_more /* the caller's own loads, queued behind the table's */) {
   constexpr int Dm = kD / M, RS = lut_row_stride(M);
   constexpr bool kWhole = NT >= 1024;
   constexpr int VW = kWhole ? (256 * kD) / (4 * NT) : 1;  // float4 per thread for the largest table
@@ -295,6 +296,10 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
     float qv[8];
 #pragma unroll
     for (int h = 0; h < 8; ++h) qv[h] = load_as_float<T>(q, min(h, G - 1) * kD + dq);
+    // Loads return in issue order: whatever the caller streams from HBM goes behind the table's
+    // (mostly L2-resident) centroids, so that the table is built while that stream arrives.
+    PQC_LOADS_ISSUED();
+    issue_more();
     PQC_LOADS_ISSUED();
     float a = qv[0];
 #pragma unroll

@@ -38,24 +38,27 @@ struct CodeChunks {
   long long unit_byte0;     // aligned-down byte offset of this unit's codes
   int lead;                 // phantom tokens before token 0
   const float* lut;         // LDS
-  __device__ __forceinline__ void init(const void* ptr, int u, int N, int units, const float* lut_) {
+  const uint8_t* spare;     // 16 readable bytes of any content
+  __device__ __forceinline__ void init(const void* ptr, int u, int N, int units, const float* lut_, const void* spare16) {
     all = static_cast<const uint8_t*>(ptr);
+    spare = static_cast<const uint8_t*>(spare16);
     total_bytes = (long long)units * N * M;
     const long long ob = (long long)u * N * M;
     unit_byte0 = ob & ~15ll;
     lead = (int)((ob - unit_byte0) / M);
     lut = lut_;
   }
-  // Unconditional 16-byte load (straight-line code keeps many loads in flight): a chunk at
-  // or beyond the tensor's last full 16 bytes is redirected to that last full chunk, and
-  // fix_tail() patches the one chunk that holds the tensor's ragged end afterwards.
+  // Unconditional 16-byte load (straight-line code keeps many loads in flight, and lets the
+  // compiler count them when it waits for earlier ones): a chunk at or beyond the tensor's last
+  // full 16 bytes is redirected to that last full chunk (to the spare bytes if the tensor has
+  // none), and fix_tail() patches the one chunk that holds the tensor's ragged end afterwards.
   __device__ __forceinline__ Raw load(int chunk) const {
     const long long last_full = (total_bytes & ~15ll) - 16;  // < 0 for tensors under 16 bytes
     long long off = unit_byte0 + 16ll * chunk;
     off = off < last_full ? off : last_full;
     off = off > 0 ? off : 0;
-    if (total_bytes < 16) return make_uint4(0u, 0u, 0u, 0u);  // uniform
-    return *reinterpret_cast<const uint4*>(all + off);
+    const uint8_t* p = total_bytes < 16 ? spare : all + off;
+    return *reinterpret_cast<const uint4*>(p);
   }
   __device__ __forceinline__ void fix_tail(Raw& r, int chunk) const {
     const long long off = unit_byte0 + 16ll * chunk;
@@ -90,7 +93,7 @@ struct ScoreChunks {
   const float* scores;  // this unit's [N] scores
   int n;
   int lead;
-  __device__ __forceinline__ void init(const void* ptr, int u, int N, int, const float*) {
+  __device__ __forceinline__ void init(const void* ptr, int u, int N, int, const float*, const void*) {
     scores = static_cast<const float*>(ptr) + (size_t)u * N;
     n = N;
     lead = 0;
@@ -129,7 +132,7 @@ __global__ __launch_bounds__(256) void lut_kernel(Shape s, const T* __restrict__
   __shared__ float tile[lut_tile_floats(256, M, 256)];
   const int u = blockIdx.y, b = u / s.Hkv, g = u % s.Hkv;
   build_lut<T, 256, M>(q + ((size_t)b * s.Hq + (size_t)g * s.G) * kD, cent + (size_t)u * M * s.C * (kD / M), s.G, s.C, lut,
-                       qs, red, tile, [](int) {});
+                       qs, red, tile, [](int) {}, []() {});
   for (int e = threadIdx.x; e < M * s.C; e += 256) table[(size_t)u * M * s.C + e] = lut[(e / s.C) * kLutRow + (e % s.C)];
 }
 
@@ -212,26 +215,32 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   PQC_NOTE(ws, 0, 15, (__builtin_amdgcn_s_getreg(20 | (3 << 11)) & 15) | (u << 8));  // XCC_ID[3:0], unit
 #endif
   SRC src;
-  src.init(src_ptr, u, s.N, units, lut);
-  // this workgroup's chunks and this thread's sample: issue the loads before anything else
+  src.init(src_ptr, u, s.N, units, lut, ws.hist);
+  // this workgroup's chunks and this thread's sample: the loads are issued before anything else,
+  // except that a table build puts its centroid loads in front of them
   const int chunks = s.tokA / P, chunk0 = bx * chunks;
   typename SRC::Raw raw[kMaxVecA];
-#pragma unroll
-  for (int v = 0; v < kMaxVecA; ++v) raw[v] = src.load(chunk0 + min(v * NT + tid, chunks - 1));
+  typename SRC::One sample;
   const bool have_sample = tid < s.sampleN;
-  const int sample_i = min(tid, s.sampleN - 1);
-  const typename SRC::One sample =
-      src.load_one(min(s.N - 1, s.I + (int)(((long long)sample_i * max(0, s.N - s.I - s.L)) / s.sampleN)), u, s.N);
-  PQC_LOADS_ISSUED();
-  for (int i = tid; i < kNB; i += NT) hist[i] = 0u;
+  auto issue_loads = [&]() {
+#pragma unroll
+    for (int v = 0; v < kMaxVecA; ++v) raw[v] = src.load(chunk0 + min(v * NT + tid, chunks - 1));
+    const int sample_i = min(tid, s.sampleN - 1);
+    sample = src.load_one(min(s.N - 1, s.I + (int)(((long long)sample_i * max(0, s.N - s.I - s.L)) / s.sampleN)), u, s.N);
+  };
   float2 bounds;
   if constexpr (SRC::kFromCodes) {
     const int b = u / s.Hkv, g = u % s.Hkv;
-    bounds = build_lut<T, NT, LM>(q + ((size_t)b * s.Hq + (size_t)g * s.G) * kD, cent + (size_t)u * LM * s.C * (kD / LM), s.G,
-                                  s.C, lut, qs, red, tile, [&](int slot) { PQC_MARK(ws, 0, slot); });
+    for (int i = tid; i < kNB; i += NT) hist[i] = 0u;
+    bounds = build_lut<T, NT, LM>(
+        q + ((size_t)b * s.Hq + (size_t)g * s.G) * kD, cent + (size_t)u * LM * s.C * (kD / LM), s.G, s.C, lut, qs, red, tile,
+        [&](int slot) { PQC_MARK(ws, 0, slot); }, issue_loads);
     if (bx == 0)
       for (int e = tid; e < LM * s.C; e += NT) ws.lut[(size_t)u * LM * s.C + e] = lut[(e / s.C) * kLutRow + (e % s.C)];
   } else {
+    issue_loads();
+    PQC_LOADS_ISSUED();
+    for (int i = tid; i < kNB; i += NT) hist[i] = 0u;
     bounds = ws.range[u];
     __syncthreads();
   }
