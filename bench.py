@@ -34,6 +34,8 @@ def main() -> int:
     ap.add_argument("--profile-steps", type=int, default=24, help="rounds of the per-kernel timing (each launches every kernel once per input set)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-indexed", action="store_true", help="skip the pqc_decode_indexed measurement")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP graph replay measurement")
+    ap.add_argument("--no-copy-ceiling", action="store_true", help="skip the device-to-device copy measurement")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--also", default="llama70b_128k", help="second workload reported alongside (step time only); '' to skip")
     ap.add_argument("--also-layers", type=int, default=3)
@@ -176,6 +178,49 @@ def main() -> int:
         result["indexed_path"] = {"entry_point": "pqc_decode_indexed", "us_per_layer": round(us_i, 3),
                                   "hbm_frac": round(path_bytes / (us_i * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
                                   "extra_input": "tokens per code pair, [units][C*C] uint32, built once per code tensor"}
+
+    # Algorithm 2 runs the step once per layer: the same `input_sets` calls recorded once into a HIP graph
+    # (stream capture) and replayed, which takes the host's launch calls out of the loop
+    if not args.no_graph:
+        side = torch.cuda.Stream(device=dev)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for a in margs:
+                ctx.decode_marshalled(a, torch.cuda.current_stream(dev).cuda_stream)
+        reps = max(1, args.steps // len(sets))
+        with torch.cuda.stream(side):
+            for _ in range(max(1, args.warmup // len(sets))):
+                graph.replay()
+            side.synchronize()
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            tg = time.perf_counter()
+            g0.record(side)
+            for _ in range(reps):
+                graph.replay()
+            g1.record(side)
+            issue_g = (time.perf_counter() - tg) * 1e3
+            side.synchronize()
+        result["graph_replay"] = {"layers_per_graph": len(sets), "replays": reps,
+                                  "us_per_layer": round(g0.elapsed_time(g1) / (reps * len(sets)) * 1e3, 3),
+                                  "host_issue_ms_per_layer": round(issue_g / (reps * len(sets)), 6)}
+        del graph
+
+    # a plain device-to-device copy (reads and writes 1 GiB each way), as the ceiling a streaming kernel reaches here
+    if not args.no_copy_ceiling:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        ev1.record()
+        torch.cuda.synchronize()
+        copy_gbps = 2 * src.numel() * 5 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+        result["copy_ceiling"] = {"gbps": round(copy_gbps, 1), "path_frac_of_copy": round(path_gbps / copy_gbps, 4),
+                                  "select_kernel_frac_of_copy": round(sel_gbps / copy_gbps, 4)}
+        del src, dst
 
     # PQ construction on the GPU (not part of the decode step): K-Means over all cached keys of one layer
     result["pq_build"] = {"ms_per_layer": round(float(np.median(build_ms)), 3), "kmeans_iters": w.kmeans_iters,

@@ -123,6 +123,13 @@ int pqc_last_hip_error(const pqc_ctx* ctx);
  *   out_attn   [B][Hq][D]            f32        attention output
  *
  * Codes of tokens inside the initial and local windows are ignored.
+ *
+ * The call enqueues kernel launches only (three; before a context's first call,
+ * and after a call that failed, one more that clears the workspace) and a completed
+ * call leaves the workspace as it found it.  It may therefore be recorded into a
+ * HIP graph by stream capture and replayed, for instance one call per layer with
+ * one context shared by all layers (Algorithm 2's loop over the layers); make one
+ * ordinary call on the context first, so that the clearing launch is not recorded.
  */
 int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes,
                const void* k_cache, const void* v_cache, int32_t* out_idx, float* out_attn,

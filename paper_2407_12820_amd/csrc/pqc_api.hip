@@ -83,7 +83,6 @@ int make_plan(const pqc_config* c, Plan* p) {
   s.nblkP = (s.Ktot + s.rowsP - 1) / s.rowsP;
   s.npart = s.nblkC > s.nblkP ? s.nblkC : s.nblkP;
   if (s.npart < 2 * kAccBatch) s.npart = 2 * kAccBatch;  // finalize_kernel reads this many slots unconditionally
-  s.parity = 0;
   p->rec_stride = (int)sizeof(CandHeader) + kD * (c->kv_dtype == PQC_F32 ? 4 : 2);
   // sample ranks that bracket the K-th largest score by 5 standard errors (+2)
   const int nmid = s.N - s.I - s.L;
@@ -101,7 +100,7 @@ int make_plan(const pqc_config* c, Plan* p) {
   p->off_ctl = off;   off = align_up(off + sizeof(BinParams) * units);
   p->off_lut = off;   off = align_up(off + sizeof(float) * units * s.M * s.C);
   p->off_range = off; off = align_up(off + sizeof(float2) * units);
-  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * 2 * units * (kHistCopies * kNB + 1));  // + record counters
+  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * units * (kHistCopies * kNB + 1));  // + record counters
   p->off_bins = off;  off = align_up(off + sizeof(unsigned short) * units * s.binStride);
   p->off_crec = off;  off = align_up(off + (size_t)p->rec_stride * kCandRec * units);
   p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * s.nblkC * s.stageStride);
@@ -138,16 +137,14 @@ int check_launch(pqc_ctx* ctx) {
   return PQC_OK;
 }
 
-// Both parities' histograms must be zero before a call uses them; finalize_kernel restores
-// that for the set it did not use.
+// Histograms and record counters must be zero when a call starts; finalize_kernel leaves them
+// so, which makes a completed call stateless (and a captured one replayable).
 int ensure_clean_hist(pqc_ctx* ctx, hipStream_t st) {
   if (ctx->hist_clean) return PQC_OK;
   const Shape& s = ctx->plan.s;
-  const size_t na = (size_t)2 * s.B * s.Hkv * (kHistCopies * kNB + 1);  // histograms and the record counters behind them
+  const size_t na = (size_t)s.B * s.Hkv * (kHistCopies * kNB + 1);  // histograms and the record counters behind them
   hipLaunchKernelGGL(reset_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, st, ctx->ws.hist, na);
-  const int rc = check_launch(ctx);
-  if (rc == PQC_OK) ctx->plan.s.parity = 0;
-  return rc;
+  return check_launch(ctx);
 }
 
 // ---- template dispatch -------------------------------------------------------
@@ -309,7 +306,7 @@ int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t wor
   ctx->ws.ctl = reinterpret_cast<BinParams*>(base + p.off_ctl);
   ctx->ws.lut = reinterpret_cast<float*>(base + p.off_lut);
   ctx->ws.hist = reinterpret_cast<unsigned*>(base + p.off_hist);
-  ctx->ws.cand_count = ctx->ws.hist + (size_t)2 * p.s.B * p.s.Hkv * kHistCopies * kNB;
+  ctx->ws.cand_count = ctx->ws.hist + (size_t)p.s.B * p.s.Hkv * kHistCopies * kNB;
   ctx->ws.range = reinterpret_cast<float2*>(base + p.off_range);
   ctx->ws.bins = reinterpret_cast<unsigned short*>(base + p.off_bins);
   ctx->ws.cand_rec = reinterpret_cast<unsigned char*>(base + p.off_crec);
@@ -349,8 +346,7 @@ static int decode_impl(pqc_ctx* ctx, const void* q, const float* centroids, cons
     launch_decode_t<bf16_t>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st, phases);
   rc = check_launch(ctx);
   if (rc == PQC_OK && (phases & 4u)) {
-    ctx->hist_clean = true;  // finalize_kernel zeroed the other parity's set, which the next call uses
-    ctx->plan.s.parity ^= 1;
+    ctx->hist_clean = true;  // finalize_kernel zeroed them again
   }
   return rc;
 }
@@ -379,7 +375,6 @@ int pqc_decode_indexed(pqc_ctx* ctx, const void* q, const float* centroids, cons
   rc = check_launch(ctx);
   if (rc == PQC_OK) {
     ctx->hist_clean = true;
-    ctx->plan.s.parity ^= 1;
   }
   return rc;
 }
@@ -462,7 +457,6 @@ int pqc_topk(pqc_ctx* ctx, const float* scores, int32_t* out_idx, void* stream) 
   rc = check_launch(ctx);
   if (rc == PQC_OK) {
     ctx->hist_clean = true;
-    ctx->plan.s.parity ^= 1;
   }
   return rc;
 }

@@ -33,7 +33,6 @@ struct Shape {
   int tokC, nblkC;  // select kernel: tokens per workgroup, workgroups per unit
   int rowsP, nblkP; // list-attention kernel: rows per workgroup, workgroups per unit
   int npart;        // partial slots per unit
-  int parity;       // which of the two histogram sets this call uses
   int binStride;    // stored bins per unit (nblkC * tokC)
   int stageStride;  // 8-byte words between the staging slots of consecutive select workgroups: tokC plus a pad, so that
                     // the slots do not all start on the same memory channels

@@ -10,8 +10,9 @@
 //                    ("candidates") are recorded with their logits and V row
 //   finalize_kernel  one workgroup per query head ranks the candidates and folds the
 //                    admitted ones and all partial softmax states into the output;
-//                    copy workgroups beside them write the indices and zero the other
-//                    parity's histogram and counter for the next call
+//                    copy workgroups beside them write the indices and zero the unit's
+//                    histogram and record counter again, which nothing reads after the
+//                    select kernel: every call leaves them as it found them
 //
 // Codes are read 16 bytes at a time (P = 16/M tokens).  A unit's codes start at byte
 // u*N*M, which need not be 16-byte aligned: chunks are laid over the aligned-down
@@ -297,7 +298,7 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   if ((tid & 63) == 0 && n_low) atomicAdd(&hist[0], (unsigned)n_low);
   __syncthreads();
   PQC_MARK(ws, 0, 3);
-  unsigned* gh = ws.hist + (((size_t)s.parity * units + u) * s.histCopies + (bx % s.histCopies)) * kNB;
+  unsigned* gh = ws.hist + ((size_t)u * s.histCopies + (bx % s.histCopies)) * kNB;
   for (int i = tid; i < kNB; i += NT)
     if (hist[i]) atomicAdd(&gh[i], hist[i]);
   PQC_MARK(ws, 0, 4);
@@ -367,7 +368,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
                                 pl, scan_sm, [&](int slot) { PQC_MARK(ws, 1, slot); });  // syncs: qlds ready
   } else {
     ThresholdSearch<NT> ts;
-    ts.load(ws.hist + ((size_t)s.parity * units + u) * s.histCopies * kNB, s.histCopies);
+    ts.load(ws.hist + (size_t)u * s.histCopies * kNB, s.histCopies);
     PQC_LOADS_ISSUED();
     if constexpr (ATTN) {
 #pragma unroll
@@ -439,7 +440,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   // record slots for this workgroup's candidates: requested now, needed only after the
   // attention below, which hides the round trip of the returning atomic
   int rec_base;  // set and read by thread 0 only; no initialiser, or the merge with it would wait for the atomic here
-  if (tid == 0 && tot_cand > 0) rec_base = (int)atomicAdd(&ws.cand_count[(size_t)s.parity * units + u], (unsigned)tot_cand);
+  if (tid == 0 && tot_cand > 0) rec_base = (int)atomicAdd(&ws.cand_count[u], (unsigned)tot_cand);
   // A candidate's exact score comes from its codes and the unit's table (same evaluation order
   // as everywhere), or from the score array of the stand-alone top-k.
   struct CandKey {
@@ -614,7 +615,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
 //                        softmax states into this head's output; head 0 also writes the
 //                        admitted candidates' indices (best first)
 //   blockIdx.x >= heads  copy workgroups: concatenate the staged lists into out_idx; the
-//                        first one also zeroes the other parity's histogram and counter
+//                        first one also zeroes the unit's histogram and record counter
 // The staged "selected" lists already hold the two windows: in workgroup order they read
 //   [0..I) , tokens above the threshold bin (ascending) , [N-L..N).
 // Fast path (at most kCandRec candidates): all a head needs is in the candidate records,
@@ -749,10 +750,10 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       }
     }
     PQC_MARK(ws, 2, 4);
-    if (cw == 0) {  // leave the other parity's histogram and record counter zeroed for the next call
-      unsigned* gh = ws.hist + ((size_t)(s.parity ^ 1) * units + u) * s.histCopies * kNB;
+    if (cw == 0) {  // the select kernel was their last reader: zero histogram and record counter for the next call
+      unsigned* gh = ws.hist + (size_t)u * s.histCopies * kNB;
       for (int i = tid; i < s.histCopies * kNB; i += NT) gh[i] = 0u;
-      if (tid == 0) ws.cand_count[(size_t)(s.parity ^ 1) * units + u] = 0u;
+      if (tid == 0) ws.cand_count[u] = 0u;
     }
     PQC_MARK(ws, 2, 5);
     return;

@@ -256,7 +256,7 @@ def test_decode_phase_by_phase_equals_decode(pqc):
     dev, ctx = upload(pqc, p), pqc.PQCache(w, DEV)
     a = run_decode(pqc, p, ctx, dev)
     idx, out = ctx.empty_outputs()
-    for _ in range(2):  # twice: the histogram parity flips after each complete pass
+    for _ in range(2):  # twice: a complete pass leaves the workspace ready for the next
         idx.zero_()
         out.zero_()
         for phase in range(3):
@@ -349,3 +349,45 @@ def test_runs_on_a_side_stream(pqc):
     idx, out = ctx.decode(dev["q"], dev["centroids"], dev["codes"], dev["k"], dev["v"], stream=st)
     st.synchronize()
     full_check(p, idx.cpu().numpy(), out.cpu().numpy())
+
+
+@pytest.mark.parametrize("indexed", [False, True])
+def test_layers_recorded_into_a_hip_graph_replay_correctly(pqc, indexed):
+    # Algorithm 2 loops over the layers: one call per layer on a shared context, recorded once by stream
+    # capture, replayed with eager calls on the same context in between.  Every replay must reproduce the
+    # eager results bit for bit (a call leaves the workspace as it found it).
+    w = _small(n_tokens=9000, topk=1100)
+    layers = [build_problem(w, seed=40 + i) for i in range(3)]
+    other = build_problem(w, seed=50)
+    devs, dev_other, ctx = [upload(pqc, p) for p in layers], upload(pqc, other), pqc.PQCache(w, DEV)
+    pcs = [pqc.pair_counts(w, d["codes"]) for d in devs] if indexed else [None] * len(layers)
+
+    def call(d, pc, oi, oa):
+        if indexed:
+            ctx.decode_indexed(d["q"], d["centroids"], d["codes"], pc, d["k"], d["v"], oi, oa)
+        else:
+            ctx.decode(d["q"], d["centroids"], d["codes"], d["k"], d["v"], oi, oa)
+
+    eager, bufs = [], []
+    for d, pc in zip(devs, pcs):  # ordinary calls first: reference results, and the context's clearing launch is behind us
+        oi, oa = ctx.empty_outputs()
+        call(d, pc, oi, oa)
+        eager.append((oi.cpu().numpy().copy(), oa.cpu().numpy().copy()))
+        bufs.append(ctx.empty_outputs())
+    torch.cuda.synchronize()
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream(device=DEV)
+    with torch.cuda.graph(graph, stream=side):
+        for d, pc, (oi, oa) in zip(devs, pcs, bufs):
+            call(d, pc, oi, oa)
+    for rep in range(3):
+        for oi, oa in bufs:
+            oi.fill_(-1)
+            oa.fill_(float("nan"))
+        ctx.decode(dev_other["q"], dev_other["centroids"], dev_other["codes"], dev_other["k"], dev_other["v"])  # eager, same context
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (ei, ea), (oi, oa) in zip(eager, bufs):
+            np.testing.assert_array_equal(oi.cpu().numpy(), ei, err_msg=f"replay {rep}")
+            np.testing.assert_array_equal(oa.cpu().numpy().view(np.uint32), ea.view(np.uint32), err_msg=f"replay {rep}")
+    full_check(layers[-1], bufs[-1][0].cpu().numpy(), bufs[-1][1].cpu().numpy())
