@@ -83,6 +83,13 @@ typedef struct pqc_config {
   int32_t n_local;       /* L, always-attended most recent tokens                    */
   int32_t kv_dtype;      /* pqc_dtype of q, k_cache and v_cache                      */
   float softmax_scale;   /* factor on q.k before softmax; <= 0 means 1/sqrt(D)       */
+  int32_t n_capacity;    /* tokens per (sequence, head) that k_cache, v_cache, keys  *
+                          * and codes have room for, >= N: where the layouts below   *
+                          * say [N] for these four tensors, the stride is n_capacity *
+                          * and the first N entries are used.  0 means N (dense).    *
+                          * At most 2^22.  A cache that grows by one token per       *
+                          * decode step keeps its buffers and changes N alone        *
+                          * (pqc_set_length).                                        */
 } pqc_config;
 
 /* Library version: major*10000 + minor*100 + patch. */
@@ -92,13 +99,26 @@ int pqc_version(void);
 const char* pqc_strerror(int status);
 
 /* Bytes of device workspace a context of this configuration needs
- * (0 when the configuration is invalid or unsupported). */
+ * (0 when the configuration is invalid or unsupported).  With n_capacity > n_tokens
+ * the figure covers every length up to the capacity, so that the context can follow a
+ * growing cache (pqc_set_length) in the same workspace. */
 size_t pqc_workspace_bytes(const pqc_config* cfg);
 
 /* Create a context.  `workspace` is device memory of at least
  * pqc_workspace_bytes(cfg) bytes, 256-byte aligned, which must stay valid and
  * untouched by the caller until pqc_destroy.  Host-only: enqueues nothing. */
 int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t workspace_bytes);
+
+/* Change the number of cached tokens N and the number of retrieved tokens K of an
+ * existing context: the decode loop of Algorithm 2 appends one token per step to every
+ * sequence, and the retrieval size follows the length (Section 4.1: a fixed share of
+ * it).  All other fields, the capacity included, stay as created (a context created
+ * without n_capacity has its first N as capacity).  Host-only, enqueues nothing; later
+ * calls on the context use the new shape: out_idx is then [B][Hkv][I+K+L] with the new
+ * K.  PQC_EINVAL when n_tokens exceeds the capacity or I + K + L exceeds n_tokens;
+ * PQC_EWORKSPACE when the workspace given to pqc_create is too small for the new shape
+ * (never the case when it was sized by pqc_workspace_bytes with the capacity set). */
+int pqc_set_length(pqc_ctx* ctx, int32_t n_tokens, int32_t topk);
 
 /* Free the host-side context (the workspace stays the caller's). NULL is allowed. */
 void pqc_destroy(pqc_ctx* ctx);
@@ -144,14 +164,17 @@ int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_
  *                                     c0 + C*c1, over all N tokens: a statistic of `codes`
  *                                     alone, built by pqc_pair_counts and kept in step with
  *                                     appended codes by pqc_pair_counts_add (caller-owned)
- * PQC_EUNSUPPORTED unless pq_m == 2, pq_centroids <= 64 and n_tokens is a multiple of 8. */
+ * PQC_EUNSUPPORTED unless pq_m == 2, pq_centroids <= 64 and the capacity (n_tokens when
+ * none is given) is a multiple of 8. */
 int pqc_decode_indexed(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes,
                        const uint32_t* pair_counts, const void* k_cache, const void* v_cache,
                        int32_t* out_idx, float* out_attn, void* stream);
 
-/* pair_counts of a whole code tensor (fully overwritten), and the update for the one code
- * pair written at `position` of every unit (call after pqc_pq_encode_token for a position
- * that was not counted before).  Need no context.  pq_m == 2 and pq_centroids <= 64. */
+/* pair_counts of the first N tokens of a code tensor (fully overwritten), and the update for
+ * the one code pair written at `position` (< capacity) of every unit: call it after
+ * pqc_pq_encode_token for a position that was not counted before.  pqc_decode_indexed
+ * expects the counts of exactly its N tokens, so in a growing cache every token is encoded
+ * and counted when it is appended.  Need no context.  pq_m == 2 and pq_centroids <= 64. */
 int pqc_pair_counts(const pqc_config* cfg, const uint8_t* codes, uint32_t* pair_counts, void* stream);
 int pqc_pair_counts_add(const pqc_config* cfg, const uint8_t* codes, int32_t position, uint32_t* pair_counts,
                         void* stream);
@@ -225,7 +248,9 @@ int pqc_pq_assign(const pqc_config* cfg, const void* keys, const float* centroid
 /* Code of one new token per (sequence, KV head) (Section 3.1: a token leaving the
  * local window is given the codes of its nearest centroids; Algorithm 2,
  * "PQArgNearest" then "Codes.append"):  key [B][Hkv][D] kv_dtype; writes
- * codes[b][h][position][0..M-1] inside the [B][Hkv][N][M] code tensor; 0 <= position < N. */
+ * codes[b][h][position][0..M-1] inside the code tensor; 0 <= position < capacity (the
+ * code of a token may be written as soon as the token exists: while the token is inside
+ * the local window its code is ignored by pqc_decode). */
 int pqc_pq_encode_token(const pqc_config* cfg, const void* key, const float* centroids,
                         uint8_t* codes, int32_t position, void* stream);
 

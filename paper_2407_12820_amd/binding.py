@@ -7,6 +7,7 @@ is no fallback: if the library has not been built, loading raises.
 from __future__ import annotations
 
 import ctypes as C
+import dataclasses
 import os
 from typing import Optional, Tuple
 
@@ -24,7 +25,7 @@ STATUS = {0: "PQC_OK", -1: "PQC_EINVAL", -2: "PQC_EUNSUPPORTED", -3: "PQC_EWORKS
 class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "n_q_heads", "n_kv_heads", "head_dim", "n_tokens", "pq_m",
                                          "pq_centroids", "topk", "n_init", "n_local", "kv_dtype")] + [
-                                             ("softmax_scale", C.c_float)]
+                                             ("softmax_scale", C.c_float), ("n_capacity", C.c_int32)]
 
 
 _lib = None
@@ -53,6 +54,8 @@ def load() -> C.CDLL:
     lib.pqc_workspace_bytes.argtypes = [cp]
     lib.pqc_create.restype = C.c_int
     lib.pqc_create.argtypes = [C.POINTER(vp), cp, vp, C.c_size_t]
+    lib.pqc_set_length.restype = C.c_int
+    lib.pqc_set_length.argtypes = [vp, C.c_int32, C.c_int32]
     lib.pqc_destroy.restype = None
     lib.pqc_destroy.argtypes = [vp]
     lib.pqc_last_hip_error.restype = C.c_int
@@ -89,9 +92,10 @@ def load() -> C.CDLL:
     return lib
 
 
-def make_config(w: Workload, softmax_scale: float = 0.0) -> Config:
+def make_config(w: Workload, softmax_scale: float = 0.0, capacity: int = 0) -> Config:
+    """capacity: tokens the K/V, key and code tensors have room for per head (0: exactly n_tokens)."""
     return Config(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_tokens, w.pq_m, w.pq_centroids, w.topk,
-                  w.n_init, w.n_local, PQC_F32 if w.dtype == "f32" else PQC_BF16, softmax_scale)
+                  w.n_init, w.n_local, PQC_F32 if w.dtype == "f32" else PQC_BF16, softmax_scale, capacity)
 
 
 class PQCacheError(RuntimeError):
@@ -104,11 +108,12 @@ class PQCacheError(RuntimeError):
 class PQCache:
     """One decode context: a configuration plus its device workspace."""
 
-    def __init__(self, w: Workload, device: str = "cuda:0", softmax_scale: float = 0.0):
+    def __init__(self, w: Workload, device: str = "cuda:0", softmax_scale: float = 0.0, capacity: int = 0):
         self.lib = load()
         self.w = w
+        self.capacity = capacity or w.n_tokens
         self.device = torch.device(device)
-        self.cfg = make_config(w, softmax_scale)
+        self.cfg = make_config(w, softmax_scale, capacity)
         nbytes = self.lib.pqc_workspace_bytes(C.byref(self.cfg))
         if nbytes == 0:
             # let pqc_create say why
@@ -120,6 +125,12 @@ class PQCache:
         if rc != 0:
             raise PQCacheError(rc, "pqc_create")
         self.kv_torch = torch.float32 if w.dtype == "f32" else torch.bfloat16
+
+    def set_length(self, n_tokens: int, topk: int) -> None:
+        """The cache now holds n_tokens tokens (<= capacity) and topk of the middle ones are retrieved."""
+        self._check(self.lib.pqc_set_length(self.handle, n_tokens, topk), "pqc_set_length")
+        self.w = dataclasses.replace(self.w, n_tokens=n_tokens, topk=topk)
+        self.cfg.n_tokens, self.cfg.topk = n_tokens, topk
 
     def close(self) -> None:
         if getattr(self, "handle", None) is not None and self.handle.value:
@@ -155,8 +166,8 @@ class PQCache:
         return {
             "q": (w.batch, w.n_q_heads, w.head_dim),
             "centroids": (w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids, w.sub_dim),
-            "codes": (w.batch, w.n_kv_heads, w.n_tokens, w.pq_m),
-            "kv": (w.batch, w.n_kv_heads, w.n_tokens, w.head_dim),
+            "codes": (w.batch, w.n_kv_heads, self.capacity, w.pq_m),
+            "kv": (w.batch, w.n_kv_heads, self.capacity, w.head_dim),
             "idx": (w.batch, w.n_kv_heads, w.n_selected),
             "out": (w.batch, w.n_q_heads, w.head_dim),
             "table": (w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids),
@@ -270,10 +281,14 @@ def _need(t: torch.Tensor, dtype, shape, what: str) -> int:
     return t.data_ptr()
 
 
-def pq_build(w: Workload, keys: torch.Tensor, init_idx: torch.Tensor, iters: Optional[int] = None, stream=None):
-    """K-Means PQ construction on the GPU -> (centroids [B,Hkv,M,C,Dm] f32, codes [B,Hkv,N,M] u8)."""
+def pq_build(w: Workload, keys: torch.Tensor, init_idx: torch.Tensor, iters: Optional[int] = None, stream=None,
+             capacity: int = 0):
+    """K-Means PQ construction on the GPU -> (centroids [B,Hkv,M,C,Dm] f32, codes [B,Hkv,N,M] u8).
+
+    capacity (here and below): token room of `keys` and `codes` per head when it exceeds w.n_tokens."""
     lib = load()
-    cfg = make_config(w)
+    cfg = make_config(w, capacity=capacity)
+    ntok = capacity or w.n_tokens
     dev = keys.device
     iters = w.kmeans_iters if iters is None else iters
     nbytes = lib.pqc_pq_build_workspace_bytes(C.byref(cfg))
@@ -281,9 +296,9 @@ def pq_build(w: Workload, keys: torch.Tensor, init_idx: torch.Tensor, iters: Opt
         raise PQCacheError(-1, "pqc_pq_build_workspace_bytes")
     ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     cent = torch.empty((w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids, w.sub_dim), dtype=torch.float32, device=dev)
-    codes = torch.empty((w.batch, w.n_kv_heads, w.n_tokens, w.pq_m), dtype=torch.uint8, device=dev)
+    codes = torch.zeros((w.batch, w.n_kv_heads, ntok, w.pq_m), dtype=torch.uint8, device=dev)
     st = (stream if stream is not None else torch.cuda.current_stream(dev)).cuda_stream
-    rc = lib.pqc_pq_build(C.byref(cfg), _need(keys, _kv_dtype(w), (w.batch, w.n_kv_heads, w.n_tokens, w.head_dim), "keys"),
+    rc = lib.pqc_pq_build(C.byref(cfg), _need(keys, _kv_dtype(w), (w.batch, w.n_kv_heads, ntok, w.head_dim), "keys"),
                           _need(init_idx, torch.int32, (w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids), "init_idx"),
                           iters, cent.data_ptr(), codes.data_ptr(), ws.data_ptr(), nbytes, st)
     if rc != 0:
@@ -291,13 +306,14 @@ def pq_build(w: Workload, keys: torch.Tensor, init_idx: torch.Tensor, iters: Opt
     return cent, codes
 
 
-def pq_assign(w: Workload, keys: torch.Tensor, centroids: torch.Tensor, stream=None) -> torch.Tensor:
+def pq_assign(w: Workload, keys: torch.Tensor, centroids: torch.Tensor, stream=None, capacity: int = 0) -> torch.Tensor:
     lib = load()
-    cfg = make_config(w)
+    cfg = make_config(w, capacity=capacity)
+    ntok = capacity or w.n_tokens
     dev = keys.device
-    codes = torch.empty((w.batch, w.n_kv_heads, w.n_tokens, w.pq_m), dtype=torch.uint8, device=dev)
+    codes = torch.zeros((w.batch, w.n_kv_heads, ntok, w.pq_m), dtype=torch.uint8, device=dev)
     st = (stream if stream is not None else torch.cuda.current_stream(dev)).cuda_stream
-    rc = lib.pqc_pq_assign(C.byref(cfg), _need(keys, _kv_dtype(w), (w.batch, w.n_kv_heads, w.n_tokens, w.head_dim), "keys"),
+    rc = lib.pqc_pq_assign(C.byref(cfg), _need(keys, _kv_dtype(w), (w.batch, w.n_kv_heads, ntok, w.head_dim), "keys"),
                            _need(centroids, torch.float32, (w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids, w.sub_dim), "centroids"),
                            codes.data_ptr(), st)
     if rc != 0:
@@ -306,23 +322,24 @@ def pq_assign(w: Workload, keys: torch.Tensor, centroids: torch.Tensor, stream=N
 
 
 def pq_encode_token(w: Workload, key: torch.Tensor, centroids: torch.Tensor, codes: torch.Tensor, position: int,
-                    stream=None) -> None:
+                    stream=None, capacity: int = 0) -> None:
     """Write the nearest-centroid codes of one new key per (sequence, KV head) at `position` of `codes`."""
     lib = load()
-    cfg = make_config(w)
+    cfg = make_config(w, capacity=capacity)
     st = (stream if stream is not None else torch.cuda.current_stream(key.device)).cuda_stream
     rc = lib.pqc_pq_encode_token(C.byref(cfg), _need(key, _kv_dtype(w), (w.batch, w.n_kv_heads, w.head_dim), "key"),
                                  _need(centroids, torch.float32, (w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids, w.sub_dim), "centroids"),
-                                 _need(codes, torch.uint8, (w.batch, w.n_kv_heads, w.n_tokens, w.pq_m), "codes"), position, st)
+                                 _need(codes, torch.uint8, (w.batch, w.n_kv_heads, capacity or w.n_tokens, w.pq_m), "codes"),
+                                 position, st)
     if rc != 0:
         raise PQCacheError(rc, "pqc_pq_encode_token")
 
 
-def pair_counts(w: Workload, codes: torch.Tensor, stream=None) -> torch.Tensor:
+def pair_counts(w: Workload, codes: torch.Tensor, stream=None, capacity: int = 0) -> torch.Tensor:
     """Tokens per pair of codes, [B][Hkv][C*C] (uint32 values in an int32 tensor); two partitions only."""
     lib = load()
-    cfg = make_config(w)
-    _need(codes, torch.uint8, (w.batch, w.n_kv_heads, w.n_tokens, w.pq_m), "codes")
+    cfg = make_config(w, capacity=capacity)
+    _need(codes, torch.uint8, (w.batch, w.n_kv_heads, capacity or w.n_tokens, w.pq_m), "codes")
     out = torch.empty((w.batch, w.n_kv_heads, w.pq_centroids * w.pq_centroids), dtype=torch.int32, device=codes.device)
     st = (stream if stream is not None else torch.cuda.current_stream(codes.device)).cuda_stream
     rc = lib.pqc_pair_counts(C.byref(cfg), codes.data_ptr(), out.data_ptr(), st)
@@ -331,9 +348,10 @@ def pair_counts(w: Workload, codes: torch.Tensor, stream=None) -> torch.Tensor:
     return out
 
 
-def pair_counts_add(w: Workload, codes: torch.Tensor, position: int, counts: torch.Tensor, stream=None) -> None:
+def pair_counts_add(w: Workload, codes: torch.Tensor, position: int, counts: torch.Tensor, stream=None,
+                    capacity: int = 0) -> None:
     lib = load()
-    cfg = make_config(w)
+    cfg = make_config(w, capacity=capacity)
     st = (stream if stream is not None else torch.cuda.current_stream(codes.device)).cuda_stream
     rc = lib.pqc_pair_counts_add(C.byref(cfg), codes.data_ptr(), position, counts.data_ptr(), st)
     if rc != 0:

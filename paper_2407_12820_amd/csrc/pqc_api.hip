@@ -31,6 +31,26 @@ int env_int(const char* name, int fallback) {
   return x > 0 ? x : fallback;
 }
 
+// Offsets of the workspace regions for the given per-unit sizes.
+void lay_out(Plan* p, size_t bins_per_unit, size_t stage_words_per_unit, size_t counts_per_unit, size_t partials_per_unit) {
+  const Shape& s = p->s;
+  const size_t units = (size_t)s.B * s.Hkv;
+  size_t off = 0;
+  p->off_ctl = off;   off = align_up(off + sizeof(BinParams) * units);
+  p->off_lut = off;   off = align_up(off + sizeof(float) * units * s.M * s.C);
+  p->off_range = off; off = align_up(off + sizeof(float2) * units);
+  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * units * (kHistCopies * kNB + 1));  // + record counters
+  p->off_bins = off;  off = align_up(off + sizeof(unsigned short) * units * bins_per_unit);
+  p->off_crec = off;  off = align_up(off + (size_t)p->rec_stride * kCandRec * units);
+  p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * stage_words_per_unit);
+  p->off_cnt = off;   off = align_up(off + sizeof(int2) * units * counts_per_unit);
+  p->off_part = off;  off = align_up(off + sizeof(float) * units * partials_per_unit * s.G * (kD + 2));
+#ifdef PQC_TRACE
+  p->off_trace = off; off = align_up(off + sizeof(unsigned long long) * 3 * kTraceWgs * kTraceSlots);
+#endif
+  p->total = off;
+}
+
 int make_plan(const pqc_config* c, Plan* p) {
   if (!c) return PQC_EINVAL;
   if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1 || c->n_tokens < 1 || c->pq_m < 1 ||
@@ -45,20 +65,22 @@ int make_plan(const pqc_config* c, Plan* p) {
   if (c->pq_m != 1 && c->pq_m != 2 && c->pq_m != 4 && c->pq_m != 8) return PQC_EUNSUPPORTED;
   if (c->pq_centroids > 256) return PQC_EUNSUPPORTED;
   if (G != 1 && G != 2 && G != 4 && G != 8) return PQC_EUNSUPPORTED;
-  if (c->n_tokens > (1 << 22)) return PQC_EUNSUPPORTED;
+  if (c->n_capacity < 0 || (c->n_capacity && c->n_capacity < c->n_tokens)) return PQC_EINVAL;
+  if (c->n_tokens > (1 << 22) || c->n_capacity > (1 << 22)) return PQC_EUNSUPPORTED;
   if ((long long)c->batch * c->n_kv_heads > 65535) return PQC_EUNSUPPORTED;
 
   Shape& s = p->s;
   s.B = c->batch; s.Hq = c->n_q_heads; s.Hkv = c->n_kv_heads; s.G = G; s.N = c->n_tokens;
+  s.cap = c->n_capacity ? c->n_capacity : c->n_tokens;
   s.M = c->pq_m; s.C = c->pq_centroids; s.Dm = c->head_dim / c->pq_m;
   s.K = c->topk; s.I = c->n_init; s.L = c->n_local; s.Ktot = s.I + s.K + s.L;
   const float scale = c->softmax_scale > 0.0f ? c->softmax_scale : 1.0f / std::sqrt((float)c->head_dim);
   s.scale_log2e = scale * 1.4426950408889634f;
   const long long units = (long long)s.B * s.Hkv;
 
-  // A unit's codes start at byte u*N*M; when that is not always 16-byte aligned the first
+  // A unit's codes start at byte u*cap*M; when that is not always 16-byte aligned the first
   // chunk of a unit begins with up to 15 phantom tokens that the grids must cover as well.
-  const int lead = ((long long)s.N * s.M) % 16 == 0 ? 0 : 15;
+  const int lead = ((long long)s.cap * s.M) % 16 == 0 ? 0 : 15;
   // histogram kernel: about one 1024-thread workgroup per compute unit over all units
   const int maxA = 4096 * (16 / s.M) < 16384 ? 4096 * (16 / s.M) : 16384;  // kMaxVecA chunks per thread
   int tokA = env_int("PQC_TOK_A", 0);
@@ -96,21 +118,30 @@ int make_plan(const pqc_config* c, Plan* p) {
     if (s.rankHi < 1) s.rankHi = 0;
   }
 
-  size_t off = 0;
-  p->off_ctl = off;   off = align_up(off + sizeof(BinParams) * units);
-  p->off_lut = off;   off = align_up(off + sizeof(float) * units * s.M * s.C);
-  p->off_range = off; off = align_up(off + sizeof(float2) * units);
-  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * units * (kHistCopies * kNB + 1));  // + record counters
-  p->off_bins = off;  off = align_up(off + sizeof(unsigned short) * units * s.binStride);
-  p->off_crec = off;  off = align_up(off + (size_t)p->rec_stride * kCandRec * units);
-  p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * s.nblkC * s.stageStride);
-  p->off_cnt = off;   off = align_up(off + sizeof(int2) * units * s.nblkC);
-  p->off_part = off;  off = align_up(off + sizeof(float) * units * s.npart * s.G * (kD + 2));
-#ifdef PQC_TRACE
-  p->off_trace = off; off = align_up(off + sizeof(unsigned long long) * 3 * kTraceWgs * kTraceSlots);
-#endif
-  p->total = off;
+  lay_out(p, (size_t)s.binStride, (size_t)s.nblkC * s.stageStride, (size_t)s.nblkC, (size_t)s.npart);
   return PQC_OK;
+}
+
+// Workspace needed by any context of this configuration whose length is changed later
+// (pqc_set_length) to anything up to the capacity: every size that depends on the length,
+// replaced by a bound over all lengths.
+size_t workspace_bound(const pqc_config* c) {
+  Plan p;
+  if (make_plan(c, &p) != PQC_OK) return 0;
+  const Shape& s = p.s;
+  if (s.cap == s.N) return p.total;
+  const size_t units = (size_t)s.B * s.Hkv, cap = (size_t)s.cap;
+  // select kernel grid: tokens per workgroup double until the grid has at most 512 workgroups or
+  // they reach 8192 (an override by environment may pin them as low as 512)
+  const size_t tok_min = env_int("PQC_TOK_C", 0) ? (size_t)env_int("PQC_TOK_C", 0) : 8192;
+  size_t nb = 512 / units;
+  if (nb < (cap + tok_min - 1) / tok_min) nb = (cap + tok_min - 1) / tok_min;
+  if (nb < 1) nb = 1;
+  size_t npart = (cap + s.rowsP - 1) / s.rowsP;
+  if (npart < nb) npart = nb;
+  if (npart < (size_t)2 * kAccBatch) npart = (size_t)2 * kAccBatch;
+  lay_out(&p, cap + 8192, cap + 8192 + 40 * nb, nb, npart);
+  return p.total;
 }
 
 }  // namespace
@@ -119,6 +150,8 @@ struct pqc_ctx {
   pqc_config cfg;
   Plan plan;
   Workspace ws;
+  char* workspace;         // the caller's device memory
+  size_t workspace_bytes;
   bool hist_clean;  // the histogram is known to be all zero
   int last_hip;
 };
@@ -218,7 +251,7 @@ void launch_indexed_t(pqc_ctx* ctx, const void* q, const float* cent, const uint
 }
 
 bool pairs_supported(const pqc_config* c) {
-  return c->pq_m == 2 && c->pq_centroids <= kPairC && c->n_tokens % 8 == 0;
+  return c->pq_m == 2 && c->pq_centroids <= kPairC && (c->n_capacity ? c->n_capacity : c->n_tokens) % 8 == 0;
 }
 
 template <typename T, int G>
@@ -264,7 +297,7 @@ void launch_scan_m(pqc_ctx* ctx, const float* table, const uint8_t* codes, float
 
 extern "C" {
 
-int pqc_version(void) { return 100; }
+int pqc_version(void) { return 200; }
 
 const char* pqc_strerror(int status) {
   switch (status) {
@@ -285,24 +318,13 @@ size_t pqc_debug_trace_offset(const pqc_config* cfg) {
 }
 #endif
 
-size_t pqc_workspace_bytes(const pqc_config* cfg) {
-  Plan p;
-  if (make_plan(cfg, &p) != PQC_OK) return 0;
-  return p.total;
-}
+size_t pqc_workspace_bytes(const pqc_config* cfg) { return workspace_bound(cfg); }
 
-int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t workspace_bytes) {
-  if (!out) return PQC_EINVAL;
-  *out = nullptr;
-  Plan p;
-  const int rc = make_plan(cfg, &p);
-  if (rc != PQC_OK) return rc;
-  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) || workspace_bytes < p.total) return PQC_EWORKSPACE;
-  pqc_ctx* ctx = new (std::nothrow) pqc_ctx;
-  if (!ctx) return PQC_EINVAL;
-  ctx->cfg = *cfg;
-  ctx->plan = p;
-  char* base = static_cast<char*>(workspace);
+namespace {
+// Point the context's views at the regions of its plan.
+void bind_workspace(pqc_ctx* ctx) {
+  const Plan& p = ctx->plan;
+  char* base = ctx->workspace;
   ctx->ws.ctl = reinterpret_cast<BinParams*>(base + p.off_ctl);
   ctx->ws.lut = reinterpret_cast<float*>(base + p.off_lut);
   ctx->ws.hist = reinterpret_cast<unsigned*>(base + p.off_hist);
@@ -317,9 +339,43 @@ int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t wor
 #ifdef PQC_TRACE
   ctx->ws.trace = reinterpret_cast<unsigned long long*>(base + p.off_trace);
 #endif
+}
+}  // namespace
+
+int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t workspace_bytes) {
+  if (!out) return PQC_EINVAL;
+  *out = nullptr;
+  Plan p;
+  const int rc = make_plan(cfg, &p);
+  if (rc != PQC_OK) return rc;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) || workspace_bytes < p.total) return PQC_EWORKSPACE;
+  pqc_ctx* ctx = new (std::nothrow) pqc_ctx;
+  if (!ctx) return PQC_EINVAL;
+  ctx->cfg = *cfg;
+  ctx->cfg.n_capacity = p.s.cap;
+  ctx->plan = p;
+  ctx->workspace = static_cast<char*>(workspace);
+  ctx->workspace_bytes = workspace_bytes;
+  bind_workspace(ctx);
   ctx->hist_clean = false;
   ctx->last_hip = 0;
   *out = ctx;
+  return PQC_OK;
+}
+
+int pqc_set_length(pqc_ctx* ctx, int32_t n_tokens, int32_t topk) {
+  if (!ctx) return PQC_EINVAL;
+  pqc_config c = ctx->cfg;
+  c.n_tokens = n_tokens;
+  c.topk = topk;
+  Plan p;
+  const int rc = make_plan(&c, &p);  // rejects a length beyond the capacity
+  if (rc != PQC_OK) return rc;
+  if (p.total > ctx->workspace_bytes) return PQC_EWORKSPACE;
+  // The histogram region does not move and a clean one is all zero, whatever the length: it stays clean.
+  ctx->cfg = c;
+  ctx->plan = p;
+  bind_workspace(ctx);
   return PQC_OK;
 }
 
@@ -390,7 +446,7 @@ int pqc_pair_counts(const pqc_config* cfg, const uint8_t* codes, uint32_t* pair_
   const size_t n = (size_t)s.B * s.Hkv * s.C * s.C;
   hipLaunchKernelGGL(reset_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, pair_counts, n);
   hipLaunchKernelGGL(pair_count_kernel, dim3((unsigned)((s.N + kPairTok - 1) / kPairTok), (unsigned)(s.B * s.Hkv)), dim3(256), 0,
-                     st, codes, s.N, s.C, pair_counts);
+                     st, codes, s.N, s.cap, s.C, pair_counts);
   return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
 }
 
@@ -398,11 +454,11 @@ int pqc_pair_counts_add(const pqc_config* cfg, const uint8_t* codes, int32_t pos
   Plan p;
   const int rc = make_plan(cfg, &p);
   if (rc != PQC_OK) return rc;
-  if (!codes || !pair_counts || position < 0 || position >= cfg->n_tokens) return PQC_EINVAL;
+  if (!codes || !pair_counts || position < 0 || position >= p.s.cap) return PQC_EINVAL;
   if (cfg->pq_m != 2 || cfg->pq_centroids > kPairC) return PQC_EUNSUPPORTED;
   const int units = p.s.B * p.s.Hkv;
   hipLaunchKernelGGL(pair_count_add_kernel, dim3((unsigned)((units + 63) / 64)), dim3(64), 0, static_cast<hipStream_t>(stream),
-                     codes, p.s.N, p.s.C, units, (int)position, pair_counts);
+                     codes, p.s.cap, p.s.C, units, (int)position, pair_counts);
   return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
 }
 
@@ -489,7 +545,7 @@ int make_build_plan(const pqc_config* cfg, BuildPlan* bp) {
   const int rc = make_plan(cfg, &p);
   if (rc != PQC_OK) return rc;
   bp->s.units = p.s.B * p.s.Hkv;
-  bp->s.N = p.s.N; bp->s.M = p.s.M; bp->s.C = p.s.C; bp->s.Dm = p.s.Dm;
+  bp->s.N = p.s.N; bp->s.M = p.s.M; bp->s.C = p.s.C; bp->s.Dm = p.s.Dm; bp->s.cap = p.s.cap;
   const size_t n = (size_t)bp->s.units * p.s.M * p.s.C;
   bp->off_sums = 0;
   bp->off_counts = align_up(sizeof(unsigned long long) * n * p.s.Dm);
@@ -532,7 +588,7 @@ int pq_build_t(const BuildPlan& bp, const T* keys, const int32_t* init_idx, int 
   const size_t ncent = (size_t)uj * s.C * s.Dm;
   hipLaunchKernelGGL((pq_init_kernel<T>), dim3(1, uj), dim3(256), 0, st, s, keys, init_idx, cent);
   for (int it = 0; it < iters; ++it) {
-    launch_assign<T>(s, keys, (int64_t)s.N * kD, s.N, 0, cent, codes, st);
+    launch_assign<T>(s, keys, (int64_t)s.cap * kD, s.N, 0, cent, codes, st);
     hipLaunchKernelGGL(pq_zero_kernel, dim3((unsigned)((nacc + 255) / 256)), dim3(256), 0, st, sums, nacc);
     {
       const dim3 grid((s.N + kAccumTok - 1) / kAccumTok, uj);
@@ -545,7 +601,7 @@ int pq_build_t(const BuildPlan& bp, const T* keys, const int32_t* init_idx, int 
     }
     hipLaunchKernelGGL(pq_mean_kernel, dim3((unsigned)((ncent + 255) / 256)), dim3(256), 0, st, s, sums, counts, cent);
   }
-  launch_assign<T>(s, keys, (int64_t)s.N * kD, s.N, 0, cent, codes, st);
+  launch_assign<T>(s, keys, (int64_t)s.cap * kD, s.N, 0, cent, codes, st);
   return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
 }
 
@@ -582,9 +638,9 @@ int pqc_pq_assign(const pqc_config* cfg, const void* keys, const float* centroid
   hipStream_t st = static_cast<hipStream_t>(stream);
   const BuildShape& s = bp.s;
   if (cfg->kv_dtype == PQC_F32)
-    launch_assign<float>(s, static_cast<const float*>(keys), (int64_t)s.N * kD, s.N, 0, centroids, codes, st);
+    launch_assign<float>(s, static_cast<const float*>(keys), (int64_t)s.cap * kD, s.N, 0, centroids, codes, st);
   else
-    launch_assign<bf16_t>(s, static_cast<const bf16_t*>(keys), (int64_t)s.N * kD, s.N, 0, centroids, codes, st);
+    launch_assign<bf16_t>(s, static_cast<const bf16_t*>(keys), (int64_t)s.cap * kD, s.N, 0, centroids, codes, st);
   return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
 }
 
@@ -593,7 +649,7 @@ int pqc_pq_encode_token(const pqc_config* cfg, const void* key, const float* cen
   BuildPlan bp;
   const int rc = make_build_plan(cfg, &bp);
   if (rc != PQC_OK) return rc;
-  if (!key || !centroids || !codes || position < 0 || position >= bp.s.N) return PQC_EINVAL;
+  if (!key || !centroids || !codes || position < 0 || position >= bp.s.cap) return PQC_EINVAL;
   if (!aligned16(key) || !aligned16(centroids) || !aligned16(codes)) return PQC_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const BuildShape& s = bp.s;

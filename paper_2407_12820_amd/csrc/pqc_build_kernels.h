@@ -19,6 +19,7 @@ constexpr int kAccumTok = 2048;   // tokens per workgroup of the accumulation ke
 
 struct BuildShape {
   int units, N, M, C, Dm;
+  int cap;  // tokens the key and code tensors hold per unit (>= N): their stride between units
 };
 
 // centroids[u][j][c][:] = keys[u][init_idx[u][j][c]][j*Dm : (j+1)*Dm]
@@ -30,7 +31,7 @@ __global__ __launch_bounds__(256) void pq_init_kernel(BuildShape s, const T* __r
     const int c = i / s.Dm, e = i % s.Dm;
     int t = init_idx[(size_t)uj * s.C + c];
     t = max(0, min(s.N - 1, t));
-    cent[(size_t)uj * s.C * s.Dm + i] = load_as_float<T>(keys, ((size_t)u * s.N + t) * kD + j * s.Dm + e);
+    cent[(size_t)uj * s.C * s.Dm + i] = load_as_float<T>(keys, ((size_t)u * s.cap + t) * kD + j * s.Dm + e);
   }
 }
 
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(256) void pq_assign_kernel(BuildShape s, const T* _
       }
     }
   }
-  if (live) codes[((size_t)u * s.N + code_pos0 + t) * s.M + j] = (uint8_t)arg;
+  if (live) codes[((size_t)u * s.cap + code_pos0 + t) * s.M + j] = (uint8_t)arg;
 }
 
 // The same assignment on the matrix cores, for bf16 keys and sub-vectors of 32, 64 or 128
@@ -209,7 +210,7 @@ __global__ __launch_bounds__(256) void pq_assign_mfma_kernel(BuildShape s, const
         take(dpp_f<0x141>(v, v), dpp_i<0x141>(x, x));
         take(dpp_f<0x140>(v, v), dpp_i<0x140>(x, x));
         const int t = tok0 + tt * 16 + 4 * quad + i;
-        if (col == 0 && t < n_tokens) codes[((size_t)u * s.N + code_pos0 + t) * s.M + j] = (uint8_t)x;
+        if (col == 0 && t < n_tokens) codes[((size_t)u * s.cap + code_pos0 + t) * s.M + j] = (uint8_t)x;
       }
   }
 }
@@ -255,10 +256,10 @@ __global__ __launch_bounds__(256) void pq_accum_kernel(BuildShape s, const T* __
 #pragma unroll
       for (int k = 0; k < U; ++k) {
         const int t = min(tb + k * step, t1 - 1);  // clamped: straight-line loads, masked below
-        c[k] = (int)codes[((size_t)u * s.N + t) * s.M + j] - c0;
+        c[k] = (int)codes[((size_t)u * s.cap + t) * s.M + j] - c0;
 #pragma unroll
         for (int e = 0; e < EPL; ++e)
-          xv[k][e] = load_as_float<T>(keys, ((size_t)u * s.N + t) * kD + j * DM + sub + e * LPT);
+          xv[k][e] = load_as_float<T>(keys, ((size_t)u * s.cap + t) * kD + j * DM + sub + e * LPT);
       }
 #pragma unroll
       for (int k = 0; k < U; ++k) {
@@ -355,13 +356,13 @@ __global__ __launch_bounds__(1024) void block_stats_kernel(const int* __restrict
 // M = 2: how many tokens of a unit carry each pair of codes (c0 + C*c1), over all N tokens.
 // A statistic of the codes alone; pqc_decode_indexed takes its threshold from it.
 constexpr int kPairTok = 8192;  // tokens per workgroup
-__global__ __launch_bounds__(256) void pair_count_kernel(const uint8_t* __restrict__ codes, int N, int C,
+__global__ __launch_bounds__(256) void pair_count_kernel(const uint8_t* __restrict__ codes, int N, int cap, int C,
                                                          unsigned* __restrict__ counts) {
   __shared__ unsigned h[4096];
   const int u = blockIdx.y, tid = threadIdx.x, np = C * C;
   for (int i = tid; i < np; i += 256) h[i] = 0u;
   __syncthreads();
-  const unsigned short* cu = reinterpret_cast<const unsigned short*>(codes) + (size_t)u * N;
+  const unsigned short* cu = reinterpret_cast<const unsigned short*>(codes) + (size_t)u * cap;
   const int t1 = min(N, ((int)blockIdx.x + 1) * kPairTok);
   for (int t = blockIdx.x * kPairTok + tid; t < t1; t += 256) {
     const unsigned cw = cu[t];
@@ -374,11 +375,11 @@ __global__ __launch_bounds__(256) void pair_count_kernel(const uint8_t* __restri
 }
 
 // one appended token per unit: its pair gains a token
-__global__ void pair_count_add_kernel(const uint8_t* __restrict__ codes, int N, int C, int units, int position,
+__global__ void pair_count_add_kernel(const uint8_t* __restrict__ codes, int cap, int C, int units, int position,
                                       unsigned* __restrict__ counts) {
   const int u = blockIdx.x * blockDim.x + threadIdx.x;
   if (u >= units) return;
-  const uint8_t* cp = codes + ((size_t)u * N + position) * 2;
+  const uint8_t* cp = codes + ((size_t)u * cap + position) * 2;
   const int pr = (int)cp[0] + C * (int)cp[1];
   if (pr < C * C) counts[(size_t)u * C * C + pr] += 1u;
 }

@@ -29,6 +29,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 // Geometry of one decode step, passed by value to every kernel.
 struct Shape {
   int B, Hq, Hkv, G, N, M, C, Dm, K, I, L, Ktot;
+  int cap;          // tokens the K/V caches and the code tensor hold per unit (>= N): their stride between units
   int tokA, nblkA;  // histogram kernel: tokens per workgroup, workgroups per unit
   int tokC, nblkC;  // select kernel: tokens per workgroup, workgroups per unit
   int rowsP, nblkP; // list-attention kernel: rows per workgroup, workgroups per unit

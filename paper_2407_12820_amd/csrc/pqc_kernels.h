@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void scan_kernel(Shape s, const float* __restr
   for (int e = threadIdx.x; e < M * s.C; e += 256) lut[(e / s.C) * kLutRow + (e % s.C)] = table[(size_t)u * M * s.C + e];
   __syncthreads();
   using W = typename CodeWord<M>::type;
-  const W* cw = reinterpret_cast<const W*>(codes) + (size_t)u * s.N;
+  const W* cw = reinterpret_cast<const W*>(codes) + (size_t)u * s.cap;
   const int t0 = blockIdx.x * 2048;
   for (int t = t0 + threadIdx.x; t < min(t0 + 2048, s.N); t += 256) {
     const bool mid = t >= s.I && t < s.N - s.L;
@@ -216,7 +216,8 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   PQC_NOTE(ws, 0, 15, (__builtin_amdgcn_s_getreg(20 | (3 << 11)) & 15) | (u << 8));  // XCC_ID[3:0], unit
 #endif
   SRC src;
-  src.init(src_ptr, u, s.N, units, lut, ws.hist);
+  const int src_stride = SRC::kFromCodes ? s.cap : s.N;  // tokens between units: code tensor, or dense score array
+  src.init(src_ptr, u, src_stride, units, lut, ws.hist);
   // this workgroup's chunks and this thread's sample: the loads are issued before anything else,
   // except that a table build puts its centroid loads in front of them
   const int chunks = s.tokA / P, chunk0 = bx * chunks;
@@ -227,7 +228,7 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
 #pragma unroll
     for (int v = 0; v < kMaxVecA; ++v) raw[v] = src.load(chunk0 + min(v * NT + tid, chunks - 1));
     const int sample_i = min(tid, s.sampleN - 1);
-    sample = src.load_one(min(s.N - 1, s.I + (int)(((long long)sample_i * max(0, s.N - s.I - s.L)) / s.sampleN)), u, s.N);
+    sample = src.load_one(min(s.N - 1, s.I + (int)(((long long)sample_i * max(0, s.N - s.I - s.L)) / s.sampleN)), u, src_stride);
   };
   float2 bounds;
   if constexpr (SRC::kFromCodes) {
@@ -331,7 +332,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   __shared__ float red[ATTN ? NW * G * (kD + 2) : 1];
   __shared__ float qlds[ATTN ? G * kD : 1];
   __shared__ __attribute__((aligned(16))) unsigned char vtile[kMfma ? NW * kVTileBytes : 16];
-  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, units = s.B * s.Hkv;
+  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = u / s.Hkv, g = u % s.Hkv;
   PQC_MARK(ws, 1, 0);
   // this wave's stored bins, the query and the histogram: all requested up front
@@ -340,9 +341,9 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   const int wave_t0 = blockIdx.x * s.tokC + w * tpw;
   // 16 bytes per group of 8 tokens: their stored bins, or (PAIRS) their codes
   const unsigned short* bins_u =
-      PAIRS ? reinterpret_cast<const unsigned short*>(static_cast<const uint8_t*>(src_ptr) + (size_t)u * s.N * 2)
+      PAIRS ? reinterpret_cast<const unsigned short*>(static_cast<const uint8_t*>(src_ptr) + (size_t)u * s.cap * 2)
             : ws.bins + (size_t)u * s.binStride;
-  const int last_group = PAIRS ? s.N - 8 : s.binStride - 8;  // PAIRS: N is a multiple of 8
+  const int last_group = PAIRS ? s.cap - 8 : s.binStride - 8;  // PAIRS: the capacity is a multiple of 8
   uint4 raw[kMaxVecC];
 #pragma unroll
   for (int v = 0; v < kMaxVecC; ++v)
@@ -364,7 +365,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
         if (x * NT + tid < G * kD) qlds[x * NT + tid] = qreg[x];
     }
     pth = pair_threshold<T, NT>(s, q + ((size_t)b * s.Hq + (size_t)g * G) * kD, cent + (size_t)u * 2 * s.C * (kD / 2),
-                                pair_counts + (size_t)u * s.C * s.C, static_cast<const uint8_t*>(src_ptr) + (size_t)u * s.N * 2,
+                                pair_counts + (size_t)u * s.C * s.C, static_cast<const uint8_t*>(src_ptr) + (size_t)u * s.cap * 2,
                                 pl, scan_sm, [&](int slot) { PQC_MARK(ws, 1, slot); });  // syncs: qlds ready
   } else {
     ThresholdSearch<NT> ts;
@@ -457,7 +458,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
     CandKey k;
     k.sc = 0.0f;
     if constexpr (SRC::kFromCodes) {
-      const uint8_t* cp = static_cast<const uint8_t*>(src_ptr) + ((size_t)u * s.N + t) * SRC::M;
+      const uint8_t* cp = static_cast<const uint8_t*>(src_ptr) + ((size_t)u * s.cap + t) * SRC::M;
 #pragma unroll
       for (int j = 0; j < SRC::M; ++j) k.cb[j] = cp[j];
     } else {
@@ -491,8 +492,8 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   int* stage32 = reinterpret_cast<int*>(stage);
   PQC_MARK(ws, 1, 3);
 
-  const T* kbase = kc + (size_t)u * s.N * kD;
-  const T* vbase = vc + (size_t)u * s.N * kD;
+  const T* kbase = kc + (size_t)u * s.cap * kD;
+  const T* vbase = vc + (size_t)u * s.cap * kD;
   // The first candidates (one per 16-lane group): their codes and K/V rows are requested now, so that
   // after the attention only the table look-up, arithmetic and the record write remain.
   const int sub = lane & 15, grp = tid >> 4;
@@ -673,7 +674,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
   __shared__ float red[ATTN ? NW * (kD + 2) : 1];
   __shared__ float half_acc[ATTN ? kD : 1];
   __shared__ float vl[ATTN ? kRankChunk * kD : 1];
-  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, units = s.B * s.Hkv;
+  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = u / s.Hkv, g = u % s.Hkv;
   int* pre_sel = dyn;
   int* pre_cand = dyn + (s.nblkC + 1);
@@ -1026,7 +1027,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       __syncthreads();
       if constexpr (ATTN) {
         auto row_at = [&](int p) -> int { return rows_sm[p]; };
-        attend_rows<T, 1, 4>(kc + (size_t)u * s.N * kD, vc + (size_t)u * s.N * kD, s.N, row_at, tot, w * 16, NW * 16, qr, st);
+        attend_rows<T, 1, 4>(kc + (size_t)u * s.cap * kD, vc + (size_t)u * s.cap * kD, s.N, row_at, tot, w * 16, NW * 16, qr, st);
       }
       __syncthreads();
       carry += tot;
@@ -1079,8 +1080,8 @@ __global__ __launch_bounds__(256) void attn_list_kernel(Shape s, Workspace ws, c
   for (int p = tid; p < count; p += NT) lst[p] = idx[(size_t)u * s.Ktot + p0 + p];
   __syncthreads();
   auto row_at = [&](int p) -> int { return lst[p]; };
-  const T* kbase = kc + (size_t)u * s.N * kD;
-  const T* vbase = vc + (size_t)u * s.N * kD;
+  const T* kbase = kc + (size_t)u * s.cap * kD;
+  const T* vbase = vc + (size_t)u * s.cap * kD;
   if constexpr (kMfma) {
     bf16x8_t qf[4];
     load_q_frags(reinterpret_cast<const bf16_t*>(q) + ((size_t)b * s.Hq + (size_t)g * G) * kD, G, qf);

@@ -1,9 +1,11 @@
 """Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the
 header declares, and its host logic (configuration checks, workspace sizing) behaves."""
 import ctypes as C
+import dataclasses
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2407_12820_amd import binding, workloads as wl
@@ -115,6 +117,56 @@ def test_argument_checks_of_the_newer_entry_points():
     assert lib.pqc_create(C.byref(h), C.byref(four), C.c_void_p(4096), need4) == 0
     assert lib.pqc_decode_indexed(h, *([p] * 9), None) == -2
     lib.pqc_destroy(h)
+
+
+def test_workspace_for_a_capacity_covers_every_length():
+    # a context that follows a growing cache keeps its workspace: the size reported for a capacity must
+    # be at least the exact size of every shorter dense shape (lengths chosen around the grid's switch points)
+    lib = binding.load()
+    for base in ("llama8b_128k", "batch8_32k", "tiny_f32"):
+        w = wl.get(base)
+        cap = w.n_tokens
+        small = dataclasses.replace(w, n_tokens=max(200, w.n_init + w.n_local + 8), topk=8)
+        bound = lib.pqc_workspace_bytes(C.byref(binding.make_config(small, capacity=cap)))
+        assert bound > 0
+        lengths = sorted({cap, cap - 1, cap // 2, cap // 2 + 1, cap // 3, 4097, 4096, 2049, 1025, 513, 512, 511, 200} |
+                         {int(x) for x in np.random.default_rng(5).integers(200, cap, 60)})
+        for n in (x for x in lengths if x <= cap):
+            for k in (0, (n - w.n_init - w.n_local) // 10, n - w.n_init - w.n_local):
+                dense = dataclasses.replace(w, n_tokens=n, topk=k)
+                need = lib.pqc_workspace_bytes(C.byref(binding.make_config(dense)))
+                assert 0 < need <= bound, (base, n, k, need, bound)
+                # the same length inside the capacity is planned the same way
+                need_cap = lib.pqc_workspace_bytes(C.byref(binding.make_config(dense, capacity=cap)))
+                assert need_cap == (need if n == cap else bound)
+
+
+def test_set_length_checks():
+    lib = binding.load()
+    w = wl.get("llama8b_32k")
+    cap = 40000
+    cfg = binding.make_config(w, capacity=cap)
+    need = lib.pqc_workspace_bytes(C.byref(cfg))
+    h = C.c_void_p()
+    assert lib.pqc_create(C.byref(h), C.byref(cfg), C.c_void_p(4096), need) == 0
+    assert lib.pqc_set_length(None, 1000, 10) == -1
+    assert lib.pqc_set_length(h, cap, 4000) == 0
+    assert lib.pqc_set_length(h, cap + 1, 4000) == -1          # beyond the capacity
+    assert lib.pqc_set_length(h, 1000, 1000) == -1             # I + K + L > N
+    assert lib.pqc_set_length(h, 68, 0) == 0                   # windows only
+    assert lib.pqc_set_length(h, 0, 0) == -1
+    lib.pqc_destroy(h)
+    # a workspace sized for the short dense shape cannot take a longer one
+    short = dataclasses.replace(w, n_tokens=2000, topk=100)
+    cfg2 = binding.make_config(short, capacity=cap)
+    exact = lib.pqc_workspace_bytes(C.byref(binding.make_config(short)))
+    assert lib.pqc_create(C.byref(h), C.byref(cfg2), C.c_void_p(4096), exact) == 0
+    assert lib.pqc_set_length(h, cap, 4000) == -3
+    assert lib.pqc_set_length(h, 1900, 100) == 0
+    lib.pqc_destroy(h)
+    # capacity below the length, or negative
+    assert lib.pqc_workspace_bytes(C.byref(binding.make_config(w, capacity=w.n_tokens - 1))) == 0
+    assert lib.pqc_workspace_bytes(C.byref(binding.make_config(w, capacity=-5))) == 0
 
 
 def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
