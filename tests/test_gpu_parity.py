@@ -150,6 +150,9 @@ def _small(**kw):
     dict(pq_m=1, pq_centroids=8, topk=700),
     dict(dtype="f32", pq_m=1, pq_centroids=32, topk=500, n_q_heads=2, n_kv_heads=2),
     dict(dtype="f32", pq_m=1, pq_centroids=4, topk=900, n_q_heads=2, n_kv_heads=1),
+    # many units: more than the 256 compute units, a multiple of 8 and not (the last ones are not interleaved over the XCDs)
+    dict(batch=40, n_q_heads=16, n_kv_heads=8, n_tokens=600, topk=60),
+    dict(batch=37, n_q_heads=6, n_kv_heads=3, n_tokens=777, topk=99, pq_m=4),
     # more select workgroups per unit than the finalize kernel has threads
     dict(n_tokens=140001, topk=9000, n_q_heads=2, n_kv_heads=1, pq_centroids=64),
 ], ids=lambda kw: ",".join(f"{k}={v}" for k, v in kw.items()))
