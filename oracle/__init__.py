@@ -180,3 +180,62 @@ def block_topk(counts: np.ndarray, k_cache: int) -> np.ndarray:
     out = np.empty((B, Hkv, k_cache), np.int32)
     _chk(lib().pqo_block_topk(_p(counts), B, Hkv, C.c_int64(nb), C.c_int64(k_cache), _p(out)), "block_topk")
     return out
+
+
+def block_cache_update(slot_block: np.ndarray, slot_stamp: np.ndarray, slot_uses: np.ndarray, counts: np.ndarray,
+                       blocks: np.ndarray, step: int, policy: str):
+    """One refresh of the block-level cache of Section 3.4, for every unit, written out sequentially.
+
+    State per unit: n_slots slots, each empty (block -1) or holding a block with the step of its last use
+    (`stamp`) and the number of steps in which it was requested (`uses`).  `counts` [B,Hkv,nb] are this
+    step's retrieved tokens per block, `blocks` [B,Hkv,k_cache] the blocks the step requests (the k_cache
+    blocks holding the most retrieved tokens), in the order they are to be served.
+
+    The retrieved tokens are first looked up in the cache as it stands: hit_tokens = retrieved tokens that
+    lie in resident blocks, hit_blocks = requested blocks that are resident.  Then the cache is refreshed:
+    a requested resident block is marked used (stamp = step, uses + 1); a requested absent block takes the
+    lowest-numbered empty slot, or else replaces the victim of the policy among the slots not requested in
+    this step -- "lru": the oldest stamp, "lfu": the fewest uses, then the oldest stamp; remaining ties go
+    to the lowest slot -- and starts with stamp = step, uses = 1; when every slot holds a block requested
+    in this step the remaining requests are dropped.
+
+    Returns (slot_block, slot_stamp, slot_uses, stats [B,Hkv,4] = hit_tokens, hit_blocks, inserted, evicted).
+    """
+    assert policy in ("lru", "lfu")
+    sb, ss, su = (np.array(a, dtype=np.int32, copy=True) for a in (slot_block, slot_stamp, slot_uses))
+    B, Hkv, n_slots = sb.shape
+    stats = np.zeros((B, Hkv, 4), np.int32)
+    for b in range(B):
+        for g in range(Hkv):
+            blk, stamp, uses = sb[b, g], ss[b, g], su[b, g]
+            resident = {int(x): s for s, x in enumerate(blk) if x >= 0}
+            stats[b, g, 0] = sum(int(counts[b, g, x]) for x in resident)
+            stats[b, g, 1] = sum(1 for x in blocks[b, g] if int(x) in resident)
+            requested_slots = set()
+            for x in (int(v) for v in blocks[b, g]):
+                if x in resident:
+                    s = resident[x]
+                    stamp[s] = step
+                    uses[s] += 1
+                    requested_slots.add(s)
+            for x in (int(v) for v in blocks[b, g]):
+                if x in resident:
+                    continue
+                empty = [s for s in range(n_slots) if blk[s] < 0]
+                if empty:
+                    s = empty[0]
+                else:
+                    free = [s for s in range(n_slots) if s not in requested_slots]
+                    if not free:
+                        break
+                    if policy == "lru":
+                        s = min(free, key=lambda t: (int(stamp[t]), t))
+                    else:
+                        s = min(free, key=lambda t: (int(uses[t]), int(stamp[t]), t))
+                    del resident[int(blk[s])]
+                    stats[b, g, 3] += 1
+                blk[s], stamp[s], uses[s] = x, step, 1
+                resident[x] = s
+                requested_slots.add(s)
+                stats[b, g, 2] += 1
+    return sb, ss, su, stats

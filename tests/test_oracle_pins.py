@@ -394,3 +394,95 @@ def test_block_counts_against_bincount():
         for g in range(3):
             np.testing.assert_array_equal(got[b, g], np.bincount(idx[b, g] // 128, minlength=40))
     assert got.sum() == idx.size
+
+
+# ------------------------------------------------------------------ block cache (Section 3.4)
+def _cache_state(n_slots, B=1, Hkv=1):
+    return (np.full((B, Hkv, n_slots), -1, np.int32), np.zeros((B, Hkv, n_slots), np.int32), np.zeros((B, Hkv, n_slots), np.int32))
+
+
+def test_block_cache_hand_example():
+    # three slots, six blocks holding 5,0,3,2,1,0 retrieved tokens, LRU; worked by hand:
+    #  step 1 requests 0,2: both absent, two empty slots filled           -> [0,2,-]  no hits
+    #  step 2 requests 2,3: 2 is resident (hit), 3 takes the empty slot   -> [0,2,3]  tokens in {0,2} = 8
+    #  step 3 requests 4,5: victims are 0 (oldest), then 2 (tie with 3 at step 2: lower slot) -> [4,5,3], tokens in {0,2,3} = 10
+    #  step 4 requests 0,1: victims 3 (oldest), then 4 (tie with 5: lower slot; slot 2 was just filled) -> [1,5,0], tokens in {4,5,3} = 3
+    counts = np.array([[[5, 0, 3, 2, 1, 0]]], np.int32)
+    st = _cache_state(3)
+    want = [([0, 2, -1], [0, 0, 2, 0]), ([0, 2, 3], [8, 1, 1, 0]), ([4, 5, 3], [10, 0, 2, 2]), ([1, 5, 0], [3, 0, 2, 2])]
+    for step, (req, (blocks, stats)) in enumerate(zip([[0, 2], [2, 3], [4, 5], [0, 1]], want), 1):
+        *st, got = oracle.block_cache_update(*st, counts, np.array([[req]], np.int32), step, "lru")
+        assert st[0][0, 0].tolist() == blocks and got[0, 0].tolist() == stats, step
+    # the same requests under LFU: at step 3 block 2 has two uses, so 0 and then 3 go -> [4,2,5]
+    st = _cache_state(3)
+    for step, req in enumerate([[0, 2], [2, 3], [4, 5]], 1):
+        *st, got = oracle.block_cache_update(*st, counts, np.array([[req]], np.int32), step, "lfu")
+    assert st[0][0, 0].tolist() == [4, 2, 5] and st[2][0, 0].tolist() == [1, 2, 1] and got[0, 0].tolist() == [10, 0, 2, 2]
+
+
+def test_block_cache_single_requests_are_the_textbook_policies():
+    # one request per step: LRU must behave like an ordered dictionary moved-to-end on use,
+    # LFU like "evict the smallest (uses, last use)"
+    from collections import OrderedDict
+    rng = np.random.default_rng(31)
+    nb, n_slots = 12, 4
+    reqs = rng.integers(0, nb, 300)
+    counts = np.ones((1, 1, nb), np.int32)
+    st = _cache_state(n_slots)
+    lru = OrderedDict()
+    for step, x in enumerate(reqs.tolist(), 1):
+        hit = x in lru
+        *st, got = oracle.block_cache_update(*st, counts, np.array([[[x]]], np.int32), step, "lru")
+        assert got[0, 0, 1] == int(hit)
+        if hit:
+            lru.move_to_end(x)
+        else:
+            if len(lru) == n_slots:
+                lru.popitem(last=False)
+            lru[x] = True
+        assert sorted(b for b in st[0][0, 0].tolist() if b >= 0) == sorted(lru)
+    st = _cache_state(n_slots)
+    lfu = {}  # block -> [uses, last use]
+    for step, x in enumerate(reqs.tolist(), 1):
+        *st, got = oracle.block_cache_update(*st, counts, np.array([[[x]]], np.int32), step, "lfu")
+        assert got[0, 0, 1] == int(x in lfu)
+        if x in lfu:
+            lfu[x] = [lfu[x][0] + 1, step]
+        else:
+            if len(lfu) == n_slots:
+                del lfu[min(lfu, key=lambda b: tuple(lfu[b]))]  # (uses, last use) is unique: one request per step
+            lfu[x] = [1, step]
+        assert sorted(b for b in st[0][0, 0].tolist() if b >= 0) == sorted(lfu)
+
+
+@pytest.mark.parametrize("policy", ["lru", "lfu"])
+@pytest.mark.parametrize("n_slots,k_cache", [(1, 1), (5, 3), (8, 8), (4, 9), (16, 0)])
+def test_block_cache_invariants(policy, n_slots, k_cache):
+    rng = np.random.default_rng(n_slots * 100 + k_cache)
+    B, Hkv, nb = 2, 2, 20
+    st = _cache_state(n_slots, B, Hkv)
+    for step in range(1, 40):
+        counts = rng.integers(0, 30, (B, Hkv, nb)).astype(np.int32)
+        blocks = np.stack([rng.permutation(nb)[:k_cache] for _ in range(B * Hkv)]).reshape(B, Hkv, k_cache).astype(np.int32)
+        before = [a.copy() for a in st]
+        *st, stats = oracle.block_cache_update(*st, counts, blocks, step, policy)
+        for b in range(B):
+            for g in range(Hkv):
+                old, new = before[0][b, g], st[0][b, g]
+                res_old, res_new = set(old[old >= 0].tolist()), new[new >= 0].tolist()
+                assert len(res_new) == len(set(res_new)) <= n_slots            # no block twice
+                req = blocks[b, g].tolist()
+                assert stats[b, g, 0] == sum(int(counts[b, g, x]) for x in res_old)
+                assert stats[b, g, 1] == len(res_old & set(req))
+                hits = [x for x in req if x in res_old]
+                misses = [x for x in req if x not in res_old]
+                assert set(hits) | set(misses[:n_slots - len(hits)]) <= set(res_new)   # served in request order until no slot is left
+                assert not set(misses[n_slots - len(hits):]) & set(res_new)
+                assert res_old & set(req) <= set(res_new)                       # a requested block is never the victim
+                assert stats[b, g, 2] == min(len(set(req) - res_old), n_slots - len(res_old & set(req)))
+                assert stats[b, g, 3] == stats[b, g, 2] - min(stats[b, g, 2], n_slots - len(res_old))
+                for s in range(n_slots):
+                    if new[s] in req:
+                        assert st[1][b, g, s] == step
+                    elif new[s] >= 0:
+                        assert new[s] == old[s] and st[1][b, g, s] == before[1][b, g, s] and st[2][b, g, s] == before[2][b, g, s]
