@@ -271,6 +271,35 @@ int pqc_pq_encode_token(const pqc_config* cfg, const void* key, const float* cen
 int pqc_block_stats(const pqc_config* cfg, const int32_t* idx, int64_t n_idx, int32_t block_tokens,
                     int32_t k_cache, int32_t* counts, int32_t* blocks, void* stream);
 
+/* Refresh of the block-level cache of Section 3.4: the retrieved tokens are looked up in the
+ * cache, then the cache is refreshed with the k_cache blocks that hold the most retrieved
+ * tokens, evicting by an LRU or an LFU policy.  The library keeps
+ * the bookkeeping only: which blocks are resident, when each was last used and how often; the
+ * K/V rows themselves already live in device memory here.  Per unit, the state is three
+ * caller-owned arrays of n_slots entries, 1 <= n_slots <= 1024, updated in place:
+ *   slot_block [B][Hkv][n_slots] int32  resident block, or -1 for an empty slot (initialise to -1)
+ *   slot_stamp [B][Hkv][n_slots] int32  `step` of the block's last use
+ *   slot_uses  [B][Hkv][n_slots] int32  steps in which the block was requested
+ * Inputs of one step (both as written by pqc_block_stats for the same cfg and block_tokens):
+ *   counts     [B][Hkv][nb]      int32  retrieved tokens per block
+ *   blocks     [B][Hkv][k_cache] int32  requested blocks, distinct, in [0, nb), served in this
+ *                                       order; 0 <= k_cache <= 1024 (NULL allowed when 0)
+ *   step       any int32 that grows from call to call
+ * First the look-up: stats[b][h] = { retrieved tokens lying in blocks that are resident before
+ * the refresh, requested blocks that are resident, blocks inserted, blocks evicted } (int32 x 4).
+ * Then the refresh: a requested resident block gets stamp = step and uses + 1; a requested
+ * absent block takes the lowest empty slot, else it replaces, among the slots holding no block
+ * requested in this step, the one used longest ago (PQC_CACHE_LRU) or the one with the fewest
+ * uses, the one used longest ago among those (PQC_CACHE_LFU), the lowest slot on remaining ties,
+ * and starts with stamp = step, uses = 1; requests left when no such slot remains are dropped.
+ * The paper names the two policies and leaves these details open.  Needs no context. */
+#define PQC_CACHE_LRU 0
+#define PQC_CACHE_LFU 1
+int pqc_block_cache_update(const pqc_config* cfg, int32_t block_tokens, int32_t n_slots, int32_t policy,
+                           int32_t step, const int32_t* counts, const int32_t* blocks, int32_t k_cache,
+                           int32_t* slot_block, int32_t* slot_stamp, int32_t* slot_uses, int32_t* stats,
+                           void* stream);
+
 #ifdef __cplusplus
 }
 #endif

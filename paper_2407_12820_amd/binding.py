@@ -86,6 +86,8 @@ def load() -> C.CDLL:
     lib.pqc_pair_counts.argtypes = [cp, vp, vp, vp]
     lib.pqc_pair_counts_add.restype = C.c_int
     lib.pqc_pair_counts_add.argtypes = [cp, vp, C.c_int32, vp, vp]
+    lib.pqc_block_cache_update.restype = C.c_int
+    lib.pqc_block_cache_update.argtypes = [cp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp, C.c_int32, vp, vp, vp, vp, vp]
     lib.pqc_block_stats.restype = C.c_int
     lib.pqc_block_stats.argtypes = [cp, vp, C.c_int64, C.c_int32, C.c_int32, vp, vp, vp]
     _lib = lib
@@ -382,3 +384,24 @@ def to_device(a, dtype: str, device="cuda:0") -> torch.Tensor:
     if a.dtype == np.uint16 and dtype == "bf16":
         return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
     return torch.from_numpy(a).to(device)
+
+
+def block_cache_update(w: Workload, block_tokens: int, policy: str, step: int, counts: torch.Tensor, blocks: torch.Tensor,
+                       slot_block: torch.Tensor, slot_stamp: torch.Tensor, slot_uses: torch.Tensor, stream=None) -> torch.Tensor:
+    """One look-up and refresh of the block cache state (updated in place) -> stats [B,Hkv,4] int32."""
+    lib = load()
+    cfg = make_config(w)
+    nb = (w.n_tokens + block_tokens - 1) // block_tokens
+    n_slots, k_cache = slot_block.shape[-1], blocks.shape[-1]
+    _need(counts, torch.int32, (w.batch, w.n_kv_heads, nb), "counts")
+    _need(blocks, torch.int32, (w.batch, w.n_kv_heads, k_cache), "blocks")
+    for t, name in ((slot_block, "slot_block"), (slot_stamp, "slot_stamp"), (slot_uses, "slot_uses")):
+        _need(t, torch.int32, (w.batch, w.n_kv_heads, n_slots), name)
+    stats = torch.empty((w.batch, w.n_kv_heads, 4), dtype=torch.int32, device=counts.device)
+    st = (stream if stream is not None else torch.cuda.current_stream(counts.device)).cuda_stream
+    rc = lib.pqc_block_cache_update(C.byref(cfg), block_tokens, n_slots, {"lru": 0, "lfu": 1}[policy], step, counts.data_ptr(),
+                                    blocks.data_ptr() if k_cache else None, k_cache, slot_block.data_ptr(),
+                                    slot_stamp.data_ptr(), slot_uses.data_ptr(), stats.data_ptr(), st)
+    if rc != 0:
+        raise PQCacheError(rc, "pqc_block_cache_update")
+    return stats

@@ -673,4 +673,20 @@ int pqc_block_stats(const pqc_config* cfg, const int32_t* idx, int64_t n_idx, in
   return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
 }
 
+int pqc_block_cache_update(const pqc_config* cfg, int32_t block_tokens, int32_t n_slots, int32_t policy, int32_t step,
+                           const int32_t* counts, const int32_t* blocks, int32_t k_cache, int32_t* slot_block,
+                           int32_t* slot_stamp, int32_t* slot_uses, int32_t* stats, void* stream) {
+  Plan p;
+  const int rc = make_plan(cfg, &p);
+  if (rc != PQC_OK) return rc;
+  if (!counts || !slot_block || !slot_stamp || !slot_uses || !stats || block_tokens < 1) return PQC_EINVAL;
+  if (n_slots < 1 || n_slots > kCacheSlots || k_cache < 0 || k_cache > kCacheSlots || (k_cache > 0 && !blocks)) return PQC_EINVAL;
+  if (policy != PQC_CACHE_LRU && policy != PQC_CACHE_LFU) return PQC_EINVAL;
+  const int nb = (p.s.N + block_tokens - 1) / block_tokens;
+  hipLaunchKernelGGL(block_cache_kernel, dim3((unsigned)(p.s.B * p.s.Hkv)), dim3(256), 0, static_cast<hipStream_t>(stream), nb,
+                     (int)n_slots, (int)k_cache, policy == PQC_CACHE_LFU ? 1 : 0, (int)step, counts, blocks, slot_block, slot_stamp,
+                     slot_uses, stats);
+  return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
+}
+
 }  // extern "C"

@@ -352,6 +352,121 @@ __global__ __launch_bounds__(1024) void block_stats_kernel(const int* __restrict
   }
 }
 
+// ------------------------------------------------------------ block cache refresh
+// Section 3.4: the block-level cache is looked up with this step's retrieved tokens, then refreshed
+// with the step's requested blocks under an LRU or LFU policy.  One workgroup per unit.  Sequentially,
+// each absent block would take the lowest empty slot or else the policy's victim among the slots not
+// requested in this step; since the order of those slots (empty ones by index, then by (uses,) last
+// use, slot) does not change while the step is served, the i-th absent block simply takes the slot of
+// rank i in that order, which is found by counting.
+constexpr int kCacheSlots = 1024;  // most slots, and most requested blocks, per unit
+__global__ __launch_bounds__(256) void block_cache_kernel(int nb, int n_slots, int k_cache, int lfu, int step,
+                                                          const int* __restrict__ counts, const int* __restrict__ blocks,
+                                                          int* __restrict__ slot_block, int* __restrict__ slot_stamp,
+                                                          int* __restrict__ slot_uses, int* __restrict__ stats) {
+  constexpr int NT = 256, NW = NT / 64;
+  __shared__ int blk[kCacheSlots], stamp[kCacheSlots], uses[kCacheSlots];
+  __shared__ int req[kCacheSlots], req_slot[kCacheSlots], miss_rank[kCacheSlots];
+  __shared__ int by_rank[kCacheSlots];                 // slot of rank r among the slots not requested in this step
+  __shared__ unsigned long long key[kCacheSlots];      // ordering key of a slot; ~0 = requested in this step
+  __shared__ int scan_sm[2 * NW + 1];
+  __shared__ int red[4];
+  const int u = blockIdx.x, tid = threadIdx.x;
+  int* sb = slot_block + (size_t)u * n_slots;
+  int* ss = slot_stamp + (size_t)u * n_slots;
+  int* su = slot_uses + (size_t)u * n_slots;
+  const int* cu = counts + (size_t)u * nb;
+  if (tid < 4) red[tid] = 0;
+  for (int s = tid; s < n_slots; s += NT) {
+    blk[s] = sb[s];
+    stamp[s] = ss[s];
+    uses[s] = su[s];
+  }
+  for (int i = tid; i < k_cache; i += NT) req[i] = blocks[(size_t)u * k_cache + i];
+  __syncthreads();
+  // look-up against the cache as it stands: retrieved tokens inside resident blocks
+  int ht = 0;
+  for (int s = tid; s < n_slots; s += NT)
+    if (blk[s] >= 0 && blk[s] < nb) ht += cu[blk[s]];
+  if (ht) atomicAdd(&red[0], ht);
+  // requested blocks that are resident: mark them used
+  int hb = 0;
+  for (int i = tid; i < k_cache; i += NT) {
+    int found = -1;
+    for (int s = 0; s < n_slots; ++s) found = blk[s] == req[i] ? s : found;
+    req_slot[i] = found;
+    hb += found >= 0;
+  }
+  if (hb) atomicAdd(&red[1], hb);
+  __syncthreads();
+  for (int s = tid; s < n_slots; s += NT) {
+    const unsigned long long st = (unsigned)stamp[s] ^ 0x80000000u;  // signed order as unsigned order
+    const unsigned long long k1 = lfu ? ((unsigned long long)(unsigned)uses[s] << 32) | st : st;
+    key[s] = blk[s] < 0 ? 0ull : (1ull << 63) | k1;
+  }
+  __syncthreads();
+  for (int i = tid; i < k_cache; i += NT) {
+    const int s = req_slot[i];
+    if (s >= 0) {
+      key[s] = ~0ull;
+      stamp[s] = step;
+      atomicAdd(&uses[s], 1);
+    }
+  }
+  __syncthreads();
+  // rank of every other slot in victim order
+  int n_free_local = 0;
+  for (int s = tid; s < n_slots; s += NT) {
+    const unsigned long long ks = key[s];
+    if (ks == ~0ull) continue;
+    int r = 0;
+    for (int t = 0; t < n_slots; ++t) {
+      const unsigned long long kt = key[t];
+      r += (kt != ~0ull) && (kt < ks || (kt == ks && t < s));
+    }
+    by_rank[r] = s;
+    ++n_free_local;
+  }
+  if (n_free_local) atomicAdd(&red[2], n_free_local);
+  // absent requests, numbered in request order
+  int carry = 0;
+  for (int i0 = 0; i0 < k_cache; i0 += NT) {
+    const int i = i0 + tid;
+    const int miss = i < k_cache && req_slot[i] < 0;
+    int total;
+    const int pos = block_exclusive_scan<NT>(miss, &total, scan_sm);
+    if (i < k_cache) miss_rank[i] = miss ? carry + pos : -1;
+    carry += total;
+  }
+  __syncthreads();
+  const int n_free = red[2], n_ins = min(carry, n_free);
+  int evicted = 0;
+  for (int i = tid; i < k_cache; i += NT) {
+    const int r = miss_rank[i];
+    if (r >= 0 && r < n_ins) {
+      const int s = by_rank[r];
+      evicted += blk[s] >= 0;
+      blk[s] = req[i];
+      stamp[s] = step;
+      uses[s] = 1;
+    }
+  }
+  if (evicted) atomicAdd(&red[3], evicted);
+  __syncthreads();
+  for (int s = tid; s < n_slots; s += NT) {
+    sb[s] = blk[s];
+    ss[s] = stamp[s];
+    su[s] = uses[s];
+  }
+  if (tid == 0) {
+    int* o = stats + (size_t)u * 4;
+    o[0] = red[0];
+    o[1] = red[1];
+    o[2] = n_ins;
+    o[3] = red[3];
+  }
+}
+
 // -------------------------------------------------------------- code-pair counts
 // M = 2: how many tokens of a unit carry each pair of codes (c0 + C*c1), over all N tokens.
 // A statistic of the codes alone; pqc_decode_indexed takes its threshold from it.

@@ -169,6 +169,24 @@ def test_set_length_checks():
     assert lib.pqc_workspace_bytes(C.byref(binding.make_config(w, capacity=-5))) == 0
 
 
+def test_block_cache_update_argument_checks():
+    lib = binding.load()
+    cfg = binding.make_config(wl.get("llama8b_32k"))
+    p = C.c_void_p(4096)
+    ok = dict(block_tokens=128, n_slots=32, policy=0, step=1, counts=p, blocks=p, k_cache=32, sb=p, ss=p, su=p, stats=p)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return lib.pqc_block_cache_update(C.byref(cfg), a["block_tokens"], a["n_slots"], a["policy"], a["step"], a["counts"],
+                                          a["blocks"], a["k_cache"], a["sb"], a["ss"], a["su"], a["stats"], None)
+
+    for bad in (dict(block_tokens=0), dict(n_slots=0), dict(n_slots=1025), dict(policy=2), dict(policy=-1), dict(k_cache=-1),
+                dict(k_cache=1025), dict(counts=None), dict(blocks=None), dict(sb=None), dict(ss=None), dict(su=None),
+                dict(stats=None)):
+        assert call(**bad) == -1, bad
+    assert lib.pqc_block_cache_update(None, 128, 32, 0, 1, p, p, 32, p, p, p, p, None) == -1
+
+
 def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
     # no CPU or PyTorch stand-in exists: a library that is not there (and is not the one the
     # package knows how to build) must raise

@@ -152,3 +152,38 @@ def test_block_stats_match_oracle(pqc, block, k_cache):
     np.testing.assert_array_equal(counts.cpu().numpy(), want_c)
     want_b = oracle.block_topk(want_c, k_cache)
     np.testing.assert_array_equal(np.sort(blocks.cpu().numpy(), -1), np.sort(want_b, -1))
+
+
+@pytest.mark.parametrize("policy", ["lru", "lfu"])
+@pytest.mark.parametrize("n_slots,k_cache,block", [(32, 32, 128), (1, 1, 128), (5, 3, 64), (4, 9, 256), (16, 0, 128),
+                                                   (1024, 200, 16), (100, 1024, 4)])
+def test_block_cache_refresh_matches_oracle(pqc, policy, n_slots, k_cache, block):
+    # Section 3.4 over a run of decode steps: look-up, then refresh with the fullest blocks; the state evolves
+    # on both sides from the same start and must stay identical
+    w = wl.Workload(name="cache", batch=2, n_q_heads=4, n_kv_heads=2, head_dim=128, n_tokens=8190, pq_m=2, pq_centroids=16,
+                    topk=800, n_init=4, n_local=64, dtype="bf16", kmeans_iters=1, recipe="plain")
+    nb = (w.n_tokens + block - 1) // block
+    k_cache = min(k_cache, nb)
+    rng = np.random.default_rng(n_slots * 7 + k_cache)
+    dev_state = [torch.full((2, 2, n_slots), -1, dtype=torch.int32, device=DEV)] + [
+        torch.zeros((2, 2, n_slots), dtype=torch.int32, device=DEV) for _ in range(2)]
+    host_state = [t.cpu().numpy() for t in dev_state]
+    hot = rng.choice(w.n_tokens, 600, replace=False)  # tokens that keep coming back, so that some blocks stay hot
+    for step in range(1, 13):
+        idx = np.stack([np.sort(np.concatenate([rng.choice(hot, 300, replace=False),
+                                                rng.choice(np.setdiff1d(np.arange(w.n_tokens), hot), w.n_selected - 300, replace=False)]))
+                        for _ in range(4)]).reshape(2, 2, -1).astype(np.int32)
+        counts, blocks = pqc.block_stats(w, torch.from_numpy(idx).to(DEV), block, k_cache)
+        stats = pqc.block_cache_update(w, block, policy, step, counts, blocks, *dev_state)
+        torch.cuda.synchronize()
+        # the oracle is fed its own counts and the request list in the order the library serves it
+        want_counts = oracle.block_counts(idx, w.n_tokens, block)
+        np.testing.assert_array_equal(counts.cpu().numpy(), want_counts)
+        req = blocks.cpu().numpy()
+        np.testing.assert_array_equal(np.sort(req, -1), np.sort(oracle.block_topk(want_counts, k_cache), -1))
+        *host_state, want_stats = oracle.block_cache_update(*host_state, want_counts, req, step, policy)
+        for got, want, name in zip(dev_state, host_state, ("block", "stamp", "uses")):
+            np.testing.assert_array_equal(got.cpu().numpy(), want, err_msg=f"step {step}: slot_{name}")
+        np.testing.assert_array_equal(stats.cpu().numpy(), want_stats, err_msg=f"step {step}: stats")
+    if k_cache and n_slots >= 4:
+        assert want_stats[..., 0].min() > 0  # the hot tokens do get hits
