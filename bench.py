@@ -35,6 +35,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-indexed", action="store_true", help="skip the pqc_decode_indexed measurement")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP graph replay measurement")
+    ap.add_argument("--no-append", action="store_true", help="skip the encode-token + decode measurement")
     ap.add_argument("--no-copy-ceiling", action="store_true", help="skip the device-to-device copy measurement")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--also", default="llama70b_128k", help="second workload reported alongside (step time only); '' to skip")
@@ -204,6 +205,46 @@ def main() -> int:
                                   "us_per_layer": round(g0.elapsed_time(g1) / (reps * len(sets)) * 1e3, 3),
                                   "host_issue_ms_per_layer": round(issue_g / (reps * len(sets)), 6)}
         del graph
+
+    # the step as it runs inside a decode loop (Algorithm 2): the code of one more token per head is written
+    # (pqc_pq_encode_token; here a token that already has that code, so the inputs stay as they are), then the step
+    if not args.no_append:
+        pos = w.n_tokens - w.n_local - 1
+        cfg = binding.make_config(w)
+        lib = binding.load()
+        import ctypes as C
+        keys1 = [st[3][:, :, pos].contiguous() for st in sets]
+        for i in range(args.warmup):
+            lib.pqc_pq_encode_token(C.byref(cfg), keys1[i % len(sets)].data_ptr(), margs[i % len(sets)][1], margs[i % len(sets)][2],
+                                    pos, stream_handle)
+            step(i)
+        torch.cuda.synchronize()
+        ev0.record()
+        for i in range(args.steps):
+            a = margs[i % len(sets)]
+            rc = lib.pqc_pq_encode_token(C.byref(cfg), keys1[i % len(sets)].data_ptr(), a[1], a[2], pos, stream_handle)
+            step(i)
+        ev1.record()
+        torch.cuda.synchronize()
+        assert rc == 0
+        us_sep = ev0.elapsed_time(ev1) / args.steps * 1e3
+        # the same through pqc_decode_append, which writes the code from inside the step's own launches;
+        # the position must be one whose code the step ignores: the last token of the local window
+        last = w.n_tokens - 1
+        keys2 = [st[3][:, :, last].contiguous() for st in sets]
+        for i in range(args.warmup + args.steps):
+            if i == args.warmup:
+                torch.cuda.synchronize()
+                ev0.record()
+            a = margs[i % len(sets)]
+            rc = lib.pqc_decode_append(ctx.handle, a[0], a[1], a[2], a[3], a[4], keys2[i % len(sets)].data_ptr(), last, a[5], a[6],
+                                       stream_handle)
+        ev1.record()
+        torch.cuda.synchronize()
+        assert rc == 0
+        result["decode_loop_step"] = {"us_per_layer": round(ev0.elapsed_time(ev1) / args.steps * 1e3, 3),
+                                      "calls": "pqc_decode_append (the appended token's code written inside the step)",
+                                      "separate_calls_us_per_layer": round(us_sep, 3)}
 
     # a plain device-to-device copy (reads and writes 1 GiB each way), as the ceiling a streaming kernel reaches here
     if not args.no_copy_ceiling:

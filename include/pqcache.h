@@ -155,6 +155,20 @@ int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_
                const void* k_cache, const void* v_cache, int32_t* out_idx, float* out_attn,
                void* stream);
 
+/* pqc_decode for a cache that has just received a token: besides the step, the code of that
+ * token is written (Algorithm 2: the PQ search of a step and the code of the token that joins
+ * the compressed part; Section 3.1: nearest centroid of each partition), inside the same three
+ * launches -- nothing in the step reads it, so it costs no launch of its own.
+ *   new_key   [B][Hkv][D]  kv_dtype   key of the token (e.g. its row of k_cache, copied)
+ *   position  where its code goes: codes[b][h][position][0..M-1] (same result as
+ *             pqc_pq_encode_token).  Must be a position whose code this call ignores: inside the
+ *             initial or the local window, or at or beyond n_tokens (below the capacity);
+ *             PQC_EINVAL otherwise.
+ * Everything else as pqc_decode; `codes` is read and, at that one position, written. */
+int pqc_decode_append(pqc_ctx* ctx, const void* q, const float* centroids, uint8_t* codes,
+                      const void* k_cache, const void* v_cache, const void* new_key, int32_t position,
+                      int32_t* out_idx, float* out_attn, void* stream);
+
 /* The same step for PQ structures with two partitions of at most 64 centroids, where a
  * token's score takes one of C*C values (one per pair of codes): the threshold of the
  * top-k selection (Section 3.1 steps 4-5) then follows from the look-up table and from how

@@ -62,6 +62,8 @@ def load() -> C.CDLL:
     lib.pqc_last_hip_error.argtypes = [vp]
     lib.pqc_decode.restype = C.c_int
     lib.pqc_decode.argtypes = [vp] * 9
+    lib.pqc_decode_append.restype = C.c_int
+    lib.pqc_decode_append.argtypes = [vp] * 7 + [C.c_int32] + [vp] * 3
     lib.pqc_decode_phase.restype = C.c_int
     lib.pqc_decode_phase.argtypes = [vp, C.c_int] + [vp] * 8
     lib.pqc_lut.restype = C.c_int
@@ -193,6 +195,23 @@ class PQCache:
                                  self._ptr(out_idx, torch.int32, sh["idx"]), self._ptr(out_attn, torch.float32, sh["out"]),
                                  self._stream(stream))
         self._check(rc, "pqc_decode")
+        return out_idx, out_attn
+
+    def decode_append(self, q, centroids, codes, k_cache, v_cache, new_key, position: int, out_idx=None, out_attn=None,
+                      stream=None):
+        """pqc_decode plus the code of the token at `position` (its key: new_key [B,Hkv,D]), in the same launches."""
+        sh = self.shapes
+        if out_idx is None or out_attn is None:
+            out_idx, out_attn = self.empty_outputs()
+        w = self.w
+        rc = self.lib.pqc_decode_append(self.handle, self._ptr(q, self.kv_torch, sh["q"]),
+                                        self._ptr(centroids, torch.float32, sh["centroids"]),
+                                        self._ptr(codes, torch.uint8, sh["codes"]),
+                                        self._ptr(k_cache, self.kv_torch, sh["kv"]), self._ptr(v_cache, self.kv_torch, sh["kv"]),
+                                        self._ptr(new_key, self.kv_torch, (w.batch, w.n_kv_heads, w.head_dim)), position,
+                                        self._ptr(out_idx, torch.int32, sh["idx"]), self._ptr(out_attn, torch.float32, sh["out"]),
+                                        self._stream(stream))
+        self._check(rc, "pqc_decode_append")
         return out_idx, out_attn
 
     def marshal_decode_args(self, q, centroids, codes, k_cache, v_cache, out_idx, out_attn):

@@ -150,6 +150,7 @@ struct pqc_ctx {
   pqc_config cfg;
   Plan plan;
   Workspace ws;
+  AppendArgs append;       // set for the duration of a pqc_decode_append call
   char* workspace;         // the caller's device memory
   size_t workspace_bytes;
   bool hist_clean;  // the histogram is known to be all zero
@@ -197,8 +198,8 @@ void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uin
     hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC, units), dim3(256),
                        s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));
   if (phases & 4u)
-    hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st,
-                       s, ctx->ws, qt, kt, vt, out_idx, out_attn);
+    hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs + (ctx->append.key ? 1 : 0), units), dim3(256),
+                       (4 * s.nblkC + 2) * sizeof(int), st, s, ctx->ws, qt, kt, vt, out_idx, out_attn, ctx->append);
 }
 
 template <typename T, int G>
@@ -236,7 +237,7 @@ void launch_indexed_tg(pqc_ctx* ctx, const void* q, const float* cent, const uin
                      s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes), cent,
                      pair_counts);
   hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st,
-                     s, ctx->ws, qt, kt, vt, out_idx, out_attn);
+                     s, ctx->ws, qt, kt, vt, out_idx, out_attn, AppendArgs{nullptr, nullptr, nullptr, 0});
 }
 
 template <typename T>
@@ -359,6 +360,7 @@ int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t wor
   bind_workspace(ctx);
   ctx->hist_clean = false;
   ctx->last_hip = 0;
+  ctx->append = AppendArgs{nullptr, nullptr, nullptr, 0};
   *out = ctx;
   return PQC_OK;
 }
@@ -410,6 +412,19 @@ static int decode_impl(pqc_ctx* ctx, const void* q, const float* centroids, cons
 int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes, const void* k_cache,
                const void* v_cache, int32_t* out_idx, float* out_attn, void* stream) {
   return decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 7u);
+}
+
+int pqc_decode_append(pqc_ctx* ctx, const void* q, const float* centroids, uint8_t* codes, const void* k_cache,
+                      const void* v_cache, const void* new_key, int32_t position, int32_t* out_idx, float* out_attn,
+                      void* stream) {
+  if (!ctx || !new_key || !aligned16(new_key)) return PQC_EINVAL;
+  const Shape& s = ctx->plan.s;
+  // only a position whose code this call does not read: inside a window, or beyond the tokens in use
+  if (position < 0 || position >= s.cap || (position >= s.I && position < s.N - s.L)) return PQC_EINVAL;
+  ctx->append = AppendArgs{new_key, centroids, codes, (int)position};
+  const int rc = decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 7u);
+  ctx->append = AppendArgs{nullptr, nullptr, nullptr, 0};
+  return rc;
 }
 
 int pqc_decode_indexed(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes,
@@ -509,7 +524,7 @@ int pqc_topk(pqc_ctx* ctx, const float* scores, int32_t* out_idx, void* stream) 
   hipLaunchKernelGGL((select_kernel<float, 1, ScoreChunks, false>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(unsigned short), st,
                      s, ctx->ws, nof, nof, nof, static_cast<const void*>(scores));
   hipLaunchKernelGGL((finalize_kernel<float, 1, false>), dim3(1 + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
-                     ctx->ws, nof, nof, nof, out_idx, static_cast<float*>(nullptr));
+                     ctx->ws, nof, nof, nof, out_idx, static_cast<float*>(nullptr), AppendArgs{nullptr, nullptr, nullptr, 0});
   rc = check_launch(ctx);
   if (rc == PQC_OK) {
     ctx->hist_clean = true;
@@ -653,10 +668,13 @@ int pqc_pq_encode_token(const pqc_config* cfg, const void* key, const float* cen
   if (!aligned16(key) || !aligned16(centroids) || !aligned16(codes)) return PQC_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const BuildShape& s = bp.s;
+  const dim3 grid((unsigned)(s.units * s.M));
   if (cfg->kv_dtype == PQC_F32)
-    launch_assign<float>(s, static_cast<const float*>(key), (int64_t)kD, 1, position, centroids, codes, st);
+    hipLaunchKernelGGL(pq_encode_kernel<float>, grid, dim3(256), 0, st, s, static_cast<const float*>(key), (int)position, centroids,
+                       codes);
   else
-    launch_assign<bf16_t>(s, static_cast<const bf16_t*>(key), (int64_t)kD, 1, position, centroids, codes, st);
+    hipLaunchKernelGGL(pq_encode_kernel<bf16_t>, grid, dim3(256), 0, st, s, static_cast<const bf16_t*>(key), (int)position,
+                       centroids, codes);
   return hipGetLastError() == hipSuccess ? PQC_OK : PQC_EHIP;
 }
 

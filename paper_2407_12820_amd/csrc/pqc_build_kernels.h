@@ -77,6 +77,37 @@ __global__ __launch_bounds__(256) void pq_assign_kernel(BuildShape s, const T* _
   if (live) codes[((size_t)u * s.cap + code_pos0 + t) * s.M + j] = (uint8_t)arg;
 }
 
+// One token per unit (the code of an appended token): one thread per centroid, the same distance chain
+// as pq_assign_kernel, the smallest (distance, centroid) pair through a 64-bit LDS minimum.
+template <typename T>
+__global__ __launch_bounds__(256) void pq_encode_kernel(BuildShape s, const T* __restrict__ key /* [units][kD] */, int position,
+                                                        const float* __restrict__ cent, uint8_t* __restrict__ codes) {
+  __shared__ float x[kD];
+  __shared__ unsigned long long best;
+  const int uj = blockIdx.x, u = uj / s.M, j = uj % s.M, c = threadIdx.x;
+  if (c < s.Dm) x[c] = load_as_float<T>(key, (size_t)u * kD + j * s.Dm + c);
+  if (c == 0) best = ~0ull;
+  __syncthreads();
+  if (c < s.C) {
+    const float* cr = cent + ((size_t)uj * s.C + c) * s.Dm;
+    float d2 = 0.0f;
+    for (int e = 0; e < s.Dm; e += 4) {  // Dm is a multiple of 4
+      const float4 cv = *reinterpret_cast<const float4*>(cr + e);
+      float df = x[e] - cv.x;
+      d2 = fmaf(df, df, d2);
+      df = x[e + 1] - cv.y;
+      d2 = fmaf(df, df, d2);
+      df = x[e + 2] - cv.z;
+      d2 = fmaf(df, df, d2);
+      df = x[e + 3] - cv.w;
+      d2 = fmaf(df, df, d2);
+    }
+    atomicMin(&best, ((unsigned long long)__float_as_uint(d2) << 32) | (unsigned)c);  // d2 >= 0: its bits order like its value
+  }
+  __syncthreads();
+  if (c == 0) codes[((size_t)u * s.cap + position) * s.M + j] = (uint8_t)(best & 0xffu);
+}
+
 // The same assignment on the matrix cores, for bf16 keys and sub-vectors of 32, 64 or 128
 // dimensions: this step is a dense contraction (tokens x dimensions by dimensions x
 // centroids).  The nearest centroid minimises |c|^2 - 2 x.c.  Keys are bf16 already; an fp32

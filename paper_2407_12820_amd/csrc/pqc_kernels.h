@@ -653,12 +653,54 @@ constexpr int kIdxLists = 4;                   // staged index lists a wave copi
 constexpr int kCopyWgs = 4;                    // copy workgroups per unit
 constexpr int kRankChunk = 64;                 // admitted rows summed per pass through LDS
 
+// The code of one appended token per unit (Section 3.1: nearest centroid of each partition): nothing in the
+// step depends on it, so one more workgroup per unit of the finalize kernel computes it beside the others.
+struct AppendArgs {
+  const void* key;    // [units][kD] in the cache's element type, or null: nothing to append
+  const float* cent;  // [units][M][C][Dm]
+  uint8_t* codes;     // the code tensor; written at `position` of every unit
+  int position;
+};
+
 template <typename T, int G, bool ATTN>
 __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, const T* __restrict__ q,
                                                        const T* __restrict__ kc, const T* __restrict__ vc,
-                                                       int* __restrict__ out_idx, float* __restrict__ out_attn) {
+                                                       int* __restrict__ out_idx, float* __restrict__ out_attn, AppendArgs ap) {
   constexpr int NT = 256, NW = 4;
   constexpr int heads = ATTN ? G : 1;
+  if (blockIdx.x == heads + kCopyWgs) {
+    // -------------------------------------------------------------- append workgroup
+    // one thread per centroid, the distance chain of pq_assign_kernel, the smallest (distance, centroid) pair
+    // of each partition through a 64-bit LDS minimum
+    __shared__ float ax[kD];
+    __shared__ unsigned long long abest[8];
+    const int u = blockIdx.y, c = threadIdx.x;
+    if (c < kD) ax[c] = load_as_float<T>(static_cast<const T*>(ap.key), (size_t)u * kD + c);
+    if (c < 8) abest[c] = ~0ull;
+    __syncthreads();
+    if (c < s.C) {
+      for (int j = 0; j < s.M; ++j) {
+        const float* cr = ap.cent + (((size_t)u * s.M + j) * s.C + c) * s.Dm;
+        const float* xj = ax + j * s.Dm;
+        float d2 = 0.0f;
+        for (int e = 0; e < s.Dm; e += 4) {  // Dm is a multiple of 4
+          const float4 cv = *reinterpret_cast<const float4*>(cr + e);
+          float df = xj[e] - cv.x;
+          d2 = fmaf(df, df, d2);
+          df = xj[e + 1] - cv.y;
+          d2 = fmaf(df, df, d2);
+          df = xj[e + 2] - cv.z;
+          d2 = fmaf(df, df, d2);
+          df = xj[e + 3] - cv.w;
+          d2 = fmaf(df, df, d2);
+        }
+        atomicMin(&abest[j], ((unsigned long long)__float_as_uint(d2) << 32) | (unsigned)c);  // d2 >= 0: bits order like values
+      }
+    }
+    __syncthreads();
+    if (c < s.M) ap.codes[((size_t)u * s.cap + ap.position) * s.M + c] = (uint8_t)(abest[c] & 0xffu);
+    return;
+  }
   constexpr int SP = ATTN ? (sizeof(T) == 2 ? 8 : 4) : 1;  // passes of 16 record V rows requested up front
   extern __shared__ int dyn[];  // pre_sel[nblkC+1], pre_cand[nblkC+1], pm[nblkC], pl[nblkC]
   __shared__ int scan_sm[2 * NW + 1];
@@ -713,7 +755,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
   if (blockIdx.x >= heads) {
     // ---------------------------------------------------------------- copy workgroup
     // one wave per list, coalesced; the local window moves behind the admitted candidates
-    const int cw = blockIdx.x - heads, ncw = gridDim.x - heads;
+    const int cw = blockIdx.x - heads, ncw = kCopyWgs;
     const int2 cnt0 = cnt[min(tid, s.nblkC - 1)];
     int ix[kIdxLists][4];  // first 256 entries of this wave's first kIdxLists lists
 #pragma unroll

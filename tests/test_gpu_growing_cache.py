@@ -117,8 +117,10 @@ def test_pq_build_inside_larger_buffers(pqc):
     np.testing.assert_array_equal(codes_a[:, :, :w.n_tokens].cpu().numpy(), codes.cpu().numpy())
 
 
-@pytest.mark.parametrize("kw", [dict(), dict(pq_m=4, pq_centroids=64, batch=2, n_q_heads=8, n_kv_heads=1)])
-def test_decode_loop_with_a_growing_cache(pqc, kw):
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+@pytest.mark.parametrize("kw", [dict(), dict(pq_m=4, pq_centroids=64, batch=2, n_q_heads=8, n_kv_heads=1),
+                                dict(pq_m=8, pq_centroids=200, dtype="f32", n_q_heads=2, n_kv_heads=2)])
+def test_decode_loop_with_a_growing_cache(pqc, kw, fused):
     # 20 decode steps: append the token's K/V, give it its code, count its code pair, lengthen the context,
     # decode (both entry points where the second applies), each step against the oracle on the dense prefix
     steps, n0, cap = 20, 1990, 2016
@@ -146,20 +148,27 @@ def test_decode_loop_with_a_growing_cache(pqc, kw):
         k_dev[:, :, n] = k_all[:, :, n]
         v_dev[:, :, n] = v_all[:, :, n]
         w_n = dataclasses.replace(w_cap, n_tokens=n, topk=n // 10)
-        pqc.pq_encode_token(w_n, k_dev[:, :, n].contiguous(), cent_dev, codes_dev, n, capacity=cap)
         want_code = oracle.nearest_codes(np.ascontiguousarray(d["k"][:, :, n]), w_cap.dtype, cent)
-        np.testing.assert_array_equal(codes_dev[:, :, n].cpu().numpy(), want_code, err_msg=f"step {step}: code of token {n}")
         codes_h[:, :, n] = want_code
+        new_key = k_dev[:, :, n].contiguous()
+        q = rng.standard_normal((w_cap.batch, w_cap.n_q_heads, 128)).astype(np.float32)
+        q = q if w_cap.dtype == "f32" else wl.f32_to_bf16_bits(q)
+        q_dev = pqc.to_device(q, w_cap.dtype, DEV)
+        if fused:
+            # the step and the new token's code in one call (the code lands in the local window, which the step ignores)
+            ctx.set_length(n + 1, (n + 1) // 10)
+            idx, out = ctx.decode_append(q_dev, cent_dev, codes_dev, k_dev, v_dev, new_key, n)
+        else:
+            pqc.pq_encode_token(w_n, new_key, cent_dev, codes_dev, n, capacity=cap)
+            ctx.set_length(n + 1, (n + 1) // 10)
+            idx, out = ctx.decode(q_dev, cent_dev, codes_dev, k_dev, v_dev)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(codes_dev[:, :, n].cpu().numpy(), want_code, err_msg=f"step {step}: code of token {n}")
         if indexed:
             pqc.pair_counts_add(w_n, codes_dev, n, counts, capacity=cap)
         n += 1
-        ctx.set_length(n, n // 10)
         w_n = ctx.w
         assert w_n.n_tokens == n and w_n.topk == n // 10
-        q = wl.f32_to_bf16_bits(rng.standard_normal((w_cap.batch, w_cap.n_q_heads, 128)).astype(np.float32))
-        q_dev = pqc.to_device(q, w_cap.dtype, DEV)
-        idx, out = ctx.decode(q_dev, cent_dev, codes_dev, k_dev, v_dev)
-        torch.cuda.synchronize()
         p = Problem(w_n, q, d["k"][:, :, :n], d["v"][:, :, :n], cent, codes_h[:, :, :n], units)
         _full_check(p, idx.cpu().numpy(), out.cpu().numpy())
         if indexed:
@@ -170,3 +179,25 @@ def test_decode_loop_with_a_growing_cache(pqc, kw):
     assert n == n0 + steps
     with pytest.raises(pqc.PQCacheError, match="PQC_EINVAL"):
         ctx.set_length(cap + 1, 10)
+
+
+def test_decode_append_rejects_a_position_the_step_reads(pqc):
+    w = _workload()
+    p = build_problem(w, seed=21)
+    dev = _upload_padded(pqc, p, 3008)
+    ctx = pqc.PQCache(w, DEV, capacity=3008)
+    key = dev["k"][:, :, 0].contiguous()
+    for bad in (-1, w.n_init, 1500, w.n_tokens - w.n_local - 1, 3008):
+        with pytest.raises(pqc.PQCacheError, match="PQC_EINVAL"):
+            ctx.decode_append(dev["q"], dev["centroids"], dev["codes"], dev["k"], dev["v"], key, bad)
+    for ok in (0, w.n_init - 1, w.n_tokens - w.n_local, w.n_tokens - 1, w.n_tokens, 3007):
+        before = dev["codes"].clone()
+        idx, out = ctx.decode_append(dev["q"], dev["centroids"], dev["codes"], dev["k"], dev["v"], key, ok)
+        torch.cuda.synchronize()
+        _full_check(p, idx.cpu().numpy(), out.cpu().numpy())
+        want = oracle.nearest_codes(np.ascontiguousarray(p.k[:, :, 0]), w.dtype, p.centroids)
+        np.testing.assert_array_equal(dev["codes"][:, :, ok].cpu().numpy(), want)
+        mask = torch.ones(3008, dtype=torch.bool, device=DEV)
+        mask[ok] = False
+        assert torch.equal(dev["codes"][:, :, mask], before[:, :, mask])
+        dev["codes"].copy_(before)
