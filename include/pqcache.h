@@ -184,6 +184,15 @@ int pqc_decode_indexed(pqc_ctx* ctx, const void* q, const float* centroids, cons
                        const uint32_t* pair_counts, const void* k_cache, const void* v_cache,
                        int32_t* out_idx, float* out_attn, void* stream);
 
+/* pqc_decode_indexed for a cache that has just received a token (as pqc_decode_append): on
+ * entry pair_counts holds the first N tokens except the one at `position`, whose code does not
+ * exist yet; the call writes that code and adds its pair to pair_counts, inside its own two
+ * launches.  `position` as for pqc_decode_append. */
+int pqc_decode_indexed_append(pqc_ctx* ctx, const void* q, const float* centroids, uint8_t* codes,
+                              uint32_t* pair_counts, const void* k_cache, const void* v_cache,
+                              const void* new_key, int32_t position, int32_t* out_idx, float* out_attn,
+                              void* stream);
+
 /* pair_counts of the first N tokens of a code tensor (fully overwritten), and the update for
  * the one code pair written at `position` (< capacity) of every unit: call it after
  * pqc_pq_encode_token for a position that was not counted before.  pqc_decode_indexed

@@ -64,6 +64,8 @@ def load() -> C.CDLL:
     lib.pqc_decode.argtypes = [vp] * 9
     lib.pqc_decode_append.restype = C.c_int
     lib.pqc_decode_append.argtypes = [vp] * 7 + [C.c_int32] + [vp] * 3
+    lib.pqc_decode_indexed_append.restype = C.c_int
+    lib.pqc_decode_indexed_append.argtypes = [vp] * 8 + [C.c_int32] + [vp] * 3
     lib.pqc_decode_phase.restype = C.c_int
     lib.pqc_decode_phase.argtypes = [vp, C.c_int] + [vp] * 8
     lib.pqc_lut.restype = C.c_int
@@ -212,6 +214,19 @@ class PQCache:
                                         self._ptr(out_idx, torch.int32, sh["idx"]), self._ptr(out_attn, torch.float32, sh["out"]),
                                         self._stream(stream))
         self._check(rc, "pqc_decode_append")
+        return out_idx, out_attn
+
+    def decode_indexed_append(self, q, centroids, codes, pair_counts, k_cache, v_cache, new_key, position: int, out_idx=None,
+                              out_attn=None, stream=None):
+        """pqc_decode_indexed plus the code (and the counted code pair) of the token at `position`."""
+        if out_idx is None or out_attn is None:
+            out_idx, out_attn = self.empty_outputs()
+        qp, cp, cdp, kp, vp_, oi, oa = self.marshal_decode_args(q, centroids, codes, k_cache, v_cache, out_idx, out_attn)
+        w = self.w
+        rc = self.lib.pqc_decode_indexed_append(self.handle, qp, cp, cdp, self._pair_ptr(pair_counts), kp, vp_,
+                                                self._ptr(new_key, self.kv_torch, (w.batch, w.n_kv_heads, w.head_dim)), position,
+                                                oi, oa, self._stream(stream))
+        self._check(rc, "pqc_decode_indexed_append")
         return out_idx, out_attn
 
     def marshal_decode_args(self, q, centroids, codes, k_cache, v_cache, out_idx, out_attn):

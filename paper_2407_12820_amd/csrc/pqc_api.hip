@@ -235,9 +235,9 @@ void launch_indexed_tg(pqc_ctx* ctx, const void* q, const float* cent, const uin
   const T* vt = static_cast<const T*>(v);
   hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<2>, true, true>), dim3(s.nblkC, units), dim3(256),
                      s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes), cent,
-                     pair_counts);
-  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st,
-                     s, ctx->ws, qt, kt, vt, out_idx, out_attn, AppendArgs{nullptr, nullptr, nullptr, 0});
+                     pair_counts, ctx->append.key ? ctx->append.position : -1);
+  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs + (ctx->append.key ? 1 : 0), units), dim3(256),
+                     (4 * s.nblkC + 2) * sizeof(int), st, s, ctx->ws, qt, kt, vt, out_idx, out_attn, ctx->append);
 }
 
 template <typename T>
@@ -360,7 +360,7 @@ int pqc_create(pqc_ctx** out, const pqc_config* cfg, void* workspace, size_t wor
   bind_workspace(ctx);
   ctx->hist_clean = false;
   ctx->last_hip = 0;
-  ctx->append = AppendArgs{nullptr, nullptr, nullptr, 0};
+  ctx->append = AppendArgs{nullptr, nullptr, nullptr, 0, nullptr};
   *out = ctx;
   return PQC_OK;
 }
@@ -421,15 +421,15 @@ int pqc_decode_append(pqc_ctx* ctx, const void* q, const float* centroids, uint8
   const Shape& s = ctx->plan.s;
   // only a position whose code this call does not read: inside a window, or beyond the tokens in use
   if (position < 0 || position >= s.cap || (position >= s.I && position < s.N - s.L)) return PQC_EINVAL;
-  ctx->append = AppendArgs{new_key, centroids, codes, (int)position};
+  ctx->append = AppendArgs{new_key, centroids, codes, (int)position, nullptr};
   const int rc = decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 7u);
-  ctx->append = AppendArgs{nullptr, nullptr, nullptr, 0};
+  ctx->append = AppendArgs{nullptr, nullptr, nullptr, 0, nullptr};
   return rc;
 }
 
-int pqc_decode_indexed(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes,
-                       const uint32_t* pair_counts, const void* k_cache, const void* v_cache, int32_t* out_idx,
-                       float* out_attn, void* stream) {
+static int indexed_impl(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes,
+                        const uint32_t* pair_counts, const void* k_cache, const void* v_cache, int32_t* out_idx,
+                        float* out_attn, void* stream) {
   if (!ctx || !q || !centroids || !codes || !pair_counts || !k_cache || !v_cache || !out_idx || !out_attn) return PQC_EINVAL;
   if (!aligned16(q) || !aligned16(centroids) || !aligned16(codes) || !aligned16(pair_counts) || !aligned16(k_cache) ||
       !aligned16(v_cache) || !aligned16(out_idx) || !aligned16(out_attn))
@@ -447,6 +447,24 @@ int pqc_decode_indexed(pqc_ctx* ctx, const void* q, const float* centroids, cons
   if (rc == PQC_OK) {
     ctx->hist_clean = true;
   }
+  return rc;
+}
+
+int pqc_decode_indexed(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes,
+                       const uint32_t* pair_counts, const void* k_cache, const void* v_cache, int32_t* out_idx,
+                       float* out_attn, void* stream) {
+  return indexed_impl(ctx, q, centroids, codes, pair_counts, k_cache, v_cache, out_idx, out_attn, stream);
+}
+
+int pqc_decode_indexed_append(pqc_ctx* ctx, const void* q, const float* centroids, uint8_t* codes, uint32_t* pair_counts,
+                              const void* k_cache, const void* v_cache, const void* new_key, int32_t position,
+                              int32_t* out_idx, float* out_attn, void* stream) {
+  if (!ctx || !new_key || !aligned16(new_key)) return PQC_EINVAL;
+  const Shape& s = ctx->plan.s;
+  if (position < 0 || position >= s.cap || (position >= s.I && position < s.N - s.L)) return PQC_EINVAL;
+  ctx->append = AppendArgs{new_key, centroids, codes, (int)position, pair_counts};
+  const int rc = indexed_impl(ctx, q, centroids, codes, pair_counts, k_cache, v_cache, out_idx, out_attn, stream);
+  ctx->append = AppendArgs{nullptr, nullptr, nullptr, 0, nullptr};
   return rc;
 }
 
@@ -524,7 +542,7 @@ int pqc_topk(pqc_ctx* ctx, const float* scores, int32_t* out_idx, void* stream) 
   hipLaunchKernelGGL((select_kernel<float, 1, ScoreChunks, false>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(unsigned short), st,
                      s, ctx->ws, nof, nof, nof, static_cast<const void*>(scores));
   hipLaunchKernelGGL((finalize_kernel<float, 1, false>), dim3(1 + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
-                     ctx->ws, nof, nof, nof, out_idx, static_cast<float*>(nullptr), AppendArgs{nullptr, nullptr, nullptr, 0});
+                     ctx->ws, nof, nof, nof, out_idx, static_cast<float*>(nullptr), AppendArgs{nullptr, nullptr, nullptr, 0, nullptr});
   rc = check_launch(ctx);
   if (rc == PQC_OK) {
     ctx->hist_clean = true;

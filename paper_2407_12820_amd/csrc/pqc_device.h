@@ -607,7 +607,8 @@ __device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T*
                                                         const float* __restrict__ cent /* [2][C][64] of the unit */,
                                                         const unsigned* __restrict__ pair_counts /* [C*C] of the unit */,
                                                         const uint8_t* __restrict__ codes_u /* [N][2] of the unit */,
-                                                        PairLds& L, int* scan_sm /* [2*(NT/64)+1] */, MarkFn mark) {
+                                                        PairLds& L, int* scan_sm /* [2*(NT/64)+1] */, MarkFn mark,
+                                                        int uncounted /* a window token the counts do not hold yet, or -1 */) {
   static_assert(NT == 256, "written for 256 threads");
   constexpr int Dm = kD / 2, PPT = kPairSlots / NT, BPT = kNB / NT;
   const int tid = threadIdx.x, C = s.C, np = C * C;
@@ -667,12 +668,10 @@ __device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T*
   }
   for (int wt = tid; wt < nwin; wt += NT) {
     unsigned short cw = wcode;
-    if (wt >= NT) {
-      const int t = wt < s.I ? wt : s.N - s.L + (wt - s.I);
-      cw = *reinterpret_cast<const unsigned short*>(codes_u + (size_t)t * 2);
-    }
+    const int t = wt < s.I ? wt : s.N - s.L + (wt - s.I);
+    if (wt >= NT) cw = *reinterpret_cast<const unsigned short*>(codes_u + (size_t)t * 2);
     const int pr = (cw & 0xff) + C * (cw >> 8);
-    if (pr < np) atomicSub(&L.cnt[pr], 1u);
+    if (pr < np && t != uncounted) atomicSub(&L.cnt[pr], 1u);
   }
   __syncthreads();
   mark(10);

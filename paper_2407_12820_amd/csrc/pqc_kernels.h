@@ -321,7 +321,8 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
                                                      const T* __restrict__ kc, const T* __restrict__ vc,
                                                      const void* __restrict__ src_ptr,
                                                      const float* __restrict__ cent = nullptr,
-                                                     const unsigned* __restrict__ pair_counts = nullptr) {
+                                                     const unsigned* __restrict__ pair_counts = nullptr,
+                                                     int uncounted = -1 /* PAIRS: a window token not in the counts yet */) {
   constexpr int NT = 256, NW = 4;
   constexpr bool kMfma = ATTN && sizeof(T) == 2;
   static_assert(!PAIRS || (SRC::kFromCodes && SRC::M == 2), "pair counts exist for two partitions only");
@@ -366,7 +367,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
     }
     pth = pair_threshold<T, NT>(s, q + ((size_t)b * s.Hq + (size_t)g * G) * kD, cent + (size_t)u * 2 * s.C * (kD / 2),
                                 pair_counts + (size_t)u * s.C * s.C, static_cast<const uint8_t*>(src_ptr) + (size_t)u * s.cap * 2,
-                                pl, scan_sm, [&](int slot) { PQC_MARK(ws, 1, slot); });  // syncs: qlds ready
+                                pl, scan_sm, [&](int slot) { PQC_MARK(ws, 1, slot); }, uncounted);  // syncs: qlds ready
   } else {
     ThresholdSearch<NT> ts;
     ts.load(ws.hist + (size_t)u * s.histCopies * kNB, s.histCopies);
@@ -660,6 +661,7 @@ struct AppendArgs {
   const float* cent;  // [units][M][C][Dm]
   uint8_t* codes;     // the code tensor; written at `position` of every unit
   int position;
+  unsigned* pair_counts;  // two partitions: [units][C*C] counts that gain the token's code pair, or null
 };
 
 template <typename T, int G, bool ATTN>
@@ -699,6 +701,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
     }
     __syncthreads();
     if (c < s.M) ap.codes[((size_t)u * s.cap + ap.position) * s.M + c] = (uint8_t)(abest[c] & 0xffu);
+    if (c == 0 && ap.pair_counts) ap.pair_counts[(size_t)u * s.C * s.C + (abest[0] & 0xffu) + s.C * (abest[1] & 0xffu)] += 1u;
     return;
   }
   constexpr int SP = ATTN ? (sizeof(T) == 2 ? 8 : 4) : 1;  // passes of 16 record V rows requested up front

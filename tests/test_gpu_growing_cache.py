@@ -164,7 +164,18 @@ def test_decode_loop_with_a_growing_cache(pqc, kw, fused):
             idx, out = ctx.decode(q_dev, cent_dev, codes_dev, k_dev, v_dev)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(codes_dev[:, :, n].cpu().numpy(), want_code, err_msg=f"step {step}: code of token {n}")
-        if indexed:
+        if indexed and fused:
+            # the same step through the indexed call, on copies that do not hold the new token yet
+            codes2, counts2 = codes_dev.clone(), counts.clone()
+            codes2[:, :, n] = 255
+            idx3, out3 = ctx.decode_indexed_append(q_dev, cent_dev, codes2, counts2, k_dev, v_dev, new_key, n)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(np.sort(idx3.cpu().numpy(), -1), np.sort(idx.cpu().numpy(), -1), err_msg=f"step {step}")
+            np.testing.assert_array_equal(out3.cpu().numpy().view(np.uint32), out.cpu().numpy().view(np.uint32))
+            assert torch.equal(codes2, codes_dev)
+            pqc.pair_counts_add(w_n, codes_dev, n, counts, capacity=cap)
+            assert torch.equal(counts2, counts)
+        elif indexed:
             pqc.pair_counts_add(w_n, codes_dev, n, counts, capacity=cap)
         n += 1
         w_n = ctx.w
