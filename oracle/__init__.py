@@ -20,7 +20,9 @@ _LIB = None
 def lib() -> C.CDLL:
     global _LIB
     if _LIB is None:
-        path = _build.LIB
+        # PQC_ORACLE_LIB: another build of pqc_oracle.c to load instead (the mutation tests plant mistakes
+        # in copies of the source and check that the pins notice)
+        path = os.environ.get("PQC_ORACLE_LIB") or _build.LIB
         if not os.path.exists(path):
             _build.build()
         _LIB = C.CDLL(path)

@@ -486,3 +486,22 @@ def test_block_cache_invariants(policy, n_slots, k_cache):
                         assert st[1][b, g, s] == step
                     elif new[s] >= 0:
                         assert new[s] == old[s] and st[1][b, g, s] == before[1][b, g, s] and st[2][b, g, s] == before[2][b, g, s]
+
+
+def test_equally_near_centroids_the_lowest_index_takes_the_token():
+    # Two identical centroids: every token is exactly as near to one as to the other.  Reading (the paper
+    # is silent): the lower index takes it; the other cluster stays empty and keeps its centroid.
+    rng = np.random.default_rng(41)
+    x = rng.standard_normal((60, 4)).astype(np.float32)
+    init = np.array([3, 3, 7], np.int32)
+    _, codes, _ = oracle.kmeans(x, 3, 0, init)       # the assignment to the starting centroids
+    assert 1 not in codes.tolist() and {0, 2} <= set(codes.tolist())
+    cent, _, _ = oracle.kmeans(x, 3, 1, init)        # one update: cluster 1 had no member
+    np.testing.assert_array_equal(cent[1], x[3])
+    assert not np.array_equal(cent[0], x[3])
+    # the same rule for the code of an appended token
+    c = np.zeros((1, 1, 2, 4, 4), np.float32)
+    c[0, 0, :, 1] = c[0, 0, :, 2] = 1.0          # centroids 1 and 2 of both partitions coincide
+    c[0, 0, :, 3] = -1.0
+    key = np.ones((1, 1, 8), np.float32)
+    assert oracle.nearest_codes(key, "f32", c)[0, 0].tolist() == [1, 1]
