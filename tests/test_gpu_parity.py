@@ -150,6 +150,11 @@ def _small(**kw):
     dict(pq_m=1, pq_centroids=8, topk=700),
     dict(dtype="f32", pq_m=1, pq_centroids=32, topk=500, n_q_heads=2, n_kv_heads=2),
     dict(dtype="f32", pq_m=1, pq_centroids=4, topk=900, n_q_heads=2, n_kv_heads=1),
+    # windows far larger than usual: most of the cache, all of it as the local window, all of it as the initial one
+    dict(n_tokens=5000, n_init=500, n_local=3000, topk=100),
+    dict(n_tokens=2500, n_init=0, n_local=2500, topk=0),
+    dict(n_tokens=2500, n_init=2500, n_local=0, topk=0),
+    dict(n_tokens=4100, n_init=1, n_local=2047, topk=2052),
     # many units: more than the 256 compute units, a multiple of 8 and not (the last ones are not interleaved over the XCDs)
     dict(batch=40, n_q_heads=16, n_kv_heads=8, n_tokens=600, topk=60),
     dict(batch=37, n_q_heads=6, n_kv_heads=3, n_tokens=777, topk=99, pq_m=4),
