@@ -105,9 +105,16 @@ def test_decode_matches_oracle_full_size(pqc, name):
     w = wl.get(name)
     print(f"[case] decode full size {w}", flush=True)
     p = build_problem(w, seed=0)
-    idx, out = run_decode(pqc, p)
+    dev, ctx = upload(pqc, p), pqc.PQCache(w, DEV)
+    idx, out = run_decode(pqc, p, ctx, dev)
     err = full_check(p, idx, out)
     print(f"[result] {name}: attention error {err:.3e}", flush=True)
+    # the code-pair path at the same size, in the launch shape the benchmark reports beside the general one
+    counts = pqc.pair_counts(w, dev["codes"])
+    idx2, out2 = ctx.decode_indexed(dev["q"], dev["centroids"], dev["codes"], counts, dev["k"], dev["v"])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(np.sort(idx2.cpu().numpy(), -1), np.sort(idx, -1))
+    assert attn_error(p, idx2.cpu().numpy(), out2.cpu().numpy()) <= ATTN_TOL[w.dtype]
 
 
 @pytest.mark.timeout(900)
