@@ -305,8 +305,9 @@ int pqc_block_stats(const pqc_config* cfg, const int32_t* idx, int64_t n_idx, in
  *   slot_uses  [B][Hkv][n_slots] int32  steps in which the block was requested
  * Inputs of one step (both as written by pqc_block_stats for the same cfg and block_tokens):
  *   counts     [B][Hkv][nb]      int32  retrieved tokens per block
- *   blocks     [B][Hkv][k_cache] int32  requested blocks, distinct, in [0, nb), served in this
- *                                       order; 0 <= k_cache <= 1024 (NULL allowed when 0)
+ *   blocks     [B][Hkv][k_cache] int32  requested blocks, distinct, served in this order;
+ *                                       entries outside [0, nb) are skipped; 0 <= k_cache <= 1024
+ *                                       (NULL allowed when 0)
  *   step       any int32 that grows from call to call
  * First the look-up: stats[b][h] = { retrieved tokens lying in blocks that are resident before
  * the refresh, requested blocks that are resident, blocks inserted, blocks evicted } (int32 x 4).

@@ -191,7 +191,8 @@ def block_cache_update(slot_block: np.ndarray, slot_stamp: np.ndarray, slot_uses
     State per unit: n_slots slots, each empty (block -1) or holding a block with the step of its last use
     (`stamp`) and the number of steps in which it was requested (`uses`).  `counts` [B,Hkv,nb] are this
     step's retrieved tokens per block, `blocks` [B,Hkv,k_cache] the blocks the step requests (the k_cache
-    blocks holding the most retrieved tokens), in the order they are to be served.
+    blocks holding the most retrieved tokens), in the order they are to be served; entries that are not
+    block numbers (outside [0, nb)) are skipped.
 
     The retrieved tokens are first looked up in the cache as it stands: hit_tokens = retrieved tokens that
     lie in resident blocks, hit_blocks = requested blocks that are resident.  Then the cache is refreshed:
@@ -210,17 +211,19 @@ def block_cache_update(slot_block: np.ndarray, slot_stamp: np.ndarray, slot_uses
     for b in range(B):
         for g in range(Hkv):
             blk, stamp, uses = sb[b, g], ss[b, g], su[b, g]
+            nb = counts.shape[-1]
+            wanted = [int(v) for v in blocks[b, g] if 0 <= int(v) < nb]  # anything else is not a block: skipped
             resident = {int(x): s for s, x in enumerate(blk) if x >= 0}
             stats[b, g, 0] = sum(int(counts[b, g, x]) for x in resident)
-            stats[b, g, 1] = sum(1 for x in blocks[b, g] if int(x) in resident)
+            stats[b, g, 1] = sum(1 for x in wanted if x in resident)
             requested_slots = set()
-            for x in (int(v) for v in blocks[b, g]):
+            for x in wanted:
                 if x in resident:
                     s = resident[x]
                     stamp[s] = step
                     uses[s] += 1
                     requested_slots.add(s)
-            for x in (int(v) for v in blocks[b, g]):
+            for x in wanted:
                 if x in resident:
                     continue
                 empty = [s for s in range(n_slots) if blk[s] < 0]

@@ -425,6 +425,7 @@ __global__ __launch_bounds__(256) void block_cache_kernel(int nb, int n_slots, i
   for (int i = tid; i < k_cache; i += NT) {
     int found = -1;
     for (int s = 0; s < n_slots; ++s) found = blk[s] == req[i] ? s : found;
+    if (req[i] < 0 || req[i] >= nb) found = -2;  // not a block: neither a hit nor a request
     req_slot[i] = found;
     hb += found >= 0;
   }
@@ -463,7 +464,7 @@ __global__ __launch_bounds__(256) void block_cache_kernel(int nb, int n_slots, i
   int carry = 0;
   for (int i0 = 0; i0 < k_cache; i0 += NT) {
     const int i = i0 + tid;
-    const int miss = i < k_cache && req_slot[i] < 0;
+    const int miss = i < k_cache && req_slot[i] == -1;
     int total;
     const int pos = block_exclusive_scan<NT>(miss, &total, scan_sm);
     if (i < k_cache) miss_rank[i] = miss ? carry + pos : -1;

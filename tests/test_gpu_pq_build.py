@@ -174,13 +174,17 @@ def test_block_cache_refresh_matches_oracle(pqc, policy, n_slots, k_cache, block
                                                 rng.choice(np.setdiff1d(np.arange(w.n_tokens), hot), w.n_selected - 300, replace=False)]))
                         for _ in range(4)]).reshape(2, 2, -1).astype(np.int32)
         counts, blocks = pqc.block_stats(w, torch.from_numpy(idx).to(DEV), block, k_cache)
+        if step % 4 == 0 and k_cache > 2:  # now and then some entries that are not block numbers: they are skipped
+            blocks[:, :, 1] = -1
+            blocks[:, 0, 2] = nb + 5
         stats = pqc.block_cache_update(w, block, policy, step, counts, blocks, *dev_state)
         torch.cuda.synchronize()
         # the oracle is fed its own counts and the request list in the order the library serves it
         want_counts = oracle.block_counts(idx, w.n_tokens, block)
         np.testing.assert_array_equal(counts.cpu().numpy(), want_counts)
         req = blocks.cpu().numpy()
-        np.testing.assert_array_equal(np.sort(req, -1), np.sort(oracle.block_topk(want_counts, k_cache), -1))
+        if not (step % 4 == 0 and k_cache > 2):
+            np.testing.assert_array_equal(np.sort(req, -1), np.sort(oracle.block_topk(want_counts, k_cache), -1))
         *host_state, want_stats = oracle.block_cache_update(*host_state, want_counts, req, step, policy)
         for got, want, name in zip(dev_state, host_state, ("block", "stamp", "uses")):
             np.testing.assert_array_equal(got.cpu().numpy(), want, err_msg=f"step {step}: slot_{name}")

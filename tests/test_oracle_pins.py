@@ -505,3 +505,10 @@ def test_equally_near_centroids_the_lowest_index_takes_the_token():
     c[0, 0, :, 3] = -1.0
     key = np.ones((1, 1, 8), np.float32)
     assert oracle.nearest_codes(key, "f32", c)[0, 0].tolist() == [1, 1]
+
+
+def test_block_cache_skips_entries_that_are_not_blocks():
+    counts = np.array([[[5, 0, 3, 2]]], np.int32)
+    st = _cache_state(2)
+    *st, stats = oracle.block_cache_update(*st, counts, np.array([[[-1, 2, 4, 7]]], np.int32), 1, "lru")
+    assert st[0][0, 0].tolist() == [2, -1] and stats[0, 0].tolist() == [0, 0, 1, 0]
