@@ -40,8 +40,9 @@ _CACHE: Dict[tuple, Problem] = {}
 
 def build_problem(w: wl.Workload, seed: int = 0, checked_units: Optional[Sequence[int]] = None) -> Problem:
     """Inputs for one workload.  With checked_units given, only those units get K-Means
-    PQ structures (the others get random centroids drawn from their keys and random
-    codes: valid inputs whose results are checked by invariants only)."""
+    PQ structures; the others get centroids drawn from their keys and random codes, which
+    are valid inputs too (scores, selection and attention need no clustering), so a test
+    can still compare every unit with the oracle by passing `units` to the checks."""
     key = (w, seed, None if checked_units is None else tuple(checked_units))
     if key in _CACHE:
         return _CACHE[key]
