@@ -61,7 +61,9 @@ typedef enum pqc_status {
   PQC_EINVAL = -1,      /* null pointer, malformed or inconsistent configuration   */
   PQC_EUNSUPPORTED = -2,/* well-formed configuration outside the supported shapes   */
   PQC_EWORKSPACE = -3,  /* workspace missing, misaligned or smaller than required   */
-  PQC_EHIP = -4         /* a HIP call failed; see pqc_last_hip_error()              */
+  PQC_EHIP = -4,        /* a HIP call failed; see pqc_last_hip_error()              */
+  PQC_ESCRATCH = -5     /* pqc_decode_static: the shape needs more scratch memory    *
+                         * than the library's static array holds                     */
 } pqc_status;
 
 typedef enum pqc_dtype { PQC_F32 = 0, PQC_BF16 = 1 } pqc_dtype;
@@ -168,6 +170,26 @@ int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_
 int pqc_decode_append(pqc_ctx* ctx, const void* q, const float* centroids, uint8_t* codes,
                       const void* k_cache, const void* v_cache, const void* new_key, int32_t position,
                       int32_t* out_idx, float* out_attn, void* stream);
+
+/* pqc_decode for callers that cannot allocate device memory and hold no workspace: code that
+ * runs under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * inputs, outputs, kernels and results as pqc_decode on a context of `cfg`; the workspace is a
+ * device array inside the library, pqc_static_scratch_bytes() bytes (24 MiB) per GPU, which a
+ * GPU holds from the library's first use on it until the process ends.  No context is needed
+ * and the call allocates nothing, on the device or on the host; it enqueues the step's launches
+ * preceded by one small fill kernel that clears the step's counters (the array keeps whatever
+ * the last call left).
+ *   - PQC_ESCRATCH when the step's workspace for n_tokens of cfg (never more than
+ *     pqc_workspace_bytes(cfg)) exceeds pqc_static_scratch_bytes(); nothing is enqueued then.
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two
+ *     streams, two threads) race and give undefined results; order them on one stream.
+ *   - The first call on a device looks the array's address up (hipGetSymbolAddress); make
+ *     that call outside stream capture.
+ * cfg is read at every call, so a growing cache needs no pqc_set_length here. */
+size_t pqc_static_scratch_bytes(void);
+int pqc_decode_static(const pqc_config* cfg, const void* q, const float* centroids, const uint8_t* codes,
+                      const void* k_cache, const void* v_cache, int32_t* out_idx, float* out_attn,
+                      void* stream);
 
 /* The same step for PQ structures with two partitions of at most 64 centroids, where a
  * token's score takes one of C*C values (one per pair of codes): the threshold of the

@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpqcache.so")
 
 PQC_F32, PQC_BF16 = 0, 1
-STATUS = {0: "PQC_OK", -1: "PQC_EINVAL", -2: "PQC_EUNSUPPORTED", -3: "PQC_EWORKSPACE", -4: "PQC_EHIP"}
+STATUS = {0: "PQC_OK", -1: "PQC_EINVAL", -2: "PQC_EUNSUPPORTED", -3: "PQC_EWORKSPACE", -4: "PQC_EHIP", -5: "PQC_ESCRATCH"}
 
 
 class Config(C.Structure):
@@ -62,6 +62,10 @@ def load() -> C.CDLL:
     lib.pqc_last_hip_error.argtypes = [vp]
     lib.pqc_decode.restype = C.c_int
     lib.pqc_decode.argtypes = [vp] * 9
+    lib.pqc_static_scratch_bytes.restype = C.c_size_t
+    lib.pqc_static_scratch_bytes.argtypes = []
+    lib.pqc_decode_static.restype = C.c_int
+    lib.pqc_decode_static.argtypes = [cp] + [vp] * 8
     lib.pqc_decode_append.restype = C.c_int
     lib.pqc_decode_append.argtypes = [vp] * 7 + [C.c_int32] + [vp] * 3
     lib.pqc_decode_indexed_append.restype = C.c_int
@@ -315,6 +319,26 @@ def _need(t: torch.Tensor, dtype, shape, what: str) -> int:
     if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype or tuple(t.shape) != tuple(shape):
         raise ValueError(f"{what}: expected contiguous device {dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
     return t.data_ptr()
+
+
+def decode_static(w: Workload, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream=None, capacity: int = 0,
+                  softmax_scale: float = 0.0) -> None:
+    """pqc_decode_static: the decode step on the library's own static scratch memory (no context, no workspace)."""
+    lib = load()
+    cfg = make_config(w, softmax_scale, capacity)
+    ntok = capacity or w.n_tokens
+    kvt = _kv_dtype(w)
+    st = (stream if stream is not None else torch.cuda.current_stream(q.device)).cuda_stream
+    rc = lib.pqc_decode_static(
+        C.byref(cfg), _need(q, kvt, (w.batch, w.n_q_heads, w.head_dim), "q"),
+        _need(centroids, torch.float32, (w.batch, w.n_kv_heads, w.pq_m, w.pq_centroids, w.sub_dim), "centroids"),
+        _need(codes, torch.uint8, (w.batch, w.n_kv_heads, ntok, w.pq_m), "codes"),
+        _need(k_cache, kvt, (w.batch, w.n_kv_heads, ntok, w.head_dim), "k_cache"),
+        _need(v_cache, kvt, (w.batch, w.n_kv_heads, ntok, w.head_dim), "v_cache"),
+        _need(out_idx, torch.int32, (w.batch, w.n_kv_heads, w.n_selected), "out_idx"),
+        _need(out_attn, torch.float32, (w.batch, w.n_q_heads, w.head_dim), "out_attn"), st)
+    if rc != 0:
+        raise PQCacheError(rc, "pqc_decode_static")
 
 
 def pq_build(w: Workload, keys: torch.Tensor, init_idx: torch.Tensor, iters: Optional[int] = None, stream=None,

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "pqc_build_kernels.h"
@@ -309,6 +310,7 @@ const char* pqc_strerror(int status) {
     case PQC_EUNSUPPORTED: return "configuration outside the supported shapes";
     case PQC_EWORKSPACE: return "workspace missing, misaligned or too small";
     case PQC_EHIP: return "HIP call failed";
+    case PQC_ESCRATCH: return "shape needs more than the static scratch of pqc_decode_static (use pqc_decode with a workspace)";
     default: return "unknown status";
   }
 }
@@ -564,6 +566,71 @@ int pqc_gather_attn(pqc_ctx* ctx, const void* q, const void* k_cache, const void
   return check_launch(ctx);
 }
 
+
+}  // extern "C"
+
+/* ------------------------------------------------- decode without an allocation */
+// For callers that can neither allocate device memory nor hold a workspace of their own (code under HIP graph
+// capture, serving loops, harnesses that forbid hipMalloc): the workspace of the step is a file-scope device
+// array.  Host code never uses the array's name as an address: its device address is looked up once per device.
+namespace {
+
+constexpr size_t kStaticScratchBytes = (size_t)24 << 20;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices];  // per device: where that device holds its copy of `scratch`
+
+// Device address of the current device's scratch array (looked up on the first call on that device).
+int static_scratch(unsigned char** out, int* hip_code) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    *hip_code = (int)e;
+    return PQC_EHIP;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      *hip_code = (int)e;
+      return PQC_EHIP;
+    }
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return PQC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t pqc_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int pqc_decode_static(const pqc_config* cfg, const void* q, const float* centroids, const uint8_t* codes, const void* k_cache,
+                      const void* v_cache, int32_t* out_idx, float* out_attn, void* stream) {
+  pqc_ctx ctx;  // on the stack: nothing is allocated, on the host either
+  const int rc = make_plan(cfg, &ctx.plan);
+  if (rc != PQC_OK) return rc;
+  if (ctx.plan.total > kStaticScratchBytes) return PQC_ESCRATCH;
+  unsigned char* base = nullptr;
+  int hip_code = 0;
+  const int rs = static_scratch(&base, &hip_code);
+  if (rs != PQC_OK) return rs;
+  ctx.cfg = *cfg;
+  ctx.cfg.n_capacity = ctx.plan.s.cap;
+  ctx.workspace = reinterpret_cast<char*>(base);
+  ctx.workspace_bytes = kStaticScratchBytes;
+  bind_workspace(&ctx);
+  ctx.hist_clean = false;  // the array keeps what the last call (of any shape) left: the step's counters are cleared first,
+                           // by a fill kernel, so that the call can be recorded into a graph
+  ctx.last_hip = 0;
+  ctx.append = AppendArgs{nullptr, nullptr, nullptr, 0, nullptr};
+  return decode_impl(&ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 7u);
+}
 
 }  // extern "C"
 
