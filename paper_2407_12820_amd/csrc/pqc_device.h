@@ -15,7 +15,8 @@ constexpr int kNB = 2048;        // score bins of the one-pass threshold search
 constexpr int kHistCopies = 4;   // histogram replica slots per unit; Shape::histCopies of them are in use
 constexpr int kD = 128;          // head dimension
 constexpr int kLutRow = 256;     // LDS stride of one partition's table (max centroids)
-constexpr int kCandRec = 1024;   // boundary-bin candidate records per unit (ranked inside LDS by the finalize kernel)
+constexpr int kCandRec = 512;    // boundary-bin candidate records per unit (ranked inside LDS by the unit's last workgroup)
+constexpr int kMaxBlkC = 512;    // select workgroups per unit, at most
 constexpr float kNegBig = -1.0e30f;
 
 struct bf16_t {
@@ -43,7 +44,7 @@ struct Shape {
   float scale_log2e;
 };
 
-// Record of one boundary-bin candidate: enough for the finalize kernel to rank it and,
+// Record of one boundary-bin candidate: enough for the unit's last workgroup to rank it and,
 // if admitted, to add it to the attention output without touching the K/V cache again.
 struct CandHeader {
   unsigned long long composite;  // (score key, ~token): larger ranks first
@@ -57,8 +58,9 @@ struct Workspace {
   BinParams* ctl;              // [units]                       score -> bin map of the unit
   float* lut;                  // [units][M][C]
   float2* range;               // [units]                       (min, max) score, stand-alone top-k only
-  unsigned* hist;              // [2][units][histCopies][kNB]   zero between uses (room for kHistCopies replicas)
-  unsigned* cand_count;        // [2][units]   records handed out so far (directly behind hist, zeroed with it)
+  unsigned* hist;              // [units][histCopies][kNB]   zero between uses (room for kHistCopies replicas)
+  unsigned* cand_count;        // [units]   records handed out so far (directly behind hist, zeroed with it)
+  unsigned* ticket;            // [units]   select workgroups of the unit that have finished (behind cand_count, zeroed with it)
   unsigned short* bins;        // [units][binStride]  per token: bin + 1, or kBinWindow inside the two windows
   unsigned char* cand_rec;     // [units][kCandRec] records of rec_stride bytes, in order of arrival
   unsigned long long* stage;   // [units][nblkC][stageStride]: selected ids (front, int32) / candidate composites (ending at word tokC)
@@ -66,7 +68,7 @@ struct Workspace {
   float* partials;             // [units][npart][G][kD+2]
   int rec_stride;
 #ifdef PQC_TRACE
-  unsigned long long* trace;   // [3 kernels][kTraceWgs][kTraceSlots] time stamps (debug builds only)
+  unsigned long long* trace;   // [3 phases][kTraceWgs][kTraceSlots] time stamps (debug builds only)
 #endif
 };
 
@@ -236,6 +238,38 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* total, int* sm /
   __syncthreads();
   const int res = inc - v + sm[NW + w];
   *total = sm[2 * NW];
+  __syncthreads();
+  return res;
+}
+
+// The same for two values at once (one set of barriers).
+template <int NT>
+__device__ __forceinline__ int2 block_exclusive_scan2(int a, int b, int2* total, int* sm /* [2*(2*(NT/64)+1)] */) {
+  constexpr int NW = NT / 64;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int ia = wave_inclusive_scan(a), ib = wave_inclusive_scan(b);
+  int* sa = sm;
+  int* sb = sm + 2 * NW + 1;
+  if (lane == 63) {
+    sa[w] = ia;
+    sb[w] = ib;
+  }
+  __syncthreads();
+  if (w == 0) {
+    const int xa = lane < NW ? sa[lane] : 0, xb = lane < NW ? sb[lane] : 0;
+    const int ya = wave_inclusive_scan(xa), yb = wave_inclusive_scan(xb);
+    if (lane < NW) {
+      sa[NW + lane] = ya - xa;
+      sb[NW + lane] = yb - xb;
+    }
+    if (lane == NW - 1) {
+      sa[2 * NW] = ya;
+      sb[2 * NW] = yb;
+    }
+  }
+  __syncthreads();
+  const int2 res = make_int2(ia - a + sa[NW + w], ib - b + sb[NW + w]);
+  *total = make_int2(sa[2 * NW], sb[2 * NW]);
   __syncthreads();
   return res;
 }
@@ -1173,27 +1207,38 @@ __device__ __forceinline__ void mfma_consume(const MfmaStage& g, int count, int 
   }
 }
 
-// Rows list(first), list(first+1), ... in stages of 16*kMfmaTiles positions, `stride` apart.
-template <class ListFn>
+// Rows list(first), list(first+1), ... in stages of 16*kMfmaTiles positions, `stride` apart.  after_first() is
+// called once, when the first stage has been consumed (at once for a wave without rows): whatever the caller
+// requested from memory before the call has arrived by then, because a wave's loads and returning atomics
+// come back in issue order, so the caller can put such a value away there without waiting for it and without
+// holding its register through the loop.
+template <class ListFn, class FirstFn>
 __device__ __forceinline__ void mfma_attend(const bf16_t* __restrict__ kbase, const bf16_t* __restrict__ vbase, int N,
                                             ListFn list, int count, int first, int stride, float scale_log2e,
                                             const bf16x8_t (&qf)[4], unsigned char* vt /* wave-private LDS [kVTileBytes] */,
-                                            MfmaState& st) {
-  if (first >= count) return;  // wave-uniform
+                                            MfmaState& st, FirstFn after_first) {
+  if (first >= count) {  // wave-uniform
+    after_first();
+    return;
+  }
   MfmaStage ga, gb;
   int base = first;
   mfma_issue(kbase, vbase, N, list, count, base, ga);
-  for (;;) {
-    mfma_issue(kbase, vbase, N, list, count, base + stride, gb);
-    PQC_LOADS_ISSUED();
-    mfma_consume(ga, count, base, scale_log2e, qf, vt, st);
-    base += stride;
-    if (base >= count) break;
+  mfma_issue(kbase, vbase, N, list, count, base + stride, gb);
+  PQC_LOADS_ISSUED();
+  mfma_consume(ga, count, base, scale_log2e, qf, vt, st);
+  after_first();
+  base += stride;
+  while (base < count) {
     mfma_issue(kbase, vbase, N, list, count, base + stride, ga);
     PQC_LOADS_ISSUED();
     mfma_consume(gb, count, base, scale_log2e, qf, vt, st);
     base += stride;
     if (base >= count) break;
+    mfma_issue(kbase, vbase, N, list, count, base + stride, gb);
+    PQC_LOADS_ISSUED();
+    mfma_consume(ga, count, base, scale_log2e, qf, vt, st);
+    base += stride;
   }
 }
 

@@ -1,18 +1,19 @@
 // Kernels of libpqcache (gfx950).  Grid layout: blockIdx.y = unit (sequence b, KV
-// head g); blockIdx.x = workgroup inside the unit (query head for finalize_kernel).
+// head g); blockIdx.x = workgroup inside the unit.
 //
-// Decode path (pqc_decode), three launches, every dependency at a kernel boundary:
+// Decode path (pqc_decode), two launches; the one dependency between all workgroups of a
+// unit that needs every one of them to be done sits at the kernel boundary, the other is
+// settled by whichever workgroup finishes last (nobody ever waits inside a kernel):
 //   hist_kernel      table -> scan codes -> histogram of scores over kNB bins, and every
 //                    token's bin number left behind for the next kernel
 //   select_kernel    threshold bin from the histogram -> tokens whose stored bin lies
 //                    above it (and the two windows) are listed in ascending order
 //                    without atomics and attended at once; tokens inside the bin
-//                    ("candidates") are recorded with their logits and V row
-//   finalize_kernel  one workgroup per query head ranks the candidates and folds the
-//                    admitted ones and all partial softmax states into the output;
-//                    copy workgroups beside them write the indices and zero the unit's
-//                    histogram and record counter again, which nothing reads after the
-//                    select kernel: every call leaves them as it found them
+//                    ("candidates") are recorded with their logits and V row.  The unit's
+//                    last workgroup to finish then ranks the candidates, folds the
+//                    admitted ones and all partial softmax states into the output, writes
+//                    the indices and zeroes the unit's histogram and counters again:
+//                    every call leaves them as it found them
 //
 // Codes are read 16 bytes at a time (P = 16/M tokens).  A unit's codes start at byte
 // u*N*M, which need not be 16-byte aligned: chunks are laid over the aligned-down
@@ -305,7 +306,481 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   PQC_MARK(ws, 0, 4);
 }
 
-// ---------------------------------------------------- 2. select (+ attention)
+// ------------------------------------------------------ 2. finishing a unit
+// The select workgroups of a unit each leave a partial softmax state per query head, the list of
+// tokens they selected and their boundary-bin candidates behind.  Whichever of them finishes last
+// (a ticket drawn from a per-unit counter with one returning atomic: nobody waits for anybody)
+// completes the unit with finalize_unit():
+//   - ranks the candidates and admits the K - n_above best (at most kCandRec candidates: all that
+//     is needed sits in their records, which arrive in a different order on every run, so every
+//     sum over candidates is taken in rank order; more candidates: an 8-bit radix select over the
+//     composites staged per workgroup, the admitted rows being attended from the K/V cache);
+//   - folds the admitted rows and all partial states (in workgroup order) into out_attn;
+//   - concatenates the staged lists into out_idx; in workgroup order they read
+//       [0..I) , tokens above the threshold bin (ascending) , [N-L..N)
+//     and the admitted candidates go between the second and the third part;
+//   - zeroes the unit's histogram, record counter and ticket counter again, which nothing reads
+//     after this point: every call leaves them as it found them.
+constexpr int kTailTiles = 16;  // index tiles (256 entries) a wave keeps in flight while copying the staged lists
+constexpr int kAccLoads = 64;   // partial accumulators a thread keeps in flight
+constexpr int kVBatch = 16;     // admitted candidates' V elements a thread keeps in flight
+
+// The code of one appended token per unit (Section 3.1: nearest centroid of each partition): nothing in the
+// step depends on it, so one more workgroup per unit of the select kernel computes it beside the others.
+struct AppendArgs {
+  const void* key;    // [units][kD] in the cache's element type, or null: nothing to append
+  const float* cent;  // [units][M][C][Dm]
+  uint8_t* codes;     // the code tensor; written at `position` of every unit
+  int position;
+  unsigned* pair_counts;  // two partitions: [units][C*C] counts that gain the token's code pair, or null
+};
+
+template <int G, bool ATTN>
+struct TailLds {
+  static constexpr int NW = 4, GA = ATTN ? G : 1;
+  struct Few {                            // at most kCandRec candidates: ranked here
+    unsigned long long comp[kCandRec];    // composites in record order
+    float p[GA][kCandRec];                // by rank: logit of head h (log2 domain), then its softmax weight
+    unsigned short ordv[kCandRec];        // by rank: record
+  };
+  struct Many {                           // more: radix select, admitted rows attended from the cache
+    unsigned rhist[256];
+    int digit[2];
+    int rows[256];
+    float red[ATTN ? NW * (G > 4 ? 4 : G) * (kD + 2) : 1];
+  };
+  union {
+    Few few;
+    Many many;
+  };
+  float wj[GA][kMaxBlkC];                 // weight of every select workgroup's partial softmax state
+  float xacc[GA][kD];                     // one more partial state per head: the admitted rows of the radix path
+  float xm[8], xl[8], xw[8];
+  float lstar[8];
+  int pre_sel[kMaxBlkC + 1];              // exclusive prefix sums of the staged list sizes
+  int pre_cand[kMaxBlkC + 1];             // and of the staged candidate counts
+  int scan_sm[2 * (2 * NW + 1)];
+};
+
+template <typename T, int G, bool ATTN>
+__device__ __forceinline__ void finalize_unit(const Shape& s, const Workspace& ws, int u, const T* __restrict__ q,
+                                              const T* __restrict__ kc, const T* __restrict__ vc, int* __restrict__ out_idx,
+                                              float* __restrict__ out_attn, const AppendArgs& ap, TailLds<G, ATTN>& L) {
+  constexpr int NT = 256, NW = 4;
+  constexpr int GA = ATTN ? G : 1;
+  constexpr int HPW = (GA + NW - 1) / NW;     // heads per wave when the softmax states are weighted
+  constexpr int HPT = GA >= 2 ? GA / 2 : 1;   // heads per thread when the outputs are summed: heads hb, hb + 2, ...
+  constexpr int JB = kAccLoads / HPT;         // partial states per batch of accumulator loads
+  constexpr int MLX = kMaxBlkC / 64;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int b = u / s.Hkv, g = u % s.Hkv, nb = s.nblkC;
+  const int2* cnt = ws.stage_cnt + (size_t)u * nb;
+  const unsigned long long* stage_u = ws.stage + (size_t)u * nb * s.stageStride;
+  const unsigned char* recs = ws.cand_rec + (size_t)u * kCandRec * ws.rec_stride;
+  const float* parts = ws.partials + (size_t)u * s.npart * G * (kD + 2);
+  int* out = out_idx + (size_t)u * s.Ktot;
+  const int d = tid & (kD - 1), hb = tid >> 7;  // output dimension; first head of this thread
+  PQC_MARK(ws, 2, 0);
+
+  // ---- everything whose address is known up front is requested first
+  const int2 c0 = cnt[min(tid, nb - 1)], c1 = cnt[min(tid + NT, nb - 1)];  // nb <= 2 * NT
+  unsigned long long rc[kCandRec / NT];  // record x*NT + tid
+  float rl[kCandRec / NT][GA];
+  {
+    const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)tid * ws.rec_stride);
+    rc[0] = hd->composite;
+#pragma unroll
+    for (int h = 0; h < GA; ++h) rl[0][h] = ATTN ? hd->logit[h] : 0.0f;
+  }
+  float2 ml[HPW][MLX];   // (m, l) of partial state x*64 + lane, head w + NW*i
+  float a0[HPT][JB];     // first batch of accumulators: partial state x, head hb + 2*i, dimension d
+  if constexpr (ATTN) {
+#pragma unroll
+    for (int i = 0; i < HPW; ++i)
+#pragma unroll
+      for (int x = 0; x < MLX; ++x) {
+        ml[i][x] = make_float2(kNegBig, 0.0f);
+        if (x * 64 < nb && w + NW * i < G)  // wave-uniform
+          ml[i][x] = *reinterpret_cast<const float2*>(parts + ((size_t)min(x * 64 + lane, nb - 1) * G + (w + NW * i)) * (kD + 2));
+      }
+#pragma unroll
+    for (int i = 0; i < HPT; ++i)
+#pragma unroll
+      for (int x = 0; x < JB; ++x)  // states that do not exist re-read the last one (a cache hit, no extra traffic)
+        a0[i][x] = parts[((size_t)min(x, nb - 1) * G + (G >= 2 ? hb + 2 * i : 0)) * (kD + 2) + 2 + d];
+  }
+  PQC_LOADS_ISSUED();
+  if (tid < 8) {
+    L.xm[tid] = kNegBig;
+    L.xl[tid] = 0.0f;
+  }
+
+  // ---- list sizes: exclusive prefix sums and totals
+  int n_list, n_cand;
+  {
+    int2 t0, t1 = make_int2(0, 0);
+    const int2 p0 = block_exclusive_scan2<NT>(tid < nb ? c0.x : 0, tid < nb ? c0.y : 0, &t0, L.scan_sm);
+    if (tid < nb) {
+      L.pre_sel[tid] = p0.x;
+      L.pre_cand[tid] = p0.y;
+    }
+    if (nb > NT) {  // uniform
+      const int2 p1 = block_exclusive_scan2<NT>(tid + NT < nb ? c1.x : 0, tid + NT < nb ? c1.y : 0, &t1, L.scan_sm);
+      if (tid + NT < nb) {
+        L.pre_sel[tid + NT] = t0.x + p1.x;
+        L.pre_cand[tid + NT] = t0.y + p1.y;
+      }
+    }
+    n_list = t0.x + t1.x;
+    n_cand = t0.y + t1.y;
+    if (tid == 0) {
+      L.pre_sel[nb] = n_list;
+      L.pre_cand[nb] = n_cand;
+    }
+    __syncthreads();
+  }
+  const int n_above = max(0, n_list - s.I - s.L);  // n_list = I + (tokens above the bin) + L
+  const int need = max(0, min(s.K - n_above, n_cand));
+  PQC_MARK(ws, 2, 1);
+
+  // ---- index output: the staged lists, one after the other; the local window moves behind the admitted candidates.
+  // Wave w copies lists w, w + NW, ...; a list is cut into tiles of 256 entries (4 per lane) and kTailTiles tiles
+  // travel at once.  Lane l of the wave describes the wave's l-th list; the tile -> list map is a ballot over the
+  // running tile counts.
+  {
+    const int lists_w = (nb - w + NW - 1) / NW;
+    for (int l0 = 0; l0 < lists_w; l0 += 64) {
+      const int jl = w + NW * (l0 + lane);
+      const int base_l = jl < nb ? L.pre_sel[jl] : 0;
+      const int n_l = jl < nb ? L.pre_sel[jl + 1] - base_l : 0;
+      const int tiles_l = (n_l + 255) >> 8;
+      const int incl = wave_inclusive_scan(tiles_l);
+      const int total = wave_last(incl);
+      for (int t0 = 0; t0 < total; t0 += kTailTiles) {
+        int v[kTailTiles][4], rem[kTailTiles], dst0[kTailTiles];
+#pragma unroll
+        for (int x = 0; x < kTailTiles; ++x) {
+          const int t = t0 + x;
+          const int lo = min(63, (int)__popcll(__ballot(incl <= t)));  // the list that holds tile t (uniform)
+          const int j = min(w + NW * (l0 + lo), nb - 1);
+          const int first = __builtin_amdgcn_readlane(incl, lo) - __builtin_amdgcn_readlane(tiles_l, lo);
+          const int n_j = __builtin_amdgcn_readlane(n_l, lo);
+          const int e0 = (t - first) * 256;
+          const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.stageStride);
+#pragma unroll
+          for (int y = 0; y < 4; ++y) v[x][y] = src[max(0, min(e0 + y * 64 + lane, n_j - 1))];
+          rem[x] = t < total ? n_j - e0 : 0;
+          dst0[x] = __builtin_amdgcn_readlane(base_l, lo) + e0;
+        }
+        PQC_LOADS_ISSUED();
+#pragma unroll
+        for (int x = 0; x < kTailTiles; ++x)
+#pragma unroll
+          for (int y = 0; y < 4; ++y) {
+            const int e = y * 64 + lane, pos = dst0[x] + e;
+            const int dst = pos < s.I + n_above ? pos : pos + need;
+            if (e < rem[x] && dst < s.Ktot) out[dst] = v[x][y];
+          }
+      }
+    }
+  }
+  PQC_MARK(ws, 2, 2);
+
+  int need_few = 0;          // admitted candidates whose weights and V rows come from the records
+  bool extra_state = false;  // the radix path left one more partial state per head in xacc / xm / xl
+  if (n_cand <= kCandRec) {
+    // rank every candidate (count of larger composites); the admitted ones are the `need` best
+    if (need > 0) {
+#pragma unroll
+      for (int x = 1; x < kCandRec / NT; ++x) {
+        rc[x] = 0ull;
+#pragma unroll
+        for (int h = 0; h < GA; ++h) rl[x][h] = 0.0f;
+        if (x * NT + tid < n_cand) {  // rare: more than NT candidates
+          const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)(x * NT + tid) * ws.rec_stride);
+          rc[x] = hd->composite;
+#pragma unroll
+          for (int h = 0; h < GA; ++h) rl[x][h] = ATTN ? hd->logit[h] : 0.0f;
+        }
+      }
+#pragma unroll
+      for (int x = 0; x < kCandRec / NT; ++x)
+        if (x * NT + tid < n_cand) L.few.comp[x * NT + tid] = rc[x];
+      __syncthreads();
+#pragma unroll
+      for (int x = 0; x < kCandRec / NT; ++x) {
+        const int k = x * NT + tid;
+        if (k < n_cand) {
+          const unsigned long long mine = rc[x];
+          int rank = 0;
+          for (int j0 = 0; j0 < n_cand; j0 += 8) {  // eight independent LDS reads per round
+            unsigned long long o[8];
+#pragma unroll
+            for (int y = 0; y < 8; ++y) o[y] = L.few.comp[min(j0 + y, n_cand - 1)];
+#pragma unroll
+            for (int y = 0; y < 8; ++y) rank += (j0 + y < n_cand && o[y] > mine) ? 1 : 0;
+          }
+          if (rank < need) {
+            const int dst = s.I + n_above + rank;  // best first
+            if (dst < s.Ktot) out[dst] = composite_token(mine);
+#pragma unroll
+            for (int h = 0; h < GA; ++h) L.few.p[h][rank] = rl[x][h] * s.scale_log2e;
+            L.few.ordv[rank] = (unsigned short)k;
+          }
+        }
+      }
+    }
+    need_few = need;
+  } else {
+    // radix select of the need-th largest staged composite, 8 bits per pass
+    auto owner = [&](int p) -> int {  // largest j with pre_cand[j] <= p
+      int lo = 0, hi = nb - 1;
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (L.pre_cand[mid] <= p) lo = mid; else hi = mid - 1;
+      }
+      return lo;
+    };
+    auto cand_at = [&](int i) -> unsigned long long {
+      const int j = owner(i);
+      return stage_u[(size_t)j * s.stageStride + s.tokC - 1 - (i - L.pre_cand[j])];
+    };
+    unsigned long long thr = ~0ull;
+    if (need > 0) {
+      unsigned long long prefix = 0;
+      int want = need;
+      for (int shift = 56; shift >= 0; shift -= 8) {
+        L.many.rhist[tid] = 0u;
+        __syncthreads();
+        for (int i = tid; i < n_cand; i += NT) {
+          const unsigned long long c = cand_at(i);
+          if (shift == 56 || (c >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&L.many.rhist[(unsigned)(c >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+          int cum = 0, dg = 255;
+          for (; dg > 0; --dg) {
+            if (cum + (int)L.many.rhist[dg] >= want) break;
+            cum += (int)L.many.rhist[dg];
+          }
+          L.many.digit[0] = dg;
+          L.many.digit[1] = want - cum;
+        }
+        __syncthreads();
+        prefix |= (unsigned long long)L.many.digit[0] << shift;
+        want = L.many.digit[1];
+        __syncthreads();
+      }
+      thr = prefix;
+    }
+    // admitted candidates in staged order, NT candidates per round: indices out, rows attended for up to four heads
+    // at a time (the rounds are repeated for the next four)
+    constexpr int GG = GA > 4 ? 4 : GA;
+    for (int h0 = 0; h0 < GA; h0 += GG) {
+      AttnState<GG> st;
+      st.init();
+      float qr[GG][8];
+      if constexpr (ATTN) load_query<T, GG>(q + ((size_t)b * s.Hq + (size_t)g * G + h0) * kD, s.scale_log2e, qr);
+      int carry = 0;
+      for (int i0 = 0; i0 < (need > 0 ? n_cand : 0); i0 += NT) {
+        const int i = i0 + tid;
+        unsigned long long c = 0;
+        if (i < n_cand) c = cand_at(i);
+        const int flag = (i < n_cand && c >= thr) ? 1 : 0;
+        int tot;
+        const int pos = block_exclusive_scan<NT>(flag, &tot, L.scan_sm);
+        if (flag) {
+          L.many.rows[pos] = composite_token(c);
+          const int dst = s.I + n_above + carry + pos;
+          if (h0 == 0 && dst < s.Ktot) out[dst] = composite_token(c);
+        }
+        __syncthreads();
+        if constexpr (ATTN) {
+          constexpr int R = sizeof(T) == 4 ? 2 : 4;
+          auto row_at = [&](int p) -> int { return L.many.rows[p]; };
+          attend_rows<T, GG, R>(kc + (size_t)u * s.cap * kD, vc + (size_t)u * s.cap * kD, s.N, row_at, tot, w * 4 * R, NW * 4 * R, qr, st);
+        }
+        __syncthreads();
+        carry += tot;
+      }
+      if constexpr (ATTN) {
+        stash_wave_state<T, GG>(st, L.many.red);
+        __syncthreads();
+        for (int o = tid; o < GG * kD; o += NT) {
+          const int h = o / kD, dd = o % kD;
+          float m, l, acc;
+          combine_waves<GG, NW>(L.many.red, h, dd, m, l, acc);
+          L.xacc[h0 + h][dd] = acc;
+          if (dd == 0) {
+            L.xm[h0 + h] = m;
+            L.xl[h0 + h] = l;
+          }
+        }
+        __syncthreads();
+        extra_state = true;
+      }
+    }
+  }
+  __syncthreads();
+  PQC_MARK(ws, 2, 3);
+
+  if constexpr (ATTN) {
+    // ---- per head (one wave each): the common maximum, the weight of every partial state and of every admitted
+    // candidate, the softmax denominator
+#pragma unroll
+    for (int i = 0; i < HPW; ++i) {
+      const int h = w + NW * i;
+      if (h < G) {  // wave-uniform
+        float mx = L.xm[h];
+#pragma unroll
+        for (int x = 0; x < MLX; ++x)
+          if (x * 64 + lane < nb) mx = fmaxf(mx, ml[i][x].x);
+        for (int r = lane; r < need_few; r += 64) mx = fmaxf(mx, L.few.p[h][r]);
+        const float mstar = wave_max(mx);
+        float lsum = 0.0f;
+#pragma unroll
+        for (int x = 0; x < MLX; ++x)
+          if (x * 64 + lane < nb) {
+            const float wv = __builtin_amdgcn_exp2f(ml[i][x].x - mstar);
+            L.wj[h][x * 64 + lane] = wv;
+            lsum = fmaf(wv, ml[i][x].y, lsum);
+          }
+        for (int r = lane; r < need_few; r += 64) {
+          const float pr = __builtin_amdgcn_exp2f(L.few.p[h][r] - mstar);
+          L.few.p[h][r] = pr;
+          lsum += pr;
+        }
+        lsum = wave_sum(lsum);
+        const float xw = __builtin_amdgcn_exp2f(L.xm[h] - mstar);
+        if (lane == 0) {
+          L.lstar[h] = fmaf(L.xl[h], xw, lsum);
+          L.xw[h] = xw;
+        }
+      }
+    }
+    __syncthreads();
+    PQC_MARK(ws, 2, 4);
+    // ---- out[h][d] = (sum_j w_j acc_j[h][d] + sum_r p_r V_r[d]) / l, partial states in workgroup order, candidates
+    // in rank order
+    if (G >= 2 || hb == 0) {
+      int hh[HPT];
+      float acc[HPT];
+#pragma unroll
+      for (int i = 0; i < HPT; ++i) {
+        hh[i] = G >= 2 ? hb + 2 * i : 0;
+        acc[i] = 0.0f;
+      }
+#pragma unroll
+      for (int x = 0; x < JB; ++x)
+#pragma unroll
+        for (int i = 0; i < HPT; ++i)
+          if (x < nb) acc[i] = fmaf(L.wj[hh[i]][x], a0[i][x], acc[i]);
+      for (int j0 = JB; j0 < nb; j0 += JB) {
+        float a[HPT][JB];
+#pragma unroll
+        for (int i = 0; i < HPT; ++i)
+#pragma unroll
+          for (int x = 0; x < JB; ++x) a[i][x] = parts[((size_t)min(j0 + x, nb - 1) * G + hh[i]) * (kD + 2) + 2 + d];
+        PQC_LOADS_ISSUED();
+#pragma unroll
+        for (int x = 0; x < JB; ++x)
+#pragma unroll
+          for (int i = 0; i < HPT; ++i)
+            if (j0 + x < nb) acc[i] = fmaf(L.wj[hh[i]][j0 + x], a[i][x], acc[i]);
+      }
+      if (extra_state) {
+#pragma unroll
+        for (int i = 0; i < HPT; ++i) acc[i] = fmaf(L.xw[hh[i]], L.xacc[hh[i]][d], acc[i]);
+      }
+      for (int r0 = 0; r0 < need_few; r0 += kVBatch) {
+        float vv[kVBatch];
+#pragma unroll
+        for (int x = 0; x < kVBatch; ++x) {
+          const int k = L.few.ordv[min(r0 + x, need_few - 1)];
+          vv[x] = load_as_float<T>(reinterpret_cast<const T*>(recs + (size_t)k * ws.rec_stride + sizeof(CandHeader)), d);
+        }
+        PQC_LOADS_ISSUED();
+#pragma unroll
+        for (int x = 0; x < kVBatch; ++x)
+#pragma unroll
+          for (int i = 0; i < HPT; ++i)
+            if (r0 + x < need_few) acc[i] = fmaf(L.few.p[hh[i]][r0 + x], vv[x], acc[i]);
+      }
+#pragma unroll
+      for (int i = 0; i < HPT; ++i)
+        out_attn[((size_t)b * s.Hq + (size_t)g * G + hh[i]) * kD + d] = acc[i] / L.lstar[hh[i]];
+    }
+    PQC_MARK(ws, 2, 5);
+  }
+
+  // ---- every select workgroup of the unit is done with them: zero histogram, record counter and ticket counter
+  {
+    uint4* gh = reinterpret_cast<uint4*>(ws.hist + (size_t)u * s.histCopies * kNB);
+    for (int i = tid; i < s.histCopies * (kNB / 4); i += NT) gh[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (tid == 0) {
+      ws.cand_count[u] = 0u;
+      ws.ticket[u] = 0u;
+      if (ap.key && ap.pair_counts) {  // the appended token's code pair joins the counts now that nobody reads them
+        const uint8_t* cp = ap.codes + ((size_t)u * s.cap + ap.position) * 2;
+        const unsigned a0c = cp[0], a1c = cp[1];
+        if (a0c < (unsigned)s.C && a1c < (unsigned)s.C) ap.pair_counts[(size_t)u * s.C * s.C + a0c + (size_t)s.C * a1c] += 1u;
+      }
+    }
+  }
+  PQC_MARK(ws, 2, 6);
+  PQC_NOTE(ws, 2, 13, n_above);
+  PQC_NOTE(ws, 2, 14, n_cand);
+  PQC_NOTE(ws, 2, 15, need);
+}
+
+// The code of the appended token of unit u (one thread per centroid, the distance chain of pq_assign_kernel, the
+// smallest (distance, centroid) pair of each partition through a 64-bit LDS minimum).
+struct AppendLds {
+  float ax[kD];
+  unsigned long long abest[8];
+};
+template <typename T>
+__device__ __forceinline__ void append_token(const Shape& s, const AppendArgs& ap, int u, AppendLds& A) {
+  const int c = threadIdx.x;
+  if (c < kD) A.ax[c] = load_as_float<T>(static_cast<const T*>(ap.key), (size_t)u * kD + c);
+  if (c < 8) A.abest[c] = ~0ull;
+  __syncthreads();
+  if (c < s.C) {
+    for (int j = 0; j < s.M; ++j) {
+      const float* cr = ap.cent + (((size_t)u * s.M + j) * s.C + c) * s.Dm;
+      const float* xj = A.ax + j * s.Dm;
+      float d2 = 0.0f;
+      for (int e = 0; e < s.Dm; e += 4) {  // Dm is a multiple of 4
+        const float4 cv = *reinterpret_cast<const float4*>(cr + e);
+        float df = xj[e] - cv.x;
+        d2 = fmaf(df, df, d2);
+        df = xj[e + 1] - cv.y;
+        d2 = fmaf(df, df, d2);
+        df = xj[e + 2] - cv.z;
+        d2 = fmaf(df, df, d2);
+        df = xj[e + 3] - cv.w;
+        d2 = fmaf(df, df, d2);
+      }
+      atomicMin(&A.abest[j], ((unsigned long long)__float_as_uint(d2) << 32) | (unsigned)c);  // d2 >= 0: bits order like values
+    }
+  }
+  __syncthreads();
+  if (c < s.M) ap.codes[((size_t)u * s.cap + ap.position) * s.M + c] = (uint8_t)(A.abest[c] & 0xffu);
+}
+
+// Draws this workgroup's ticket of unit u; true for the workgroup that draws the last of `total`.  Every thread's
+// stores are made visible to the device before the ticket is drawn, and the last workgroup sees all of them.
+__device__ __forceinline__ bool last_of_unit(const Workspace& ws, int u, int total, int* ticket_sm) {
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) *ticket_sm = (int)atomicAdd(&ws.ticket[u], 1u);
+  __syncthreads();
+  const bool last = *ticket_sm == total - 1;
+  if (last) __threadfence();
+  return last;
+}
+
+// ---------------------------------------------------- 3. select (+ attention)
 // One workgroup owns tokens [blockIdx.x*tokC, +tokC) of its unit; its 4 waves each own
 // a contiguous quarter.  The histogram kernel left every token's bin behind, so a token
 // is classified by comparing that number with the threshold bin.  Per wave, lanes hold
@@ -316,25 +791,92 @@ constexpr int kMaxVecC = 4;  // 8-token groups per lane (tokC <= 8192)
 
 // PAIRS (M = 2 only): there is no histogram kernel in front; the threshold comes from the
 // code-pair counts (pair_threshold) and tokens are classified by their exact score keys.
+//
+// Grid (nblkC [+ 1], units): workgroup nblkC of a unit, present when a token is appended, computes
+// that token's code.  The last workgroup of a unit to finish completes the unit (finalize_unit);
+// the LDS of that step overlays the LDS of the selection, which is dead by then.
+template <typename T, int G, bool ATTN, bool PAIRS>
+struct SelectLds {
+  static constexpr int NW = 4;
+  static constexpr bool kMfma = ATTN && sizeof(T) == 2;
+  std::conditional_t<PAIRS, PairLds, int> pl;
+  int scan_sm[2 * NW + 1 + 4];
+  int wcnt[2 * NW];
+  float red[ATTN ? NW * G * (kD + 2) : 1];
+  float qlds[ATTN ? G * kD : 1];
+  __attribute__((aligned(16))) unsigned char vtile[kMfma ? NW * kVTileBytes : 16];
+};
+template <class A, class B, class C>
+constexpr size_t max_size() {
+  return sizeof(A) > sizeof(B) ? (sizeof(A) > sizeof(C) ? sizeof(A) : sizeof(C)) : (sizeof(B) > sizeof(C) ? sizeof(B) : sizeof(C));
+}
+
+// All arguments of the select kernel in one block, so that the step that completes a unit can read them again
+// from the kernel-argument segment when it runs (late_kernel_args) instead of holding them in registers throughout.
+struct SelectArgs {
+  Shape s;
+  Workspace ws;
+  const void* q;            // [B][Hq][kD]
+  const void* kc;           // K cache
+  const void* vc;           // V cache
+  const void* src;          // codes, or the score array of the stand-alone top-k
+  int* out_idx;
+  float* out_attn;
+  AppendArgs ap;
+  const float* cent;            // PAIRS: centroids
+  const unsigned* pair_counts;  // PAIRS: tokens per code pair
+  int uncounted;                // PAIRS: a window token not in the counts yet, or -1
+};
+
+// The kernel's argument block (its only parameter), read where this is called: scalar loads from the
+// kernel-argument segment.  The pointer is made opaque first, so that the loads stay behind this point.
+template <class A>
+__device__ __forceinline__ const A& late_kernel_args() {
+  auto p = (const __attribute__((address_space(4))) A*)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(p));
+  return *(const A*)p;
+}
+
+template <typename T, int G, bool ATTN>
+__device__ __forceinline__ void finish_unit_late(int u, unsigned char* smem) {
+  const SelectArgs& a = late_kernel_args<SelectArgs>();
+  finalize_unit<T, G, ATTN>(a.s, a.ws, u, static_cast<const T*>(a.q), static_cast<const T*>(a.kc), static_cast<const T*>(a.vc),
+                            a.out_idx, a.out_attn, a.ap, *reinterpret_cast<TailLds<G, ATTN>*>(smem));
+}
+
 template <typename T, int G, class SRC, bool ATTN, bool PAIRS = false>
-__global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, const T* __restrict__ q,
-                                                     const T* __restrict__ kc, const T* __restrict__ vc,
-                                                     const void* __restrict__ src_ptr,
-                                                     const float* __restrict__ cent = nullptr,
-                                                     const unsigned* __restrict__ pair_counts = nullptr,
-                                                     int uncounted = -1 /* PAIRS: a window token not in the counts yet */) {
+__global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
+  const Shape& s = args.s;
+  const Workspace& ws = args.ws;
+  const T* __restrict__ q = static_cast<const T*>(args.q);
+  const T* __restrict__ kc = static_cast<const T*>(args.kc);
+  const T* __restrict__ vc = static_cast<const T*>(args.vc);
+  const void* __restrict__ src_ptr = args.src;
+  const float* __restrict__ cent = args.cent;
+  const unsigned* __restrict__ pair_counts = args.pair_counts;
+  const int uncounted = args.uncounted;
   constexpr int NT = 256, NW = 4;
   constexpr bool kMfma = ATTN && sizeof(T) == 2;
   static_assert(!PAIRS || (SRC::kFromCodes && SRC::M == 2), "pair counts exist for two partitions only");
+  using SelLds = SelectLds<T, G, ATTN, PAIRS>;
+  using EndLds = TailLds<G, ATTN>;
   extern __shared__ unsigned short list[];  // [tokC] token offsets from the workgroup's first token
-  __shared__ std::conditional_t<PAIRS, PairLds, int> pl;
-  __shared__ int scan_sm[2 * NW + 1 + 4];
-  __shared__ int wcnt[2 * NW];
-  __shared__ float red[ATTN ? NW * G * (kD + 2) : 1];
-  __shared__ float qlds[ATTN ? G * kD : 1];
-  __shared__ __attribute__((aligned(16))) unsigned char vtile[kMfma ? NW * kVTileBytes : 16];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[max_size<SelLds, EndLds, AppendLds>()];
+  __shared__ int ticket_sm;
+  SelLds& S = *reinterpret_cast<SelLds*>(smem);
+  auto& pl = S.pl;
+  int* scan_sm = S.scan_sm;
+  int* wcnt = S.wcnt;
+  float* red = S.red;
+  float* qlds = S.qlds;
+  unsigned char* vtile = S.vtile;
   const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = u / s.Hkv, g = u % s.Hkv;
+  if ((int)blockIdx.x == s.nblkC) {  // the appended token's code; nothing in the step reads it
+    append_token<T>(s, args.ap, u, *reinterpret_cast<AppendLds*>(smem));
+    if (last_of_unit(ws, u, s.nblkC + 1, &ticket_sm)) finish_unit_late<T, G, ATTN>(u, smem);
+    return;
+  }
   PQC_MARK(ws, 1, 0);
   // this wave's stored bins, the query and the histogram: all requested up front
   const int tpw = s.tokC / NW;           // tokens per wave, in groups of 8 per lane
@@ -443,6 +985,11 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
   // attention below, which hides the round trip of the returning atomic
   int rec_base;  // set and read by thread 0 only; no initialiser, or the merge with it would wait for the atomic here
   if (tid == 0 && tot_cand > 0) rec_base = (int)atomicAdd(&ws.cand_count[u], (unsigned)tot_cand);
+  // put away (in LDS) once the attention's first loads are back, which arrive after it: no wait, and no register
+  // held through the attention
+  auto put_rec_base = [&]() {
+    if (tid == 0 && tot_cand > 0) scan_sm[0] = rec_base;  // scan_sm is idle since the threshold search
+  };
   // A candidate's exact score comes from its codes and the unit's table (same evaluation order
   // as everywhere), or from the score array of the stand-alone top-k.
   struct CandKey {
@@ -488,7 +1035,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
     return wg_t0 + list[i * segN + (p - csel[i])];
   };
 
-  // selected list for the finalize kernel's index output
+  // selected list for the index output
   unsigned long long* stage = ws.stage + ((size_t)u * s.nblkC + blockIdx.x) * s.stageStride;
   int* stage32 = reinterpret_cast<int*>(stage);
   PQC_MARK(ws, 1, 3);
@@ -535,7 +1082,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
       MfmaState st;
       st.init();
       mfma_attend(reinterpret_cast<const bf16_t*>(kbase), reinterpret_cast<const bf16_t*>(vbase), s.N, att_at, n_att,
-                  w * 16 * kMfmaTiles, NW * 16 * kMfmaTiles, s.scale_log2e, qf, vtile + w * kVTileBytes, st);
+                  w * 16 * kMfmaTiles, NW * 16 * kMfmaTiles, s.scale_log2e, qf, vtile + w * kVTileBytes, st, put_rec_base);
       PQC_MARK(ws, 1, 4);
       mfma_stash_wave_state<G>(st, red);
     } else {
@@ -545,6 +1092,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
       st.init();
       constexpr int R = (G >= 8 || sizeof(T) == 4) ? 2 : 4;
       attend_rows<T, G, R>(kbase, vbase, s.N, att_at, n_att, w * 4 * R, NW * 4 * R, qr, st);
+      put_rec_base();
       PQC_MARK(ws, 1, 4);
       stash_wave_state<T, G>(st, red);
     }
@@ -561,6 +1109,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
       }
     }
   }
+  if constexpr (!ATTN) put_rec_base();
   // (written after the attention: stores issued while the K/V loads of the co-resident workgroup
   // fill the memory pipeline would only delay this workgroup's own first loads)
   for (int p = tid; p < tot_sel; p += NT) stage32[p] = sel_at(p);
@@ -571,8 +1120,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
 
   // candidates (few): composite for the generic path, and a full record while slots last
   if (tot_cand > 0) {  // workgroup-uniform
-    if (tid == 0) scan_sm[0] = rec_base;
-    __syncthreads();
+    __syncthreads();  // rec_base was put away by thread 0 (put_rec_base)
     const int base = scan_sm[0];
     for (int c = grp; c < tot_cand; c += NT / 16) {
       int t = c0_t;
@@ -608,22 +1156,15 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
       }
     }
   }
+  PQC_MARK(ws, 1, 6);
+  // the unit's last workgroup to get here completes the unit
+  {
+    const SelectArgs& late = late_kernel_args<SelectArgs>();
+    if (last_of_unit(late.ws, u, late.s.nblkC + (late.ap.key ? 1 : 0), &ticket_sm)) finish_unit_late<T, G, ATTN>(u, smem);
+  }
 }
 
-// ------------------------------------------------------------- 3. finalize
-// Grid (heads + kCopyWgs, units), 256 threads; heads = the group's query heads (1 for
-// the stand-alone top-k).
-//   blockIdx.x <  heads  ranks the candidates and folds the admitted ones and all partial
-//                        softmax states into this head's output; head 0 also writes the
-//                        admitted candidates' indices (best first)
-//   blockIdx.x >= heads  copy workgroups: concatenate the staged lists into out_idx; the
-//                        first one also zeroes the unit's histogram and record counter
-// The staged "selected" lists already hold the two windows: in workgroup order they read
-//   [0..I) , tokens above the threshold bin (ascending) , [N-L..N).
-// Fast path (at most kCandRec candidates): all a head needs is in the candidate records,
-// which sit densely in order of arrival.  That order differs from run to run, so every
-// sum over candidates is taken in rank order.  Generic path: candidates are the
-// composites staged per select workgroup; admitted rows are gathered from the K/V cache.
+// ------------------------------------------------------------ block reductions
 template <int NT>
 __device__ __forceinline__ float block_max(float v, float* sm /* [NT/64] */) {
   v = wave_max(v);
@@ -645,464 +1186,6 @@ __device__ __forceinline__ float block_sum(float v, float* sm /* [NT/64] */) {
   for (int i = 1; i < NT / 64; ++i) r += sm[i];
   __syncthreads();
   return r;
-}
-
-constexpr int kHdrPerThread = kCandRec / 256;  // candidate record headers per thread
-constexpr int kAccBatch = 32;                  // partial accumulators a thread keeps in flight at once
-constexpr int kVPass = 4;                      // dependent V-row passes in flight (16 rows each), many-candidate case
-constexpr int kIdxLists = 4;                   // staged index lists a wave copies with loads issued up front
-constexpr int kCopyWgs = 4;                    // copy workgroups per unit
-constexpr int kRankChunk = 64;                 // admitted rows summed per pass through LDS
-
-// The code of one appended token per unit (Section 3.1: nearest centroid of each partition): nothing in the
-// step depends on it, so one more workgroup per unit of the finalize kernel computes it beside the others.
-struct AppendArgs {
-  const void* key;    // [units][kD] in the cache's element type, or null: nothing to append
-  const float* cent;  // [units][M][C][Dm]
-  uint8_t* codes;     // the code tensor; written at `position` of every unit
-  int position;
-  unsigned* pair_counts;  // two partitions: [units][C*C] counts that gain the token's code pair, or null
-};
-
-template <typename T, int G, bool ATTN>
-__global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, const T* __restrict__ q,
-                                                       const T* __restrict__ kc, const T* __restrict__ vc,
-                                                       int* __restrict__ out_idx, float* __restrict__ out_attn, AppendArgs ap) {
-  constexpr int NT = 256, NW = 4;
-  constexpr int heads = ATTN ? G : 1;
-  if (blockIdx.x == heads + kCopyWgs) {
-    // -------------------------------------------------------------- append workgroup
-    // one thread per centroid, the distance chain of pq_assign_kernel, the smallest (distance, centroid) pair
-    // of each partition through a 64-bit LDS minimum
-    __shared__ float ax[kD];
-    __shared__ unsigned long long abest[8];
-    const int u = blockIdx.y, c = threadIdx.x;
-    if (c < kD) ax[c] = load_as_float<T>(static_cast<const T*>(ap.key), (size_t)u * kD + c);
-    if (c < 8) abest[c] = ~0ull;
-    __syncthreads();
-    if (c < s.C) {
-      for (int j = 0; j < s.M; ++j) {
-        const float* cr = ap.cent + (((size_t)u * s.M + j) * s.C + c) * s.Dm;
-        const float* xj = ax + j * s.Dm;
-        float d2 = 0.0f;
-        for (int e = 0; e < s.Dm; e += 4) {  // Dm is a multiple of 4
-          const float4 cv = *reinterpret_cast<const float4*>(cr + e);
-          float df = xj[e] - cv.x;
-          d2 = fmaf(df, df, d2);
-          df = xj[e + 1] - cv.y;
-          d2 = fmaf(df, df, d2);
-          df = xj[e + 2] - cv.z;
-          d2 = fmaf(df, df, d2);
-          df = xj[e + 3] - cv.w;
-          d2 = fmaf(df, df, d2);
-        }
-        atomicMin(&abest[j], ((unsigned long long)__float_as_uint(d2) << 32) | (unsigned)c);  // d2 >= 0: bits order like values
-      }
-    }
-    __syncthreads();
-    if (c < s.M) ap.codes[((size_t)u * s.cap + ap.position) * s.M + c] = (uint8_t)(abest[c] & 0xffu);
-    if (c == 0 && ap.pair_counts) ap.pair_counts[(size_t)u * s.C * s.C + (abest[0] & 0xffu) + s.C * (abest[1] & 0xffu)] += 1u;
-    return;
-  }
-  constexpr int SP = ATTN ? (sizeof(T) == 2 ? 8 : 4) : 1;  // passes of 16 record V rows requested up front
-  extern __shared__ int dyn[];  // pre_sel[nblkC+1], pre_cand[nblkC+1], pm[nblkC], pl[nblkC]
-  __shared__ int scan_sm[2 * NW + 1];
-  __shared__ float fsm[NW];
-  __shared__ int ism[2 * NW];
-  __shared__ unsigned long long comp[kCandRec];  // candidate composites, in record order
-  __shared__ float lgk[kCandRec];                // by rank: logit, then softmax weight of the admitted ones
-  __shared__ unsigned short ordv[kCandRec];      // by rank: record
-  __shared__ unsigned short rankv[kCandRec];     // by record: rank if admitted, 0xffff otherwise
-  __shared__ unsigned rhist[256];
-  __shared__ int digit_sm[2];
-  __shared__ int rows_sm[NT];
-  __shared__ float red[ATTN ? NW * (kD + 2) : 1];
-  __shared__ float half_acc[ATTN ? kD : 1];
-  __shared__ float vl[ATTN ? kRankChunk * kD : 1];
-  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int b = u / s.Hkv, g = u % s.Hkv;
-  int* pre_sel = dyn;
-  int* pre_cand = dyn + (s.nblkC + 1);
-  float* pm = reinterpret_cast<float*>(dyn + 2 * (s.nblkC + 1));
-  float* pl = pm + s.nblkC;
-  const int2* cnt = ws.stage_cnt + (size_t)u * s.nblkC;
-  const unsigned long long* stage_u = ws.stage + (size_t)u * s.nblkC * s.stageStride;
-  int* out = out_idx + (size_t)u * s.Ktot;
-  PQC_MARK(ws, 2, 0);
-
-  // exclusive prefix sums of the per-workgroup list sizes (into LDS); returns the totals
-  auto scan_counts = [&](const int2 cnt0, int& n_list, int& n_cand) {
-    int carry_s = 0, carry_c = 0;
-    for (int j0 = 0; j0 < s.nblkC; j0 += NT) {
-      const int j = j0 + tid;
-      const int2 c = j < s.nblkC ? (j0 == 0 ? cnt0 : cnt[j]) : make_int2(0, 0);
-      int ts, tc;
-      const int ps = block_exclusive_scan<NT>(c.x, &ts, scan_sm);
-      const int pc = block_exclusive_scan<NT>(c.y, &tc, scan_sm);
-      if (j < s.nblkC) {
-        pre_sel[j] = carry_s + ps;
-        pre_cand[j] = carry_c + pc;
-      }
-      carry_s += ts;
-      carry_c += tc;
-    }
-    if (tid == 0) {
-      pre_sel[s.nblkC] = carry_s;
-      pre_cand[s.nblkC] = carry_c;
-    }
-    __syncthreads();
-    n_list = carry_s;
-    n_cand = carry_c;
-  };
-
-  if (blockIdx.x >= heads) {
-    // ---------------------------------------------------------------- copy workgroup
-    // one wave per list, coalesced; the local window moves behind the admitted candidates
-    const int cw = blockIdx.x - heads, ncw = kCopyWgs;
-    const int2 cnt0 = cnt[min(tid, s.nblkC - 1)];
-    int ix[kIdxLists][4];  // first 256 entries of this wave's first kIdxLists lists
-#pragma unroll
-    for (int x = 0; x < kIdxLists; ++x) {
-      const int j = min(cw * NW + w + x * ncw * NW, s.nblkC - 1);
-      const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.stageStride);
-#pragma unroll
-      for (int y = 0; y < 4; ++y) ix[x][y] = src[min(y * 64 + lane, 2 * s.tokC - 1)];
-    }
-    PQC_LOADS_ISSUED();
-    int n_list, n_cand;
-    scan_counts(cnt0, n_list, n_cand);
-    const int n_above = max(0, n_list - s.I - s.L);
-    const int need = max(0, min(s.K - n_above, n_cand));
-    PQC_MARK(ws, 2, 1);
-    int x = 0;
-    for (int j = cw * NW + w; j < s.nblkC; j += ncw * NW, ++x) {
-      const int base = pre_sel[j], n = pre_sel[j + 1] - base;
-      const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.stageStride);
-      for (int p0 = 0; p0 < n; p0 += 256) {
-        int v[4];
-        if (x < kIdxLists && p0 == 0) {
-#pragma unroll
-          for (int y = 0; y < 4; ++y) v[y] = x == 0 ? ix[0][y] : x == 1 ? ix[1][y] : x == 2 ? ix[2][y] : ix[3][y];
-        } else {
-#pragma unroll
-          for (int y = 0; y < 4; ++y)
-            if (p0 + y * 64 + lane < n) v[y] = src[p0 + y * 64 + lane];
-        }
-#pragma unroll
-        for (int y = 0; y < 4; ++y) {
-          const int pos = base + p0 + y * 64 + lane;
-          if (p0 + y * 64 + lane < n) out[pos < s.I + n_above ? pos : pos + need] = v[y];
-        }
-      }
-    }
-    PQC_MARK(ws, 2, 4);
-    if (cw == 0) {  // the select kernel was their last reader: zero histogram and record counter for the next call
-      unsigned* gh = ws.hist + (size_t)u * s.histCopies * kNB;
-      for (int i = tid; i < s.histCopies * kNB; i += NT) gh[i] = 0u;
-      if (tid == 0) ws.cand_count[u] = 0u;
-    }
-    PQC_MARK(ws, 2, 5);
-    return;
-  }
-
-  // ------------------------------------------------------------------ head workgroup
-  const int hq = blockIdx.x;
-  const int d = tid & (kD - 1), half = tid >> 7;  // output dimension and half of the partials this thread sums
-  const int sub = tid & 15, grp = tid >> 4;       // 16 lanes per candidate V row
-  // ---- everything whose address is known up front is requested first
-  const unsigned char* recs = ws.cand_rec + (size_t)u * kCandRec * ws.rec_stride;
-  unsigned long long rc[kHdrPerThread];  // record x*NT + tid; the first NT are requested up front
-  float rl[kHdrPerThread];
-  {
-    const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)tid * ws.rec_stride);
-    rc[0] = hd->composite;
-    rl[0] = ATTN ? hd->logit[hq] : 0.0f;
-  }
-  const float* parts = ws.partials + (size_t)u * s.npart * G * (kD + 2);
-  const int jc = min(tid, s.nblkC - 1);
-  const int2 cnt0 = cnt[jc];  // list sizes of the first NT select workgroups
-  float pm0 = 0.0f, pl0 = 0.0f;
-  float a0[kAccBatch];  // first batch of this thread's partial accumulators: lists half, half+2, ...
-  RowRaw<T> vspec[SP];  // V rows of the first 16*sp records
-  // with many head workgroups in flight the unused part of this guess is real traffic: guess less
-  const int sp = (int)gridDim.y * heads <= 64 ? SP : SP / 2;
-  if constexpr (ATTN) {
-    pm0 = parts[((size_t)jc * G + hq) * (kD + 2)];
-    pl0 = parts[((size_t)jc * G + hq) * (kD + 2) + 1];
-    const float* a0p = parts + ((size_t)half * G + hq) * (kD + 2) + 2 + d;
-#pragma unroll
-    for (int x = 0; x < kAccBatch; ++x)  // lists that do not exist re-read the first one (a cache hit, no extra traffic)
-      a0[x] = a0p[half + 2 * x < s.nblkC ? (size_t)x * (2 * G * (kD + 2)) : (size_t)0];
-#pragma unroll
-    for (int x = 0; x < SP; ++x)
-      if (x < sp) vspec[x].load_row(recs + (size_t)(x * 16 + grp) * ws.rec_stride + sizeof(CandHeader), sub);
-  }
-  PQC_LOADS_ISSUED();
-  if constexpr (ATTN) {
-    if (tid < s.nblkC) {
-      pm[tid] = pm0;
-      pl[tid] = pl0;
-    }
-    for (int j = NT + tid; j < s.nblkC; j += NT) {  // beyond the first NT lists (very long contexts)
-      pm[j] = parts[((size_t)j * G + hq) * (kD + 2)];
-      pl[j] = parts[((size_t)j * G + hq) * (kD + 2) + 1];
-    }
-  }
-  // totals of the per-workgroup list sizes
-  int n_list, n_cand;
-  {
-    int ss = tid < s.nblkC ? cnt0.x : 0, sc = tid < s.nblkC ? cnt0.y : 0;
-    for (int j = NT + tid; j < s.nblkC; j += NT) {
-      const int2 c = cnt[j];
-      ss += c.x;
-      sc += c.y;
-    }
-    ss = wave_sum(ss);
-    sc = wave_sum(sc);
-    if (lane == 0) {
-      ism[w] = ss;
-      ism[NW + w] = sc;
-    }
-    __syncthreads();  // also: pm, pl visible
-    n_list = 0;
-    n_cand = 0;
-#pragma unroll
-    for (int i = 0; i < NW; ++i) {
-      n_list += ism[i];
-      n_cand += ism[NW + i];
-    }
-  }
-  const int n_above = max(0, n_list - s.I - s.L);  // n_list = I + (tokens above the bin) + L
-  const int need = max(0, min(s.K - n_above, n_cand));
-  PQC_MARK(ws, 2, 1);
-
-  if (n_cand <= kCandRec) {
-    // rank every candidate (count of larger composites); the admitted ones are the `need` best
-    if (need > 0) {
-#pragma unroll
-      for (int x = 1; x < kHdrPerThread; ++x) {
-        rc[x] = 0ull;
-        rl[x] = 0.0f;
-        if (x * NT + tid < n_cand) {  // rare: more than NT candidates
-          const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)(x * NT + tid) * ws.rec_stride);
-          rc[x] = hd->composite;
-          rl[x] = ATTN ? hd->logit[hq] : 0.0f;
-        }
-      }
-#pragma unroll
-      for (int x = 0; x < kHdrPerThread; ++x)
-        if (x * NT + tid < n_cand) comp[x * NT + tid] = rc[x];
-      __syncthreads();
-#pragma unroll
-      for (int x = 0; x < kHdrPerThread; ++x) {
-        const int k = x * NT + tid;
-        if (k < n_cand) {
-          const unsigned long long mine = rc[x];
-          int rank = 0;
-          for (int j = 0; j < n_cand; ++j) rank += comp[j] > mine ? 1 : 0;
-          if (rank < need) {
-            if (hq == 0) out[s.I + n_above + rank] = composite_token(mine);  // best first
-            lgk[rank] = rl[x] * s.scale_log2e;
-            ordv[rank] = (unsigned short)k;
-            rankv[k] = (unsigned short)rank;
-          } else {
-            rankv[k] = 0xffffu;
-          }
-        }
-      }
-      __syncthreads();
-    }
-    if constexpr (ATTN) {
-      float mx = kNegBig;
-      for (int k = tid; k < need; k += NT) mx = fmaxf(mx, lgk[k]);
-      for (int j = tid; j < s.nblkC; j += NT) mx = fmaxf(mx, pm[j]);
-      const float mstar = block_max<NT>(mx, fsm);
-      float lsum = 0.0f;
-      for (int k = tid; k < need; k += NT) {
-        const float p = __builtin_amdgcn_exp2f(lgk[k] - mstar);
-        lgk[k] = p;
-        lsum += p;
-      }
-      for (int j = tid; j < s.nblkC; j += NT) {
-        const float wj = __builtin_amdgcn_exp2f(pm[j] - mstar);
-        pm[j] = wj;
-        lsum = fmaf(wj, pl[j], lsum);
-      }
-      const float lstar = block_sum<NT>(lsum, fsm);  // its barriers make lgk and pm visible
-      PQC_MARK(ws, 2, 2);
-      // out[d] = (sum_j w_j acc_j[d] + sum_k p_k V_k[d]) / l ; two threads per dimension
-      float acc = 0.0f;
-      {
-        float wv[kAccBatch];
-#pragma unroll
-        for (int x = 0; x < kAccBatch; ++x) wv[x] = pm[min(half + 2 * x, s.nblkC - 1)];
-#pragma unroll
-        for (int x = 0; x < kAccBatch; ++x) acc = fmaf(wv[x], half + 2 * x < s.nblkC ? a0[x] : 0.0f, acc);
-      }
-      for (int j0 = half + 2 * kAccBatch; j0 < s.nblkC; j0 += 2 * kAccBatch) {
-        float a[kAccBatch];
-#pragma unroll
-        for (int x = 0; x < kAccBatch; ++x) {
-          const int j = j0 + 2 * x;
-          a[x] = j < s.nblkC ? parts[((size_t)j * G + hq) * (kD + 2) + 2 + d] : 0.0f;
-        }
-#pragma unroll
-        for (int x = 0; x < kAccBatch; ++x) {
-          const int j = j0 + 2 * x;
-          if (j < s.nblkC) acc = fmaf(pm[j], a[x], acc);
-        }
-      }
-      if (need > 0 && n_cand <= 16 * sp) {
-        // the V rows are already here: weighted rows go to LDS at their rank, then are summed in rank order
-        for (int r0 = 0; r0 < need; r0 += kRankChunk) {
-          const int nr = min(kRankChunk, need - r0);
-#pragma unroll
-          for (int x = 0; x < SP; ++x) {
-            const int k = x * 16 + grp;
-            const int r = (k < n_cand ? (int)rankv[k] : 0xffff) - r0;
-            if (r >= 0 && r < nr) {
-              const float p = lgk[r0 + r];
-              float vf[8];
-              vspec[x].unpack(vf);
-#pragma unroll
-              for (int e = 0; e < 8; ++e) vl[r * kD + owned_dim<T>(sub, e)] = p * vf[e];
-            }
-          }
-          __syncthreads();
-          for (int r = half; r < nr; r += 2) acc += vl[r * kD + d];
-          __syncthreads();
-        }
-      } else if (need > 0) {
-        // many candidates: admitted rows are fetched in rank order, 16 rows at a time per pass
-        float va[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) va[e] = 0.0f;
-        for (int k0 = 0; k0 < need; k0 += 16 * kVPass) {
-          RowRaw<T> vr[kVPass];
-#pragma unroll
-          for (int x = 0; x < kVPass; ++x) {
-            const int k = min(k0 + x * 16 + grp, need - 1);
-            vr[x].load_row(recs + (size_t)ordv[k] * ws.rec_stride + sizeof(CandHeader), sub);
-          }
-          PQC_LOADS_ISSUED();
-#pragma unroll
-          for (int x = 0; x < kVPass; ++x) {
-            const int k = k0 + x * 16 + grp;
-            const float p = k < need ? lgk[k] : 0.0f;
-            float vf[8];
-            vr[x].unpack(vf);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) va[e] = fmaf(p, vf[e], va[e]);
-          }
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) vl[grp * kD + owned_dim<T>(sub, e)] = va[e];
-        __syncthreads();
-#pragma unroll
-        for (int x = 0; x < 8; ++x) acc += vl[(half * 8 + x) * kD + d];
-      }
-      if (half == 1) half_acc[d] = acc;
-      __syncthreads();
-      if (half == 0) out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + d] = (acc + half_acc[d]) / lstar;
-      PQC_MARK(ws, 2, 3);
-    }
-  } else {
-    // generic path: radix select of the need-th largest staged composite, 8 bits per pass
-    {
-      int nl, nc;
-      scan_counts(cnt0, nl, nc);
-    }
-    auto owner = [&](int p) -> int {  // largest j with pre_cand[j] <= p
-      int lo = 0, hi = s.nblkC - 1;
-      while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (pre_cand[mid] <= p) lo = mid; else hi = mid - 1;
-      }
-      return lo;
-    };
-    auto cand_at = [&](int i) -> unsigned long long {
-      const int j = owner(i);
-      return stage_u[(size_t)j * s.stageStride + s.tokC - 1 - (i - pre_cand[j])];
-    };
-    unsigned long long thr = ~0ull;
-    if (need > 0) {
-      unsigned long long prefix = 0;
-      int want = need;
-      for (int shift = 56; shift >= 0; shift -= 8) {
-        rhist[tid] = 0u;
-        __syncthreads();
-        for (int i = tid; i < n_cand; i += NT) {
-          const unsigned long long c = cand_at(i);
-          if (shift == 56 || (c >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&rhist[(unsigned)(c >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        if (tid == 0) {
-          int cum = 0, dg = 255;
-          for (; dg > 0; --dg) {
-            if (cum + (int)rhist[dg] >= want) break;
-            cum += (int)rhist[dg];
-          }
-          digit_sm[0] = dg;
-          digit_sm[1] = want - cum;
-        }
-        __syncthreads();
-        prefix |= (unsigned long long)digit_sm[0] << shift;
-        want = digit_sm[1];
-        __syncthreads();
-      }
-      thr = prefix;
-    }
-    // admitted candidates in token order, NT candidates per round: indices out, rows attended
-    AttnState<1> st;
-    st.init();
-    float qr[1][8];
-    if constexpr (ATTN) load_query<T, 1>(q + ((size_t)b * s.Hq + (size_t)g * G + hq) * kD, s.scale_log2e, qr);
-    int carry = 0;
-    for (int i0 = 0; i0 < (need > 0 ? n_cand : 0); i0 += NT) {
-      const int i = i0 + tid;
-      unsigned long long c = 0;
-      if (i < n_cand) c = cand_at(i);
-      const int flag = (i < n_cand && c >= thr) ? 1 : 0;
-      int tot;
-      const int pos = block_exclusive_scan<NT>(flag, &tot, scan_sm);
-      if (flag) {
-        rows_sm[pos] = composite_token(c);
-        if (hq == 0) out[s.I + n_above + carry + pos] = composite_token(c);
-      }
-      __syncthreads();
-      if constexpr (ATTN) {
-        auto row_at = [&](int p) -> int { return rows_sm[p]; };
-        attend_rows<T, 1, 4>(kc + (size_t)u * s.cap * kD, vc + (size_t)u * s.cap * kD, s.N, row_at, tot, w * 16, NW * 16, qr, st);
-      }
-      __syncthreads();
-      carry += tot;
-    }
-    if constexpr (ATTN) {
-      stash_wave_state<T, 1>(st, red);
-      __syncthreads();
-      float m_own, l_own, acc;
-      combine_waves<1, NW>(red, 0, d, m_own, l_own, acc);
-      float mx = m_own;
-      for (int j = tid; j < s.nblkC; j += NT) mx = fmaxf(mx, pm[j]);
-      const float mstar = block_max<NT>(mx, fsm);
-      float lsum = 0.0f;
-      for (int j = tid; j < s.nblkC; j += NT) {
-        const float wj = __builtin_amdgcn_exp2f(pm[j] - mstar);
-        pm[j] = wj;
-        lsum = fmaf(wj, pl[j], lsum);
-      }
-      const float f_own = __builtin_amdgcn_exp2f(m_own - mstar);
-      const float lstar = block_sum<NT>(lsum, fsm) + l_own * f_own;
-      acc = half == 0 ? acc * f_own : 0.0f;
-      for (int j = half; j < s.nblkC; j += 2) acc = fmaf(pm[j], parts[((size_t)j * G + hq) * (kD + 2) + 2 + d], acc);
-      if (half == 1) half_acc[d] = acc;
-      __syncthreads();
-      if (half == 0) out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + d] = (acc + half_acc[d]) / lstar;
-    }
-  }
-  PQC_NOTE(ws, 2, 13, n_above);
-  PQC_NOTE(ws, 2, 14, n_cand);
-  PQC_NOTE(ws, 2, 15, need);
 }
 
 // ---------------------------------------------- stand-alone attention over a list
@@ -1133,7 +1216,7 @@ __global__ __launch_bounds__(256) void attn_list_kernel(Shape s, Workspace ws, c
     MfmaState st;
     st.init();
     mfma_attend(reinterpret_cast<const bf16_t*>(kbase), reinterpret_cast<const bf16_t*>(vbase), s.N, row_at, count,
-                w * 16 * kMfmaTiles, NW * 16 * kMfmaTiles, s.scale_log2e, qf, vtile + w * kVTileBytes, st);
+                w * 16 * kMfmaTiles, NW * 16 * kMfmaTiles, s.scale_log2e, qf, vtile + w * kVTileBytes, st, []() {});
     mfma_stash_wave_state<G>(st, red);
   } else {
     float qr[G][8];
