@@ -21,7 +21,8 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
   Shape s;
-  size_t off_ctl, off_lut, off_range, off_hist, off_bins, off_crec, off_stage, off_cnt, off_part, off_trace, total;
+  size_t off_ctl, off_lut, off_range, off_hist, off_bins, off_crec, off_stage, off_cnt, off_part, off_gpart, off_trace, total;
+  size_t zero_words;  // 32-bit words of the region at off_hist that must be zero when a call starts
   int rec_stride;
 };
 
@@ -40,12 +41,15 @@ void lay_out(Plan* p, size_t bins_per_unit, size_t stage_words_per_unit, size_t 
   p->off_ctl = off;   off = align_up(off + sizeof(BinParams) * units);
   p->off_lut = off;   off = align_up(off + sizeof(float) * units * s.M * s.C);
   p->off_range = off; off = align_up(off + sizeof(float2) * units);
-  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * units * (kHistCopies * kNB + 2));  // + record and ticket counters
+  // histograms, then the counters and published list sizes that are zero between calls like them
+  p->zero_words = units * ((size_t)kHistCopies * kNB + 2 + kMaxGroups + 2 * counts_per_unit);
+  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * p->zero_words);
   p->off_bins = off;  off = align_up(off + sizeof(unsigned short) * units * bins_per_unit);
   p->off_crec = off;  off = align_up(off + (size_t)p->rec_stride * kCandRec * units);
   p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * stage_words_per_unit);
   p->off_cnt = off;   off = align_up(off + sizeof(int2) * units * counts_per_unit);
   p->off_part = off;  off = align_up(off + sizeof(float) * units * partials_per_unit * s.G * (kD + 2));
+  p->off_gpart = off; off = align_up(off + sizeof(float) * units * kMaxGroups * s.G * (kD + 2));
 #ifdef PQC_TRACE
   p->off_trace = off; off = align_up(off + sizeof(unsigned long long) * 3 * kTraceWgs * kTraceSlots);
 #endif
@@ -107,6 +111,10 @@ int make_plan(const pqc_config* c, Plan* p) {
   s.rowsP = env_int("PQC_ROWS_P", 256);
   s.nblkP = (s.Ktot + s.rowsP - 1) / s.rowsP;
   s.npart = s.nblkC > s.nblkP ? s.nblkC : s.nblkP;
+  // the states of grpC consecutive select workgroups are folded into one before the unit's last workgroup reads them
+  s.grpC = G >= 8 ? 4 : 8;
+  s.ngrp = (s.nblkC + s.grpC - 1) / s.grpC;
+  if (s.ngrp <= 1) s.grpC = s.ngrp = 0;
   p->rec_stride = (int)sizeof(CandHeader) + kD * (c->kv_dtype == PQC_F32 ? 4 : 2);
   // sample ranks that bracket the K-th largest score by 5 standard errors (+2)
   const int nmid = s.N - s.I - s.L;
@@ -181,8 +189,7 @@ int ensure_clean_hist(pqc_ctx* ctx, hipStream_t st) {
     ctx->next_phase = 0;
   }
   if (ctx->hist_clean) return PQC_OK;
-  const Shape& s = ctx->plan.s;
-  const size_t na = (size_t)s.B * s.Hkv * (kHistCopies * kNB + 2);  // histograms and the record and ticket counters behind them
+  const size_t na = ctx->plan.zero_words;  // histograms and the counters behind them
   hipLaunchKernelGGL(reset_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, st, ctx->ws.hist, na);
   return check_launch(ctx);
 }
@@ -331,6 +338,9 @@ void bind_workspace(pqc_ctx* ctx) {
   ctx->ws.hist = reinterpret_cast<unsigned*>(base + p.off_hist);
   ctx->ws.cand_count = ctx->ws.hist + (size_t)p.s.B * p.s.Hkv * kHistCopies * kNB;
   ctx->ws.ticket = ctx->ws.cand_count + (size_t)p.s.B * p.s.Hkv;
+  ctx->ws.gticket = ctx->ws.ticket + (size_t)p.s.B * p.s.Hkv;
+  ctx->ws.pub = reinterpret_cast<unsigned long long*>(ctx->ws.gticket + (size_t)p.s.B * p.s.Hkv * kMaxGroups);
+  ctx->ws.gparts = reinterpret_cast<float*>(base + p.off_gpart);
   ctx->ws.range = reinterpret_cast<float2*>(base + p.off_range);
   ctx->ws.bins = reinterpret_cast<unsigned short*>(base + p.off_bins);
   ctx->ws.cand_rec = reinterpret_cast<unsigned char*>(base + p.off_crec);

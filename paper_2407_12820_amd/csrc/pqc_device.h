@@ -34,6 +34,7 @@ struct Shape {
   int tokA, nblkA;  // histogram kernel: tokens per workgroup, workgroups per unit
   int tokC, nblkC;  // select kernel: tokens per workgroup, workgroups per unit
   int rowsP, nblkP; // list-attention kernel: rows per workgroup, workgroups per unit
+  int grpC, ngrp;   // select workgroups per group whose states are folded first, and groups per unit (0, 0: no such level)
   int npart;        // partial slots per unit
   int binStride;    // stored bins per unit (nblkC * tokC)
   int stageStride;  // 8-byte words between the staging slots of consecutive select workgroups: tokC plus a pad, so that
@@ -60,7 +61,10 @@ struct Workspace {
   float2* range;               // [units]                       (min, max) score, stand-alone top-k only
   unsigned* hist;              // [units][histCopies][kNB]   zero between uses (room for kHistCopies replicas)
   unsigned* cand_count;        // [units]   records handed out so far (directly behind hist, zeroed with it)
-  unsigned* ticket;            // [units]   select workgroups of the unit that have finished (behind cand_count, zeroed with it)
+  unsigned* ticket;            // [units]   groups (or select workgroups) of the unit that have finished (zeroed with hist)
+  unsigned* gticket;           // [units][kMaxGroups]   select workgroups of the group that have finished (likewise)
+  unsigned long long* pub;     // [units][nblkC]   per select workgroup (candidates << 32) | (list size + 1), 0: not known yet (likewise)
+  float* gparts;               // [units][kMaxGroups][G][kD+2]   the groups' folded softmax states
   unsigned short* bins;        // [units][binStride]  per token: bin + 1, or kBinWindow inside the two windows
   unsigned char* cand_rec;     // [units][kCandRec] records of rec_stride bytes, in order of arrival
   unsigned long long* stage;   // [units][nblkC][stageStride]: selected ids (front, int32) / candidate composites (ending at word tokC)
@@ -103,6 +107,19 @@ constexpr int kTraceWgs = 4096, kTraceSlots = 16;
 // (left alone it tends to interleave load and use to save registers, which turns one
 // memory round trip into many).
 #define PQC_LOADS_ISSUED() __builtin_amdgcn_sched_barrier(0)
+
+// Stores whose values another workgroup of the same launch reads: written through to device memory (agent scope),
+// because the L2 caches of the chip's XCDs are not coherent with each other for ordinary stores, and writing a
+// whole L2 back from every workgroup instead (a release fence) takes far longer than the kernel itself.
+template <class V>
+__device__ __forceinline__ void store_through(V* p, V v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_through16(void* p, const uint4& v) {
+  unsigned long long* q = static_cast<unsigned long long*>(p);
+  store_through(q, ((unsigned long long)v.y << 32) | v.x);
+  store_through(q + 1, ((unsigned long long)v.w << 32) | v.z);
+}
 
 // ---------------------------------------------------------------- small helpers
 __device__ __forceinline__ unsigned score_key(float f) {
@@ -856,6 +873,7 @@ struct RowRaw<bf16_t> {
     f[7] = __uint_as_float(a.w & 0xffff0000u);
   }
   __device__ __forceinline__ void store(unsigned char* dst, int sub) const { *reinterpret_cast<uint4*>(dst + sub * 16) = a; }
+  __device__ __forceinline__ void store_through(unsigned char* dst, int sub) const { store_through16(dst + sub * 16, a); }
 };
 template <>
 struct RowRaw<float> {
@@ -879,6 +897,10 @@ struct RowRaw<float> {
   __device__ __forceinline__ void store(unsigned char* dst, int sub) const {
     *reinterpret_cast<float4*>(dst + sub * 16) = a;
     *reinterpret_cast<float4*>(dst + 256 + sub * 16) = b;
+  }
+  __device__ __forceinline__ void store_through(unsigned char* dst, int sub) const {
+    store_through16(dst + sub * 16, make_uint4(__float_as_uint(a.x), __float_as_uint(a.y), __float_as_uint(a.z), __float_as_uint(a.w)));
+    store_through16(dst + 256 + sub * 16, make_uint4(__float_as_uint(b.x), __float_as_uint(b.y), __float_as_uint(b.z), __float_as_uint(b.w)));
   }
 };
 

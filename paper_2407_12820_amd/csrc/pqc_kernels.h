@@ -307,23 +307,31 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
 }
 
 // ------------------------------------------------------ 2. finishing a unit
-// The select workgroups of a unit each leave a partial softmax state per query head, the list of
-// tokens they selected and their boundary-bin candidates behind.  Whichever of them finishes last
-// (a ticket drawn from a per-unit counter with one returning atomic: nobody waits for anybody)
-// completes the unit with finalize_unit():
-//   - ranks the candidates and admits the K - n_above best (at most kCandRec candidates: all that
-//     is needed sits in their records, which arrive in a different order on every run, so every
-//     sum over candidates is taken in rank order; more candidates: an 8-bit radix select over the
-//     composites staged per workgroup, the admitted rows being attended from the K/V cache);
-//   - folds the admitted rows and all partial states (in workgroup order) into out_attn;
-//   - concatenates the staged lists into out_idx; in workgroup order they read
-//       [0..I) , tokens above the threshold bin (ascending) , [N-L..N)
-//     and the admitted candidates go between the second and the third part;
-//   - zeroes the unit's histogram, record counter and ticket counter again, which nothing reads
-//     after this point: every call leaves them as it found them.
-constexpr int kTailTiles = 16;  // index tiles (256 entries) a wave keeps in flight while copying the staged lists
-constexpr int kAccLoads = 64;   // partial accumulators a thread keeps in flight
-constexpr int kVBatch = 16;     // admitted candidates' V elements a thread keeps in flight
+// The select workgroups of a unit each leave a partial softmax state per query head and their boundary-bin
+// candidates behind.  Nobody ever waits for anybody inside the kernel: whoever finishes last does the next step,
+// which it learns from a ticket drawn with one returning atomic.
+//   - Groups of grpC consecutive workgroups: the last one of a group folds the group's partial states into one
+//     (fold_group), so that the unit's last workgroup has few states to read: a single compute unit reads
+//     memory that other compute units wrote at a small fraction of the chip's bandwidth, so what it reads must be small.
+//     (Units with at most grpC workgroups skip this level.)
+//   - The unit's last workgroup (finalize_unit) ranks the candidates and admits the K - n_above best (at most
+//     kCandRec candidates: all that is needed sits in their records, which arrive in a different order on every
+//     run, so every sum over candidates is taken in rank order; more candidates: an 8-bit radix select over the
+//     composites staged per workgroup, the admitted rows being attended from the K/V cache), folds the group
+//     states (in order) and the admitted rows into out_attn, writes the admitted candidates' indices, and zeroes
+//     the unit's histogram and counters again, which nothing reads after this point: every call leaves them as it
+//     found them.
+// Index output: every select workgroup publishes its list sizes as soon as it has classified its tokens; when it
+// is done attending it reads the sizes of all workgroups of the unit and, if they are all there (they practically
+// always are), writes its list straight into out_idx behind those of the workgroups before it.  Otherwise it
+// stages the list and the unit's last workgroup copies it.  In workgroup order the lists read
+//     [0..I) , tokens above the threshold bin (ascending) , [N-L..N)
+// and the admitted candidates go between the second and the third part.
+constexpr int kVBatch = 32;                     // admitted candidates' V elements a thread keeps in flight
+constexpr int kMaxGroups = 128;                 // groups per unit, at most (kMaxBlkC / 4)
+constexpr unsigned kStagedFlag = 0x40000000u;   // in a stored list size: the list sits in its staging slot, not in out_idx
+template <int G>
+constexpr int fold_width() { return G >= 8 ? 4 : 8; }  // states folded at once = workgroups per group (about 16 KB of states)
 
 // The code of one appended token per unit (Section 3.1: nearest centroid of each partition): nothing in the
 // step depends on it, so one more workgroup per unit of the select kernel computes it beside the others.
@@ -335,51 +343,105 @@ struct AppendArgs {
   unsigned* pair_counts;  // two partitions: [units][C*C] counts that gain the token's code pair, or null
 };
 
+// Softmax states of the heads a thread owns (heads hb, hb + 2, ... of the group; one head when the group has one),
+// for output dimension d.
+template <int G>
+struct Folded {
+  static constexpr int HPT = G >= 2 ? G / 2 : 1;
+  float m[HPT], l[HPT], acc[HPT];
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int i = 0; i < HPT; ++i) {
+      m[i] = kNegBig;
+      l[i] = 0.0f;
+      acc[i] = 0.0f;
+    }
+  }
+};
+
+// Folds `count` states -- per state G heads of { m, l, acc[kD] } -- into r, in order, fold_width() states at a time
+// (all their loads in flight together).  The result depends on the states and their order alone.
+template <int G>
+__device__ __forceinline__ void fold_states(const float* __restrict__ src, int count, int d, int hb, Folded<G>& r) {
+  constexpr int F = fold_width<G>(), HPT = Folded<G>::HPT;
+  constexpr size_t stride = (size_t)G * (kD + 2);
+#pragma unroll 1
+  for (int j0 = 0; j0 < count; j0 += F) {
+    float2 ml[HPT][F];
+    float a[HPT][F];
+#pragma unroll
+    for (int x = 0; x < F; ++x) {
+      const float* p = src + (size_t)min(j0 + x, count - 1) * stride;
+#pragma unroll
+      for (int i = 0; i < HPT; ++i) {
+        const float* ph = p + (G >= 2 ? hb + 2 * i : 0) * (kD + 2);
+        ml[i][x] = *reinterpret_cast<const float2*>(ph);
+        a[i][x] = ph[2 + d];
+      }
+    }
+    PQC_LOADS_ISSUED();
+#pragma unroll
+    for (int i = 0; i < HPT; ++i) {
+      float mc = r.m[i];
+#pragma unroll
+      for (int x = 0; x < F; ++x) mc = j0 + x < count ? fmaxf(mc, ml[i][x].x) : mc;
+      const float f = __builtin_amdgcn_exp2f(r.m[i] - mc);
+      r.l[i] *= f;
+      r.acc[i] *= f;
+      r.m[i] = mc;
+#pragma unroll
+      for (int x = 0; x < F; ++x) {
+        const float wv = j0 + x < count ? __builtin_amdgcn_exp2f(ml[i][x].x - mc) : 0.0f;
+        r.l[i] = fmaf(wv, ml[i][x].y, r.l[i]);
+        r.acc[i] = fmaf(wv, a[i][x], r.acc[i]);
+      }
+    }
+  }
+}
+
 template <int G, bool ATTN>
 struct TailLds {
-  static constexpr int NW = 4, GA = ATTN ? G : 1;
+  static constexpr int NW = 4, GA = ATTN ? G : 1, GG = GA > 4 ? 4 : GA;
   struct Few {                            // at most kCandRec candidates: ranked here
     unsigned long long comp[kCandRec];    // composites in record order
-    float p[GA][kCandRec];                // by rank: logit of head h (log2 domain), then its softmax weight
+    float lg[GA][kCandRec];               // by rank: logit of head h (log2 domain)
     unsigned short ordv[kCandRec];        // by rank: record
   };
   struct Many {                           // more: radix select, admitted rows attended from the cache
     unsigned rhist[256];
     int digit[2];
     int rows[256];
-    float red[ATTN ? NW * (G > 4 ? 4 : G) * (kD + 2) : 1];
+    float red[ATTN ? NW * GG * (kD + 2) : 1];
+    float xacc[GA][kD];                   // one more state per head: the admitted rows
+    float xm[8], xl[8];
   };
   union {
     Few few;
     Many many;
   };
-  float wj[GA][kMaxBlkC];                 // weight of every select workgroup's partial softmax state
-  float xacc[GA][kD];                     // one more partial state per head: the admitted rows of the radix path
-  float xm[8], xl[8], xw[8];
-  float lstar[8];
-  int pre_sel[kMaxBlkC + 1];              // exclusive prefix sums of the staged list sizes
-  int pre_cand[kMaxBlkC + 1];             // and of the staged candidate counts
+  int lsize[kMaxBlkC];                    // list sizes as stored (with kStagedFlag); only when a list was staged
+  int pre_sel[kMaxBlkC + 1];              // exclusive prefix sums of the list sizes; likewise
+  int pre_cand[kMaxBlkC + 1];             // and of the staged candidate counts (radix path)
   int scan_sm[2 * (2 * NW + 1)];
+  int tot[3 * NW];
 };
 
 template <typename T, int G, bool ATTN>
 __device__ __forceinline__ void finalize_unit(const Shape& s, const Workspace& ws, int u, const T* __restrict__ q,
                                               const T* __restrict__ kc, const T* __restrict__ vc, int* __restrict__ out_idx,
-                                              float* __restrict__ out_attn, const AppendArgs& ap, TailLds<G, ATTN>& L) {
+                                              float* __restrict__ out_attn, const AppendArgs& ap, TailLds<G, ATTN>& L,
+                                              Folded<ATTN ? G : 1>& r /* the unit's folded states, for this thread's heads */) {
   constexpr int NT = 256, NW = 4;
   constexpr int GA = ATTN ? G : 1;
-  constexpr int HPW = (GA + NW - 1) / NW;     // heads per wave when the softmax states are weighted
-  constexpr int HPT = GA >= 2 ? GA / 2 : 1;   // heads per thread when the outputs are summed: heads hb, hb + 2, ...
-  constexpr int JB = kAccLoads / HPT;         // partial states per batch of accumulator loads
-  constexpr int MLX = kMaxBlkC / 64;
+  constexpr int HPT = Folded<GA>::HPT;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = u / s.Hkv, g = u % s.Hkv, nb = s.nblkC;
   const int2* cnt = ws.stage_cnt + (size_t)u * nb;
   const unsigned long long* stage_u = ws.stage + (size_t)u * nb * s.stageStride;
   const unsigned char* recs = ws.cand_rec + (size_t)u * kCandRec * ws.rec_stride;
-  const float* parts = ws.partials + (size_t)u * s.npart * G * (kD + 2);
   int* out = out_idx + (size_t)u * s.Ktot;
   const int d = tid & (kD - 1), hb = tid >> 7;  // output dimension; first head of this thread
+  const bool owner = GA >= 2 || hb == 0;        // this thread owns outputs
   PQC_MARK(ws, 2, 0);
 
   // ---- everything whose address is known up front is requested first
@@ -392,103 +454,87 @@ __device__ __forceinline__ void finalize_unit(const Shape& s, const Workspace& w
 #pragma unroll
     for (int h = 0; h < GA; ++h) rl[0][h] = ATTN ? hd->logit[h] : 0.0f;
   }
-  float2 ml[HPW][MLX];   // (m, l) of partial state x*64 + lane, head w + NW*i
-  float a0[HPT][JB];     // first batch of accumulators: partial state x, head hb + 2*i, dimension d
-  if constexpr (ATTN) {
-#pragma unroll
-    for (int i = 0; i < HPW; ++i)
-#pragma unroll
-      for (int x = 0; x < MLX; ++x) {
-        ml[i][x] = make_float2(kNegBig, 0.0f);
-        if (x * 64 < nb && w + NW * i < G)  // wave-uniform
-          ml[i][x] = *reinterpret_cast<const float2*>(parts + ((size_t)min(x * 64 + lane, nb - 1) * G + (w + NW * i)) * (kD + 2));
-      }
-#pragma unroll
-    for (int i = 0; i < HPT; ++i)
-#pragma unroll
-      for (int x = 0; x < JB; ++x)  // states that do not exist re-read the last one (a cache hit, no extra traffic)
-        a0[i][x] = parts[((size_t)min(x, nb - 1) * G + (G >= 2 ? hb + 2 * i : 0)) * (kD + 2) + 2 + d];
-  }
-  PQC_LOADS_ISSUED();
-  if (tid < 8) {
-    L.xm[tid] = kNegBig;
-    L.xl[tid] = 0.0f;
-  }
-
-  // ---- list sizes: exclusive prefix sums and totals
+  // ---- totals of the list sizes
   int n_list, n_cand;
+  bool any_staged;
   {
-    int2 t0, t1 = make_int2(0, 0);
-    const int2 p0 = block_exclusive_scan2<NT>(tid < nb ? c0.x : 0, tid < nb ? c0.y : 0, &t0, L.scan_sm);
+    int vs = 0, vc2 = 0, vf = 0;
     if (tid < nb) {
-      L.pre_sel[tid] = p0.x;
-      L.pre_cand[tid] = p0.y;
+      vs = c0.x & (int)~kStagedFlag;
+      vc2 = c0.y;
+      vf = (c0.x & (int)kStagedFlag) ? 1 : 0;
     }
-    if (nb > NT) {  // uniform
-      const int2 p1 = block_exclusive_scan2<NT>(tid + NT < nb ? c1.x : 0, tid + NT < nb ? c1.y : 0, &t1, L.scan_sm);
-      if (tid + NT < nb) {
-        L.pre_sel[tid + NT] = t0.x + p1.x;
-        L.pre_cand[tid + NT] = t0.y + p1.y;
-      }
+    if (tid + NT < nb) {
+      vs += c1.x & (int)~kStagedFlag;
+      vc2 += c1.y;
+      vf += (c1.x & (int)kStagedFlag) ? 1 : 0;
     }
-    n_list = t0.x + t1.x;
-    n_cand = t0.y + t1.y;
-    if (tid == 0) {
-      L.pre_sel[nb] = n_list;
-      L.pre_cand[nb] = n_cand;
+    vs = wave_last(wave_inclusive_scan(vs));
+    vc2 = wave_last(wave_inclusive_scan(vc2));
+    vf = wave_last(wave_inclusive_scan(vf));
+    if (lane == 0) {
+      L.tot[w] = vs;
+      L.tot[NW + w] = vc2;
+      L.tot[2 * NW + w] = vf;
     }
     __syncthreads();
+    n_list = 0;
+    n_cand = 0;
+    int nf = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+      n_list += L.tot[i];
+      n_cand += L.tot[NW + i];
+      nf += L.tot[2 * NW + i];
+    }
+    any_staged = nf > 0;
   }
   const int n_above = max(0, n_list - s.I - s.L);  // n_list = I + (tokens above the bin) + L
   const int need = max(0, min(s.K - n_above, n_cand));
   PQC_MARK(ws, 2, 1);
 
-  // ---- index output: the staged lists, one after the other; the local window moves behind the admitted candidates.
-  // Wave w copies lists w, w + NW, ...; a list is cut into tiles of 256 entries (4 per lane) and kTailTiles tiles
-  // travel at once.  Lane l of the wave describes the wave's l-th list; the tile -> list map is a ballot over the
-  // running tile counts.
-  {
-    const int lists_w = (nb - w + NW - 1) / NW;
-    for (int l0 = 0; l0 < lists_w; l0 += 64) {
-      const int jl = w + NW * (l0 + lane);
-      const int base_l = jl < nb ? L.pre_sel[jl] : 0;
-      const int n_l = jl < nb ? L.pre_sel[jl + 1] - base_l : 0;
-      const int tiles_l = (n_l + 255) >> 8;
-      const int incl = wave_inclusive_scan(tiles_l);
-      const int total = wave_last(incl);
-      for (int t0 = 0; t0 < total; t0 += kTailTiles) {
-        int v[kTailTiles][4], rem[kTailTiles], dst0[kTailTiles];
-#pragma unroll
-        for (int x = 0; x < kTailTiles; ++x) {
-          const int t = t0 + x;
-          const int lo = min(63, (int)__popcll(__ballot(incl <= t)));  // the list that holds tile t (uniform)
-          const int j = min(w + NW * (l0 + lo), nb - 1);
-          const int first = __builtin_amdgcn_readlane(incl, lo) - __builtin_amdgcn_readlane(tiles_l, lo);
-          const int n_j = __builtin_amdgcn_readlane(n_l, lo);
-          const int e0 = (t - first) * 256;
-          const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.stageStride);
-#pragma unroll
-          for (int y = 0; y < 4; ++y) v[x][y] = src[max(0, min(e0 + y * 64 + lane, n_j - 1))];
-          rem[x] = t < total ? n_j - e0 : 0;
-          dst0[x] = __builtin_amdgcn_readlane(base_l, lo) + e0;
+  const bool few = n_cand <= kCandRec;
+  if (__builtin_expect(any_staged || !few, 0)) {
+    // exclusive prefix sums of list sizes and candidate counts
+    int2 t0, t1 = make_int2(0, 0);
+    const int2 p0 = block_exclusive_scan2<NT>(tid < nb ? c0.x & (int)~kStagedFlag : 0, tid < nb ? c0.y : 0, &t0, L.scan_sm);
+    if (tid < nb) {
+      L.pre_sel[tid] = p0.x;
+      L.pre_cand[tid] = p0.y;
+      L.lsize[tid] = c0.x;
+    }
+    if (nb > NT) {  // uniform
+      const int2 p1 = block_exclusive_scan2<NT>(tid + NT < nb ? c1.x & (int)~kStagedFlag : 0, tid + NT < nb ? c1.y : 0, &t1, L.scan_sm);
+      if (tid + NT < nb) {
+        L.pre_sel[tid + NT] = t0.x + p1.x;
+        L.pre_cand[tid + NT] = t0.y + p1.y;
+        L.lsize[tid + NT] = c1.x;
+      }
+    }
+    if (tid == 0) {
+      L.pre_sel[nb] = n_list;
+      L.pre_cand[nb] = n_cand;
+    }
+    __syncthreads();
+    // staged lists (rare: a workgroup that could not see every other workgroup's list size when it was done)
+#pragma unroll 1
+    for (int j = w; j < nb; j += NW) {
+      if (L.lsize[j] & (int)kStagedFlag) {
+        const int base = L.pre_sel[j], n = L.pre_sel[j + 1] - base;
+        const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.stageStride);
+#pragma unroll 1
+        for (int p = lane; p < n; p += 64) {
+          const int pos = base + p, dst = pos < s.I + n_above ? pos : pos + need;
+          if (dst < s.Ktot) out[dst] = src[p];
         }
-        PQC_LOADS_ISSUED();
-#pragma unroll
-        for (int x = 0; x < kTailTiles; ++x)
-#pragma unroll
-          for (int y = 0; y < 4; ++y) {
-            const int e = y * 64 + lane, pos = dst0[x] + e;
-            const int dst = pos < s.I + n_above ? pos : pos + need;
-            if (e < rem[x] && dst < s.Ktot) out[dst] = v[x][y];
-          }
       }
     }
   }
   PQC_MARK(ws, 2, 2);
 
-  int need_few = 0;          // admitted candidates whose weights and V rows come from the records
-  bool extra_state = false;  // the radix path left one more partial state per head in xacc / xm / xl
-  if (n_cand <= kCandRec) {
+  int need_few = 0;          // admitted candidates whose logits and V rows come from the records
+  bool extra_state = false;  // the radix path left one more state per head in LDS
+  if (__builtin_expect(few, 1)) {
     // rank every candidate (count of larger composites); the admitted ones are the `need` best
     if (need > 0) {
 #pragma unroll
@@ -513,6 +559,7 @@ __device__ __forceinline__ void finalize_unit(const Shape& s, const Workspace& w
         if (k < n_cand) {
           const unsigned long long mine = rc[x];
           int rank = 0;
+#pragma unroll 1
           for (int j0 = 0; j0 < n_cand; j0 += 8) {  // eight independent LDS reads per round
             unsigned long long o[8];
 #pragma unroll
@@ -524,7 +571,7 @@ __device__ __forceinline__ void finalize_unit(const Shape& s, const Workspace& w
             const int dst = s.I + n_above + rank;  // best first
             if (dst < s.Ktot) out[dst] = composite_token(mine);
 #pragma unroll
-            for (int h = 0; h < GA; ++h) L.few.p[h][rank] = rl[x][h] * s.scale_log2e;
+            for (int h = 0; h < GA; ++h) L.few.lg[h][rank] = rl[x][h] * s.scale_log2e;
             L.few.ordv[rank] = (unsigned short)k;
           }
         }
@@ -533,7 +580,7 @@ __device__ __forceinline__ void finalize_unit(const Shape& s, const Workspace& w
     need_few = need;
   } else {
     // radix select of the need-th largest staged composite, 8 bits per pass
-    auto owner = [&](int p) -> int {  // largest j with pre_cand[j] <= p
+    auto owner_of = [&](int p) -> int {  // largest j with pre_cand[j] <= p
       int lo = 0, hi = nb - 1;
       while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
@@ -542,7 +589,7 @@ __device__ __forceinline__ void finalize_unit(const Shape& s, const Workspace& w
       return lo;
     };
     auto cand_at = [&](int i) -> unsigned long long {
-      const int j = owner(i);
+      const int j = owner_of(i);
       return stage_u[(size_t)j * s.stageStride + s.tokC - 1 - (i - L.pre_cand[j])];
     };
     unsigned long long thr = ~0ull;
@@ -575,7 +622,7 @@ __device__ __forceinline__ void finalize_unit(const Shape& s, const Workspace& w
     }
     // admitted candidates in staged order, NT candidates per round: indices out, rows attended for up to four heads
     // at a time (the rounds are repeated for the next four)
-    constexpr int GG = GA > 4 ? 4 : GA;
+    constexpr int GG = TailLds<G, ATTN>::GG;
     for (int h0 = 0; h0 < GA; h0 += GG) {
       AttnState<GG> st;
       st.init();
@@ -610,10 +657,10 @@ __device__ __forceinline__ void finalize_unit(const Shape& s, const Workspace& w
           const int h = o / kD, dd = o % kD;
           float m, l, acc;
           combine_waves<GG, NW>(L.many.red, h, dd, m, l, acc);
-          L.xacc[h0 + h][dd] = acc;
+          L.many.xacc[h0 + h][dd] = acc;
           if (dd == 0) {
-            L.xm[h0 + h] = m;
-            L.xl[h0 + h] = l;
+            L.many.xm[h0 + h] = m;
+            L.many.xl[h0 + h] = l;
           }
         }
         __syncthreads();
@@ -625,98 +672,63 @@ __device__ __forceinline__ void finalize_unit(const Shape& s, const Workspace& w
   PQC_MARK(ws, 2, 3);
 
   if constexpr (ATTN) {
-    // ---- per head (one wave each): the common maximum, the weight of every partial state and of every admitted
-    // candidate, the softmax denominator
-#pragma unroll
-    for (int i = 0; i < HPW; ++i) {
-      const int h = w + NW * i;
-      if (h < G) {  // wave-uniform
-        float mx = L.xm[h];
-#pragma unroll
-        for (int x = 0; x < MLX; ++x)
-          if (x * 64 + lane < nb) mx = fmaxf(mx, ml[i][x].x);
-        for (int r = lane; r < need_few; r += 64) mx = fmaxf(mx, L.few.p[h][r]);
-        const float mstar = wave_max(mx);
-        float lsum = 0.0f;
-#pragma unroll
-        for (int x = 0; x < MLX; ++x)
-          if (x * 64 + lane < nb) {
-            const float wv = __builtin_amdgcn_exp2f(ml[i][x].x - mstar);
-            L.wj[h][x * 64 + lane] = wv;
-            lsum = fmaf(wv, ml[i][x].y, lsum);
-          }
-        for (int r = lane; r < need_few; r += 64) {
-          const float pr = __builtin_amdgcn_exp2f(L.few.p[h][r] - mstar);
-          L.few.p[h][r] = pr;
-          lsum += pr;
-        }
-        lsum = wave_sum(lsum);
-        const float xw = __builtin_amdgcn_exp2f(L.xm[h] - mstar);
-        if (lane == 0) {
-          L.lstar[h] = fmaf(L.xl[h], xw, lsum);
-          L.xw[h] = xw;
-        }
-      }
-    }
-    __syncthreads();
-    PQC_MARK(ws, 2, 4);
-    // ---- out[h][d] = (sum_j w_j acc_j[h][d] + sum_r p_r V_r[d]) / l, partial states in workgroup order, candidates
-    // in rank order
-    if (G >= 2 || hb == 0) {
+    // ---- out[h][d] = (folded states + admitted candidates, in rank order) / l
+    if (owner) {
       int hh[HPT];
-      float acc[HPT];
 #pragma unroll
-      for (int i = 0; i < HPT; ++i) {
-        hh[i] = G >= 2 ? hb + 2 * i : 0;
-        acc[i] = 0.0f;
-      }
-#pragma unroll
-      for (int x = 0; x < JB; ++x)
-#pragma unroll
-        for (int i = 0; i < HPT; ++i)
-          if (x < nb) acc[i] = fmaf(L.wj[hh[i]][x], a0[i][x], acc[i]);
-      for (int j0 = JB; j0 < nb; j0 += JB) {
-        float a[HPT][JB];
-#pragma unroll
-        for (int i = 0; i < HPT; ++i)
-#pragma unroll
-          for (int x = 0; x < JB; ++x) a[i][x] = parts[((size_t)min(j0 + x, nb - 1) * G + hh[i]) * (kD + 2) + 2 + d];
-        PQC_LOADS_ISSUED();
-#pragma unroll
-        for (int x = 0; x < JB; ++x)
-#pragma unroll
-          for (int i = 0; i < HPT; ++i)
-            if (j0 + x < nb) acc[i] = fmaf(L.wj[hh[i]][j0 + x], a[i][x], acc[i]);
-      }
+      for (int i = 0; i < HPT; ++i) hh[i] = G >= 2 ? hb + 2 * i : 0;
       if (extra_state) {
 #pragma unroll
-        for (int i = 0; i < HPT; ++i) acc[i] = fmaf(L.xw[hh[i]], L.xacc[hh[i]][d], acc[i]);
-      }
-      for (int r0 = 0; r0 < need_few; r0 += kVBatch) {
-        float vv[kVBatch];
-#pragma unroll
-        for (int x = 0; x < kVBatch; ++x) {
-          const int k = L.few.ordv[min(r0 + x, need_few - 1)];
-          vv[x] = load_as_float<T>(reinterpret_cast<const T*>(recs + (size_t)k * ws.rec_stride + sizeof(CandHeader)), d);
+        for (int i = 0; i < HPT; ++i) {
+          const float xm = L.many.xm[hh[i]], mc = fmaxf(r.m[i], xm);
+          const float f = __builtin_amdgcn_exp2f(r.m[i] - mc), fx = __builtin_amdgcn_exp2f(xm - mc);
+          r.l[i] = fmaf(L.many.xl[hh[i]], fx, r.l[i] * f);
+          r.acc[i] = fmaf(L.many.xacc[hh[i]][d], fx, r.acc[i] * f);
+          r.m[i] = mc;
         }
-        PQC_LOADS_ISSUED();
+      }
+      if (need_few > 0) {
 #pragma unroll
-        for (int x = 0; x < kVBatch; ++x)
+        for (int i = 0; i < HPT; ++i) {
+          float mc = r.m[i];
+#pragma unroll 4
+          for (int k = 0; k < need_few; ++k) mc = fmaxf(mc, L.few.lg[hh[i]][k]);
+          const float f = __builtin_amdgcn_exp2f(r.m[i] - mc);
+          r.l[i] *= f;
+          r.acc[i] *= f;
+          r.m[i] = mc;
+        }
+#pragma unroll 1
+        for (int r0 = 0; r0 < need_few; r0 += kVBatch) {
+          float vv[kVBatch];
 #pragma unroll
-          for (int i = 0; i < HPT; ++i)
-            if (r0 + x < need_few) acc[i] = fmaf(L.few.p[hh[i]][r0 + x], vv[x], acc[i]);
+          for (int x = 0; x < kVBatch; ++x) {
+            const int k = L.few.ordv[min(r0 + x, need_few - 1)];
+            vv[x] = load_as_float<T>(reinterpret_cast<const T*>(recs + (size_t)k * ws.rec_stride + sizeof(CandHeader)), d);
+          }
+          PQC_LOADS_ISSUED();
+#pragma unroll
+          for (int x = 0; x < kVBatch; ++x)
+#pragma unroll
+            for (int i = 0; i < HPT; ++i) {
+              const float p = r0 + x < need_few ? __builtin_amdgcn_exp2f(L.few.lg[hh[i]][min(r0 + x, need_few - 1)] - r.m[i]) : 0.0f;
+              r.l[i] += p;
+              r.acc[i] = fmaf(p, vv[x], r.acc[i]);
+            }
+        }
       }
 #pragma unroll
-      for (int i = 0; i < HPT; ++i)
-        out_attn[((size_t)b * s.Hq + (size_t)g * G + hh[i]) * kD + d] = acc[i] / L.lstar[hh[i]];
+      for (int i = 0; i < HPT; ++i) out_attn[((size_t)b * s.Hq + (size_t)g * G + hh[i]) * kD + d] = r.acc[i] / r.l[i];
     }
     PQC_MARK(ws, 2, 5);
   }
 
-  // ---- every select workgroup of the unit is done with them: zero histogram, record counter and ticket counter
+  // ---- every select workgroup of the unit is done with them: zero the histogram and the unit's counters
   {
     uint4* gh = reinterpret_cast<uint4*>(ws.hist + (size_t)u * s.histCopies * kNB);
     for (int i = tid; i < s.histCopies * (kNB / 4); i += NT) gh[i] = make_uint4(0u, 0u, 0u, 0u);
+    for (int i = tid; i < nb; i += NT) ws.pub[(size_t)u * nb + i] = 0ull;
+    if (tid < kMaxGroups) ws.gticket[(size_t)u * kMaxGroups + tid] = 0u;
     if (tid == 0) {
       ws.cand_count[u] = 0u;
       ws.ticket[u] = 0u;
@@ -765,23 +777,25 @@ __device__ __forceinline__ void append_token(const Shape& s, const AppendArgs& a
     }
   }
   __syncthreads();
-  if (c < s.M) ap.codes[((size_t)u * s.cap + ap.position) * s.M + c] = (uint8_t)(A.abest[c] & 0xffu);
+  if (c < s.M) store_through(&ap.codes[((size_t)u * s.cap + ap.position) * s.M + c], (uint8_t)(A.abest[c] & 0xffu));
 }
 
-// Draws this workgroup's ticket of unit u; true for the workgroup that draws the last of `total`.  Every thread's
-// stores are made visible to the device before the ticket is drawn, and the last workgroup sees all of them.
-__device__ __forceinline__ bool last_of_unit(const Workspace& ws, int u, int total, int* ticket_sm) {
-  __threadfence();
+// Draws a ticket from `counter`; true for the workgroup that draws the last of `total`.  What a workgroup leaves
+// for whoever draws the last ticket was stored with store_through(); those stores have completed (every wave waits
+// for its own, then the barrier) before the ticket is drawn, and the last workgroup drops whatever its caches hold
+// before it reads the others' data.
+__device__ __forceinline__ bool last_ticket(unsigned* counter, int total, int* ticket_sm) {
+  __builtin_amdgcn_s_waitcnt(0);  // all counters at zero: this wave's stores are acknowledged
   __syncthreads();
-  if (threadIdx.x == 0) *ticket_sm = (int)atomicAdd(&ws.ticket[u], 1u);
+  if (threadIdx.x == 0) *ticket_sm = (int)atomicAdd(counter, 1u);
   __syncthreads();
   const bool last = *ticket_sm == total - 1;
-  if (last) __threadfence();
+  if (last) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   return last;
 }
 
 // ---------------------------------------------------- 3. select (+ attention)
-// One workgroup owns tokens [blockIdx.x*tokC, +tokC) of its unit; its 4 waves each own
+// One workgroup owns tokens [bx*tokC, +tokC) of its unit (bx: its number inside the unit); its 4 waves each own
 // a contiguous quarter.  The histogram kernel left every token's bin behind, so a token
 // is classified by comparing that number with the threshold bin.  Per wave, lanes hold
 // 8 consecutive tokens, counts are prefix-summed across lanes, and the wave appends to
@@ -837,11 +851,49 @@ __device__ __forceinline__ const A& late_kernel_args() {
   return *(const A*)p;
 }
 
+// What a workgroup does when it is done with its own part: draw a ticket; the last of a group folds the group's
+// states into one and draws a ticket of the unit; the last of the unit folds the groups' states and completes the
+// unit.  Both levels run the same loop body, so that the second pass finds its instructions in the cache.
+// level: 0 for a select workgroup of a unit with groups, 1 otherwise (units without groups, the appending workgroup).
 template <typename T, int G, bool ATTN>
-__device__ __forceinline__ void finish_unit_late(int u, unsigned char* smem) {
+__device__ __forceinline__ void finish_late(int u, int bx, unsigned char* smem, int* ticket_sm) {
+  constexpr int GA = ATTN ? G : 1, HPT = Folded<GA>::HPT;
   const SelectArgs& a = late_kernel_args<SelectArgs>();
+  const int grpC = ATTN ? a.s.grpC : 0, extra = a.ap.key ? 1 : 0;
+  const int tid = threadIdx.x, d = tid & (kD - 1), hb = tid >> 7;
+  const bool owner = GA >= 2 || hb == 0;
+  const int grp = grpC > 0 ? bx / max(grpC, 1) : 0;
+  Folded<GA> r;
+#pragma unroll 1
+  for (int level = (grpC > 0 && bx < a.s.nblkC) ? 0 : 1; level < 2; ++level) {
+    unsigned* counter = level == 0 ? &a.ws.gticket[(size_t)u * kMaxGroups + grp] : &a.ws.ticket[u];
+    const int total = level == 0 ? min(grpC, a.s.nblkC - grp * grpC) : (grpC > 0 ? a.s.ngrp : a.s.nblkC) + extra;
+    if (!last_ticket(counter, total, ticket_sm)) return;
+    r.init();
+    if constexpr (ATTN) {
+      const bool from_groups = level == 1 && grpC > 0;
+      const float* src = from_groups ? a.ws.gparts + (size_t)u * kMaxGroups * G * (kD + 2)
+                                     : a.ws.partials + ((size_t)u * a.s.npart + (level == 0 ? grp * grpC : 0)) * G * (kD + 2);
+      const int count = level == 0 ? total : (grpC > 0 ? a.s.ngrp : a.s.nblkC);
+      if (owner) {
+        fold_states<G>(src, count, d, hb, r);
+        if (level == 0) {
+          float* dst = a.ws.gparts + ((size_t)u * kMaxGroups + grp) * G * (kD + 2);
+#pragma unroll
+          for (int i = 0; i < HPT; ++i) {
+            float* dh = dst + (G >= 2 ? hb + 2 * i : 0) * (kD + 2);
+            store_through(&dh[2 + d], r.acc[i]);
+            if (d == 0) {
+              store_through(&dh[0], r.m[i]);
+              store_through(&dh[1], r.l[i]);
+            }
+          }
+        }
+      }
+    }
+  }
   finalize_unit<T, G, ATTN>(a.s, a.ws, u, static_cast<const T*>(a.q), static_cast<const T*>(a.kc), static_cast<const T*>(a.vc),
-                            a.out_idx, a.out_attn, a.ap, *reinterpret_cast<TailLds<G, ATTN>*>(smem));
+                            a.out_idx, a.out_attn, a.ap, *reinterpret_cast<TailLds<G, ATTN>*>(smem), r);
 }
 
 template <typename T, int G, class SRC, bool ATTN, bool PAIRS = false>
@@ -870,18 +922,26 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
   float* red = S.red;
   float* qlds = S.qlds;
   unsigned char* vtile = S.vtile;
-  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int b = u / s.Hkv, g = u % s.Hkv;
-  if ((int)blockIdx.x == s.nblkC) {  // the appended token's code; nothing in the step reads it
-    append_token<T>(s, args.ap, u, *reinterpret_cast<AppendLds*>(smem));
-    if (last_of_unit(ws, u, s.nblkC + 1, &ticket_sm)) finish_unit_late<T, G, ATTN>(u, smem);
-    return;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  // Workgroups are handed to the 8 XCDs round-robin in launch order (x fastest).  Eight units at a time are
+  // interleaved, so that the workgroups of one unit share an XCD: what they leave for the unit's last workgroup
+  // is then found in that XCD's L2 (a matter of speed only: the exchange is correct wherever they run).
+  int u = blockIdx.y, bx = blockIdx.x;
+  {
+    const int nx = gridDim.x, lin = blockIdx.y * nx + blockIdx.x, units = s.B * s.Hkv;
+    if (lin < (units & ~7) * nx) {
+      const int i = lin % (8 * nx);
+      u = (lin / (8 * nx)) * 8 + (i & 7);
+      bx = i >> 3;
+    }
   }
+  const int b = u / s.Hkv, g = u % s.Hkv;
+  auto select_and_attend = [&]() {
   PQC_MARK(ws, 1, 0);
   // this wave's stored bins, the query and the histogram: all requested up front
   const int tpw = s.tokC / NW;           // tokens per wave, in groups of 8 per lane
   const int gpw = (tpw + 511) / 512;     // groups per lane: 1, 2 or 4 (the last lanes idle when tpw < 512)
-  const int wave_t0 = blockIdx.x * s.tokC + w * tpw;
+  const int wave_t0 = bx * s.tokC + w * tpw;
   // 16 bytes per group of 8 tokens: their stored bins, or (PAIRS) their codes
   const unsigned short* bins_u =
       PAIRS ? reinterpret_cast<const unsigned short*>(static_cast<const uint8_t*>(src_ptr) + (size_t)u * s.cap * 2)
@@ -925,7 +985,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
 
   const int segN = s.tokC / NW;
   unsigned short* seg = list + w * segN;
-  const int wg_t0 = blockIdx.x * s.tokC;
+  const int wg_t0 = bx * s.tokC;
   int nsel = 0, ncand = 0;
   const unsigned thr = (unsigned)th.bstar + 1u;  // in stored form
 #pragma unroll
@@ -985,10 +1045,16 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
   // attention below, which hides the round trip of the returning atomic
   int rec_base;  // set and read by thread 0 only; no initialiser, or the merge with it would wait for the atomic here
   if (tid == 0 && tot_cand > 0) rec_base = (int)atomicAdd(&ws.cand_count[u], (unsigned)tot_cand);
+  // this workgroup's list sizes, for the other workgroups of the unit to place their lists in out_idx
+  if (tid == 0) store_through(&ws.pub[(size_t)u * s.nblkC + bx], ((unsigned long long)(unsigned)tot_cand << 32) | (unsigned)(tot_sel + 1));
   // put away (in LDS) once the attention's first loads are back, which arrive after it: no wait, and no register
   // held through the attention
+  // Likewise the list sizes of the unit's first 64 workgroups (wave 0, one per lane) are requested there: the
+  // workgroups of a unit start together and publish their sizes long before anyone's first rows are back.
+  unsigned long long pw0 = 0ull;
   auto put_rec_base = [&]() {
     if (tid == 0 && tot_cand > 0) scan_sm[0] = rec_base;  // scan_sm is idle since the threshold search
+    if (w == 0) pw0 = __hip_atomic_load(&ws.pub[(size_t)u * s.nblkC + min(lane, s.nblkC - 1)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   };
   // A candidate's exact score comes from its codes and the unit's table (same evaluation order
   // as everywhere), or from the score array of the stand-alone top-k.
@@ -1036,7 +1102,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
   };
 
   // selected list for the index output
-  unsigned long long* stage = ws.stage + ((size_t)u * s.nblkC + blockIdx.x) * s.stageStride;
+  unsigned long long* stage = ws.stage + ((size_t)u * s.nblkC + bx) * s.stageStride;
   int* stage32 = reinterpret_cast<int*>(stage);
   PQC_MARK(ws, 1, 3);
 
@@ -1065,15 +1131,30 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
   // window tokens it happens to hold (the list's first nI and last nL entries), every
   // nblkC-th token of the two windows, so that the window rows are spread over the unit's
   // workgroups.
-  const int tok_lo = (int)blockIdx.x * s.tokC, tok_hi = min(s.N, ((int)blockIdx.x + 1) * s.tokC);
+  const int tok_lo = bx * s.tokC, tok_hi = min(s.N, (bx + 1) * s.tokC);
   const int nI = max(0, min(s.I, tok_hi) - tok_lo), nL = max(0, tok_hi - max(s.N - s.L, tok_lo));
   const int n_own = tot_sel - nI - nL;
-  const int n_win = (int)blockIdx.x < s.I + s.L ? (s.I + s.L - (int)blockIdx.x + s.nblkC - 1) / s.nblkC : 0;
+  const int n_win = bx < s.I + s.L ? (s.I + s.L - bx + s.nblkC - 1) / s.nblkC : 0;
   const int n_att = n_own + n_win;
   auto att_at = [&](int p) -> int {
     if (p < n_own) return sel_at(p + nI);
-    const int wt = (int)blockIdx.x + (p - n_own) * s.nblkC;
+    const int wt = bx + (p - n_own) * s.nblkC;
     return wt < s.I ? wt : s.N - s.L + (wt - s.I);
+  };
+  // the list sizes of the unit's workgroups (wave 0): requested when the attention is done, read further down
+  constexpr int PWX = kMaxBlkC / 64;
+  unsigned long long pw[PWX];
+  auto poll_sizes = [&]() {
+    if (w == 0) {
+      pw[0] = pw0;
+      const bool again = __any(lane < s.nblkC && (unsigned)pw0 == 0u) != 0;  // uniform: some size was not there yet
+#pragma unroll
+      for (int x = 0; x < PWX; ++x) {
+        if (x > 0) pw[x] = 0ull;
+        if (x * 64 < s.nblkC && (x > 0 || again))  // uniform
+          pw[x] = __hip_atomic_load(&ws.pub[(size_t)u * s.nblkC + min(x * 64 + lane, s.nblkC - 1)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
   };
   if constexpr (ATTN) {
     if constexpr (kMfma) {
@@ -1084,6 +1165,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
       mfma_attend(reinterpret_cast<const bf16_t*>(kbase), reinterpret_cast<const bf16_t*>(vbase), s.N, att_at, n_att,
                   w * 16 * kMfmaTiles, NW * 16 * kMfmaTiles, s.scale_log2e, qf, vtile + w * kVTileBytes, st, put_rec_base);
       PQC_MARK(ws, 1, 4);
+      poll_sizes();
       mfma_stash_wave_state<G>(st, red);
     } else {
       float qr[G][8];
@@ -1094,26 +1176,70 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
       attend_rows<T, G, R>(kbase, vbase, s.N, att_at, n_att, w * 4 * R, NW * 4 * R, qr, st);
       put_rec_base();
       PQC_MARK(ws, 1, 4);
+      poll_sizes();
       stash_wave_state<T, G>(st, red);
     }
     __syncthreads();
-    float* part = ws.partials + ((size_t)u * s.npart + blockIdx.x) * G * (kD + 2);
+    float* part = ws.partials + ((size_t)u * s.npart + bx) * G * (kD + 2);
     for (int o = tid; o < G * kD; o += NT) {
       const int h = o / kD, d = o % kD;
       float m, l, acc;
       combine_waves<G, NW>(red, h, d, m, l, acc);
-      part[h * (kD + 2) + 2 + d] = acc;
+      store_through(&part[h * (kD + 2) + 2 + d], acc);
       if (d == 0) {
-        part[h * (kD + 2)] = m;
-        part[h * (kD + 2) + 1] = l;
+        store_through(&part[h * (kD + 2)], m);
+        store_through(&part[h * (kD + 2) + 1], l);
       }
     }
+  } else {
+    put_rec_base();
+    poll_sizes();
   }
-  if constexpr (!ATTN) put_rec_base();
-  // (written after the attention: stores issued while the K/V loads of the co-resident workgroup
-  // fill the memory pipeline would only delay this workgroup's own first loads)
-  for (int p = tid; p < tot_sel; p += NT) stage32[p] = sel_at(p);
-  if (tid == 0) ws.stage_cnt[(size_t)u * s.nblkC + blockIdx.x] = make_int2(tot_sel, tot_cand);
+  // Where this workgroup's list goes in out_idx: behind the lists of the workgroups before it, if every
+  // workgroup's sizes are known by now; otherwise the list is staged for the unit's last workgroup.
+  if (w == 0) {
+    int before = 0, all_sel = 0, all_cand = 0;
+    bool known = true;
+#pragma unroll
+    for (int x = 0; x < PWX; ++x) {
+      if (x * 64 < s.nblkC) {  // uniform
+        const int j = x * 64 + lane;
+        const unsigned lo = (unsigned)pw[x], hi = (unsigned)(pw[x] >> 32);
+        if (j < s.nblkC) {
+          known = known && lo != 0u;
+          const int sz = lo != 0u ? (int)lo - 1 : 0;
+          all_sel += sz;
+          all_cand += (int)hi;
+          before += j < bx ? sz : 0;
+        }
+      }
+    }
+    known = __all(known) != 0;
+    before = wave_last(wave_inclusive_scan(before));
+    all_sel = wave_last(wave_inclusive_scan(all_sel));
+    all_cand = wave_last(wave_inclusive_scan(all_cand));
+    if (lane == 0) {
+      scan_sm[1] = known ? before : -1;
+      scan_sm[2] = all_sel;
+      scan_sm[3] = all_cand;
+    }
+  }
+  __syncthreads();
+  const int my_off = scan_sm[1];
+  if (my_off >= 0) {  // uniform
+    const int n_above_u = max(0, scan_sm[2] - s.I - s.L);
+    const int need_u = max(0, min(s.K - n_above_u, scan_sm[3]));
+    int* out = args.out_idx + (size_t)u * s.Ktot;
+    for (int p = tid; p < tot_sel; p += NT) {
+      const int pos = my_off + p, dst = pos < s.I + n_above_u ? pos : pos + need_u;  // the local window goes behind the admitted candidates
+      if (dst < s.Ktot) out[dst] = sel_at(p);
+    }
+  } else {
+    for (int p = tid; p < tot_sel; p += NT) store_through(&stage32[p], sel_at(p));
+  }
+  if (tid == 0)
+    store_through(reinterpret_cast<unsigned long long*>(ws.stage_cnt + (size_t)u * s.nblkC + bx),
+                  ((unsigned long long)(unsigned)tot_cand << 32) | ((unsigned)tot_sel | (my_off >= 0 ? 0u : kStagedFlag)));
   PQC_MARK(ws, 1, 5);
   PQC_NOTE(ws, 1, 14, tot_sel);
   PQC_NOTE(ws, 1, 15, tot_cand);
@@ -1135,11 +1261,11 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
         }
       }
       const unsigned long long comp = make_composite(cand_score(key), t);
-      if (sub == 0) stage[s.tokC - 1 - c] = comp;
+      if (sub == 0) store_through(&stage[s.tokC - 1 - c], comp);
       if (base + c < kCandRec) {
         unsigned char* rec = ws.cand_rec + ((size_t)u * kCandRec + base + c) * ws.rec_stride;
         CandHeader* hd = reinterpret_cast<CandHeader*>(rec);
-        if (sub == 0) hd->composite = comp;
+        if (sub == 0) store_through(&hd->composite, comp);
         if constexpr (ATTN) {
           float kf[8];
           kr.unpack(kf);
@@ -1149,19 +1275,21 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) d = fmaf(qlds[h * kD + owned_dim<T>(sub, e)], kf[e], d);
             d = group16_sum(d);
-            if (sub == 0) hd->logit[h] = d;
+            if (sub == 0) store_through(&hd->logit[h], d);
           }
-          vr.store(rec + sizeof(CandHeader), sub);
+          vr.store_through(rec + sizeof(CandHeader), sub);
         }
       }
     }
   }
   PQC_MARK(ws, 1, 6);
-  // the unit's last workgroup to get here completes the unit
-  {
-    const SelectArgs& late = late_kernel_args<SelectArgs>();
-    if (last_of_unit(late.ws, u, late.s.nblkC + (late.ap.key ? 1 : 0), &ticket_sm)) finish_unit_late<T, G, ATTN>(u, smem);
-  }
+  };  // select_and_attend
+  if (bx == s.nblkC)  // the appended token's code; nothing in the step reads it
+    append_token<T>(s, args.ap, u, *reinterpret_cast<AppendLds*>(smem));
+  else
+    select_and_attend();
+  // whoever finishes last does the next step: fold the group's states, complete the unit
+  finish_late<T, G, ATTN>(u, bx, smem, &ticket_sm);
 }
 
 // ------------------------------------------------------------ block reductions
