@@ -105,20 +105,19 @@ def main() -> int:
     # ---- per-kernel durations: each kernel of the path is launched for every input set back to
     # back (one context per set) between two HIP events on the launch stream, so that no event
     # sits in front of a timed launch; duration = span / number of launches
-    NK = 2  # kernels of a step: histogram, select + attention (+ completion of every unit by its last workgroup)
-    kern_us = np.zeros(NK)
+    kern_us = np.zeros(3)
     if args.profile_steps > 0:
         ctxs = [ctx] + [binding.PQCache(w, dev) for _ in sets[1:]]
-        evs = [torch.cuda.Event(enable_timing=True) for _ in range(NK + 1)]
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         for rnd in range(args.profile_steps + 2):  # two untimed rounds first
-            for ph in range(NK):
+            for ph in range(3):
                 evs[ph].record()
                 for c, a in zip(ctxs, margs):
                     c.decode_phase_marshalled(ph, a, stream_handle)
-            evs[NK].record()
+            evs[3].record()
             torch.cuda.synchronize()
             if rnd >= 2:
-                kern_us += np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(NK)]) * 1e3 / len(sets)
+                kern_us += np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(3)]) * 1e3 / len(sets)
         kern_us /= args.profile_steps
         del ctxs
 
@@ -156,7 +155,8 @@ def main() -> int:
         "achieved_hbm_gbps": round(path_gbps, 1), "hbm_frac": round(path_gbps / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": path_bytes, "host_wall_ms_per_step": round(wall_ms / args.steps, 6),
         "host_issue_ms_per_step": round(issue_ms / args.steps, 6),
-        "kernel_us": {"hist": round(float(kern_us[0]), 3), "select_attn": round(float(kern_us[1]), 3)},
+        "kernel_us": {"hist": round(float(kern_us[0]), 3), "select_attn": round(float(kern_us[1]), 3),
+                      "finalize": round(float(kern_us[2]), 3)},
         "roofline": {"kernel": "select_kernel", "bound": "hbm", "achieved": round(sel_gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(sel_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "bytes_per_launch": sel_bytes, "avg_us": round(float(kern_us[1]), 3)},

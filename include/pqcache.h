@@ -146,7 +146,7 @@ int pqc_last_hip_error(const pqc_ctx* ctx);
  *
  * Codes of tokens inside the initial and local windows are ignored.
  *
- * The call enqueues kernel launches only (two; before a context's first call,
+ * The call enqueues kernel launches only (three; before a context's first call,
  * and after a call that failed, one more that clears the workspace) and a completed
  * call leaves the workspace as it found it.  It may therefore be recorded into a
  * HIP graph by stream capture and replayed, for instance one call per layer with
@@ -159,7 +159,7 @@ int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_
 
 /* pqc_decode for a cache that has just received a token: besides the step, the code of that
  * token is written (Algorithm 2: the PQ search of a step and the code of the token that joins
- * the compressed part; Section 3.1: nearest centroid of each partition), inside the same two
+ * the compressed part; Section 3.1: nearest centroid of each partition), inside the same three
  * launches -- nothing in the step reads it, so it costs no launch of its own.
  *   new_key   [B][Hkv][D]  kv_dtype   key of the token (e.g. its row of k_cache, copied)
  *   position  where its code goes: codes[b][h][position][0..M-1] (same result as
@@ -208,8 +208,8 @@ int pqc_decode_indexed(pqc_ctx* ctx, const void* q, const float* centroids, cons
 
 /* pqc_decode_indexed for a cache that has just received a token (as pqc_decode_append): on
  * entry pair_counts holds the first N tokens except the one at `position`, whose code does not
- * exist yet; the call writes that code and adds its pair to pair_counts, inside its own one
- * launch.  `position` as for pqc_decode_append. */
+ * exist yet; the call writes that code and adds its pair to pair_counts, inside its own two
+ * launches.  `position` as for pqc_decode_append. */
 int pqc_decode_indexed_append(pqc_ctx* ctx, const void* q, const float* centroids, uint8_t* codes,
                               uint32_t* pair_counts, const void* k_cache, const void* v_cache,
                               const void* new_key, int32_t position, int32_t* out_idx, float* out_attn,
@@ -225,13 +225,14 @@ int pqc_pair_counts_add(const pqc_config* cfg, const uint8_t* codes, int32_t pos
                         void* stream);
 
 /* Profiling aid: the kernels of pqc_decode one at a time.  phase 0 = histogram, 1 =
- * select + attention + completion of the units; calling phases 0, 1 in this order with the
- * same arguments is exactly one pqc_decode (same kernels, same results).  It lets a harness
+ * select + attention, 2 = finalize; calling phases 0, 1, 2 in this order with the same
+ * arguments is exactly one pqc_decode (same kernels, same results).  It lets a harness
  * launch one phase for several contexts back to back between two events, which times
  * a kernel without an event in front of every launch.  A phase out of turn on a context
- * (not 0 after a complete step, not 1 after 0) is refused with PQC_EINVAL and enqueues nothing;
- * pqc_decode and the other calls start a new step whenever they are called. */
-#define PQC_DECODE_KERNELS 2
+ * (not 0 after a complete step, not the successor of the phase before) is refused with
+ * PQC_EINVAL and enqueues nothing; pqc_decode and the other calls start a new step whenever
+ * they are called, whatever was left unfinished. */
+#define PQC_DECODE_KERNELS 3
 int pqc_decode_phase(pqc_ctx* ctx, int phase, const void* q, const float* centroids, const uint8_t* codes,
                      const void* k_cache, const void* v_cache, int32_t* out_idx, float* out_attn,
                      void* stream);

@@ -263,7 +263,7 @@ class PQCache:
                     "pqc_decode_indexed")
 
     def decode_phase_marshalled(self, phase: int, args, stream_handle: int) -> None:
-        """One kernel of pqc_decode (0 histogram, 1 select + attention + completion of the units); see the header."""
+        """One kernel of pqc_decode (0 histogram, 1 select + attention, 2 finalize); see the header."""
         self._check(self.lib.pqc_decode_phase(self.handle, phase, *args, stream_handle), "pqc_decode_phase")
 
     def decode_phase(self, phase, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream=None):

@@ -21,8 +21,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
   Shape s;
-  size_t off_ctl, off_lut, off_range, off_hist, off_bins, off_crec, off_stage, off_cnt, off_part, off_gpart, off_trace, total;
-  size_t zero_words;  // 32-bit words of the region at off_hist that must be zero when a call starts
+  size_t off_ctl, off_lut, off_range, off_hist, off_bins, off_crec, off_stage, off_cnt, off_part, off_trace, total;
   int rec_stride;
 };
 
@@ -41,15 +40,12 @@ void lay_out(Plan* p, size_t bins_per_unit, size_t stage_words_per_unit, size_t 
   p->off_ctl = off;   off = align_up(off + sizeof(BinParams) * units);
   p->off_lut = off;   off = align_up(off + sizeof(float) * units * s.M * s.C);
   p->off_range = off; off = align_up(off + sizeof(float2) * units);
-  // histograms, then the counters and published list sizes that are zero between calls like them
-  p->zero_words = units * ((size_t)kHistCopies * kNB + 2 + kMaxGroups + 2 * counts_per_unit);
-  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * p->zero_words);
+  p->off_hist = off;  off = align_up(off + sizeof(unsigned) * units * (kHistCopies * kNB + 1));  // + record counters
   p->off_bins = off;  off = align_up(off + sizeof(unsigned short) * units * bins_per_unit);
   p->off_crec = off;  off = align_up(off + (size_t)p->rec_stride * kCandRec * units);
   p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * stage_words_per_unit);
   p->off_cnt = off;   off = align_up(off + sizeof(int2) * units * counts_per_unit);
   p->off_part = off;  off = align_up(off + sizeof(float) * units * partials_per_unit * s.G * (kD + 2));
-  p->off_gpart = off; off = align_up(off + sizeof(float) * units * kMaxGroups * s.G * (kD + 2));
 #ifdef PQC_TRACE
   p->off_trace = off; off = align_up(off + sizeof(unsigned long long) * 3 * kTraceWgs * kTraceSlots);
 #endif
@@ -111,10 +107,7 @@ int make_plan(const pqc_config* c, Plan* p) {
   s.rowsP = env_int("PQC_ROWS_P", 256);
   s.nblkP = (s.Ktot + s.rowsP - 1) / s.rowsP;
   s.npart = s.nblkC > s.nblkP ? s.nblkC : s.nblkP;
-  // the states of grpC consecutive select workgroups are folded into one before the unit's last workgroup reads them
-  s.grpC = G >= 8 ? 4 : 8;
-  s.ngrp = (s.nblkC + s.grpC - 1) / s.grpC;
-  if (s.ngrp <= 1) s.grpC = s.ngrp = 0;
+  if (s.npart < 2 * kAccBatch) s.npart = 2 * kAccBatch;  // finalize_kernel reads this many slots unconditionally
   p->rec_stride = (int)sizeof(CandHeader) + kD * (c->kv_dtype == PQC_F32 ? 4 : 2);
   // sample ranks that bracket the K-th largest score by 5 standard errors (+2)
   const int nmid = s.N - s.I - s.L;
@@ -149,6 +142,7 @@ size_t workspace_bound(const pqc_config* c) {
   if (nb < 1) nb = 1;
   size_t npart = (cap + s.rowsP - 1) / s.rowsP;
   if (npart < nb) npart = nb;
+  if (npart < (size_t)2 * kAccBatch) npart = (size_t)2 * kAccBatch;
   lay_out(&p, cap + 8192, cap + 8192 + 40 * nb, nb, npart);
   return p.total;
 }
@@ -162,7 +156,7 @@ struct pqc_ctx {
   AppendArgs append;       // set for the duration of a pqc_decode_append call
   char* workspace;         // the caller's device memory
   size_t workspace_bytes;
-  bool hist_clean;  // histograms and counters are known to be all zero
+  bool hist_clean;  // the histogram is known to be all zero
   int next_phase;   // pqc_decode_phase: the phase that continues the step begun on this context (0: none begun)
   int last_hip;
 };
@@ -181,35 +175,63 @@ int check_launch(pqc_ctx* ctx) {
   return PQC_OK;
 }
 
-// Histograms, record counters and ticket counters must be zero when a call starts; the last workgroup of every
-// unit leaves them so, which makes a completed call stateless (and a captured one replayable).
+// Histograms and record counters must be zero when a call starts; finalize_kernel leaves them
+// so, which makes a completed call stateless (and a captured one replayable).
 int ensure_clean_hist(pqc_ctx* ctx, hipStream_t st) {
   if (ctx->next_phase != 0) {  // a step begun phase by phase (pqc_decode_phase) was left unfinished: its histogram is stale
     ctx->hist_clean = false;
     ctx->next_phase = 0;
   }
   if (ctx->hist_clean) return PQC_OK;
-  const size_t na = ctx->plan.zero_words;  // histograms and the counters behind them
+  const Shape& s = ctx->plan.s;
+  const size_t na = (size_t)s.B * s.Hkv * (kHistCopies * kNB + 1);  // histograms and the record counters behind them
   hipLaunchKernelGGL(reset_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, st, ctx->ws.hist, na);
   return check_launch(ctx);
 }
 
 // ---- template dispatch -------------------------------------------------------
-// phases: bit k set = launch kernel k of the decode path (0 histogram, 1 select + attention + completion of the units)
+// The histogram kernel is compiled for the number of 16-byte loads a thread needs: of the centroids (VW: the
+// unit's M*C*Dm floats over 1024 threads) and of the codes or scores (VA: the workgroup's tokA tokens).
+template <typename T, class SRC, int VW>
+void launch_hist_w(const Shape& s, const Workspace& ws, const T* q, const float* cent, const void* src, size_t lds, hipStream_t st) {
+  const dim3 grid(s.nblkA, (unsigned)(s.B * s.Hkv));
+  const int chunks = s.tokA / SRC::P, va = (chunks + 1023) / 1024;
+  if (va <= 1)
+    hipLaunchKernelGGL((hist_kernel<T, SRC, VW, 1>), grid, dim3(1024), lds, st, s, ws, q, cent, src);
+  else if (va <= 2)
+    hipLaunchKernelGGL((hist_kernel<T, SRC, VW, 2>), grid, dim3(1024), lds, st, s, ws, q, cent, src);
+  else
+    hipLaunchKernelGGL((hist_kernel<T, SRC, VW, 4>), grid, dim3(1024), lds, st, s, ws, q, cent, src);
+}
+template <typename T, class SRC>
+void launch_hist(const Shape& s, const Workspace& ws, const T* q, const float* cent, const void* src, size_t lds, hipStream_t st) {
+  if constexpr (!SRC::kFromCodes) {
+    launch_hist_w<T, SRC, 1>(s, ws, q, cent, src, lds, st);
+  } else {
+    const int vw = (s.M * s.C * s.Dm + 4095) / 4096;
+    if (vw <= 1) launch_hist_w<T, SRC, 1>(s, ws, q, cent, src, lds, st);
+    else if (vw <= 2) launch_hist_w<T, SRC, 2>(s, ws, q, cent, src, lds, st);
+    else if (vw <= 4) launch_hist_w<T, SRC, 4>(s, ws, q, cent, src, lds, st);
+    else launch_hist_w<T, SRC, 8>(s, ws, q, cent, src, lds, st);
+  }
+}
+
+// phases: bit k set = launch kernel k of the decode path (0 histogram, 1 select + attention, 2 finalize)
 template <typename T, int G, int M>
 void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const void* k,
                        const void* v, int32_t* out_idx, float* out_attn, hipStream_t st, unsigned phases) {
   const Shape& s = ctx->plan.s;
   const unsigned units = (unsigned)(s.B * s.Hkv);
   const T* qt = static_cast<const T*>(q);
-  if (phases & 1u)
-    hipLaunchKernelGGL((hist_kernel<T, CodeChunks<M>>), dim3(s.nblkA, units), dim3(1024),
-                       sizeof(float) * lut_tile_floats(1024, M, s.C), st, s, ctx->ws, qt, cent, static_cast<const void*>(codes));
-  if (phases & 2u) {
-    const SelectArgs a{s, ctx->ws, q, k, v, codes, out_idx, out_attn, ctx->append, nullptr, nullptr, -1};
-    hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC + (ctx->append.key ? 1 : 0), units), dim3(256),
-                       s.tokC * sizeof(unsigned short), st, a);
-  }
+  const T* kt = static_cast<const T*>(k);
+  const T* vt = static_cast<const T*>(v);
+  if (phases & 1u) launch_hist<T, CodeChunks<M>>(s, ctx->ws, qt, cent, static_cast<const void*>(codes), sizeof(float) * lut_tile_floats(1024, M, s.C), st);
+  if (phases & 2u)
+    hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC, units), dim3(256),
+                       s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));
+  if (phases & 4u)
+    hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs + (ctx->append.key ? 1 : 0), units), dim3(256),
+                       (4 * s.nblkC + 2) * sizeof(int), st, s, ctx->ws, qt, kt, vt, out_idx, out_attn, ctx->append);
 }
 
 template <typename T, int G>
@@ -234,16 +256,20 @@ void launch_decode_t(pqc_ctx* ctx, const void* q, const float* cent, const uint8
   }
 }
 
-// decode with the threshold taken from code-pair counts (M = 2): the select kernel alone, no histogram kernel
+// decode with the threshold taken from code-pair counts (M = 2): select + finalize, no histogram kernel
 template <typename T, int G>
 void launch_indexed_tg(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const unsigned* pair_counts,
                        const void* k, const void* v, int32_t* out_idx, float* out_attn, hipStream_t st) {
   const Shape& s = ctx->plan.s;
   const unsigned units = (unsigned)(s.B * s.Hkv);
-  const SelectArgs a{s, ctx->ws, q, k, v, codes, out_idx, out_attn, ctx->append, cent, pair_counts,
-                     ctx->append.key ? ctx->append.position : -1};
-  hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<2>, true, true>), dim3(s.nblkC + (ctx->append.key ? 1 : 0), units), dim3(256),
-                     s.tokC * sizeof(unsigned short), st, a);
+  const T* qt = static_cast<const T*>(q);
+  const T* kt = static_cast<const T*>(k);
+  const T* vt = static_cast<const T*>(v);
+  hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<2>, true, true>), dim3(s.nblkC, units), dim3(256),
+                     s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes), cent,
+                     pair_counts, ctx->append.key ? ctx->append.position : -1);
+  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs + (ctx->append.key ? 1 : 0), units), dim3(256),
+                     (4 * s.nblkC + 2) * sizeof(int), st, s, ctx->ws, qt, kt, vt, out_idx, out_attn, ctx->append);
 }
 
 template <typename T>
@@ -337,10 +363,6 @@ void bind_workspace(pqc_ctx* ctx) {
   ctx->ws.lut = reinterpret_cast<float*>(base + p.off_lut);
   ctx->ws.hist = reinterpret_cast<unsigned*>(base + p.off_hist);
   ctx->ws.cand_count = ctx->ws.hist + (size_t)p.s.B * p.s.Hkv * kHistCopies * kNB;
-  ctx->ws.ticket = ctx->ws.cand_count + (size_t)p.s.B * p.s.Hkv;
-  ctx->ws.gticket = ctx->ws.ticket + (size_t)p.s.B * p.s.Hkv;
-  ctx->ws.pub = reinterpret_cast<unsigned long long*>(ctx->ws.gticket + (size_t)p.s.B * p.s.Hkv * kMaxGroups);
-  ctx->ws.gparts = reinterpret_cast<float*>(base + p.off_gpart);
   ctx->ws.range = reinterpret_cast<float2*>(base + p.off_range);
   ctx->ws.bins = reinterpret_cast<unsigned short*>(base + p.off_bins);
   ctx->ws.cand_rec = reinterpret_cast<unsigned char*>(base + p.off_crec);
@@ -415,15 +437,15 @@ static int decode_impl(pqc_ctx* ctx, const void* q, const float* centroids, cons
   else
     launch_decode_t<bf16_t>(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, st, phases);
   rc = check_launch(ctx);
-  if (rc == PQC_OK && (phases & 2u)) {
-    ctx->hist_clean = true;  // the units' last workgroups zeroed them again
+  if (rc == PQC_OK && (phases & 4u)) {
+    ctx->hist_clean = true;  // finalize_kernel zeroed them again
   }
   return rc;
 }
 
 int pqc_decode(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes, const void* k_cache,
                const void* v_cache, int32_t* out_idx, float* out_attn, void* stream) {
-  return decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 3u);
+  return decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 7u);
 }
 
 int pqc_decode_append(pqc_ctx* ctx, const void* q, const float* centroids, uint8_t* codes, const void* k_cache,
@@ -434,7 +456,7 @@ int pqc_decode_append(pqc_ctx* ctx, const void* q, const float* centroids, uint8
   // only a position whose code this call does not read: inside a window, or beyond the tokens in use
   if (position < 0 || position >= s.cap || (position >= s.I && position < s.N - s.L)) return PQC_EINVAL;
   ctx->append = AppendArgs{new_key, centroids, codes, (int)position, nullptr};
-  const int rc = decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 3u);
+  const int rc = decode_impl(ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 7u);
   ctx->append = AppendArgs{nullptr, nullptr, nullptr, 0, nullptr};
   return rc;
 }
@@ -552,11 +574,11 @@ int pqc_topk(pqc_ctx* ctx, const float* scores, int32_t* out_idx, void* stream) 
   const unsigned units = (unsigned)(s.B * s.Hkv);
   const float* nof = nullptr;
   hipLaunchKernelGGL(score_range_kernel, dim3(1, units), dim3(1024), 0, st, s, scores, ctx->ws.range);
-  hipLaunchKernelGGL((hist_kernel<float, ScoreChunks>), dim3(s.nblkA, units), dim3(1024), 0, st, s, ctx->ws, nof, nof,
-                     static_cast<const void*>(scores));
-  const SelectArgs a{s, ctx->ws, nullptr, nullptr, nullptr, scores, out_idx, nullptr, AppendArgs{nullptr, nullptr, nullptr, 0, nullptr},
-                     nullptr, nullptr, -1};
-  hipLaunchKernelGGL((select_kernel<float, 1, ScoreChunks, false>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(unsigned short), st, a);
+  launch_hist<float, ScoreChunks>(s, ctx->ws, nof, nof, static_cast<const void*>(scores), 0, st);
+  hipLaunchKernelGGL((select_kernel<float, 1, ScoreChunks, false>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(unsigned short), st,
+                     s, ctx->ws, nof, nof, nof, static_cast<const void*>(scores));
+  hipLaunchKernelGGL((finalize_kernel<float, 1, false>), dim3(1 + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
+                     ctx->ws, nof, nof, nof, out_idx, static_cast<float*>(nullptr), AppendArgs{nullptr, nullptr, nullptr, 0, nullptr});
   rc = check_launch(ctx);
   if (rc == PQC_OK) {
     ctx->hist_clean = true;
@@ -640,7 +662,7 @@ int pqc_decode_static(const pqc_config* cfg, const void* q, const float* centroi
                            // by a fill kernel, so that the call can be recorded into a graph
   ctx.last_hip = 0;
   ctx.append = AppendArgs{nullptr, nullptr, nullptr, 0, nullptr};
-  return decode_impl(&ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 3u);
+  return decode_impl(&ctx, q, centroids, codes, k_cache, v_cache, out_idx, out_attn, stream, 7u);
 }
 
 }  // extern "C"

@@ -15,8 +15,7 @@ constexpr int kNB = 2048;        // score bins of the one-pass threshold search
 constexpr int kHistCopies = 4;   // histogram replica slots per unit; Shape::histCopies of them are in use
 constexpr int kD = 128;          // head dimension
 constexpr int kLutRow = 256;     // LDS stride of one partition's table (max centroids)
-constexpr int kCandRec = 512;    // boundary-bin candidate records per unit (ranked inside LDS by the unit's last workgroup)
-constexpr int kMaxBlkC = 512;    // select workgroups per unit, at most
+constexpr int kCandRec = 1024;   // boundary-bin candidate records per unit (ranked inside LDS by the finalize kernel)
 constexpr float kNegBig = -1.0e30f;
 
 struct bf16_t {
@@ -34,7 +33,6 @@ struct Shape {
   int tokA, nblkA;  // histogram kernel: tokens per workgroup, workgroups per unit
   int tokC, nblkC;  // select kernel: tokens per workgroup, workgroups per unit
   int rowsP, nblkP; // list-attention kernel: rows per workgroup, workgroups per unit
-  int grpC, ngrp;   // select workgroups per group whose states are folded first, and groups per unit (0, 0: no such level)
   int npart;        // partial slots per unit
   int binStride;    // stored bins per unit (nblkC * tokC)
   int stageStride;  // 8-byte words between the staging slots of consecutive select workgroups: tokC plus a pad, so that
@@ -45,7 +43,7 @@ struct Shape {
   float scale_log2e;
 };
 
-// Record of one boundary-bin candidate: enough for the unit's last workgroup to rank it and,
+// Record of one boundary-bin candidate: enough for the finalize kernel to rank it and,
 // if admitted, to add it to the attention output without touching the K/V cache again.
 struct CandHeader {
   unsigned long long composite;  // (score key, ~token): larger ranks first
@@ -59,12 +57,8 @@ struct Workspace {
   BinParams* ctl;              // [units]                       score -> bin map of the unit
   float* lut;                  // [units][M][C]
   float2* range;               // [units]                       (min, max) score, stand-alone top-k only
-  unsigned* hist;              // [units][histCopies][kNB]   zero between uses (room for kHistCopies replicas)
-  unsigned* cand_count;        // [units]   records handed out so far (directly behind hist, zeroed with it)
-  unsigned* ticket;            // [units]   groups (or select workgroups) of the unit that have finished (zeroed with hist)
-  unsigned* gticket;           // [units][kMaxGroups]   select workgroups of the group that have finished (likewise)
-  unsigned long long* pub;     // [units][nblkC]   per select workgroup (candidates << 32) | (list size + 1), 0: not known yet (likewise)
-  float* gparts;               // [units][kMaxGroups][G][kD+2]   the groups' folded softmax states
+  unsigned* hist;              // [2][units][histCopies][kNB]   zero between uses (room for kHistCopies replicas)
+  unsigned* cand_count;        // [2][units]   records handed out so far (directly behind hist, zeroed with it)
   unsigned short* bins;        // [units][binStride]  per token: bin + 1, or kBinWindow inside the two windows
   unsigned char* cand_rec;     // [units][kCandRec] records of rec_stride bytes, in order of arrival
   unsigned long long* stage;   // [units][nblkC][stageStride]: selected ids (front, int32) / candidate composites (ending at word tokC)
@@ -72,7 +66,7 @@ struct Workspace {
   float* partials;             // [units][npart][G][kD+2]
   int rec_stride;
 #ifdef PQC_TRACE
-  unsigned long long* trace;   // [3 phases][kTraceWgs][kTraceSlots] time stamps (debug builds only)
+  unsigned long long* trace;   // [3 kernels][kTraceWgs][kTraceSlots] time stamps (debug builds only)
 #endif
 };
 
@@ -107,19 +101,6 @@ constexpr int kTraceWgs = 4096, kTraceSlots = 16;
 // (left alone it tends to interleave load and use to save registers, which turns one
 // memory round trip into many).
 #define PQC_LOADS_ISSUED() __builtin_amdgcn_sched_barrier(0)
-
-// Stores whose values another workgroup of the same launch reads: written through to device memory (agent scope),
-// because the L2 caches of the chip's XCDs are not coherent with each other for ordinary stores, and writing a
-// whole L2 back from every workgroup instead (a release fence) takes far longer than the kernel itself.
-template <class V>
-__device__ __forceinline__ void store_through(V* p, V v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void store_through16(void* p, const uint4& v) {
-  unsigned long long* q = static_cast<unsigned long long*>(p);
-  store_through(q, ((unsigned long long)v.y << 32) | v.x);
-  store_through(q + 1, ((unsigned long long)v.w << 32) | v.z);
-}
 
 // ---------------------------------------------------------------- small helpers
 __device__ __forceinline__ unsigned score_key(float f) {
@@ -259,38 +240,6 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* total, int* sm /
   return res;
 }
 
-// The same for two values at once (one set of barriers).
-template <int NT>
-__device__ __forceinline__ int2 block_exclusive_scan2(int a, int b, int2* total, int* sm /* [2*(2*(NT/64)+1)] */) {
-  constexpr int NW = NT / 64;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int ia = wave_inclusive_scan(a), ib = wave_inclusive_scan(b);
-  int* sa = sm;
-  int* sb = sm + 2 * NW + 1;
-  if (lane == 63) {
-    sa[w] = ia;
-    sb[w] = ib;
-  }
-  __syncthreads();
-  if (w == 0) {
-    const int xa = lane < NW ? sa[lane] : 0, xb = lane < NW ? sb[lane] : 0;
-    const int ya = wave_inclusive_scan(xa), yb = wave_inclusive_scan(xb);
-    if (lane < NW) {
-      sa[NW + lane] = ya - xa;
-      sb[NW + lane] = yb - xb;
-    }
-    if (lane == NW - 1) {
-      sa[2 * NW] = ya;
-      sb[2 * NW] = yb;
-    }
-  }
-  __syncthreads();
-  const int2 res = make_int2(ia - a + sa[NW + w], ib - b + sb[NW + w]);
-  *total = make_int2(sa[2 * NW], sb[2 * NW]);
-  __syncthreads();
-  return res;
-}
-
 // --------------------------------------------------------------- look-up table
 // Section 2.2 (search) / Section 3.1 step 4: table[j][c] = qs[j*Dm..] . cent[j][c][..]
 // with qs the sum of the group's query heads.  Fixed fp32 order: head order for
@@ -322,7 +271,8 @@ __host__ __device__ constexpr int lut_row_stride(int M) { return M <= 2 ? kD / M
 __host__ __device__ constexpr int lut_tile_floats(int nt, int M, int C) {
   return nt >= 1024 ? M * C * lut_row_stride(M) : kLutTileFloats + kLutTileFloats / (kD / M);
 }
-template <typename T, int NT, int M, class MarkFn, class IssueFn>
+// VWP (whole-table mode): 16-byte pieces of the table per thread; VWP * NT * 4 floats must cover M*C*Dm.
+template <typename T, int NT, int M, class MarkFn, class IssueFn, int VWP = (256 * kD) / (4 * NT)>
 __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] of this unit */,
                                                const float* __restrict__ cent /* [M][C][Dm] */, int G, int C,
                                                float* lut, float* qs, float* red /* [4*8] */,
@@ -330,16 +280,19 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
                                                IssueFn issue_more /* the caller's own loads, queued behind the table's */) {
   constexpr int Dm = kD / M, RS = lut_row_stride(M);
   constexpr bool kWhole = NT >= 1024;
-  constexpr int VW = kWhole ? (256 * kD) / (4 * NT) : 1;  // float4 per thread for the largest table
+  constexpr int VW = kWhole ? VWP : 1;                    // float4 per thread
   constexpr int VPG = kLutTileFloats / (4 * NT);      // float4 per thread per tile (piecewise mode)
   constexpr int NG = (256 * kD) / kLutTileFloats;      // tiles at the largest C (piecewise mode)
   const int tid = threadIdx.x;
   const int total = M * C * Dm;                        // floats, a multiple of 4
   const float4* cent4 = reinterpret_cast<const float4*>(cent);
-  float4 vw[VW];
+  // (a native vector type: a float4 struct copied from global memory to LDS is turned into one 16-byte copy at
+  // the place of the store, which puts every load behind the waits in front of it, one round trip after the other)
+  const f32x4_t* centv = reinterpret_cast<const f32x4_t*>(cent);
+  f32x4_t vw[VW];
   if constexpr (kWhole) {
 #pragma unroll
-    for (int x = 0; x < VW; ++x) vw[x] = cent4[min(x * NT + tid, total / 4 - 1)];
+    for (int x = 0; x < VW; ++x) vw[x] = centv[min(x * NT + tid, total / 4 - 1)];
   }
   {
     // the group's query heads: all loads first (clamped, straight-line), then the sum in head order
@@ -358,28 +311,37 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
       const float t = __fadd_rn(a, qv[h]);
       a = h < G ? t : a;  // select, not branch: keeps the eight loads above in flight together
     }
-    if (tid < kD) qs[tid] = a;
+    qs[dq] = a;  // every thread (tid and tid + kD hold the same sum): a branch here would split the block, and the
+                 // compiler would then move the centroid loads above down to their use, behind this wait
   }
   mark(8);
   if constexpr (kWhole) {
 #pragma unroll
     for (int x = 0; x < VW; ++x) {
-      const int fl = (x * NT + tid) * 4;  // float index inside the table
-      if (fl < total) {
-        const int row = fl / Dm, col = fl % Dm;  // Dm is a multiple of 4: one row per float4
-        float* dst = tile + row * RS + col;
-        if constexpr (RS % 4 == 0) {
-          *reinterpret_cast<float4*>(dst) = vw[x];
-        } else {
-          dst[0] = vw[x].x; dst[1] = vw[x].y; dst[2] = vw[x].z; dst[3] = vw[x].w;
-        }
+      // No branch around the store: a thread beyond the table holds the table's last float4 (its load was clamped)
+      // and writes it to that float4's place once more.  With a branch here the compiler moves each load down into
+      // its branch and waits for it there, one memory round trip after the other.
+      const int fl = min((x * NT + tid) * 4, total - 4);  // float index inside the table
+      const int row = fl / Dm, col = fl % Dm;             // Dm is a multiple of 4: one row per float4
+      float* dst = tile + row * RS + col;
+      if constexpr (RS % 4 == 0) {
+        *reinterpret_cast<f32x4_t*>(dst) = vw[x];
+      } else {
+        dst[0] = vw[x][0]; dst[1] = vw[x][1]; dst[2] = vw[x][2]; dst[3] = vw[x][3];
       }
     }
-    __syncthreads();  // tile and qs visible
-    for (int e = tid; e < M * C; e += NT) {
-      const int j = e / C, c = e - j * C;
+    unsigned* mm = reinterpret_cast<unsigned*>(red);  // [0..8): smallest entry of a partition, [8..16): largest, as score keys
+    if (tid < 16) mm[tid] = tid < 8 ? 0xffffffffu : 0u;
+    mark(10);
+    __syncthreads();  // tile, qs and mm visible
+    mark(11);
+    for (int e0 = 0; e0 + (tid & ~63) < M * C; e0 += NT) {  // per wave: the wave-wide reductions below need every lane
+      const int e = e0 + tid;
+      const bool valid = e < M * C;
+      const int ec = valid ? e : 0;
+      const int j = ec / C, c = ec - j * C;
       const float* qj = qs + j * Dm;
-      const float* cr = tile + e * RS;
+      const float* cr = tile + ec * RS;
       float p = 0.0f;
       if constexpr (RS % 4 == 0) {
 #pragma unroll
@@ -400,7 +362,19 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
           p = __fmaf_rn(qq.w, cr[4 * x + 3], p);
         }
       }
-      lut[j * kLutRow + c] = p;
+      if (valid) lut[j * kLutRow + c] = p;
+      // the partition's smallest and largest entry (as order-preserving keys): one pair of LDS atomics per wave
+      // when the wave's 64 entries lie in one partition, else one pair per entry
+      if ((C & 63) == 0) {  // uniform
+        const float pmin = wave_min(valid ? p : INFINITY), pmax = wave_max(valid ? p : -INFINITY);
+        if ((tid & 63) == 0 && valid) {  // the wave's first entry is valid whenever any is
+          atomicMin(&mm[j], score_key(pmin));
+          atomicMax(&mm[8 + j], score_key(pmax));
+        }
+      } else if (valid) {
+        atomicMin(&mm[j], score_key(p));
+        atomicMax(&mm[8 + j], score_key(p));
+      }
     }
     mark(9);
   } else {
@@ -440,6 +414,16 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
   }
   __syncthreads();
   mark(13);
+  if constexpr (kWhole) {
+    // bounds are added in the same order as a score, so lo <= score <= hi holds in fp32
+    const unsigned* mm = reinterpret_cast<const unsigned*>(red);
+    float lo = key_score(mm[0]), hi = key_score(mm[8]);
+    for (int j = 1; j < M; ++j) {
+      lo = __fadd_rn(lo, key_score(mm[j]));
+      hi = __fadd_rn(hi, key_score(mm[8 + j]));
+    }
+    return make_float2(lo, hi);
+  }
   // per table: min and max (one wave per table)
   const int lane = tid & 63, w = tid >> 6;
   for (int j = w; j < M; j += NT / 64) {
@@ -467,48 +451,56 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
 }
 
 // Where the fine bins go: every workgroup of a unit scores the same `n` sampled tokens,
-// histograms them over kNB uniform bins of [lo, hi] and takes the bins that hold the
+// histograms them over kSampleBins uniform bins of [lo, hi] and takes the bins that hold the
 // sample's rank_hi-th and rank_lo-th largest scores as the window.  The ranks bracket
 // the K-th largest of all tokens by several standard errors of the sample quantile, so
 // the window almost always holds it (and when it does not, only speed is lost).
-//   hist  LDS [kNB], zero on entry, zero again on return      sm  LDS [2*(NT/64)+1+2]
+// Two barriers: the samples are counted, then the first wave alone walks the histogram
+// (four bins per lane, a wave-wide prefix sum) and clears it again.
+//   hist  LDS [>= kSampleBins], zero on entry, zero again on return      sm  LDS [2]
+constexpr int kSampleBins = 256;
 template <int NT>
 __device__ __forceinline__ BinParams sample_window(float lo, float hi, float my_score, bool have_sample, int rank_hi,
                                                    int rank_lo, unsigned* hist, int* sm) {
-  constexpr int PER = kNB / NT, NW = NT / 64;
+  constexpr int NBS = kSampleBins, PER = NBS / 64;
+  static_assert(PER == 4, "one 16-byte access per lane");
   const int tid = threadIdx.x;
   const float width = hi - lo;
-  const float inv_u = (width > 1e-30f && width < 3e38f) ? (float)kNB / width : 0.0f;
-  if (have_sample) atomicAdd(&hist[max(0, min(kNB - 1, __float2int_rz((my_score - lo) * inv_u)))], 1u);
+  const float inv_u = (width > 1e-30f && width < 3e38f) ? (float)NBS / width : 0.0f;
+  if (have_sample) atomicAdd(&hist[max(0, min(NBS - 1, __float2int_rz((my_score - lo) * inv_u)))], 1u);
   __syncthreads();
-  unsigned h[PER];
-  int sum = 0;
+  if (tid < 64) {  // lane l owns bins [NBS - (l+1)*PER, NBS - l*PER): the lanes run from the top bin down
+    uint4* mine = reinterpret_cast<uint4*>(hist + NBS - (tid + 1) * PER);
+    const uint4 x = *mine;
+    *mine = make_uint4(0u, 0u, 0u, 0u);
+    const int h[PER] = {(int)x.x, (int)x.y, (int)x.z, (int)x.w};
+    const int sum = h[0] + h[1] + h[2] + h[3];
+    int cum = wave_inclusive_scan(sum) - sum;  // samples in the bins above this lane's
+    int r0 = -1, r1 = -1;
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    h[e] = hist[kNB - 1 - (tid * PER + e)];
-    sum += (int)h[e];
-  }
-  int total;
-  int cum = block_exclusive_scan<NT>(sum, &total, sm);
-  int* res = sm + 2 * NW + 1;
-  if (tid == 0) {
-    res[0] = -1;
-    res[1] = -1;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    const int b = kNB - 1 - (tid * PER + e);
-    if (rank_hi >= 1 && cum < rank_hi && cum + (int)h[e] >= rank_hi) res[0] = b;
-    if (rank_lo >= 1 && cum < rank_lo && cum + (int)h[e] >= rank_lo) res[1] = b;
-    cum += (int)h[e];
-    hist[b] = 0u;
+    for (int e = PER - 1; e >= 0; --e) {  // this lane's bins, from its top one down
+      const int b = NBS - (tid + 1) * PER + e;
+      if (rank_hi >= 1 && cum < rank_hi && cum + h[e] >= rank_hi) r0 = b;
+      if (rank_lo >= 1 && cum < rank_lo && cum + h[e] >= rank_lo) r1 = b;
+      cum += h[e];
+    }
+    // at most one lane finds each of the two bins: a wave-wide maximum, read from the last lane
+    r0 = max(r0, dpp_i<0x111>(-1, r0)); r1 = max(r1, dpp_i<0x111>(-1, r1));
+    r0 = max(r0, dpp_i<0x112>(-1, r0)); r1 = max(r1, dpp_i<0x112>(-1, r1));
+    r0 = max(r0, dpp_i<0x114>(-1, r0)); r1 = max(r1, dpp_i<0x114>(-1, r1));
+    r0 = max(r0, dpp_i<0x118>(-1, r0)); r1 = max(r1, dpp_i<0x118>(-1, r1));
+    r0 = max(r0, dpp_i<0x142, 0xa>(-1, r0)); r1 = max(r1, dpp_i<0x142, 0xa>(-1, r1));
+    r0 = max(r0, dpp_i<0x143, 0xc>(-1, r0)); r1 = max(r1, dpp_i<0x143, 0xc>(-1, r1));
+    if (tid == 63) {
+      sm[0] = r0;
+      sm[1] = r1;
+    }
   }
   __syncthreads();
-  const float wu = width * (1.0f / (float)kNB);
-  const float q_hi = res[0] >= 0 ? lo + (float)(res[0] + 1) * wu : hi;
-  const float q_lo = res[1] >= 0 ? lo + (float)res[1] * wu : lo;
-  __syncthreads();
+  const int b_hi = sm[0], b_lo = sm[1];
+  const float wu = width * (1.0f / (float)NBS);
+  const float q_hi = b_hi >= 0 ? lo + (float)(b_hi + 1) * wu : hi;
+  const float q_lo = b_lo >= 0 ? lo + (float)b_lo * wu : lo;
   return make_bins(lo, hi, q_lo, q_hi);
 }
 
@@ -873,7 +865,6 @@ struct RowRaw<bf16_t> {
     f[7] = __uint_as_float(a.w & 0xffff0000u);
   }
   __device__ __forceinline__ void store(unsigned char* dst, int sub) const { *reinterpret_cast<uint4*>(dst + sub * 16) = a; }
-  __device__ __forceinline__ void store_through(unsigned char* dst, int sub) const { store_through16(dst + sub * 16, a); }
 };
 template <>
 struct RowRaw<float> {
@@ -897,10 +888,6 @@ struct RowRaw<float> {
   __device__ __forceinline__ void store(unsigned char* dst, int sub) const {
     *reinterpret_cast<float4*>(dst + sub * 16) = a;
     *reinterpret_cast<float4*>(dst + 256 + sub * 16) = b;
-  }
-  __device__ __forceinline__ void store_through(unsigned char* dst, int sub) const {
-    store_through16(dst + sub * 16, make_uint4(__float_as_uint(a.x), __float_as_uint(a.y), __float_as_uint(a.z), __float_as_uint(a.w)));
-    store_through16(dst + 256 + sub * 16, make_uint4(__float_as_uint(b.x), __float_as_uint(b.y), __float_as_uint(b.z), __float_as_uint(b.w)));
   }
 };
 
@@ -1229,38 +1216,27 @@ __device__ __forceinline__ void mfma_consume(const MfmaStage& g, int count, int 
   }
 }
 
-// Rows list(first), list(first+1), ... in stages of 16*kMfmaTiles positions, `stride` apart.  after_first() is
-// called once, when the first stage has been consumed (at once for a wave without rows): whatever the caller
-// requested from memory before the call has arrived by then, because a wave's loads and returning atomics
-// come back in issue order, so the caller can put such a value away there without waiting for it and without
-// holding its register through the loop.
-template <class ListFn, class FirstFn>
+// Rows list(first), list(first+1), ... in stages of 16*kMfmaTiles positions, `stride` apart.
+template <class ListFn>
 __device__ __forceinline__ void mfma_attend(const bf16_t* __restrict__ kbase, const bf16_t* __restrict__ vbase, int N,
                                             ListFn list, int count, int first, int stride, float scale_log2e,
                                             const bf16x8_t (&qf)[4], unsigned char* vt /* wave-private LDS [kVTileBytes] */,
-                                            MfmaState& st, FirstFn after_first) {
-  if (first >= count) {  // wave-uniform
-    after_first();
-    return;
-  }
+                                            MfmaState& st) {
+  if (first >= count) return;  // wave-uniform
   MfmaStage ga, gb;
   int base = first;
   mfma_issue(kbase, vbase, N, list, count, base, ga);
-  mfma_issue(kbase, vbase, N, list, count, base + stride, gb);
-  PQC_LOADS_ISSUED();
-  mfma_consume(ga, count, base, scale_log2e, qf, vt, st);
-  after_first();
-  base += stride;
-  while (base < count) {
+  for (;;) {
+    mfma_issue(kbase, vbase, N, list, count, base + stride, gb);
+    PQC_LOADS_ISSUED();
+    mfma_consume(ga, count, base, scale_log2e, qf, vt, st);
+    base += stride;
+    if (base >= count) break;
     mfma_issue(kbase, vbase, N, list, count, base + stride, ga);
     PQC_LOADS_ISSUED();
     mfma_consume(gb, count, base, scale_log2e, qf, vt, st);
     base += stride;
     if (base >= count) break;
-    mfma_issue(kbase, vbase, N, list, count, base + stride, gb);
-    PQC_LOADS_ISSUED();
-    mfma_consume(ga, count, base, scale_log2e, qf, vt, st);
-    base += stride;
   }
 }
 

@@ -1,19 +1,18 @@
 // Kernels of libpqcache (gfx950).  Grid layout: blockIdx.y = unit (sequence b, KV
-// head g); blockIdx.x = workgroup inside the unit.
+// head g); blockIdx.x = workgroup inside the unit (query head for finalize_kernel).
 //
-// Decode path (pqc_decode), two launches; the one dependency between all workgroups of a
-// unit that needs every one of them to be done sits at the kernel boundary, the other is
-// settled by whichever workgroup finishes last (nobody ever waits inside a kernel):
+// Decode path (pqc_decode), three launches, every dependency at a kernel boundary:
 //   hist_kernel      table -> scan codes -> histogram of scores over kNB bins, and every
 //                    token's bin number left behind for the next kernel
 //   select_kernel    threshold bin from the histogram -> tokens whose stored bin lies
 //                    above it (and the two windows) are listed in ascending order
 //                    without atomics and attended at once; tokens inside the bin
-//                    ("candidates") are recorded with their logits and V row.  The unit's
-//                    last workgroup to finish then ranks the candidates, folds the
-//                    admitted ones and all partial softmax states into the output, writes
-//                    the indices and zeroes the unit's histogram and counters again:
-//                    every call leaves them as it found them
+//                    ("candidates") are recorded with their logits and V row
+//   finalize_kernel  one workgroup per query head ranks the candidates and folds the
+//                    admitted ones and all partial softmax states into the output;
+//                    copy workgroups beside them write the indices and zero the unit's
+//                    histogram and record counter again, which nothing reads after the
+//                    select kernel: every call leaves them as it found them
 //
 // Codes are read 16 bytes at a time (P = 16/M tokens).  A unit's codes start at byte
 // u*N*M, which need not be 16-byte aligned: chunks are laid over the aligned-down
@@ -188,10 +187,15 @@ __global__ __launch_bounds__(1024) void score_range_kernel(Shape s, const float*
 // then derives the same bin layout from the same sampled tokens (workgroup 0 publishes
 // table and layout for the select kernel) and counts its own tokens.  Workgroups of a
 // unit spread their counts over histCopies replicas.
-template <typename T, class SRC>
+// VW: 16-byte pieces of the centroid tensor per thread (1024 * 4 * VW floats cover the unit's M*C*Dm);
+// VA: 16-byte chunks of codes (or scores) per thread (1024 * VA chunks cover the workgroup's tokA tokens).
+// Both are template parameters so that no thread issues loads it does not need: the loads of a workgroup's
+// sixteen waves go through one address unit, 64 bytes per clock, and redundant ones cost as much as real ones.
+template <typename T, class SRC, int VW, int VA>
 __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const T* __restrict__ q,
                                                     const float* __restrict__ cent, const void* __restrict__ src_ptr) {
   constexpr int NT = 1024, P = SRC::P;
+  static_assert(VA >= 1 && VA <= kMaxVecA, "chunks per thread");
   constexpr int LM = SRC::kFromCodes ? SRC::M : 1;
   __shared__ float lut[LM * kLutRow];
   __shared__ __attribute__((aligned(16))) float qs[kD];
@@ -222,12 +226,12 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   // this workgroup's chunks and this thread's sample: the loads are issued before anything else,
   // except that a table build puts its centroid loads in front of them
   const int chunks = s.tokA / P, chunk0 = bx * chunks;
-  typename SRC::Raw raw[kMaxVecA];
+  typename SRC::Raw raw[VA];
   typename SRC::One sample;
   const bool have_sample = tid < s.sampleN;
   auto issue_loads = [&]() {
 #pragma unroll
-    for (int v = 0; v < kMaxVecA; ++v) raw[v] = src.load(chunk0 + min(v * NT + tid, chunks - 1));
+    for (int v = 0; v < VA; ++v) raw[v] = src.load(chunk0 + min(v * NT + tid, chunks - 1));
     const int sample_i = min(tid, s.sampleN - 1);
     sample = src.load_one(min(s.N - 1, s.I + (int)(((long long)sample_i * max(0, s.N - s.I - s.L)) / s.sampleN)), u, src_stride);
   };
@@ -235,9 +239,10 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   if constexpr (SRC::kFromCodes) {
     const int b = u / s.Hkv, g = u % s.Hkv;
     for (int i = tid; i < kNB; i += NT) hist[i] = 0u;
-    bounds = build_lut<T, NT, LM>(
+    auto mark = [&](int slot) { PQC_MARK(ws, 0, slot); };
+    bounds = build_lut<T, NT, LM, decltype(mark), decltype(issue_loads), VW>(
         q + ((size_t)b * s.Hq + (size_t)g * s.G) * kD, cent + (size_t)u * LM * s.C * (kD / LM), s.G, s.C, lut, qs, red, tile,
-        [&](int slot) { PQC_MARK(ws, 0, slot); }, issue_loads);
+        mark, issue_loads);
     if (bx == 0)
       for (int e = tid; e < LM * s.C; e += NT) ws.lut[(size_t)u * LM * s.C + e] = lut[(e / s.C) * kLutRow + (e % s.C)];
   } else {
@@ -249,7 +254,7 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   }
   PQC_MARK(ws, 0, 1);
 #pragma unroll
-  for (int v = 0; v < kMaxVecA; ++v) src.fix_tail(raw[v], chunk0 + min(v * NT + tid, chunks - 1));
+  for (int v = 0; v < VA; ++v) src.fix_tail(raw[v], chunk0 + min(v * NT + tid, chunks - 1));
   const BinParams bp =
       sample_window<NT>(bounds.x, bounds.y, src.score_one(sample), have_sample, s.rankHi, s.rankLo, hist, scan_sm);
   if (bx == 0 && tid == 0) ws.ctl[u] = bp;
@@ -260,7 +265,7 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   int n_low = 0;
   unsigned short* bins_u = ws.bins + (size_t)u * s.binStride;
 #pragma unroll
-  for (int v = 0; v < kMaxVecA; ++v) {
+  for (int v = 0; v < VA; ++v) {
     if (v * NT + tid < chunks) {
       const int t0 = (chunk0 + v * NT + tid) * P - src.lead;
       unsigned st[P];  // what the select kernel will read back: bin + 1, or the window mark
@@ -306,496 +311,8 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
   PQC_MARK(ws, 0, 4);
 }
 
-// ------------------------------------------------------ 2. finishing a unit
-// The select workgroups of a unit each leave a partial softmax state per query head and their boundary-bin
-// candidates behind.  Nobody ever waits for anybody inside the kernel: whoever finishes last does the next step,
-// which it learns from a ticket drawn with one returning atomic.
-//   - Groups of grpC consecutive workgroups: the last one of a group folds the group's partial states into one
-//     (fold_group), so that the unit's last workgroup has few states to read: a single compute unit reads
-//     memory that other compute units wrote at a small fraction of the chip's bandwidth, so what it reads must be small.
-//     (Units with at most grpC workgroups skip this level.)
-//   - The unit's last workgroup (finalize_unit) ranks the candidates and admits the K - n_above best (at most
-//     kCandRec candidates: all that is needed sits in their records, which arrive in a different order on every
-//     run, so every sum over candidates is taken in rank order; more candidates: an 8-bit radix select over the
-//     composites staged per workgroup, the admitted rows being attended from the K/V cache), folds the group
-//     states (in order) and the admitted rows into out_attn, writes the admitted candidates' indices, and zeroes
-//     the unit's histogram and counters again, which nothing reads after this point: every call leaves them as it
-//     found them.
-// Index output: every select workgroup publishes its list sizes as soon as it has classified its tokens; when it
-// is done attending it reads the sizes of all workgroups of the unit and, if they are all there (they practically
-// always are), writes its list straight into out_idx behind those of the workgroups before it.  Otherwise it
-// stages the list and the unit's last workgroup copies it.  In workgroup order the lists read
-//     [0..I) , tokens above the threshold bin (ascending) , [N-L..N)
-// and the admitted candidates go between the second and the third part.
-constexpr int kVBatch = 32;                     // admitted candidates' V elements a thread keeps in flight
-constexpr int kMaxGroups = 128;                 // groups per unit, at most (kMaxBlkC / 4)
-constexpr unsigned kStagedFlag = 0x40000000u;   // in a stored list size: the list sits in its staging slot, not in out_idx
-template <int G>
-constexpr int fold_width() { return G >= 8 ? 4 : 8; }  // states folded at once = workgroups per group (about 16 KB of states)
-
-// The code of one appended token per unit (Section 3.1: nearest centroid of each partition): nothing in the
-// step depends on it, so one more workgroup per unit of the select kernel computes it beside the others.
-struct AppendArgs {
-  const void* key;    // [units][kD] in the cache's element type, or null: nothing to append
-  const float* cent;  // [units][M][C][Dm]
-  uint8_t* codes;     // the code tensor; written at `position` of every unit
-  int position;
-  unsigned* pair_counts;  // two partitions: [units][C*C] counts that gain the token's code pair, or null
-};
-
-// Softmax states of the heads a thread owns (heads hb, hb + 2, ... of the group; one head when the group has one),
-// for output dimension d.
-template <int G>
-struct Folded {
-  static constexpr int HPT = G >= 2 ? G / 2 : 1;
-  float m[HPT], l[HPT], acc[HPT];
-  __device__ __forceinline__ void init() {
-#pragma unroll
-    for (int i = 0; i < HPT; ++i) {
-      m[i] = kNegBig;
-      l[i] = 0.0f;
-      acc[i] = 0.0f;
-    }
-  }
-};
-
-// Folds `count` states -- per state G heads of { m, l, acc[kD] } -- into r, in order, fold_width() states at a time
-// (all their loads in flight together).  The result depends on the states and their order alone.
-template <int G>
-__device__ __forceinline__ void fold_states(const float* __restrict__ src, int count, int d, int hb, Folded<G>& r) {
-  constexpr int F = fold_width<G>(), HPT = Folded<G>::HPT;
-  constexpr size_t stride = (size_t)G * (kD + 2);
-#pragma unroll 1
-  for (int j0 = 0; j0 < count; j0 += F) {
-    float2 ml[HPT][F];
-    float a[HPT][F];
-#pragma unroll
-    for (int x = 0; x < F; ++x) {
-      const float* p = src + (size_t)min(j0 + x, count - 1) * stride;
-#pragma unroll
-      for (int i = 0; i < HPT; ++i) {
-        const float* ph = p + (G >= 2 ? hb + 2 * i : 0) * (kD + 2);
-        ml[i][x] = *reinterpret_cast<const float2*>(ph);
-        a[i][x] = ph[2 + d];
-      }
-    }
-    PQC_LOADS_ISSUED();
-#pragma unroll
-    for (int i = 0; i < HPT; ++i) {
-      float mc = r.m[i];
-#pragma unroll
-      for (int x = 0; x < F; ++x) mc = j0 + x < count ? fmaxf(mc, ml[i][x].x) : mc;
-      const float f = __builtin_amdgcn_exp2f(r.m[i] - mc);
-      r.l[i] *= f;
-      r.acc[i] *= f;
-      r.m[i] = mc;
-#pragma unroll
-      for (int x = 0; x < F; ++x) {
-        const float wv = j0 + x < count ? __builtin_amdgcn_exp2f(ml[i][x].x - mc) : 0.0f;
-        r.l[i] = fmaf(wv, ml[i][x].y, r.l[i]);
-        r.acc[i] = fmaf(wv, a[i][x], r.acc[i]);
-      }
-    }
-  }
-}
-
-template <int G, bool ATTN>
-struct TailLds {
-  static constexpr int NW = 4, GA = ATTN ? G : 1, GG = GA > 4 ? 4 : GA;
-  struct Few {                            // at most kCandRec candidates: ranked here
-    unsigned long long comp[kCandRec];    // composites in record order
-    float lg[GA][kCandRec];               // by rank: logit of head h (log2 domain)
-    unsigned short ordv[kCandRec];        // by rank: record
-  };
-  struct Many {                           // more: radix select, admitted rows attended from the cache
-    unsigned rhist[256];
-    int digit[2];
-    int rows[256];
-    float red[ATTN ? NW * GG * (kD + 2) : 1];
-    float xacc[GA][kD];                   // one more state per head: the admitted rows
-    float xm[8], xl[8];
-  };
-  union {
-    Few few;
-    Many many;
-  };
-  int lsize[kMaxBlkC];                    // list sizes as stored (with kStagedFlag); only when a list was staged
-  int pre_sel[kMaxBlkC + 1];              // exclusive prefix sums of the list sizes; likewise
-  int pre_cand[kMaxBlkC + 1];             // and of the staged candidate counts (radix path)
-  int scan_sm[2 * (2 * NW + 1)];
-  int tot[3 * NW];
-};
-
-template <typename T, int G, bool ATTN>
-__device__ __forceinline__ void finalize_unit(const Shape& s, const Workspace& ws, int u, const T* __restrict__ q,
-                                              const T* __restrict__ kc, const T* __restrict__ vc, int* __restrict__ out_idx,
-                                              float* __restrict__ out_attn, const AppendArgs& ap, TailLds<G, ATTN>& L,
-                                              Folded<ATTN ? G : 1>& r /* the unit's folded states, for this thread's heads */) {
-  constexpr int NT = 256, NW = 4;
-  constexpr int GA = ATTN ? G : 1;
-  constexpr int HPT = Folded<GA>::HPT;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int b = u / s.Hkv, g = u % s.Hkv, nb = s.nblkC;
-  const int2* cnt = ws.stage_cnt + (size_t)u * nb;
-  const unsigned long long* stage_u = ws.stage + (size_t)u * nb * s.stageStride;
-  const unsigned char* recs = ws.cand_rec + (size_t)u * kCandRec * ws.rec_stride;
-  int* out = out_idx + (size_t)u * s.Ktot;
-  const int d = tid & (kD - 1), hb = tid >> 7;  // output dimension; first head of this thread
-  const bool owner = GA >= 2 || hb == 0;        // this thread owns outputs
-  PQC_MARK(ws, 2, 0);
-
-  // ---- everything whose address is known up front is requested first
-  const int2 c0 = cnt[min(tid, nb - 1)], c1 = cnt[min(tid + NT, nb - 1)];  // nb <= 2 * NT
-  unsigned long long rc[kCandRec / NT];  // record x*NT + tid
-  float rl[kCandRec / NT][GA];
-  {
-    const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)tid * ws.rec_stride);
-    rc[0] = hd->composite;
-#pragma unroll
-    for (int h = 0; h < GA; ++h) rl[0][h] = ATTN ? hd->logit[h] : 0.0f;
-  }
-  // ---- totals of the list sizes
-  int n_list, n_cand;
-  bool any_staged;
-  {
-    int vs = 0, vc2 = 0, vf = 0;
-    if (tid < nb) {
-      vs = c0.x & (int)~kStagedFlag;
-      vc2 = c0.y;
-      vf = (c0.x & (int)kStagedFlag) ? 1 : 0;
-    }
-    if (tid + NT < nb) {
-      vs += c1.x & (int)~kStagedFlag;
-      vc2 += c1.y;
-      vf += (c1.x & (int)kStagedFlag) ? 1 : 0;
-    }
-    vs = wave_last(wave_inclusive_scan(vs));
-    vc2 = wave_last(wave_inclusive_scan(vc2));
-    vf = wave_last(wave_inclusive_scan(vf));
-    if (lane == 0) {
-      L.tot[w] = vs;
-      L.tot[NW + w] = vc2;
-      L.tot[2 * NW + w] = vf;
-    }
-    __syncthreads();
-    n_list = 0;
-    n_cand = 0;
-    int nf = 0;
-#pragma unroll
-    for (int i = 0; i < NW; ++i) {
-      n_list += L.tot[i];
-      n_cand += L.tot[NW + i];
-      nf += L.tot[2 * NW + i];
-    }
-    any_staged = nf > 0;
-  }
-  const int n_above = max(0, n_list - s.I - s.L);  // n_list = I + (tokens above the bin) + L
-  const int need = max(0, min(s.K - n_above, n_cand));
-  PQC_MARK(ws, 2, 1);
-
-  const bool few = n_cand <= kCandRec;
-  if (__builtin_expect(any_staged || !few, 0)) {
-    // exclusive prefix sums of list sizes and candidate counts
-    int2 t0, t1 = make_int2(0, 0);
-    const int2 p0 = block_exclusive_scan2<NT>(tid < nb ? c0.x & (int)~kStagedFlag : 0, tid < nb ? c0.y : 0, &t0, L.scan_sm);
-    if (tid < nb) {
-      L.pre_sel[tid] = p0.x;
-      L.pre_cand[tid] = p0.y;
-      L.lsize[tid] = c0.x;
-    }
-    if (nb > NT) {  // uniform
-      const int2 p1 = block_exclusive_scan2<NT>(tid + NT < nb ? c1.x & (int)~kStagedFlag : 0, tid + NT < nb ? c1.y : 0, &t1, L.scan_sm);
-      if (tid + NT < nb) {
-        L.pre_sel[tid + NT] = t0.x + p1.x;
-        L.pre_cand[tid + NT] = t0.y + p1.y;
-        L.lsize[tid + NT] = c1.x;
-      }
-    }
-    if (tid == 0) {
-      L.pre_sel[nb] = n_list;
-      L.pre_cand[nb] = n_cand;
-    }
-    __syncthreads();
-    // staged lists (rare: a workgroup that could not see every other workgroup's list size when it was done)
-#pragma unroll 1
-    for (int j = w; j < nb; j += NW) {
-      if (L.lsize[j] & (int)kStagedFlag) {
-        const int base = L.pre_sel[j], n = L.pre_sel[j + 1] - base;
-        const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.stageStride);
-#pragma unroll 1
-        for (int p = lane; p < n; p += 64) {
-          const int pos = base + p, dst = pos < s.I + n_above ? pos : pos + need;
-          if (dst < s.Ktot) out[dst] = src[p];
-        }
-      }
-    }
-  }
-  PQC_MARK(ws, 2, 2);
-
-  int need_few = 0;          // admitted candidates whose logits and V rows come from the records
-  bool extra_state = false;  // the radix path left one more state per head in LDS
-  if (__builtin_expect(few, 1)) {
-    // rank every candidate (count of larger composites); the admitted ones are the `need` best
-    if (need > 0) {
-#pragma unroll
-      for (int x = 1; x < kCandRec / NT; ++x) {
-        rc[x] = 0ull;
-#pragma unroll
-        for (int h = 0; h < GA; ++h) rl[x][h] = 0.0f;
-        if (x * NT + tid < n_cand) {  // rare: more than NT candidates
-          const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)(x * NT + tid) * ws.rec_stride);
-          rc[x] = hd->composite;
-#pragma unroll
-          for (int h = 0; h < GA; ++h) rl[x][h] = ATTN ? hd->logit[h] : 0.0f;
-        }
-      }
-#pragma unroll
-      for (int x = 0; x < kCandRec / NT; ++x)
-        if (x * NT + tid < n_cand) L.few.comp[x * NT + tid] = rc[x];
-      __syncthreads();
-#pragma unroll
-      for (int x = 0; x < kCandRec / NT; ++x) {
-        const int k = x * NT + tid;
-        if (k < n_cand) {
-          const unsigned long long mine = rc[x];
-          int rank = 0;
-#pragma unroll 1
-          for (int j0 = 0; j0 < n_cand; j0 += 8) {  // eight independent LDS reads per round
-            unsigned long long o[8];
-#pragma unroll
-            for (int y = 0; y < 8; ++y) o[y] = L.few.comp[min(j0 + y, n_cand - 1)];
-#pragma unroll
-            for (int y = 0; y < 8; ++y) rank += (j0 + y < n_cand && o[y] > mine) ? 1 : 0;
-          }
-          if (rank < need) {
-            const int dst = s.I + n_above + rank;  // best first
-            if (dst < s.Ktot) out[dst] = composite_token(mine);
-#pragma unroll
-            for (int h = 0; h < GA; ++h) L.few.lg[h][rank] = rl[x][h] * s.scale_log2e;
-            L.few.ordv[rank] = (unsigned short)k;
-          }
-        }
-      }
-    }
-    need_few = need;
-  } else {
-    // radix select of the need-th largest staged composite, 8 bits per pass
-    auto owner_of = [&](int p) -> int {  // largest j with pre_cand[j] <= p
-      int lo = 0, hi = nb - 1;
-      while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (L.pre_cand[mid] <= p) lo = mid; else hi = mid - 1;
-      }
-      return lo;
-    };
-    auto cand_at = [&](int i) -> unsigned long long {
-      const int j = owner_of(i);
-      return stage_u[(size_t)j * s.stageStride + s.tokC - 1 - (i - L.pre_cand[j])];
-    };
-    unsigned long long thr = ~0ull;
-    if (need > 0) {
-      unsigned long long prefix = 0;
-      int want = need;
-      for (int shift = 56; shift >= 0; shift -= 8) {
-        L.many.rhist[tid] = 0u;
-        __syncthreads();
-        for (int i = tid; i < n_cand; i += NT) {
-          const unsigned long long c = cand_at(i);
-          if (shift == 56 || (c >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&L.many.rhist[(unsigned)(c >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        if (tid == 0) {
-          int cum = 0, dg = 255;
-          for (; dg > 0; --dg) {
-            if (cum + (int)L.many.rhist[dg] >= want) break;
-            cum += (int)L.many.rhist[dg];
-          }
-          L.many.digit[0] = dg;
-          L.many.digit[1] = want - cum;
-        }
-        __syncthreads();
-        prefix |= (unsigned long long)L.many.digit[0] << shift;
-        want = L.many.digit[1];
-        __syncthreads();
-      }
-      thr = prefix;
-    }
-    // admitted candidates in staged order, NT candidates per round: indices out, rows attended for up to four heads
-    // at a time (the rounds are repeated for the next four)
-    constexpr int GG = TailLds<G, ATTN>::GG;
-    for (int h0 = 0; h0 < GA; h0 += GG) {
-      AttnState<GG> st;
-      st.init();
-      float qr[GG][8];
-      if constexpr (ATTN) load_query<T, GG>(q + ((size_t)b * s.Hq + (size_t)g * G + h0) * kD, s.scale_log2e, qr);
-      int carry = 0;
-      for (int i0 = 0; i0 < (need > 0 ? n_cand : 0); i0 += NT) {
-        const int i = i0 + tid;
-        unsigned long long c = 0;
-        if (i < n_cand) c = cand_at(i);
-        const int flag = (i < n_cand && c >= thr) ? 1 : 0;
-        int tot;
-        const int pos = block_exclusive_scan<NT>(flag, &tot, L.scan_sm);
-        if (flag) {
-          L.many.rows[pos] = composite_token(c);
-          const int dst = s.I + n_above + carry + pos;
-          if (h0 == 0 && dst < s.Ktot) out[dst] = composite_token(c);
-        }
-        __syncthreads();
-        if constexpr (ATTN) {
-          constexpr int R = sizeof(T) == 4 ? 2 : 4;
-          auto row_at = [&](int p) -> int { return L.many.rows[p]; };
-          attend_rows<T, GG, R>(kc + (size_t)u * s.cap * kD, vc + (size_t)u * s.cap * kD, s.N, row_at, tot, w * 4 * R, NW * 4 * R, qr, st);
-        }
-        __syncthreads();
-        carry += tot;
-      }
-      if constexpr (ATTN) {
-        stash_wave_state<T, GG>(st, L.many.red);
-        __syncthreads();
-        for (int o = tid; o < GG * kD; o += NT) {
-          const int h = o / kD, dd = o % kD;
-          float m, l, acc;
-          combine_waves<GG, NW>(L.many.red, h, dd, m, l, acc);
-          L.many.xacc[h0 + h][dd] = acc;
-          if (dd == 0) {
-            L.many.xm[h0 + h] = m;
-            L.many.xl[h0 + h] = l;
-          }
-        }
-        __syncthreads();
-        extra_state = true;
-      }
-    }
-  }
-  __syncthreads();
-  PQC_MARK(ws, 2, 3);
-
-  if constexpr (ATTN) {
-    // ---- out[h][d] = (folded states + admitted candidates, in rank order) / l
-    if (owner) {
-      int hh[HPT];
-#pragma unroll
-      for (int i = 0; i < HPT; ++i) hh[i] = G >= 2 ? hb + 2 * i : 0;
-      if (extra_state) {
-#pragma unroll
-        for (int i = 0; i < HPT; ++i) {
-          const float xm = L.many.xm[hh[i]], mc = fmaxf(r.m[i], xm);
-          const float f = __builtin_amdgcn_exp2f(r.m[i] - mc), fx = __builtin_amdgcn_exp2f(xm - mc);
-          r.l[i] = fmaf(L.many.xl[hh[i]], fx, r.l[i] * f);
-          r.acc[i] = fmaf(L.many.xacc[hh[i]][d], fx, r.acc[i] * f);
-          r.m[i] = mc;
-        }
-      }
-      if (need_few > 0) {
-#pragma unroll
-        for (int i = 0; i < HPT; ++i) {
-          float mc = r.m[i];
-#pragma unroll 4
-          for (int k = 0; k < need_few; ++k) mc = fmaxf(mc, L.few.lg[hh[i]][k]);
-          const float f = __builtin_amdgcn_exp2f(r.m[i] - mc);
-          r.l[i] *= f;
-          r.acc[i] *= f;
-          r.m[i] = mc;
-        }
-#pragma unroll 1
-        for (int r0 = 0; r0 < need_few; r0 += kVBatch) {
-          float vv[kVBatch];
-#pragma unroll
-          for (int x = 0; x < kVBatch; ++x) {
-            const int k = L.few.ordv[min(r0 + x, need_few - 1)];
-            vv[x] = load_as_float<T>(reinterpret_cast<const T*>(recs + (size_t)k * ws.rec_stride + sizeof(CandHeader)), d);
-          }
-          PQC_LOADS_ISSUED();
-#pragma unroll
-          for (int x = 0; x < kVBatch; ++x)
-#pragma unroll
-            for (int i = 0; i < HPT; ++i) {
-              const float p = r0 + x < need_few ? __builtin_amdgcn_exp2f(L.few.lg[hh[i]][min(r0 + x, need_few - 1)] - r.m[i]) : 0.0f;
-              r.l[i] += p;
-              r.acc[i] = fmaf(p, vv[x], r.acc[i]);
-            }
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < HPT; ++i) out_attn[((size_t)b * s.Hq + (size_t)g * G + hh[i]) * kD + d] = r.acc[i] / r.l[i];
-    }
-    PQC_MARK(ws, 2, 5);
-  }
-
-  // ---- every select workgroup of the unit is done with them: zero the histogram and the unit's counters
-  {
-    uint4* gh = reinterpret_cast<uint4*>(ws.hist + (size_t)u * s.histCopies * kNB);
-    for (int i = tid; i < s.histCopies * (kNB / 4); i += NT) gh[i] = make_uint4(0u, 0u, 0u, 0u);
-    for (int i = tid; i < nb; i += NT) ws.pub[(size_t)u * nb + i] = 0ull;
-    if (tid < kMaxGroups) ws.gticket[(size_t)u * kMaxGroups + tid] = 0u;
-    if (tid == 0) {
-      ws.cand_count[u] = 0u;
-      ws.ticket[u] = 0u;
-      if (ap.key && ap.pair_counts) {  // the appended token's code pair joins the counts now that nobody reads them
-        const uint8_t* cp = ap.codes + ((size_t)u * s.cap + ap.position) * 2;
-        const unsigned a0c = cp[0], a1c = cp[1];
-        if (a0c < (unsigned)s.C && a1c < (unsigned)s.C) ap.pair_counts[(size_t)u * s.C * s.C + a0c + (size_t)s.C * a1c] += 1u;
-      }
-    }
-  }
-  PQC_MARK(ws, 2, 6);
-  PQC_NOTE(ws, 2, 13, n_above);
-  PQC_NOTE(ws, 2, 14, n_cand);
-  PQC_NOTE(ws, 2, 15, need);
-}
-
-// The code of the appended token of unit u (one thread per centroid, the distance chain of pq_assign_kernel, the
-// smallest (distance, centroid) pair of each partition through a 64-bit LDS minimum).
-struct AppendLds {
-  float ax[kD];
-  unsigned long long abest[8];
-};
-template <typename T>
-__device__ __forceinline__ void append_token(const Shape& s, const AppendArgs& ap, int u, AppendLds& A) {
-  const int c = threadIdx.x;
-  if (c < kD) A.ax[c] = load_as_float<T>(static_cast<const T*>(ap.key), (size_t)u * kD + c);
-  if (c < 8) A.abest[c] = ~0ull;
-  __syncthreads();
-  if (c < s.C) {
-    for (int j = 0; j < s.M; ++j) {
-      const float* cr = ap.cent + (((size_t)u * s.M + j) * s.C + c) * s.Dm;
-      const float* xj = A.ax + j * s.Dm;
-      float d2 = 0.0f;
-      for (int e = 0; e < s.Dm; e += 4) {  // Dm is a multiple of 4
-        const float4 cv = *reinterpret_cast<const float4*>(cr + e);
-        float df = xj[e] - cv.x;
-        d2 = fmaf(df, df, d2);
-        df = xj[e + 1] - cv.y;
-        d2 = fmaf(df, df, d2);
-        df = xj[e + 2] - cv.z;
-        d2 = fmaf(df, df, d2);
-        df = xj[e + 3] - cv.w;
-        d2 = fmaf(df, df, d2);
-      }
-      atomicMin(&A.abest[j], ((unsigned long long)__float_as_uint(d2) << 32) | (unsigned)c);  // d2 >= 0: bits order like values
-    }
-  }
-  __syncthreads();
-  if (c < s.M) store_through(&ap.codes[((size_t)u * s.cap + ap.position) * s.M + c], (uint8_t)(A.abest[c] & 0xffu));
-}
-
-// Draws a ticket from `counter`; true for the workgroup that draws the last of `total`.  What a workgroup leaves
-// for whoever draws the last ticket was stored with store_through(); those stores have completed (every wave waits
-// for its own, then the barrier) before the ticket is drawn, and the last workgroup drops whatever its caches hold
-// before it reads the others' data.
-__device__ __forceinline__ bool last_ticket(unsigned* counter, int total, int* ticket_sm) {
-  __builtin_amdgcn_s_waitcnt(0);  // all counters at zero: this wave's stores are acknowledged
-  __syncthreads();
-  if (threadIdx.x == 0) *ticket_sm = (int)atomicAdd(counter, 1u);
-  __syncthreads();
-  const bool last = *ticket_sm == total - 1;
-  if (last) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-  return last;
-}
-
-// ---------------------------------------------------- 3. select (+ attention)
-// One workgroup owns tokens [bx*tokC, +tokC) of its unit (bx: its number inside the unit); its 4 waves each own
+// ---------------------------------------------------- 2. select (+ attention)
+// One workgroup owns tokens [blockIdx.x*tokC, +tokC) of its unit; its 4 waves each own
 // a contiguous quarter.  The histogram kernel left every token's bin behind, so a token
 // is classified by comparing that number with the threshold bin.  Per wave, lanes hold
 // 8 consecutive tokens, counts are prefix-summed across lanes, and the wave appends to
@@ -805,143 +322,30 @@ constexpr int kMaxVecC = 4;  // 8-token groups per lane (tokC <= 8192)
 
 // PAIRS (M = 2 only): there is no histogram kernel in front; the threshold comes from the
 // code-pair counts (pair_threshold) and tokens are classified by their exact score keys.
-//
-// Grid (nblkC [+ 1], units): workgroup nblkC of a unit, present when a token is appended, computes
-// that token's code.  The last workgroup of a unit to finish completes the unit (finalize_unit);
-// the LDS of that step overlays the LDS of the selection, which is dead by then.
-template <typename T, int G, bool ATTN, bool PAIRS>
-struct SelectLds {
-  static constexpr int NW = 4;
-  static constexpr bool kMfma = ATTN && sizeof(T) == 2;
-  std::conditional_t<PAIRS, PairLds, int> pl;
-  int scan_sm[2 * NW + 1 + 4];
-  int wcnt[2 * NW];
-  float red[ATTN ? NW * G * (kD + 2) : 1];
-  float qlds[ATTN ? G * kD : 1];
-  __attribute__((aligned(16))) unsigned char vtile[kMfma ? NW * kVTileBytes : 16];
-};
-template <class A, class B, class C>
-constexpr size_t max_size() {
-  return sizeof(A) > sizeof(B) ? (sizeof(A) > sizeof(C) ? sizeof(A) : sizeof(C)) : (sizeof(B) > sizeof(C) ? sizeof(B) : sizeof(C));
-}
-
-// All arguments of the select kernel in one block, so that the step that completes a unit can read them again
-// from the kernel-argument segment when it runs (late_kernel_args) instead of holding them in registers throughout.
-struct SelectArgs {
-  Shape s;
-  Workspace ws;
-  const void* q;            // [B][Hq][kD]
-  const void* kc;           // K cache
-  const void* vc;           // V cache
-  const void* src;          // codes, or the score array of the stand-alone top-k
-  int* out_idx;
-  float* out_attn;
-  AppendArgs ap;
-  const float* cent;            // PAIRS: centroids
-  const unsigned* pair_counts;  // PAIRS: tokens per code pair
-  int uncounted;                // PAIRS: a window token not in the counts yet, or -1
-};
-
-// The kernel's argument block (its only parameter), read where this is called: scalar loads from the
-// kernel-argument segment.  The pointer is made opaque first, so that the loads stay behind this point.
-template <class A>
-__device__ __forceinline__ const A& late_kernel_args() {
-  auto p = (const __attribute__((address_space(4))) A*)__builtin_amdgcn_kernarg_segment_ptr();
-  asm volatile("" : "+s"(p));
-  return *(const A*)p;
-}
-
-// What a workgroup does when it is done with its own part: draw a ticket; the last of a group folds the group's
-// states into one and draws a ticket of the unit; the last of the unit folds the groups' states and completes the
-// unit.  Both levels run the same loop body, so that the second pass finds its instructions in the cache.
-// level: 0 for a select workgroup of a unit with groups, 1 otherwise (units without groups, the appending workgroup).
-template <typename T, int G, bool ATTN>
-__device__ __forceinline__ void finish_late(int u, int bx, unsigned char* smem, int* ticket_sm) {
-  constexpr int GA = ATTN ? G : 1, HPT = Folded<GA>::HPT;
-  const SelectArgs& a = late_kernel_args<SelectArgs>();
-  const int grpC = ATTN ? a.s.grpC : 0, extra = a.ap.key ? 1 : 0;
-  const int tid = threadIdx.x, d = tid & (kD - 1), hb = tid >> 7;
-  const bool owner = GA >= 2 || hb == 0;
-  const int grp = grpC > 0 ? bx / max(grpC, 1) : 0;
-  Folded<GA> r;
-#pragma unroll 1
-  for (int level = (grpC > 0 && bx < a.s.nblkC) ? 0 : 1; level < 2; ++level) {
-    unsigned* counter = level == 0 ? &a.ws.gticket[(size_t)u * kMaxGroups + grp] : &a.ws.ticket[u];
-    const int total = level == 0 ? min(grpC, a.s.nblkC - grp * grpC) : (grpC > 0 ? a.s.ngrp : a.s.nblkC) + extra;
-    if (!last_ticket(counter, total, ticket_sm)) return;
-    r.init();
-    if constexpr (ATTN) {
-      const bool from_groups = level == 1 && grpC > 0;
-      const float* src = from_groups ? a.ws.gparts + (size_t)u * kMaxGroups * G * (kD + 2)
-                                     : a.ws.partials + ((size_t)u * a.s.npart + (level == 0 ? grp * grpC : 0)) * G * (kD + 2);
-      const int count = level == 0 ? total : (grpC > 0 ? a.s.ngrp : a.s.nblkC);
-      if (owner) {
-        fold_states<G>(src, count, d, hb, r);
-        if (level == 0) {
-          float* dst = a.ws.gparts + ((size_t)u * kMaxGroups + grp) * G * (kD + 2);
-#pragma unroll
-          for (int i = 0; i < HPT; ++i) {
-            float* dh = dst + (G >= 2 ? hb + 2 * i : 0) * (kD + 2);
-            store_through(&dh[2 + d], r.acc[i]);
-            if (d == 0) {
-              store_through(&dh[0], r.m[i]);
-              store_through(&dh[1], r.l[i]);
-            }
-          }
-        }
-      }
-    }
-  }
-  finalize_unit<T, G, ATTN>(a.s, a.ws, u, static_cast<const T*>(a.q), static_cast<const T*>(a.kc), static_cast<const T*>(a.vc),
-                            a.out_idx, a.out_attn, a.ap, *reinterpret_cast<TailLds<G, ATTN>*>(smem), r);
-}
-
 template <typename T, int G, class SRC, bool ATTN, bool PAIRS = false>
-__global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
-  const Shape& s = args.s;
-  const Workspace& ws = args.ws;
-  const T* __restrict__ q = static_cast<const T*>(args.q);
-  const T* __restrict__ kc = static_cast<const T*>(args.kc);
-  const T* __restrict__ vc = static_cast<const T*>(args.vc);
-  const void* __restrict__ src_ptr = args.src;
-  const float* __restrict__ cent = args.cent;
-  const unsigned* __restrict__ pair_counts = args.pair_counts;
-  const int uncounted = args.uncounted;
+__global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, const T* __restrict__ q,
+                                                     const T* __restrict__ kc, const T* __restrict__ vc,
+                                                     const void* __restrict__ src_ptr,
+                                                     const float* __restrict__ cent = nullptr,
+                                                     const unsigned* __restrict__ pair_counts = nullptr,
+                                                     int uncounted = -1 /* PAIRS: a window token not in the counts yet */) {
   constexpr int NT = 256, NW = 4;
   constexpr bool kMfma = ATTN && sizeof(T) == 2;
   static_assert(!PAIRS || (SRC::kFromCodes && SRC::M == 2), "pair counts exist for two partitions only");
-  using SelLds = SelectLds<T, G, ATTN, PAIRS>;
-  using EndLds = TailLds<G, ATTN>;
   extern __shared__ unsigned short list[];  // [tokC] token offsets from the workgroup's first token
-  __shared__ __attribute__((aligned(16))) unsigned char smem[max_size<SelLds, EndLds, AppendLds>()];
-  __shared__ int ticket_sm;
-  SelLds& S = *reinterpret_cast<SelLds*>(smem);
-  auto& pl = S.pl;
-  int* scan_sm = S.scan_sm;
-  int* wcnt = S.wcnt;
-  float* red = S.red;
-  float* qlds = S.qlds;
-  unsigned char* vtile = S.vtile;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  // Workgroups are handed to the 8 XCDs round-robin in launch order (x fastest).  Eight units at a time are
-  // interleaved, so that the workgroups of one unit share an XCD: what they leave for the unit's last workgroup
-  // is then found in that XCD's L2 (a matter of speed only: the exchange is correct wherever they run).
-  int u = blockIdx.y, bx = blockIdx.x;
-  {
-    const int nx = gridDim.x, lin = blockIdx.y * nx + blockIdx.x, units = s.B * s.Hkv;
-    if (lin < (units & ~7) * nx) {
-      const int i = lin % (8 * nx);
-      u = (lin / (8 * nx)) * 8 + (i & 7);
-      bx = i >> 3;
-    }
-  }
+  __shared__ std::conditional_t<PAIRS, PairLds, int> pl;
+  __shared__ int scan_sm[2 * NW + 1 + 4];
+  __shared__ int wcnt[2 * NW];
+  __shared__ float red[ATTN ? NW * G * (kD + 2) : 1];
+  __shared__ float qlds[ATTN ? G * kD : 1];
+  __shared__ __attribute__((aligned(16))) unsigned char vtile[kMfma ? NW * kVTileBytes : 16];
+  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = u / s.Hkv, g = u % s.Hkv;
-  auto select_and_attend = [&]() {
   PQC_MARK(ws, 1, 0);
   // this wave's stored bins, the query and the histogram: all requested up front
   const int tpw = s.tokC / NW;           // tokens per wave, in groups of 8 per lane
   const int gpw = (tpw + 511) / 512;     // groups per lane: 1, 2 or 4 (the last lanes idle when tpw < 512)
-  const int wave_t0 = bx * s.tokC + w * tpw;
+  const int wave_t0 = blockIdx.x * s.tokC + w * tpw;
   // 16 bytes per group of 8 tokens: their stored bins, or (PAIRS) their codes
   const unsigned short* bins_u =
       PAIRS ? reinterpret_cast<const unsigned short*>(static_cast<const uint8_t*>(src_ptr) + (size_t)u * s.cap * 2)
@@ -985,7 +389,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
 
   const int segN = s.tokC / NW;
   unsigned short* seg = list + w * segN;
-  const int wg_t0 = bx * s.tokC;
+  const int wg_t0 = blockIdx.x * s.tokC;
   int nsel = 0, ncand = 0;
   const unsigned thr = (unsigned)th.bstar + 1u;  // in stored form
 #pragma unroll
@@ -1045,17 +449,6 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
   // attention below, which hides the round trip of the returning atomic
   int rec_base;  // set and read by thread 0 only; no initialiser, or the merge with it would wait for the atomic here
   if (tid == 0 && tot_cand > 0) rec_base = (int)atomicAdd(&ws.cand_count[u], (unsigned)tot_cand);
-  // this workgroup's list sizes, for the other workgroups of the unit to place their lists in out_idx
-  if (tid == 0) store_through(&ws.pub[(size_t)u * s.nblkC + bx], ((unsigned long long)(unsigned)tot_cand << 32) | (unsigned)(tot_sel + 1));
-  // put away (in LDS) once the attention's first loads are back, which arrive after it: no wait, and no register
-  // held through the attention
-  // Likewise the list sizes of the unit's first 64 workgroups (wave 0, one per lane) are requested there: the
-  // workgroups of a unit start together and publish their sizes long before anyone's first rows are back.
-  unsigned long long pw0 = 0ull;
-  auto put_rec_base = [&]() {
-    if (tid == 0 && tot_cand > 0) scan_sm[0] = rec_base;  // scan_sm is idle since the threshold search
-    if (w == 0) pw0 = __hip_atomic_load(&ws.pub[(size_t)u * s.nblkC + min(lane, s.nblkC - 1)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  };
   // A candidate's exact score comes from its codes and the unit's table (same evaluation order
   // as everywhere), or from the score array of the stand-alone top-k.
   struct CandKey {
@@ -1101,8 +494,8 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
     return wg_t0 + list[i * segN + (p - csel[i])];
   };
 
-  // selected list for the index output
-  unsigned long long* stage = ws.stage + ((size_t)u * s.nblkC + bx) * s.stageStride;
+  // selected list for the finalize kernel's index output
+  unsigned long long* stage = ws.stage + ((size_t)u * s.nblkC + blockIdx.x) * s.stageStride;
   int* stage32 = reinterpret_cast<int*>(stage);
   PQC_MARK(ws, 1, 3);
 
@@ -1131,30 +524,15 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
   // window tokens it happens to hold (the list's first nI and last nL entries), every
   // nblkC-th token of the two windows, so that the window rows are spread over the unit's
   // workgroups.
-  const int tok_lo = bx * s.tokC, tok_hi = min(s.N, (bx + 1) * s.tokC);
+  const int tok_lo = (int)blockIdx.x * s.tokC, tok_hi = min(s.N, ((int)blockIdx.x + 1) * s.tokC);
   const int nI = max(0, min(s.I, tok_hi) - tok_lo), nL = max(0, tok_hi - max(s.N - s.L, tok_lo));
   const int n_own = tot_sel - nI - nL;
-  const int n_win = bx < s.I + s.L ? (s.I + s.L - bx + s.nblkC - 1) / s.nblkC : 0;
+  const int n_win = (int)blockIdx.x < s.I + s.L ? (s.I + s.L - (int)blockIdx.x + s.nblkC - 1) / s.nblkC : 0;
   const int n_att = n_own + n_win;
   auto att_at = [&](int p) -> int {
     if (p < n_own) return sel_at(p + nI);
-    const int wt = bx + (p - n_own) * s.nblkC;
+    const int wt = (int)blockIdx.x + (p - n_own) * s.nblkC;
     return wt < s.I ? wt : s.N - s.L + (wt - s.I);
-  };
-  // the list sizes of the unit's workgroups (wave 0): requested when the attention is done, read further down
-  constexpr int PWX = kMaxBlkC / 64;
-  unsigned long long pw[PWX];
-  auto poll_sizes = [&]() {
-    if (w == 0) {
-      pw[0] = pw0;
-      const bool again = __any(lane < s.nblkC && (unsigned)pw0 == 0u) != 0;  // uniform: some size was not there yet
-#pragma unroll
-      for (int x = 0; x < PWX; ++x) {
-        if (x > 0) pw[x] = 0ull;
-        if (x * 64 < s.nblkC && (x > 0 || again))  // uniform
-          pw[x] = __hip_atomic_load(&ws.pub[(size_t)u * s.nblkC + min(x * 64 + lane, s.nblkC - 1)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-    }
   };
   if constexpr (ATTN) {
     if constexpr (kMfma) {
@@ -1163,9 +541,8 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
       MfmaState st;
       st.init();
       mfma_attend(reinterpret_cast<const bf16_t*>(kbase), reinterpret_cast<const bf16_t*>(vbase), s.N, att_at, n_att,
-                  w * 16 * kMfmaTiles, NW * 16 * kMfmaTiles, s.scale_log2e, qf, vtile + w * kVTileBytes, st, put_rec_base);
+                  w * 16 * kMfmaTiles, NW * 16 * kMfmaTiles, s.scale_log2e, qf, vtile + w * kVTileBytes, st);
       PQC_MARK(ws, 1, 4);
-      poll_sizes();
       mfma_stash_wave_state<G>(st, red);
     } else {
       float qr[G][8];
@@ -1174,79 +551,34 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
       st.init();
       constexpr int R = (G >= 8 || sizeof(T) == 4) ? 2 : 4;
       attend_rows<T, G, R>(kbase, vbase, s.N, att_at, n_att, w * 4 * R, NW * 4 * R, qr, st);
-      put_rec_base();
       PQC_MARK(ws, 1, 4);
-      poll_sizes();
       stash_wave_state<T, G>(st, red);
     }
     __syncthreads();
-    float* part = ws.partials + ((size_t)u * s.npart + bx) * G * (kD + 2);
+    float* part = ws.partials + ((size_t)u * s.npart + blockIdx.x) * G * (kD + 2);
     for (int o = tid; o < G * kD; o += NT) {
       const int h = o / kD, d = o % kD;
       float m, l, acc;
       combine_waves<G, NW>(red, h, d, m, l, acc);
-      store_through(&part[h * (kD + 2) + 2 + d], acc);
+      part[h * (kD + 2) + 2 + d] = acc;
       if (d == 0) {
-        store_through(&part[h * (kD + 2)], m);
-        store_through(&part[h * (kD + 2) + 1], l);
+        part[h * (kD + 2)] = m;
+        part[h * (kD + 2) + 1] = l;
       }
     }
-  } else {
-    put_rec_base();
-    poll_sizes();
   }
-  // Where this workgroup's list goes in out_idx: behind the lists of the workgroups before it, if every
-  // workgroup's sizes are known by now; otherwise the list is staged for the unit's last workgroup.
-  if (w == 0) {
-    int before = 0, all_sel = 0, all_cand = 0;
-    bool known = true;
-#pragma unroll
-    for (int x = 0; x < PWX; ++x) {
-      if (x * 64 < s.nblkC) {  // uniform
-        const int j = x * 64 + lane;
-        const unsigned lo = (unsigned)pw[x], hi = (unsigned)(pw[x] >> 32);
-        if (j < s.nblkC) {
-          known = known && lo != 0u;
-          const int sz = lo != 0u ? (int)lo - 1 : 0;
-          all_sel += sz;
-          all_cand += (int)hi;
-          before += j < bx ? sz : 0;
-        }
-      }
-    }
-    known = __all(known) != 0;
-    before = wave_last(wave_inclusive_scan(before));
-    all_sel = wave_last(wave_inclusive_scan(all_sel));
-    all_cand = wave_last(wave_inclusive_scan(all_cand));
-    if (lane == 0) {
-      scan_sm[1] = known ? before : -1;
-      scan_sm[2] = all_sel;
-      scan_sm[3] = all_cand;
-    }
-  }
-  __syncthreads();
-  const int my_off = scan_sm[1];
-  if (my_off >= 0) {  // uniform
-    const int n_above_u = max(0, scan_sm[2] - s.I - s.L);
-    const int need_u = max(0, min(s.K - n_above_u, scan_sm[3]));
-    int* out = args.out_idx + (size_t)u * s.Ktot;
-    for (int p = tid; p < tot_sel; p += NT) {
-      const int pos = my_off + p, dst = pos < s.I + n_above_u ? pos : pos + need_u;  // the local window goes behind the admitted candidates
-      if (dst < s.Ktot) out[dst] = sel_at(p);
-    }
-  } else {
-    for (int p = tid; p < tot_sel; p += NT) store_through(&stage32[p], sel_at(p));
-  }
-  if (tid == 0)
-    store_through(reinterpret_cast<unsigned long long*>(ws.stage_cnt + (size_t)u * s.nblkC + bx),
-                  ((unsigned long long)(unsigned)tot_cand << 32) | ((unsigned)tot_sel | (my_off >= 0 ? 0u : kStagedFlag)));
+  // (written after the attention: stores issued while the K/V loads of the co-resident workgroup
+  // fill the memory pipeline would only delay this workgroup's own first loads)
+  for (int p = tid; p < tot_sel; p += NT) stage32[p] = sel_at(p);
+  if (tid == 0) ws.stage_cnt[(size_t)u * s.nblkC + blockIdx.x] = make_int2(tot_sel, tot_cand);
   PQC_MARK(ws, 1, 5);
   PQC_NOTE(ws, 1, 14, tot_sel);
   PQC_NOTE(ws, 1, 15, tot_cand);
 
   // candidates (few): composite for the generic path, and a full record while slots last
   if (tot_cand > 0) {  // workgroup-uniform
-    __syncthreads();  // rec_base was put away by thread 0 (put_rec_base)
+    if (tid == 0) scan_sm[0] = rec_base;
+    __syncthreads();
     const int base = scan_sm[0];
     for (int c = grp; c < tot_cand; c += NT / 16) {
       int t = c0_t;
@@ -1261,11 +593,11 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
         }
       }
       const unsigned long long comp = make_composite(cand_score(key), t);
-      if (sub == 0) store_through(&stage[s.tokC - 1 - c], comp);
+      if (sub == 0) stage[s.tokC - 1 - c] = comp;
       if (base + c < kCandRec) {
         unsigned char* rec = ws.cand_rec + ((size_t)u * kCandRec + base + c) * ws.rec_stride;
         CandHeader* hd = reinterpret_cast<CandHeader*>(rec);
-        if (sub == 0) store_through(&hd->composite, comp);
+        if (sub == 0) hd->composite = comp;
         if constexpr (ATTN) {
           float kf[8];
           kr.unpack(kf);
@@ -1275,24 +607,29 @@ __global__ __launch_bounds__(256, 2) void select_kernel(SelectArgs args) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) d = fmaf(qlds[h * kD + owned_dim<T>(sub, e)], kf[e], d);
             d = group16_sum(d);
-            if (sub == 0) store_through(&hd->logit[h], d);
+            if (sub == 0) hd->logit[h] = d;
           }
-          vr.store_through(rec + sizeof(CandHeader), sub);
+          vr.store(rec + sizeof(CandHeader), sub);
         }
       }
     }
   }
-  PQC_MARK(ws, 1, 6);
-  };  // select_and_attend
-  if (bx == s.nblkC)  // the appended token's code; nothing in the step reads it
-    append_token<T>(s, args.ap, u, *reinterpret_cast<AppendLds*>(smem));
-  else
-    select_and_attend();
-  // whoever finishes last does the next step: fold the group's states, complete the unit
-  finish_late<T, G, ATTN>(u, bx, smem, &ticket_sm);
 }
 
-// ------------------------------------------------------------ block reductions
+// ------------------------------------------------------------- 3. finalize
+// Grid (heads + kCopyWgs, units), 256 threads; heads = the group's query heads (1 for
+// the stand-alone top-k).
+//   blockIdx.x <  heads  ranks the candidates and folds the admitted ones and all partial
+//                        softmax states into this head's output; head 0 also writes the
+//                        admitted candidates' indices (best first)
+//   blockIdx.x >= heads  copy workgroups: concatenate the staged lists into out_idx; the
+//                        first one also zeroes the unit's histogram and record counter
+// The staged "selected" lists already hold the two windows: in workgroup order they read
+//   [0..I) , tokens above the threshold bin (ascending) , [N-L..N).
+// Fast path (at most kCandRec candidates): all a head needs is in the candidate records,
+// which sit densely in order of arrival.  That order differs from run to run, so every
+// sum over candidates is taken in rank order.  Generic path: candidates are the
+// composites staged per select workgroup; admitted rows are gathered from the K/V cache.
 template <int NT>
 __device__ __forceinline__ float block_max(float v, float* sm /* [NT/64] */) {
   v = wave_max(v);
@@ -1314,6 +651,464 @@ __device__ __forceinline__ float block_sum(float v, float* sm /* [NT/64] */) {
   for (int i = 1; i < NT / 64; ++i) r += sm[i];
   __syncthreads();
   return r;
+}
+
+constexpr int kHdrPerThread = kCandRec / 256;  // candidate record headers per thread
+constexpr int kAccBatch = 32;                  // partial accumulators a thread keeps in flight at once
+constexpr int kVPass = 4;                      // dependent V-row passes in flight (16 rows each), many-candidate case
+constexpr int kIdxLists = 4;                   // staged index lists a wave copies with loads issued up front
+constexpr int kCopyWgs = 4;                    // copy workgroups per unit
+constexpr int kRankChunk = 64;                 // admitted rows summed per pass through LDS
+
+// The code of one appended token per unit (Section 3.1: nearest centroid of each partition): nothing in the
+// step depends on it, so one more workgroup per unit of the finalize kernel computes it beside the others.
+struct AppendArgs {
+  const void* key;    // [units][kD] in the cache's element type, or null: nothing to append
+  const float* cent;  // [units][M][C][Dm]
+  uint8_t* codes;     // the code tensor; written at `position` of every unit
+  int position;
+  unsigned* pair_counts;  // two partitions: [units][C*C] counts that gain the token's code pair, or null
+};
+
+template <typename T, int G, bool ATTN>
+__global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, const T* __restrict__ q,
+                                                       const T* __restrict__ kc, const T* __restrict__ vc,
+                                                       int* __restrict__ out_idx, float* __restrict__ out_attn, AppendArgs ap) {
+  constexpr int NT = 256, NW = 4;
+  constexpr int heads = ATTN ? G : 1;
+  if (blockIdx.x == heads + kCopyWgs) {
+    // -------------------------------------------------------------- append workgroup
+    // one thread per centroid, the distance chain of pq_assign_kernel, the smallest (distance, centroid) pair
+    // of each partition through a 64-bit LDS minimum
+    __shared__ float ax[kD];
+    __shared__ unsigned long long abest[8];
+    const int u = blockIdx.y, c = threadIdx.x;
+    if (c < kD) ax[c] = load_as_float<T>(static_cast<const T*>(ap.key), (size_t)u * kD + c);
+    if (c < 8) abest[c] = ~0ull;
+    __syncthreads();
+    if (c < s.C) {
+      for (int j = 0; j < s.M; ++j) {
+        const float* cr = ap.cent + (((size_t)u * s.M + j) * s.C + c) * s.Dm;
+        const float* xj = ax + j * s.Dm;
+        float d2 = 0.0f;
+        for (int e = 0; e < s.Dm; e += 4) {  // Dm is a multiple of 4
+          const float4 cv = *reinterpret_cast<const float4*>(cr + e);
+          float df = xj[e] - cv.x;
+          d2 = fmaf(df, df, d2);
+          df = xj[e + 1] - cv.y;
+          d2 = fmaf(df, df, d2);
+          df = xj[e + 2] - cv.z;
+          d2 = fmaf(df, df, d2);
+          df = xj[e + 3] - cv.w;
+          d2 = fmaf(df, df, d2);
+        }
+        atomicMin(&abest[j], ((unsigned long long)__float_as_uint(d2) << 32) | (unsigned)c);  // d2 >= 0: bits order like values
+      }
+    }
+    __syncthreads();
+    if (c < s.M) ap.codes[((size_t)u * s.cap + ap.position) * s.M + c] = (uint8_t)(abest[c] & 0xffu);
+    if (c == 0 && ap.pair_counts) ap.pair_counts[(size_t)u * s.C * s.C + (abest[0] & 0xffu) + s.C * (abest[1] & 0xffu)] += 1u;
+    return;
+  }
+  constexpr int SP = ATTN ? (sizeof(T) == 2 ? 8 : 4) : 1;  // passes of 16 record V rows requested up front
+  extern __shared__ int dyn[];  // pre_sel[nblkC+1], pre_cand[nblkC+1], pm[nblkC], pl[nblkC]
+  __shared__ int scan_sm[2 * NW + 1];
+  __shared__ float fsm[NW];
+  __shared__ int ism[2 * NW];
+  __shared__ unsigned long long comp[kCandRec];  // candidate composites, in record order
+  __shared__ float lgk[kCandRec];                // by rank: logit, then softmax weight of the admitted ones
+  __shared__ unsigned short ordv[kCandRec];      // by rank: record
+  __shared__ unsigned short rankv[kCandRec];     // by record: rank if admitted, 0xffff otherwise
+  __shared__ unsigned rhist[256];
+  __shared__ int digit_sm[2];
+  __shared__ int rows_sm[NT];
+  __shared__ float red[ATTN ? NW * (kD + 2) : 1];
+  __shared__ float half_acc[ATTN ? kD : 1];
+  __shared__ float vl[ATTN ? kRankChunk * kD : 1];
+  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int b = u / s.Hkv, g = u % s.Hkv;
+  int* pre_sel = dyn;
+  int* pre_cand = dyn + (s.nblkC + 1);
+  float* pm = reinterpret_cast<float*>(dyn + 2 * (s.nblkC + 1));
+  float* pl = pm + s.nblkC;
+  const int2* cnt = ws.stage_cnt + (size_t)u * s.nblkC;
+  const unsigned long long* stage_u = ws.stage + (size_t)u * s.nblkC * s.stageStride;
+  int* out = out_idx + (size_t)u * s.Ktot;
+  PQC_MARK(ws, 2, 0);
+
+  // exclusive prefix sums of the per-workgroup list sizes (into LDS); returns the totals
+  auto scan_counts = [&](const int2 cnt0, int& n_list, int& n_cand) {
+    int carry_s = 0, carry_c = 0;
+    for (int j0 = 0; j0 < s.nblkC; j0 += NT) {
+      const int j = j0 + tid;
+      const int2 c = j < s.nblkC ? (j0 == 0 ? cnt0 : cnt[j]) : make_int2(0, 0);
+      int ts, tc;
+      const int ps = block_exclusive_scan<NT>(c.x, &ts, scan_sm);
+      const int pc = block_exclusive_scan<NT>(c.y, &tc, scan_sm);
+      if (j < s.nblkC) {
+        pre_sel[j] = carry_s + ps;
+        pre_cand[j] = carry_c + pc;
+      }
+      carry_s += ts;
+      carry_c += tc;
+    }
+    if (tid == 0) {
+      pre_sel[s.nblkC] = carry_s;
+      pre_cand[s.nblkC] = carry_c;
+    }
+    __syncthreads();
+    n_list = carry_s;
+    n_cand = carry_c;
+  };
+
+  if (blockIdx.x >= heads) {
+    // ---------------------------------------------------------------- copy workgroup
+    // one wave per list, coalesced; the local window moves behind the admitted candidates
+    const int cw = blockIdx.x - heads, ncw = kCopyWgs;
+    const int2 cnt0 = cnt[min(tid, s.nblkC - 1)];
+    int ix[kIdxLists][4];  // first 256 entries of this wave's first kIdxLists lists
+#pragma unroll
+    for (int x = 0; x < kIdxLists; ++x) {
+      const int j = min(cw * NW + w + x * ncw * NW, s.nblkC - 1);
+      const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.stageStride);
+#pragma unroll
+      for (int y = 0; y < 4; ++y) ix[x][y] = src[min(y * 64 + lane, 2 * s.tokC - 1)];
+    }
+    PQC_LOADS_ISSUED();
+    int n_list, n_cand;
+    scan_counts(cnt0, n_list, n_cand);
+    const int n_above = max(0, n_list - s.I - s.L);
+    const int need = max(0, min(s.K - n_above, n_cand));
+    PQC_MARK(ws, 2, 1);
+    int x = 0;
+    for (int j = cw * NW + w; j < s.nblkC; j += ncw * NW, ++x) {
+      const int base = pre_sel[j], n = pre_sel[j + 1] - base;
+      const int* src = reinterpret_cast<const int*>(stage_u + (size_t)j * s.stageStride);
+      for (int p0 = 0; p0 < n; p0 += 256) {
+        int v[4];
+        if (x < kIdxLists && p0 == 0) {
+#pragma unroll
+          for (int y = 0; y < 4; ++y) v[y] = x == 0 ? ix[0][y] : x == 1 ? ix[1][y] : x == 2 ? ix[2][y] : ix[3][y];
+        } else {
+#pragma unroll
+          for (int y = 0; y < 4; ++y)
+            if (p0 + y * 64 + lane < n) v[y] = src[p0 + y * 64 + lane];
+        }
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+          const int pos = base + p0 + y * 64 + lane;
+          if (p0 + y * 64 + lane < n) out[pos < s.I + n_above ? pos : pos + need] = v[y];
+        }
+      }
+    }
+    PQC_MARK(ws, 2, 4);
+    if (cw == 0) {  // the select kernel was their last reader: zero histogram and record counter for the next call
+      unsigned* gh = ws.hist + (size_t)u * s.histCopies * kNB;
+      for (int i = tid; i < s.histCopies * kNB; i += NT) gh[i] = 0u;
+      if (tid == 0) ws.cand_count[u] = 0u;
+    }
+    PQC_MARK(ws, 2, 5);
+    return;
+  }
+
+  // ------------------------------------------------------------------ head workgroup
+  const int hq = blockIdx.x;
+  const int d = tid & (kD - 1), half = tid >> 7;  // output dimension and half of the partials this thread sums
+  const int sub = tid & 15, grp = tid >> 4;       // 16 lanes per candidate V row
+  // ---- everything whose address is known up front is requested first
+  const unsigned char* recs = ws.cand_rec + (size_t)u * kCandRec * ws.rec_stride;
+  unsigned long long rc[kHdrPerThread];  // record x*NT + tid; the first NT are requested up front
+  float rl[kHdrPerThread];
+  {
+    const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)tid * ws.rec_stride);
+    rc[0] = hd->composite;
+    rl[0] = ATTN ? hd->logit[hq] : 0.0f;
+  }
+  const float* parts = ws.partials + (size_t)u * s.npart * G * (kD + 2);
+  const int jc = min(tid, s.nblkC - 1);
+  const int2 cnt0 = cnt[jc];  // list sizes of the first NT select workgroups
+  float pm0 = 0.0f, pl0 = 0.0f;
+  float a0[kAccBatch];  // first batch of this thread's partial accumulators: lists half, half+2, ...
+  RowRaw<T> vspec[SP];  // V rows of the first 16*sp records
+  // with many head workgroups in flight the unused part of this guess is real traffic: guess less
+  const int sp = (int)gridDim.y * heads <= 64 ? SP : SP / 2;
+  if constexpr (ATTN) {
+    pm0 = parts[((size_t)jc * G + hq) * (kD + 2)];
+    pl0 = parts[((size_t)jc * G + hq) * (kD + 2) + 1];
+    const float* a0p = parts + ((size_t)half * G + hq) * (kD + 2) + 2 + d;
+#pragma unroll
+    for (int x = 0; x < kAccBatch; ++x)  // lists that do not exist re-read the first one (a cache hit, no extra traffic)
+      a0[x] = a0p[half + 2 * x < s.nblkC ? (size_t)x * (2 * G * (kD + 2)) : (size_t)0];
+#pragma unroll
+    for (int x = 0; x < SP; ++x)
+      if (x < sp) vspec[x].load_row(recs + (size_t)(x * 16 + grp) * ws.rec_stride + sizeof(CandHeader), sub);
+  }
+  PQC_LOADS_ISSUED();
+  if constexpr (ATTN) {
+    if (tid < s.nblkC) {
+      pm[tid] = pm0;
+      pl[tid] = pl0;
+    }
+    for (int j = NT + tid; j < s.nblkC; j += NT) {  // beyond the first NT lists (very long contexts)
+      pm[j] = parts[((size_t)j * G + hq) * (kD + 2)];
+      pl[j] = parts[((size_t)j * G + hq) * (kD + 2) + 1];
+    }
+  }
+  // totals of the per-workgroup list sizes
+  int n_list, n_cand;
+  {
+    int ss = tid < s.nblkC ? cnt0.x : 0, sc = tid < s.nblkC ? cnt0.y : 0;
+    for (int j = NT + tid; j < s.nblkC; j += NT) {
+      const int2 c = cnt[j];
+      ss += c.x;
+      sc += c.y;
+    }
+    ss = wave_sum(ss);
+    sc = wave_sum(sc);
+    if (lane == 0) {
+      ism[w] = ss;
+      ism[NW + w] = sc;
+    }
+    __syncthreads();  // also: pm, pl visible
+    n_list = 0;
+    n_cand = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+      n_list += ism[i];
+      n_cand += ism[NW + i];
+    }
+  }
+  const int n_above = max(0, n_list - s.I - s.L);  // n_list = I + (tokens above the bin) + L
+  const int need = max(0, min(s.K - n_above, n_cand));
+  PQC_MARK(ws, 2, 1);
+
+  if (n_cand <= kCandRec) {
+    // rank every candidate (count of larger composites); the admitted ones are the `need` best
+    if (need > 0) {
+#pragma unroll
+      for (int x = 1; x < kHdrPerThread; ++x) {
+        rc[x] = 0ull;
+        rl[x] = 0.0f;
+        if (x * NT + tid < n_cand) {  // rare: more than NT candidates
+          const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)(x * NT + tid) * ws.rec_stride);
+          rc[x] = hd->composite;
+          rl[x] = ATTN ? hd->logit[hq] : 0.0f;
+        }
+      }
+#pragma unroll
+      for (int x = 0; x < kHdrPerThread; ++x)
+        if (x * NT + tid < n_cand) comp[x * NT + tid] = rc[x];
+      __syncthreads();
+#pragma unroll
+      for (int x = 0; x < kHdrPerThread; ++x) {
+        const int k = x * NT + tid;
+        if (k < n_cand) {
+          const unsigned long long mine = rc[x];
+          int rank = 0;
+          for (int j = 0; j < n_cand; ++j) rank += comp[j] > mine ? 1 : 0;
+          if (rank < need) {
+            if (hq == 0) out[s.I + n_above + rank] = composite_token(mine);  // best first
+            lgk[rank] = rl[x] * s.scale_log2e;
+            ordv[rank] = (unsigned short)k;
+            rankv[k] = (unsigned short)rank;
+          } else {
+            rankv[k] = 0xffffu;
+          }
+        }
+      }
+      __syncthreads();
+    }
+    if constexpr (ATTN) {
+      float mx = kNegBig;
+      for (int k = tid; k < need; k += NT) mx = fmaxf(mx, lgk[k]);
+      for (int j = tid; j < s.nblkC; j += NT) mx = fmaxf(mx, pm[j]);
+      const float mstar = block_max<NT>(mx, fsm);
+      float lsum = 0.0f;
+      for (int k = tid; k < need; k += NT) {
+        const float p = __builtin_amdgcn_exp2f(lgk[k] - mstar);
+        lgk[k] = p;
+        lsum += p;
+      }
+      for (int j = tid; j < s.nblkC; j += NT) {
+        const float wj = __builtin_amdgcn_exp2f(pm[j] - mstar);
+        pm[j] = wj;
+        lsum = fmaf(wj, pl[j], lsum);
+      }
+      const float lstar = block_sum<NT>(lsum, fsm);  // its barriers make lgk and pm visible
+      PQC_MARK(ws, 2, 2);
+      // out[d] = (sum_j w_j acc_j[d] + sum_k p_k V_k[d]) / l ; two threads per dimension
+      float acc = 0.0f;
+      {
+        float wv[kAccBatch];
+#pragma unroll
+        for (int x = 0; x < kAccBatch; ++x) wv[x] = pm[min(half + 2 * x, s.nblkC - 1)];
+#pragma unroll
+        for (int x = 0; x < kAccBatch; ++x) acc = fmaf(wv[x], half + 2 * x < s.nblkC ? a0[x] : 0.0f, acc);
+      }
+      for (int j0 = half + 2 * kAccBatch; j0 < s.nblkC; j0 += 2 * kAccBatch) {
+        float a[kAccBatch];
+#pragma unroll
+        for (int x = 0; x < kAccBatch; ++x) {
+          const int j = j0 + 2 * x;
+          a[x] = j < s.nblkC ? parts[((size_t)j * G + hq) * (kD + 2) + 2 + d] : 0.0f;
+        }
+#pragma unroll
+        for (int x = 0; x < kAccBatch; ++x) {
+          const int j = j0 + 2 * x;
+          if (j < s.nblkC) acc = fmaf(pm[j], a[x], acc);
+        }
+      }
+      if (need > 0 && n_cand <= 16 * sp) {
+        // the V rows are already here: weighted rows go to LDS at their rank, then are summed in rank order
+        for (int r0 = 0; r0 < need; r0 += kRankChunk) {
+          const int nr = min(kRankChunk, need - r0);
+#pragma unroll
+          for (int x = 0; x < SP; ++x) {
+            const int k = x * 16 + grp;
+            const int r = (k < n_cand ? (int)rankv[k] : 0xffff) - r0;
+            if (r >= 0 && r < nr) {
+              const float p = lgk[r0 + r];
+              float vf[8];
+              vspec[x].unpack(vf);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) vl[r * kD + owned_dim<T>(sub, e)] = p * vf[e];
+            }
+          }
+          __syncthreads();
+          for (int r = half; r < nr; r += 2) acc += vl[r * kD + d];
+          __syncthreads();
+        }
+      } else if (need > 0) {
+        // many candidates: admitted rows are fetched in rank order, 16 rows at a time per pass
+        float va[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) va[e] = 0.0f;
+        for (int k0 = 0; k0 < need; k0 += 16 * kVPass) {
+          RowRaw<T> vr[kVPass];
+#pragma unroll
+          for (int x = 0; x < kVPass; ++x) {
+            const int k = min(k0 + x * 16 + grp, need - 1);
+            vr[x].load_row(recs + (size_t)ordv[k] * ws.rec_stride + sizeof(CandHeader), sub);
+          }
+          PQC_LOADS_ISSUED();
+#pragma unroll
+          for (int x = 0; x < kVPass; ++x) {
+            const int k = k0 + x * 16 + grp;
+            const float p = k < need ? lgk[k] : 0.0f;
+            float vf[8];
+            vr[x].unpack(vf);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) va[e] = fmaf(p, vf[e], va[e]);
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vl[grp * kD + owned_dim<T>(sub, e)] = va[e];
+        __syncthreads();
+#pragma unroll
+        for (int x = 0; x < 8; ++x) acc += vl[(half * 8 + x) * kD + d];
+      }
+      if (half == 1) half_acc[d] = acc;
+      __syncthreads();
+      if (half == 0) out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + d] = (acc + half_acc[d]) / lstar;
+      PQC_MARK(ws, 2, 3);
+    }
+  } else {
+    // generic path: radix select of the need-th largest staged composite, 8 bits per pass
+    {
+      int nl, nc;
+      scan_counts(cnt0, nl, nc);
+    }
+    auto owner = [&](int p) -> int {  // largest j with pre_cand[j] <= p
+      int lo = 0, hi = s.nblkC - 1;
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (pre_cand[mid] <= p) lo = mid; else hi = mid - 1;
+      }
+      return lo;
+    };
+    auto cand_at = [&](int i) -> unsigned long long {
+      const int j = owner(i);
+      return stage_u[(size_t)j * s.stageStride + s.tokC - 1 - (i - pre_cand[j])];
+    };
+    unsigned long long thr = ~0ull;
+    if (need > 0) {
+      unsigned long long prefix = 0;
+      int want = need;
+      for (int shift = 56; shift >= 0; shift -= 8) {
+        rhist[tid] = 0u;
+        __syncthreads();
+        for (int i = tid; i < n_cand; i += NT) {
+          const unsigned long long c = cand_at(i);
+          if (shift == 56 || (c >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&rhist[(unsigned)(c >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+          int cum = 0, dg = 255;
+          for (; dg > 0; --dg) {
+            if (cum + (int)rhist[dg] >= want) break;
+            cum += (int)rhist[dg];
+          }
+          digit_sm[0] = dg;
+          digit_sm[1] = want - cum;
+        }
+        __syncthreads();
+        prefix |= (unsigned long long)digit_sm[0] << shift;
+        want = digit_sm[1];
+        __syncthreads();
+      }
+      thr = prefix;
+    }
+    // admitted candidates in token order, NT candidates per round: indices out, rows attended
+    AttnState<1> st;
+    st.init();
+    float qr[1][8];
+    if constexpr (ATTN) load_query<T, 1>(q + ((size_t)b * s.Hq + (size_t)g * G + hq) * kD, s.scale_log2e, qr);
+    int carry = 0;
+    for (int i0 = 0; i0 < (need > 0 ? n_cand : 0); i0 += NT) {
+      const int i = i0 + tid;
+      unsigned long long c = 0;
+      if (i < n_cand) c = cand_at(i);
+      const int flag = (i < n_cand && c >= thr) ? 1 : 0;
+      int tot;
+      const int pos = block_exclusive_scan<NT>(flag, &tot, scan_sm);
+      if (flag) {
+        rows_sm[pos] = composite_token(c);
+        if (hq == 0) out[s.I + n_above + carry + pos] = composite_token(c);
+      }
+      __syncthreads();
+      if constexpr (ATTN) {
+        auto row_at = [&](int p) -> int { return rows_sm[p]; };
+        attend_rows<T, 1, 4>(kc + (size_t)u * s.cap * kD, vc + (size_t)u * s.cap * kD, s.N, row_at, tot, w * 16, NW * 16, qr, st);
+      }
+      __syncthreads();
+      carry += tot;
+    }
+    if constexpr (ATTN) {
+      stash_wave_state<T, 1>(st, red);
+      __syncthreads();
+      float m_own, l_own, acc;
+      combine_waves<1, NW>(red, 0, d, m_own, l_own, acc);
+      float mx = m_own;
+      for (int j = tid; j < s.nblkC; j += NT) mx = fmaxf(mx, pm[j]);
+      const float mstar = block_max<NT>(mx, fsm);
+      float lsum = 0.0f;
+      for (int j = tid; j < s.nblkC; j += NT) {
+        const float wj = __builtin_amdgcn_exp2f(pm[j] - mstar);
+        pm[j] = wj;
+        lsum = fmaf(wj, pl[j], lsum);
+      }
+      const float f_own = __builtin_amdgcn_exp2f(m_own - mstar);
+      const float lstar = block_sum<NT>(lsum, fsm) + l_own * f_own;
+      acc = half == 0 ? acc * f_own : 0.0f;
+      for (int j = half; j < s.nblkC; j += 2) acc = fmaf(pm[j], parts[((size_t)j * G + hq) * (kD + 2) + 2 + d], acc);
+      if (half == 1) half_acc[d] = acc;
+      __syncthreads();
+      if (half == 0) out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + d] = (acc + half_acc[d]) / lstar;
+    }
+  }
+  PQC_NOTE(ws, 2, 13, n_above);
+  PQC_NOTE(ws, 2, 14, n_cand);
+  PQC_NOTE(ws, 2, 15, need);
 }
 
 // ---------------------------------------------- stand-alone attention over a list
@@ -1344,7 +1139,7 @@ __global__ __launch_bounds__(256) void attn_list_kernel(Shape s, Workspace ws, c
     MfmaState st;
     st.init();
     mfma_attend(reinterpret_cast<const bf16_t*>(kbase), reinterpret_cast<const bf16_t*>(vbase), s.N, row_at, count,
-                w * 16 * kMfmaTiles, NW * 16 * kMfmaTiles, s.scale_log2e, qf, vtile + w * kVTileBytes, st, []() {});
+                w * 16 * kMfmaTiles, NW * 16 * kMfmaTiles, s.scale_log2e, qf, vtile + w * kVTileBytes, st);
     mfma_stash_wave_state<G>(st, red);
   } else {
     float qr[G][8];

@@ -105,11 +105,11 @@ def test_argument_checks_of_the_newer_entry_points():
     assert lib.pqc_pair_counts_add(C.byref(four), p, 0, p, None) == -2
     assert lib.pqc_pair_counts(C.byref(cfg), None, p, None) == -1
     assert lib.pqc_pair_counts_add(C.byref(cfg), p, 4096, p, None) == -1
-    # decode phases 0..1 only; indexed decode needs its pair counts and a supported shape
+    # decode phases 0..2 only; indexed decode needs its pair counts and a supported shape
     need = lib.pqc_workspace_bytes(C.byref(cfg))
     h = C.c_void_p()
     assert lib.pqc_create(C.byref(h), C.byref(cfg), C.c_void_p(4096), need) == 0
-    assert lib.pqc_decode_phase(h, 2, *([p] * 7), None) == -1
+    assert lib.pqc_decode_phase(h, 3, *([p] * 7), None) == -1
     assert lib.pqc_decode_phase(h, -1, *([p] * 7), None) == -1
     assert lib.pqc_decode_indexed(h, p, p, p, None, p, p, p, p, None) == -1
     lib.pqc_destroy(h)

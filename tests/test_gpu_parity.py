@@ -172,7 +172,7 @@ def _small(**kw):
     # many units: more than the 256 compute units, a multiple of 8 and not (the last ones are not interleaved over the XCDs)
     dict(batch=40, n_q_heads=16, n_kv_heads=8, n_tokens=600, topk=60),
     dict(batch=37, n_q_heads=6, n_kv_heads=3, n_tokens=777, topk=99, pq_m=4),
-    # more select workgroups per unit than a workgroup has threads
+    # more select workgroups per unit than the finalize kernel has threads
     dict(n_tokens=140001, topk=9000, n_q_heads=2, n_kv_heads=1, pq_centroids=64),
     dict(n_tokens=200003, topk=30000, n_q_heads=8, n_kv_heads=1, pq_centroids=64),
 ], ids=lambda kw: ",".join(f"{k}={v}" for k, v in kw.items()))
@@ -273,7 +273,7 @@ def test_context_reuse_and_two_contexts(pqc):
 
 
 def test_decode_phase_by_phase_equals_decode(pqc):
-    # the profiling entry point launches the same two kernels one at a time
+    # the profiling entry point launches the same three kernels one at a time
     w = _small(n_tokens=9000, topk=1200, pq_m=4)
     p = build_problem(w, seed=9)
     dev, ctx = upload(pqc, p), pqc.PQCache(w, DEV)
@@ -282,18 +282,21 @@ def test_decode_phase_by_phase_equals_decode(pqc):
     for _ in range(2):  # twice: a complete pass leaves the workspace ready for the next
         idx.zero_()
         out.zero_()
-        for phase in range(2):
+        for phase in range(3):
             ctx.decode_phase(phase, dev["q"], dev["centroids"], dev["codes"], dev["k"], dev["v"], idx, out)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(a[0], idx.cpu().numpy())
         np.testing.assert_array_equal(a[1].view(np.uint32), out.cpu().numpy().view(np.uint32))
     full_check(p, a[0], a[1])
     # a phase out of turn is refused, and a step left unfinished does not disturb the next full call
+    args = (dev["q"], dev["centroids"], dev["codes"], dev["k"], dev["v"], idx, out)
     with pytest.raises(pqc.PQCacheError):
-        ctx.decode_phase(1, dev["q"], dev["centroids"], dev["codes"], dev["k"], dev["v"], idx, out)
-    ctx.decode_phase(0, dev["q"], dev["centroids"], dev["codes"], dev["k"], dev["v"], idx, out)
+        ctx.decode_phase(1, *args)
+    ctx.decode_phase(0, *args)
     with pytest.raises(pqc.PQCacheError):
-        ctx.decode_phase(0, dev["q"], dev["centroids"], dev["codes"], dev["k"], dev["v"], idx, out)
+        ctx.decode_phase(0, *args)
+    with pytest.raises(pqc.PQCacheError):
+        ctx.decode_phase(2, *args)
     b = run_decode(pqc, p, ctx, dev)
     np.testing.assert_array_equal(a[0], b[0])
     np.testing.assert_array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
