@@ -201,7 +201,9 @@ int pqc_decode_static(const pqc_config* cfg, const void* q, const float* centroi
  *                                     alone, built by pqc_pair_counts and kept in step with
  *                                     appended codes by pqc_pair_counts_add (caller-owned)
  * PQC_EUNSUPPORTED unless pq_m == 2, pq_centroids <= 64 and the capacity (n_tokens when
- * none is given) is a multiple of 8. */
+ * none is given) is a multiple of 8.  pair_counts that do not belong to `codes` (a token
+ * appended and not counted, or counted twice) give an unspecified selection; every write
+ * still stays inside out_idx and out_attn. */
 int pqc_decode_indexed(pqc_ctx* ctx, const void* q, const float* centroids, const uint8_t* codes,
                        const uint32_t* pair_counts, const void* k_cache, const void* v_cache,
                        int32_t* out_idx, float* out_attn, void* stream);
@@ -310,10 +312,10 @@ int pqc_pq_encode_token(const pqc_config* cfg, const void* key, const float* cen
  *                                    the entries of one unit must be distinct
  *   counts  [B][Hkv][nb]     int32   listed tokens per block (fully overwritten)
  *   blocks  [B][Hkv][k_cache] int32  the k_cache blocks with the largest counts, a lower
- *                                    block index winning among equal counts: first the
- *                                    blocks above the cut in ascending order, then those
- *                                    admitted at the cut in ascending order; may be NULL
- *                                    when k_cache == 0.  0 <= k_cache <= nb.
+ *                                    block index winning among equal counts, in the order
+ *                                    in which pqc_block_cache_update serves them: fullest
+ *                                    first, lower index first among equal counts; may be
+ *                                    NULL when k_cache == 0.  0 <= k_cache <= nb.
  * Needs no context and no workspace.  PQC_EINVAL on null pointers or sizes out of range. */
 int pqc_block_stats(const pqc_config* cfg, const int32_t* idx, int64_t n_idx, int32_t block_tokens,
                     int32_t k_cache, int32_t* counts, int32_t* blocks, void* stream);

@@ -25,11 +25,18 @@ struct Plan {
   int rec_stride;
 };
 
+// Launch-shape overrides from the environment, for sweeps: debug builds (-DPQC_TRACE) only.  The shipped library
+// reads no environment variable.
 int env_int(const char* name, int fallback) {
+#ifdef PQC_TRACE
   const char* v = std::getenv(name);
   if (!v || !*v) return fallback;
   const int x = std::atoi(v);
   return x > 0 ? x : fallback;
+#else
+  (void)name;
+  return fallback;
+#endif
 }
 
 // Offsets of the workspace regions for the given per-unit sizes.

@@ -326,20 +326,30 @@ __global__ __launch_bounds__(256) void pq_mean_kernel(BuildShape s, const unsign
 // most retrieved tokens.  One workgroup per unit: counts per block (global atomics, read
 // back through the L2 with returning atomics), a histogram of the count values (a count
 // never exceeds the block size when the listed tokens are distinct), the cut c* and the
-// number of blocks to admit at the cut, then an ordered compaction: blocks above the cut in
-// ascending order, then the lowest-numbered blocks at the cut.
+// number of blocks to admit at the cut, then the blocks in the order in which the cache
+// refresh serves them: fullest first, the lower block number first among equal counts.  A
+// block's place is (blocks with a larger count) + (blocks before it with the same count);
+// the second term comes from a counter per count value that the waves of a chunk of 1024
+// blocks advance one after the other, lanes with equal counts being ranked inside a wave
+// by ballots.
 constexpr int kCountBins = 2048;
 __global__ __launch_bounds__(1024) void block_stats_kernel(const int* __restrict__ idx, long long n_idx, int N, int bt,
                                                            int nb, int k_cache, int* __restrict__ counts,
                                                            int* __restrict__ blocks) {
   constexpr int NT = 1024, NW = NT / 64;
   __shared__ unsigned hist[kCountBins];
+  __shared__ int above[kCountBins];  // blocks with a larger count
+  __shared__ int run[kCountBins];    // blocks with this count placed so far
   __shared__ int scan_sm[2 * NW + 1];
   __shared__ int res[2];
-  const int u = blockIdx.x, tid = threadIdx.x;
+  __shared__ int any_sm;
+  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   int* cu = counts + (size_t)u * nb;
   for (int i = tid; i < nb; i += NT) cu[i] = 0;
-  for (int i = tid; i < kCountBins; i += NT) hist[i] = 0u;
+  for (int i = tid; i < kCountBins; i += NT) {
+    hist[i] = 0u;
+    run[i] = 0;
+  }
   if (tid == 0) {
     res[0] = kCountBins;  // cut (no block reaches it when k_cache == 0)
     res[1] = 0;           // blocks above the cut
@@ -359,6 +369,8 @@ __global__ __launch_bounds__(1024) void block_stats_kernel(const int* __restrict
   const int h0 = (int)hist[kCountBins - 1 - 2 * tid], h1 = (int)hist[kCountBins - 2 - 2 * tid];
   int total;
   int cum = block_exclusive_scan<NT>(h0 + h1, &total, scan_sm);
+  above[kCountBins - 1 - 2 * tid] = cum;
+  above[kCountBins - 2 - 2 * tid] = cum + h0;
   if (k_cache > 0 && cum < k_cache && cum + h0 >= k_cache) {
     res[0] = kCountBins - 1 - 2 * tid;
     res[1] = cum;
@@ -369,17 +381,49 @@ __global__ __launch_bounds__(1024) void block_stats_kernel(const int* __restrict
   __syncthreads();
   const int cut = res[0], n_above = res[1], need = k_cache - n_above;
   int* out = blocks + (size_t)u * k_cache;
-  int carry_a = 0, carry_t = 0;
+  int carry_t = 0;
   for (int i0 = 0; i0 < (k_cache > 0 ? nb : 0); i0 += NT) {
     const int i = i0 + tid;
     const int c = i < nb ? min(atomicAdd(&cu[i], 0), kCountBins - 1) : -1;
-    int ta, tt;
-    const int pa = block_exclusive_scan<NT>(c > cut ? 1 : 0, &ta, scan_sm);
+    const bool a = c > cut;
+    // blocks at the cut: the lowest-numbered `need` of them, behind all blocks above the cut
+    int tt;
     const int pt = block_exclusive_scan<NT>(c == cut ? 1 : 0, &tt, scan_sm);
-    if (c > cut) out[carry_a + pa] = i;
     if (c == cut && carry_t + pt < need) out[n_above + carry_t + pt] = i;
-    carry_a += ta;
     carry_t += tt;
+    // blocks above the cut (chunks without any skip the ordered part)
+    if (tid == 0) any_sm = 0;
+    __syncthreads();
+    if (a) any_sm = 1;
+    __syncthreads();
+    if (any_sm) {  // uniform
+      // rank among the wave's lanes with the same count (lanes ascend with the block number), one count value per round
+      int rank_w = 0, cnt_w = 0;
+      bool leader = false;
+      unsigned long long todo = __ballot(a);
+      while (todo) {  // wave-uniform
+        const int src = __ffsll((long long)todo) - 1;
+        const int k0 = __shfl(c, src);
+        const unsigned long long m = __ballot(a && c == k0);
+        if (a && c == k0) {
+          rank_w = __popcll(m & ((1ull << lane) - 1ull));
+          cnt_w = __popcll(m);
+          leader = lane == src;
+        }
+        todo &= ~m;
+      }
+      // the waves advance the per-count counters one after the other (a wave's LDS accesses stay in program order:
+      // every lane has read the counter before the leader of its count value moves it on)
+      int base = 0;
+      for (int ww = 0; ww < NW; ++ww) {
+        if (w == ww && a) {
+          base = run[c];
+          if (leader) run[c] = base + cnt_w;
+        }
+        __syncthreads();
+      }
+      if (a) out[above[c] + base + rank_w] = i;
+    }
   }
 }
 
@@ -513,8 +557,8 @@ __global__ __launch_bounds__(256) void pair_count_kernel(const uint8_t* __restri
   const int t1 = min(N, ((int)blockIdx.x + 1) * kPairTok);
   for (int t = blockIdx.x * kPairTok + tid; t < t1; t += 256) {
     const unsigned cw = cu[t];
-    const int pr = (int)(cw & 0xffu) + C * (int)(cw >> 8);
-    if (pr < np) atomicAdd(&h[pr], 1u);
+    const int c0 = (int)(cw & 0xffu), c1 = (int)(cw >> 8);
+    if (c0 < C && c1 < C) atomicAdd(&h[c0 + C * c1], 1u);  // a code outside [0, C) names no pair: not counted
   }
   __syncthreads();
   for (int i = tid; i < np; i += 256)
@@ -527,8 +571,8 @@ __global__ void pair_count_add_kernel(const uint8_t* __restrict__ codes, int cap
   const int u = blockIdx.x * blockDim.x + threadIdx.x;
   if (u >= units) return;
   const uint8_t* cp = codes + ((size_t)u * cap + position) * 2;
-  const int pr = (int)cp[0] + C * (int)cp[1];
-  if (pr < C * C) counts[(size_t)u * C * C + pr] += 1u;
+  const int c0 = (int)cp[0], c1 = (int)cp[1];
+  if (c0 < C && c1 < C) counts[(size_t)u * C * C + c0 + C * c1] += 1u;
 }
 
 }  // namespace pqc

@@ -713,8 +713,8 @@ __device__ __forceinline__ PairThreshold pair_threshold(const Shape& s, const T*
     unsigned short cw = wcode;
     const int t = wt < s.I ? wt : s.N - s.L + (wt - s.I);
     if (wt >= NT) cw = *reinterpret_cast<const unsigned short*>(codes_u + (size_t)t * 2);
-    const int pr = (cw & 0xff) + C * (cw >> 8);
-    if (pr < np && t != uncounted) atomicSub(&L.cnt[pr], 1u);
+    const int w0 = cw & 0xff, w1 = cw >> 8;  // a code outside [0, C) was never counted
+    if (w0 < C && w1 < C && t != uncounted) atomicSub(&L.cnt[w0 + C * w1], 1u);
   }
   __syncthreads();
   mark(10);

@@ -797,7 +797,9 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
 #pragma unroll
         for (int y = 0; y < 4; ++y) {
           const int pos = base + p0 + y * 64 + lane;
-          if (p0 + y * 64 + lane < n) out[pos < s.I + n_above ? pos : pos + need] = v[y];
+          // (the bound only matters when the caller's pair counts do not belong to the codes: then n_above can exceed K)
+          const int dst = pos < s.I + n_above ? pos : pos + need;
+          if (p0 + y * 64 + lane < n && dst < s.Ktot) out[dst] = v[y];
         }
       }
     }
@@ -907,7 +909,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
           int rank = 0;
           for (int j = 0; j < n_cand; ++j) rank += comp[j] > mine ? 1 : 0;
           if (rank < need) {
-            if (hq == 0) out[s.I + n_above + rank] = composite_token(mine);  // best first
+            if (hq == 0 && s.I + n_above + rank < s.Ktot) out[s.I + n_above + rank] = composite_token(mine);  // best first
             lgk[rank] = rl[x] * s.scale_log2e;
             ordv[rank] = (unsigned short)k;
             rankv[k] = (unsigned short)rank;
@@ -1073,7 +1075,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       const int pos = block_exclusive_scan<NT>(flag, &tot, scan_sm);
       if (flag) {
         rows_sm[pos] = composite_token(c);
-        if (hq == 0) out[s.I + n_above + carry + pos] = composite_token(c);
+        if (hq == 0 && s.I + n_above + carry + pos < s.Ktot) out[s.I + n_above + carry + pos] = composite_token(c);
       }
       __syncthreads();
       if constexpr (ATTN) {

@@ -426,3 +426,59 @@ def test_layers_recorded_into_a_hip_graph_replay_correctly(pqc, indexed):
             np.testing.assert_array_equal(oi.cpu().numpy(), ei, err_msg=f"replay {rep}")
             np.testing.assert_array_equal(oa.cpu().numpy().view(np.uint32), ea.view(np.uint32), err_msg=f"replay {rep}")
     full_check(layers[-1], bufs[-1][0].cpu().numpy(), bufs[-1][1].cpu().numpy())
+
+
+def test_indexed_decode_with_counts_of_other_codes_stays_inside_its_outputs(pqc):
+    # pair counts that do not belong to the codes (here: the counts of another code tensor, and counts that are all
+    # zero but one) make the selection meaningless, but nothing may be written outside out_idx and out_attn: the
+    # outputs are slices of larger buffers whose surroundings must stay as they were.  Codes 20..39 with 16 centroids
+    # are out of range below 255 and name no pair either.
+    w = _small(pq_m=2, pq_centroids=16, n_tokens=3000 - 3000 % 8, topk=300)
+    p = build_problem(w, seed=17)
+    dev, ctx = upload(pqc, p), pqc.PQCache(w, DEV)
+    rng = np.random.default_rng(5)
+    other = torch.from_numpy(rng.integers(0, 16, size=p.codes.shape, dtype=np.uint8)).to(DEV)
+    skew = torch.zeros((w.batch, w.n_kv_heads, 256), dtype=torch.int32, device=DEV)
+    skew[:, :, 7] = w.n_tokens
+    for counts in (pqc.pair_counts(w, other), skew):
+        pad = 4096
+        big_i = torch.full((pad + w.batch * w.n_kv_heads * w.n_selected + pad,), -77, dtype=torch.int32, device=DEV)
+        big_o = torch.full((pad + w.batch * w.n_q_heads * w.head_dim + pad,), 123.0, dtype=torch.float32, device=DEV)
+        oi = big_i[pad:-pad].view(w.batch, w.n_kv_heads, w.n_selected)
+        oo = big_o[pad:-pad].view(w.batch, w.n_q_heads, w.head_dim)
+        ctx.decode_indexed(dev["q"], dev["centroids"], dev["codes"], counts, dev["k"], dev["v"], oi, oo)
+        torch.cuda.synchronize()
+        assert bool((big_i[:pad] == -77).all()) and bool((big_i[-pad:] == -77).all())
+        assert bool((big_o[:pad] == 123.0).all()) and bool((big_o[-pad:] == 123.0).all())
+        got = oi.cpu().numpy()
+        written = got[got != -77]
+        assert written.min() >= 0 and written.max() < w.n_tokens
+    # and the context is none the worse for it
+    idx, out = run_decode(pqc, p, ctx, dev)
+    full_check(p, idx, out)
+
+
+def test_pair_counts_skip_codes_that_name_no_centroid(pqc):
+    # 16 centroids: a code byte of 20 in the first partition must not be counted as pair (4, 1)
+    w = _small(pq_m=2, pq_centroids=16, n_tokens=1000)
+    rng = np.random.default_rng(4)
+    codes = rng.integers(0, 16, size=(1, 2, 1000, 2), dtype=np.uint8)
+    codes[0, 0, 10] = (20, 0)
+    codes[0, 1, 11] = (3, 16)
+    codes[0, 1, 12] = (200, 200)
+    counts = pqc.pair_counts(w, torch.from_numpy(codes).to(DEV))
+    torch.cuda.synchronize()
+    want = np.zeros((1, 2, 256), np.int64)
+    for g in range(2):
+        for c0, c1 in codes[0, g]:
+            if c0 < 16 and c1 < 16:
+                want[0, g, int(c0) + 16 * int(c1)] += 1
+    np.testing.assert_array_equal(counts.cpu().numpy(), want)
+    assert int(counts.sum().item()) == 2000 - 3
+    # the single-token update applies the same rule
+    cd = torch.from_numpy(codes).to(DEV)
+    before = counts.clone()
+    pqc.pair_counts_add(w, cd, 10, counts)   # unit 0: (20, 0) names no pair; unit 1: an ordinary code
+    torch.cuda.synchronize()
+    diff = (counts - before).cpu().numpy()
+    assert diff[0, 0].sum() == 0 and diff[0, 1].sum() == 1
