@@ -1052,6 +1052,14 @@ __device__ __forceinline__ void combine_waves(const float* red, int h, int d, fl
   }
 }
 
+// Build switch for the record of why the matrix cores are used: with -DPQC_VECTOR_ATTENTION bf16 caches take the
+// vector-ALU attention above, like fp32 caches (a compile-time choice, there is no run-time dispatch between the two).
+#ifdef PQC_VECTOR_ATTENTION
+constexpr bool kMatrixCoreAttention = false;
+#else
+constexpr bool kMatrixCoreAttention = true;
+#endif
+
 // ------------------------------------------------------ attention, matrix cores
 // bf16 caches.  Per wave and per tile of 16 listed rows:
 //   S[token][head] = K_tile[16 x 128] . Q^T[128 x 16]     4 x v_mfma_f32_16x16x32_bf16

@@ -330,7 +330,7 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
                                                      const unsigned* __restrict__ pair_counts = nullptr,
                                                      int uncounted = -1 /* PAIRS: a window token not in the counts yet */) {
   constexpr int NT = 256, NW = 4;
-  constexpr bool kMfma = ATTN && sizeof(T) == 2;
+  constexpr bool kMfma = ATTN && sizeof(T) == 2 && kMatrixCoreAttention;
   static_assert(!PAIRS || (SRC::kFromCodes && SRC::M == 2), "pair counts exist for two partitions only");
   extern __shared__ unsigned short list[];  // [tokC] token offsets from the workgroup's first token
   __shared__ std::conditional_t<PAIRS, PairLds, int> pl;
@@ -1120,7 +1120,7 @@ __global__ __launch_bounds__(256) void attn_list_kernel(Shape s, Workspace ws, c
                                                         const T* __restrict__ kc, const T* __restrict__ vc,
                                                         const int* __restrict__ idx) {
   constexpr int NT = 256, NW = 4;
-  constexpr bool kMfma = sizeof(T) == 2;
+  constexpr bool kMfma = sizeof(T) == 2 && kMatrixCoreAttention;
   __shared__ float red[NW * G * (kD + 2)];
   __shared__ __attribute__((aligned(16))) unsigned char vtile[kMfma ? NW * kVTileBytes : 16];
   const int u = blockIdx.y, tid = threadIdx.x, w = tid >> 6;
