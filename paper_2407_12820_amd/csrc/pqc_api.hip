@@ -49,7 +49,7 @@ void lay_out(Plan* p, size_t bins_per_unit, size_t stage_words_per_unit, size_t 
   p->off_range = off; off = align_up(off + sizeof(float2) * units);
   p->off_hist = off;  off = align_up(off + sizeof(unsigned) * units * (kHistCopies * kNB + 1));  // + record counters
   p->off_bins = off;  off = align_up(off + sizeof(unsigned short) * units * bins_per_unit);
-  p->off_crec = off;  off = align_up(off + (size_t)p->rec_stride * kCandRec * units);
+  p->off_crec = off;  off = align_up(off + (size_t)p->rec_stride * units);
   p->off_stage = off; off = align_up(off + sizeof(unsigned long long) * units * stage_words_per_unit);
   p->off_cnt = off;   off = align_up(off + sizeof(int2) * units * counts_per_unit);
   p->off_part = off;  off = align_up(off + sizeof(float) * units * partials_per_unit * s.G * (kD + 2));
@@ -114,8 +114,11 @@ int make_plan(const pqc_config* c, Plan* p) {
   s.rowsP = env_int("PQC_ROWS_P", 256);
   s.nblkP = (s.Ktot + s.rowsP - 1) / s.rowsP;
   s.npart = s.nblkC > s.nblkP ? s.nblkC : s.nblkP;
-  if (s.npart < 2 * kAccBatch) s.npart = 2 * kAccBatch;  // finalize_kernel reads this many slots unconditionally
-  p->rec_stride = (int)sizeof(CandHeader) + kD * (c->kv_dtype == PQC_F32 ? 4 : 2);
+  p->rec_stride = (int)cand_unit_bytes(G, c->kv_dtype == PQC_F32 ? 4 : 2);
+  // finalize kernel: as many workgroups per query head (each with its share of the output dimensions) as keep the
+  // grid within about two workgroups per compute unit
+  s.slices = 1;
+  while (s.slices < kMaxSlices && units * (2 * s.slices * G + kCopyWgs) <= 512) s.slices *= 2;
   // sample ranks that bracket the K-th largest score by 5 standard errors (+2)
   const int nmid = s.N - s.I - s.L;
   s.sampleN = nmid < 1024 ? (nmid > 0 ? nmid : 1) : 1024;
@@ -149,7 +152,6 @@ size_t workspace_bound(const pqc_config* c) {
   if (nb < 1) nb = 1;
   size_t npart = (cap + s.rowsP - 1) / s.rowsP;
   if (npart < nb) npart = nb;
-  if (npart < (size_t)2 * kAccBatch) npart = (size_t)2 * kAccBatch;
   lay_out(&p, cap + 8192, cap + 8192 + 40 * nb, nb, npart);
   return p.total;
 }
@@ -237,7 +239,7 @@ void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uin
     hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC, units), dim3(256),
                        s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));
   if (phases & 4u)
-    hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs + (ctx->append.key ? 1 : 0), units), dim3(256),
+    hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G * s.slices + kCopyWgs + (ctx->append.key ? 1 : 0), units), dim3(256),
                        (4 * s.nblkC + 2) * sizeof(int), st, s, ctx->ws, qt, kt, vt, out_idx, out_attn, ctx->append);
 }
 
@@ -275,7 +277,7 @@ void launch_indexed_tg(pqc_ctx* ctx, const void* q, const float* cent, const uin
   hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<2>, true, true>), dim3(s.nblkC, units), dim3(256),
                      s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes), cent,
                      pair_counts, ctx->append.key ? ctx->append.position : -1);
-  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G + kCopyWgs + (ctx->append.key ? 1 : 0), units), dim3(256),
+  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G * s.slices + kCopyWgs + (ctx->append.key ? 1 : 0), units), dim3(256),
                      (4 * s.nblkC + 2) * sizeof(int), st, s, ctx->ws, qt, kt, vt, out_idx, out_attn, ctx->append);
 }
 

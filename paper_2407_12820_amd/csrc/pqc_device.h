@@ -34,6 +34,7 @@ struct Shape {
   int tokC, nblkC;  // select kernel: tokens per workgroup, workgroups per unit
   int rowsP, nblkP; // list-attention kernel: rows per workgroup, workgroups per unit
   int npart;        // partial slots per unit
+  int slices;       // finalize kernel: workgroups per query head (1, 2 or 4), each producing kD/slices output dimensions
   int binStride;    // stored bins per unit (nblkC * tokC)
   int stageStride;  // 8-byte words between the staging slots of consecutive select workgroups: tokC plus a pad, so that
                     // the slots do not all start on the same memory channels
@@ -43,13 +44,27 @@ struct Shape {
   float scale_log2e;
 };
 
-// Record of one boundary-bin candidate: enough for the finalize kernel to rank it and,
-// if admitted, to add it to the attention output without touching the K/V cache again.
-struct CandHeader {
-  unsigned long long composite;  // (score key, ~token): larger ranks first
-  float logit[8];                // q_h . k for the group's heads (raw, unscaled)
-  unsigned pad[6];
-};                               // 64 bytes, followed by the V row
+// What a select workgroup leaves behind for every boundary-bin candidate, enough for the finalize kernel to rank it
+// and, if admitted, to add it to the attention output without touching the K/V cache again.  Per unit, as arrays
+// over the candidates in order of arrival (at most kCandRec), so that what a finalize workgroup reads of them is dense:
+//   composite  [kCandRec]      uint64   (score key, ~token): larger ranks first
+//   logit      [G][kCandRec]   float    q_h . k for the group's heads (raw, unscaled)
+//   v          [kCandRec][kD]  T        the V row
+struct CandView {
+  unsigned long long* composite;
+  float* logit;
+  unsigned char* v;
+};
+__host__ __device__ constexpr size_t cand_unit_bytes(int G, int elem_bytes) {
+  return ((size_t)kCandRec * 8 + (size_t)G * kCandRec * 4 + (size_t)kCandRec * kD * elem_bytes + 255) / 256 * 256;
+}
+__device__ __forceinline__ CandView cand_view(unsigned char* unit_base, int G) {
+  CandView c;
+  c.composite = reinterpret_cast<unsigned long long*>(unit_base);
+  c.logit = reinterpret_cast<float*>(unit_base + (size_t)kCandRec * 8);
+  c.v = unit_base + (size_t)kCandRec * 8 + (size_t)G * kCandRec * 4;
+  return c;
+}
 
 struct BinParams;
 // Device pointers carved out of the caller's workspace.
@@ -60,7 +75,7 @@ struct Workspace {
   unsigned* hist;              // [2][units][histCopies][kNB]   zero between uses (room for kHistCopies replicas)
   unsigned* cand_count;        // [2][units]   records handed out so far (directly behind hist, zeroed with it)
   unsigned short* bins;        // [units][binStride]  per token: bin + 1, or kBinWindow inside the two windows
-  unsigned char* cand_rec;     // [units][kCandRec] records of rec_stride bytes, in order of arrival
+  unsigned char* cand_rec;     // [units] blocks of rec_stride bytes: the candidates' composites, logits and V rows (CandView)
   unsigned long long* stage;   // [units][nblkC][stageStride]: selected ids (front, int32) / candidate composites (ending at word tokC)
   int2* stage_cnt;             // [units][nblkC]     (selected, candidates)
   float* partials;             // [units][npart][G][kD+2]

@@ -555,16 +555,16 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
       stash_wave_state<T, G>(st, red);
     }
     __syncthreads();
-    float* part = ws.partials + ((size_t)u * s.npart + blockIdx.x) * G * (kD + 2);
+    // this workgroup's partial state: the accumulators as 128 floats per head ([j][h][kD] over the unit's workgroups j),
+    // the (m, l) pairs in a dense array per head behind all accumulators ([units][h][j]); see finalize_kernel
+    float* pacc = ws.partials + (((size_t)u * s.npart + blockIdx.x) * G) * kD;
+    float2* pml = reinterpret_cast<float2*>(ws.partials + (size_t)s.B * s.Hkv * s.npart * G * kD) + (size_t)u * G * s.npart + blockIdx.x;
     for (int o = tid; o < G * kD; o += NT) {
       const int h = o / kD, d = o % kD;
       float m, l, acc;
       combine_waves<G, NW>(red, h, d, m, l, acc);
-      part[h * (kD + 2) + 2 + d] = acc;
-      if (d == 0) {
-        part[h * (kD + 2)] = m;
-        part[h * (kD + 2) + 1] = l;
-      }
+      pacc[h * kD + d] = acc;
+      if (d == 0) pml[(size_t)h * s.npart] = make_float2(m, l);
     }
   }
   // (written after the attention: stores issued while the K/V loads of the co-resident workgroup
@@ -595,9 +595,8 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
       const unsigned long long comp = make_composite(cand_score(key), t);
       if (sub == 0) stage[s.tokC - 1 - c] = comp;
       if (base + c < kCandRec) {
-        unsigned char* rec = ws.cand_rec + ((size_t)u * kCandRec + base + c) * ws.rec_stride;
-        CandHeader* hd = reinterpret_cast<CandHeader*>(rec);
-        if (sub == 0) hd->composite = comp;
+        const CandView cv = cand_view(ws.cand_rec + (size_t)u * ws.rec_stride, ATTN ? G : 1);
+        if (sub == 0) cv.composite[base + c] = comp;
         if constexpr (ATTN) {
           float kf[8];
           kr.unpack(kf);
@@ -607,9 +606,9 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
 #pragma unroll
             for (int e = 0; e < 8; ++e) d = fmaf(qlds[h * kD + owned_dim<T>(sub, e)], kf[e], d);
             d = group16_sum(d);
-            if (sub == 0) hd->logit[h] = d;
+            if (sub == 0) cv.logit[h * kCandRec + base + c] = d;
           }
-          vr.store(rec + sizeof(CandHeader), sub);
+          vr.store(cv.v + (size_t)(base + c) * kD * sizeof(T), sub);
         }
       }
     }
@@ -617,12 +616,13 @@ __global__ __launch_bounds__(256, 2) void select_kernel(Shape s, Workspace ws, c
 }
 
 // ------------------------------------------------------------- 3. finalize
-// Grid (heads + kCopyWgs, units), 256 threads; heads = the group's query heads (1 for
-// the stand-alone top-k).
-//   blockIdx.x <  heads  ranks the candidates and folds the admitted ones and all partial
-//                        softmax states into this head's output; head 0 also writes the
-//                        admitted candidates' indices (best first)
-//   blockIdx.x >= heads  copy workgroups: concatenate the staged lists into out_idx; the
+// Grid (heads * SL + kCopyWgs, units), 256 threads; heads = the group's query heads, SL = Shape::slices (one
+// head, one slice for the stand-alone top-k).
+//   blockIdx.x <  heads * SL  slice blockIdx.x % SL of head blockIdx.x / SL: ranks the candidates and
+//                        folds the admitted ones and all partial softmax states into kD / SL dimensions
+//                        of this head's output; workgroup 0 also writes the admitted candidates'
+//                        indices (best first)
+//   blockIdx.x >= heads * SL  copy workgroups: concatenate the staged lists into out_idx; the
 //                        first one also zeroes the unit's histogram and record counter
 // The staged "selected" lists already hold the two windows: in workgroup order they read
 //   [0..I) , tokens above the threshold bin (ascending) , [N-L..N).
@@ -654,11 +654,11 @@ __device__ __forceinline__ float block_sum(float v, float* sm /* [NT/64] */) {
 }
 
 constexpr int kHdrPerThread = kCandRec / 256;  // candidate record headers per thread
-constexpr int kAccBatch = 32;                  // partial accumulators a thread keeps in flight at once
-constexpr int kVPass = 4;                      // dependent V-row passes in flight (16 rows each), many-candidate case
+constexpr int kAccPer = 8;                     // partial states a thread keeps in flight at once (every eighth state is its own)
+constexpr int kWarmPer = 4;                    // candidates per thread whose V rows are brought into the cache before the ranking knows which it needs
+constexpr int kMaxSlices = 4;                  // workgroups per query head, at most (32 output dimensions each)
 constexpr int kIdxLists = 4;                   // staged index lists a wave copies with loads issued up front
 constexpr int kCopyWgs = 4;                    // copy workgroups per unit
-constexpr int kRankChunk = 64;                 // admitted rows summed per pass through LDS
 
 // The code of one appended token per unit (Section 3.1: nearest centroid of each partition): nothing in the
 // step depends on it, so one more workgroup per unit of the finalize kernel computes it beside the others.
@@ -676,7 +676,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
                                                        int* __restrict__ out_idx, float* __restrict__ out_attn, AppendArgs ap) {
   constexpr int NT = 256, NW = 4;
   constexpr int heads = ATTN ? G : 1;
-  if (blockIdx.x == heads + kCopyWgs) {
+  const int SL = ATTN ? s.slices : 1;  // head workgroups per head
+  if ((int)blockIdx.x == heads * SL + kCopyWgs) {
     // -------------------------------------------------------------- append workgroup
     // one thread per centroid, the distance chain of pq_assign_kernel, the smallest (distance, centroid) pair
     // of each partition through a 64-bit LDS minimum
@@ -710,7 +711,6 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
     if (c == 0 && ap.pair_counts) ap.pair_counts[(size_t)u * s.C * s.C + (abest[0] & 0xffu) + s.C * (abest[1] & 0xffu)] += 1u;
     return;
   }
-  constexpr int SP = ATTN ? (sizeof(T) == 2 ? 8 : 4) : 1;  // passes of 16 record V rows requested up front
   extern __shared__ int dyn[];  // pre_sel[nblkC+1], pre_cand[nblkC+1], pm[nblkC], pl[nblkC]
   __shared__ int scan_sm[2 * NW + 1];
   __shared__ float fsm[NW];
@@ -718,13 +718,13 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
   __shared__ unsigned long long comp[kCandRec];  // candidate composites, in record order
   __shared__ float lgk[kCandRec];                // by rank: logit, then softmax weight of the admitted ones
   __shared__ unsigned short ordv[kCandRec];      // by rank: record
-  __shared__ unsigned short rankv[kCandRec];     // by record: rank if admitted, 0xffff otherwise
   __shared__ unsigned rhist[256];
   __shared__ int digit_sm[2];
   __shared__ int rows_sm[NT];
   __shared__ float red[ATTN ? NW * (kD + 2) : 1];
   __shared__ float half_acc[ATTN ? kD : 1];
-  __shared__ float vl[ATTN ? kRankChunk * kD : 1];
+  __shared__ float slice_sm[ATTN ? 256 : 1];  // [threads per dimension][dimensions of the workgroup]
+  __shared__ float lsm[8];
   const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = u / s.Hkv, g = u % s.Hkv;
   int* pre_sel = dyn;
@@ -761,10 +761,10 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
     n_cand = carry_c;
   };
 
-  if (blockIdx.x >= heads) {
+  if ((int)blockIdx.x >= heads * SL) {
     // ---------------------------------------------------------------- copy workgroup
     // one wave per list, coalesced; the local window moves behind the admitted candidates
-    const int cw = blockIdx.x - heads, ncw = kCopyWgs;
+    const int cw = blockIdx.x - heads * SL, ncw = kCopyWgs;
     const int2 cnt0 = cnt[min(tid, s.nblkC - 1)];
     int ix[kIdxLists][4];  // first 256 entries of this wave's first kIdxLists lists
 #pragma unroll
@@ -814,49 +814,57 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
   }
 
   // ------------------------------------------------------------------ head workgroup
-  const int hq = blockIdx.x;
-  const int d = tid & (kD - 1), half = tid >> 7;  // output dimension and half of the partials this thread sums
-  const int sub = tid & 15, grp = tid >> 4;       // 16 lanes per candidate V row
+  // One of SL workgroups of query head hq: it produces output dimensions [dims*sl, dims*sl + dims), dims = kD / SL.
+  // A compute unit reads what other compute units wrote at a small fraction of the chip's bandwidth (about a hundred
+  // cache lines per microsecond), so with few units the partial states of a head are spread over several workgroups,
+  // each reading only its dimensions of every state, and everything a workgroup reads of the candidates is dense.
+  const int hq = (int)blockIdx.x / SL, sl = (int)blockIdx.x % SL;
+  const int dims = kD / SL, nps = NT / dims;   // output dimensions of this workgroup; threads per dimension (2, 4 or 8)
+  const int dl = tid & (dims - 1), ps = tid / dims;  // dimension inside the slice; which share of the states and admitted rows
+  const int d = dims * sl + dl;
+  const int units = s.B * s.Hkv;
   // ---- everything whose address is known up front is requested first
-  const unsigned char* recs = ws.cand_rec + (size_t)u * kCandRec * ws.rec_stride;
-  unsigned long long rc[kHdrPerThread];  // record x*NT + tid; the first NT are requested up front
+  const CandView cv = cand_view(ws.cand_rec + (size_t)u * ws.rec_stride, heads);
+  unsigned long long rc[kHdrPerThread];  // candidate x*NT + tid; the first NT are requested up front
   float rl[kHdrPerThread];
-  {
-    const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)tid * ws.rec_stride);
-    rc[0] = hd->composite;
-    rl[0] = ATTN ? hd->logit[hq] : 0.0f;
-  }
-  const float* parts = ws.partials + (size_t)u * s.npart * G * (kD + 2);
+  rc[0] = cv.composite[tid];
+  rl[0] = ATTN ? cv.logit[hq * kCandRec + tid] : 0.0f;
+  const float* pacc = ws.partials + (size_t)u * s.npart * G * kD;                                   // [j][h][kD]
+  const float2* pml = reinterpret_cast<const float2*>(ws.partials + (size_t)units * s.npart * G * kD) +
+                      ((size_t)u * G + hq) * s.npart;                                                // [j] of this head
   const int jc = min(tid, s.nblkC - 1);
   const int2 cnt0 = cnt[jc];  // list sizes of the first NT select workgroups
-  float pm0 = 0.0f, pl0 = 0.0f;
-  float a0[kAccBatch];  // first batch of this thread's partial accumulators: lists half, half+2, ...
-  RowRaw<T> vspec[SP];  // V rows of the first 16*sp records
-  // with many head workgroups in flight the unused part of this guess is real traffic: guess less
-  const int sp = (int)gridDim.y * heads <= 64 ? SP : SP / 2;
+  float2 ml0 = make_float2(kNegBig, 0.0f);
+  float a0[kAccPer];  // this thread's first states: ps, ps + nps, ...
   if constexpr (ATTN) {
-    pm0 = parts[((size_t)jc * G + hq) * (kD + 2)];
-    pl0 = parts[((size_t)jc * G + hq) * (kD + 2) + 1];
-    const float* a0p = parts + ((size_t)half * G + hq) * (kD + 2) + 2 + d;
+    ml0 = pml[jc];
 #pragma unroll
-    for (int x = 0; x < kAccBatch; ++x)  // lists that do not exist re-read the first one (a cache hit, no extra traffic)
-      a0[x] = a0p[half + 2 * x < s.nblkC ? (size_t)x * (2 * G * (kD + 2)) : (size_t)0];
+    for (int x = 0; x < kAccPer; ++x)  // states that do not exist re-read the first one (a cache hit, no extra traffic)
+      a0[x] = pacc[((size_t)(ps + nps * x < s.nblkC ? ps + nps * x : 0) * G + hq) * kD + d];
+    // the V rows of the first candidates, this workgroup's dimensions: nothing is done with them here, but the rows
+    // the ranking picks further down are then found in the cache instead of in memory
 #pragma unroll
-    for (int x = 0; x < SP; ++x)
-      if (x < sp) vspec[x].load_row(recs + (size_t)(x * 16 + grp) * ws.rec_stride + sizeof(CandHeader), sub);
+    for (int x = 0; x < kWarmPer; ++x) {
+      const float warm = load_as_float<T>(reinterpret_cast<const T*>(cv.v) + (size_t)(ps + nps * x) * kD, d);
+      asm volatile("" ::"v"(warm));
+    }
   }
   PQC_LOADS_ISSUED();
+  float mpart = kNegBig;  // largest maximum of the partial states
   if constexpr (ATTN) {
     if (tid < s.nblkC) {
-      pm[tid] = pm0;
-      pl[tid] = pl0;
+      pm[tid] = ml0.x;
+      pl[tid] = ml0.y;
+      mpart = ml0.x;
     }
     for (int j = NT + tid; j < s.nblkC; j += NT) {  // beyond the first NT lists (very long contexts)
-      pm[j] = parts[((size_t)j * G + hq) * (kD + 2)];
-      pl[j] = parts[((size_t)j * G + hq) * (kD + 2) + 1];
+      const float2 v = pml[j];
+      pm[j] = v.x;
+      pl[j] = v.y;
+      mpart = fmaxf(mpart, v.x);
     }
   }
-  // totals of the per-workgroup list sizes
+  // totals of the per-workgroup list sizes, and that maximum (one barrier)
   int n_list, n_cand;
   {
     int ss = tid < s.nblkC ? cnt0.x : 0, sc = tid < s.nblkC ? cnt0.y : 0;
@@ -865,11 +873,13 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       ss += c.x;
       sc += c.y;
     }
-    ss = wave_sum(ss);
-    sc = wave_sum(sc);
+    ss = wave_last(wave_inclusive_scan(ss));
+    sc = wave_last(wave_inclusive_scan(sc));
+    mpart = wave_max(mpart);
     if (lane == 0) {
       ism[w] = ss;
       ism[NW + w] = sc;
+      fsm[w] = mpart;
     }
     __syncthreads();  // also: pm, pl visible
     n_list = 0;
@@ -878,6 +888,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
     for (int i = 0; i < NW; ++i) {
       n_list += ism[i];
       n_cand += ism[NW + i];
+      mpart = fmaxf(mpart, fsm[i]);
     }
   }
   const int n_above = max(0, n_list - s.I - s.L);  // n_list = I + (tokens above the bin) + L
@@ -892,9 +903,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
         rc[x] = 0ull;
         rl[x] = 0.0f;
         if (x * NT + tid < n_cand) {  // rare: more than NT candidates
-          const CandHeader* hd = reinterpret_cast<const CandHeader*>(recs + (size_t)(x * NT + tid) * ws.rec_stride);
-          rc[x] = hd->composite;
-          rl[x] = ATTN ? hd->logit[hq] : 0.0f;
+          rc[x] = cv.composite[x * NT + tid];
+          rl[x] = ATTN ? cv.logit[hq * kCandRec + x * NT + tid] : 0.0f;
         }
       }
 #pragma unroll
@@ -909,113 +919,78 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
           int rank = 0;
           for (int j = 0; j < n_cand; ++j) rank += comp[j] > mine ? 1 : 0;
           if (rank < need) {
-            if (hq == 0 && s.I + n_above + rank < s.Ktot) out[s.I + n_above + rank] = composite_token(mine);  // best first
+            if (blockIdx.x == 0 && s.I + n_above + rank < s.Ktot) out[s.I + n_above + rank] = composite_token(mine);  // best first
             lgk[rank] = rl[x] * s.scale_log2e;
             ordv[rank] = (unsigned short)k;
-            rankv[k] = (unsigned short)rank;
-          } else {
-            rankv[k] = 0xffffu;
           }
         }
       }
       __syncthreads();
     }
     if constexpr (ATTN) {
-      float mx = kNegBig;
-      for (int k = tid; k < need; k += NT) mx = fmaxf(mx, lgk[k]);
-      for (int j = tid; j < s.nblkC; j += NT) mx = fmaxf(mx, pm[j]);
-      const float mstar = block_max<NT>(mx, fsm);
-      float lsum = 0.0f;
-      for (int k = tid; k < need; k += NT) {
-        const float p = __builtin_amdgcn_exp2f(lgk[k] - mstar);
-        lgk[k] = p;
-        lsum += p;
-      }
-      for (int j = tid; j < s.nblkC; j += NT) {
-        const float wj = __builtin_amdgcn_exp2f(pm[j] - mstar);
-        pm[j] = wj;
-        lsum = fmaf(wj, pl[j], lsum);
-      }
-      const float lstar = block_sum<NT>(lsum, fsm);  // its barriers make lgk and pm visible
-      PQC_MARK(ws, 2, 2);
-      // out[d] = (sum_j w_j acc_j[d] + sum_k p_k V_k[d]) / l ; two threads per dimension
-      float acc = 0.0f;
-      {
-        float wv[kAccBatch];
+      // out[d] = (sum_j w_j acc_j[d] + sum_r p_r V_r[d]) / l with w_j = exp2(m_j - m*), p_r = exp2(logit_r - m*):
+      // nps threads per dimension, thread ps taking the states j = ps (mod nps) and the admitted rows r = ps (mod nps),
+      // each in ascending order; the nps sums are added in order.  Every thread finds m* by itself (the states' maximum
+      // came with the totals above, the admitted logits are few), and the threads of dimension 0 sum l alongside.
+      float mstar = mpart;
+      for (int k = 0; k < need; ++k) mstar = fmaxf(mstar, lgk[k]);
+      float acc = 0.0f, lsum = 0.0f;
 #pragma unroll
-        for (int x = 0; x < kAccBatch; ++x) wv[x] = pm[min(half + 2 * x, s.nblkC - 1)];
-#pragma unroll
-        for (int x = 0; x < kAccBatch; ++x) acc = fmaf(wv[x], half + 2 * x < s.nblkC ? a0[x] : 0.0f, acc);
-      }
-      for (int j0 = half + 2 * kAccBatch; j0 < s.nblkC; j0 += 2 * kAccBatch) {
-        float a[kAccBatch];
-#pragma unroll
-        for (int x = 0; x < kAccBatch; ++x) {
-          const int j = j0 + 2 * x;
-          a[x] = j < s.nblkC ? parts[((size_t)j * G + hq) * (kD + 2) + 2 + d] : 0.0f;
-        }
-#pragma unroll
-        for (int x = 0; x < kAccBatch; ++x) {
-          const int j = j0 + 2 * x;
-          if (j < s.nblkC) acc = fmaf(pm[j], a[x], acc);
+      for (int x = 0; x < kAccPer; ++x) {
+        const int j = ps + nps * x;
+        if (j < s.nblkC) {
+          const float wj = __builtin_amdgcn_exp2f(pm[j] - mstar);
+          acc = fmaf(wj, a0[x], acc);
+          lsum = fmaf(wj, pl[j], lsum);
         }
       }
-      if (need > 0 && n_cand <= 16 * sp) {
-        // the V rows are already here: weighted rows go to LDS at their rank, then are summed in rank order
-        for (int r0 = 0; r0 < need; r0 += kRankChunk) {
-          const int nr = min(kRankChunk, need - r0);
+      for (int j0 = nps * kAccPer + ps; j0 < s.nblkC; j0 += nps * kAccPer) {
+        float a[kAccPer];
 #pragma unroll
-          for (int x = 0; x < SP; ++x) {
-            const int k = x * 16 + grp;
-            const int r = (k < n_cand ? (int)rankv[k] : 0xffff) - r0;
-            if (r >= 0 && r < nr) {
-              const float p = lgk[r0 + r];
-              float vf[8];
-              vspec[x].unpack(vf);
+        for (int x = 0; x < kAccPer; ++x) a[x] = pacc[((size_t)min(j0 + nps * x, s.nblkC - 1) * G + hq) * kD + d];
 #pragma unroll
-              for (int e = 0; e < 8; ++e) vl[r * kD + owned_dim<T>(sub, e)] = p * vf[e];
-            }
-          }
-          __syncthreads();
-          for (int r = half; r < nr; r += 2) acc += vl[r * kD + d];
-          __syncthreads();
-        }
-      } else if (need > 0) {
-        // many candidates: admitted rows are fetched in rank order, 16 rows at a time per pass
-        float va[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) va[e] = 0.0f;
-        for (int k0 = 0; k0 < need; k0 += 16 * kVPass) {
-          RowRaw<T> vr[kVPass];
-#pragma unroll
-          for (int x = 0; x < kVPass; ++x) {
-            const int k = min(k0 + x * 16 + grp, need - 1);
-            vr[x].load_row(recs + (size_t)ordv[k] * ws.rec_stride + sizeof(CandHeader), sub);
-          }
-          PQC_LOADS_ISSUED();
-#pragma unroll
-          for (int x = 0; x < kVPass; ++x) {
-            const int k = k0 + x * 16 + grp;
-            const float p = k < need ? lgk[k] : 0.0f;
-            float vf[8];
-            vr[x].unpack(vf);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) va[e] = fmaf(p, vf[e], va[e]);
+        for (int x = 0; x < kAccPer; ++x) {
+          const int j = j0 + nps * x;
+          if (j < s.nblkC) {
+            const float wj = __builtin_amdgcn_exp2f(pm[j] - mstar);
+            acc = fmaf(wj, a[x], acc);
+            lsum = fmaf(wj, pl[j], lsum);
           }
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) vl[grp * kD + owned_dim<T>(sub, e)] = va[e];
-        __syncthreads();
-#pragma unroll
-        for (int x = 0; x < 8; ++x) acc += vl[(half * 8 + x) * kD + d];
       }
-      if (half == 1) half_acc[d] = acc;
+      for (int r0 = ps; r0 < need; r0 += nps * kAccPer) {
+        float vv[kAccPer];
+#pragma unroll
+        for (int x = 0; x < kAccPer; ++x)
+          vv[x] = load_as_float<T>(reinterpret_cast<const T*>(cv.v) + (size_t)ordv[min(r0 + nps * x, need - 1)] * kD, d);
+#pragma unroll
+        for (int x = 0; x < kAccPer; ++x) {
+          const int r = r0 + nps * x;
+          if (r < need) {
+            const float p = __builtin_amdgcn_exp2f(lgk[r] - mstar);
+            acc = fmaf(p, vv[x], acc);
+            lsum += p;
+          }
+        }
+      }
+      slice_sm[ps * dims + dl] = acc;
+      if (dl == 0) lsm[ps] = lsum;
       __syncthreads();
-      if (half == 0) out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + d] = (acc + half_acc[d]) / lstar;
+      PQC_MARK(ws, 2, 2);
+      if (tid < dims) {
+        float tot = slice_sm[tid], lstar = lsm[0];
+        for (int x = 1; x < nps; ++x) {
+          tot += slice_sm[x * dims + tid];
+          lstar += lsm[x];
+        }
+        out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + dims * sl + tid] = tot / lstar;
+      }
       PQC_MARK(ws, 2, 3);
     }
-  } else {
-    // generic path: radix select of the need-th largest staged composite, 8 bits per pass
+  } else if (sl == 0) {
+    // generic path (one workgroup per head does all 128 dimensions): radix select of the need-th largest staged
+    // composite, 8 bits per pass
+    const int d128 = tid & (kD - 1), half = tid >> 7;
     {
       int nl, nc;
       scan_counts(cnt0, nl, nc);
@@ -1089,7 +1064,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       stash_wave_state<T, 1>(st, red);
       __syncthreads();
       float m_own, l_own, acc;
-      combine_waves<1, NW>(red, 0, d, m_own, l_own, acc);
+      combine_waves<1, NW>(red, 0, d128, m_own, l_own, acc);
       float mx = m_own;
       for (int j = tid; j < s.nblkC; j += NT) mx = fmaxf(mx, pm[j]);
       const float mstar = block_max<NT>(mx, fsm);
@@ -1102,10 +1077,10 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       const float f_own = __builtin_amdgcn_exp2f(m_own - mstar);
       const float lstar = block_sum<NT>(lsum, fsm) + l_own * f_own;
       acc = half == 0 ? acc * f_own : 0.0f;
-      for (int j = half; j < s.nblkC; j += 2) acc = fmaf(pm[j], parts[((size_t)j * G + hq) * (kD + 2) + 2 + d], acc);
-      if (half == 1) half_acc[d] = acc;
+      for (int j = half; j < s.nblkC; j += 2) acc = fmaf(pm[j], pacc[((size_t)j * G + hq) * kD + d128], acc);
+      if (half == 1) half_acc[d128] = acc;
       __syncthreads();
-      if (half == 0) out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + d] = (acc + half_acc[d]) / lstar;
+      if (half == 0) out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + d128] = (acc + half_acc[d128]) / lstar;
     }
   }
   PQC_NOTE(ws, 2, 13, n_above);
