@@ -154,15 +154,12 @@ struct BinParams {
 };
 // The layout travels as scalars held in registers (selecting among the fields of a struct
 // in memory makes the compiler index it like an array, which lands it in scratch or LDS).
-__device__ __forceinline__ int fine_index(float s, float c0, float inv_c) {
-  return min(kFineBins - 1, __float2int_rz((s - c0) * inv_c));
-}
+// (one subtraction, one multiplication and one conversion per score: the piece is selected first)
 __device__ __forceinline__ int score_bin(float s, float c0, float c1, float inv_c, float inv_hi) {
-  const int b_c = 1 + fine_index(s, c0, inv_c);
-  const int b_hi = 1 + kFineBins + min(kHighBins - 1, __float2int_rz((s - c1) * inv_hi));
-  int b = s < c0 ? 0 : b_c;
-  b = s > c1 ? b_hi : b;
-  return b;
+  const bool up = s > c1;
+  const float x = (s - (up ? c1 : c0)) * (up ? inv_hi : inv_c);
+  const int b = min((int)x, up ? kHighBins - 1 : kFineBins - 1) + (up ? 1 + kFineBins : 1);  // the conversion truncates
+  return s < c0 ? 0 : b;
 }
 // Bin layout from bounds lo <= score <= hi and a window [q_lo, q_hi] expected to hold
 // the K-th largest score.
@@ -318,7 +315,7 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
     // Loads return in issue order: whatever the caller streams from HBM goes behind the table's
     // (mostly L2-resident) centroids, so that the table is built while that stream arrives.
     PQC_LOADS_ISSUED();
-    issue_more();
+    if constexpr (!kWhole) issue_more();
     PQC_LOADS_ISSUED();
     float a = qv[0];
 #pragma unroll
@@ -345,6 +342,10 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
         dst[0] = vw[x][0]; dst[1] = vw[x][1]; dst[2] = vw[x][2]; dst[3] = vw[x][3];
       }
     }
+    // the caller's stream from HBM is requested now, behind every wave's centroid loads (a compute unit's loads
+    // pass through one address unit): the table is built while that stream arrives
+    issue_more();
+    PQC_LOADS_ISSUED();
     unsigned* mm = reinterpret_cast<unsigned*>(red);  // [0..8): smallest entry of a partition, [8..16): largest, as score keys
     if (tid < 16) mm[tid] = tid < 8 ? 0xffffffffu : 0u;
     mark(10);

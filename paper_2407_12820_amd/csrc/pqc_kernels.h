@@ -269,15 +269,26 @@ __global__ __launch_bounds__(1024) void hist_kernel(Shape s, Workspace ws, const
     if (v * NT + tid < chunks) {
       const int t0 = (chunk0 + v * NT + tid) * P - src.lead;
       unsigned st[P];  // what the select kernel will read back: bin + 1, or the window mark
+      if (t0 >= s.I && t0 + P <= s.N - s.L) {  // all P tokens are middle tokens (all but the chunks at the two ends)
 #pragma unroll
-      for (int i = 0; i < P; ++i) {
-        const int t = t0 + i;
-        const float sc = src.score(raw[v], i);
-        const bool mid = t >= s.I && t < s.N - s.L;
-        const int bin = score_bin(sc, b_c0, b_c1, b_ic, b_ihi);
-        if (mid && !(sc < b_c0)) atomicAdd(&hist[bin], 1u);
-        n_low += (mid && sc < b_c0) ? 1 : 0;
-        st[i] = mid ? (unsigned)bin + 1u : kBinWindow;
+        for (int i = 0; i < P; ++i) {
+          const float sc = src.score(raw[v], i);
+          const int bin = score_bin(sc, b_c0, b_c1, b_ic, b_ihi);
+          if (!(sc < b_c0)) atomicAdd(&hist[bin], 1u);
+          n_low += sc < b_c0 ? 1 : 0;
+          st[i] = (unsigned)bin + 1u;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < P; ++i) {
+          const int t = t0 + i;
+          const float sc = src.score(raw[v], i);
+          const bool mid = t >= s.I && t < s.N - s.L;
+          const int bin = score_bin(sc, b_c0, b_c1, b_ic, b_ihi);
+          if (mid && !(sc < b_c0)) atomicAdd(&hist[bin], 1u);
+          n_low += (mid && sc < b_c0) ? 1 : 0;
+          st[i] = mid ? (unsigned)bin + 1u : kBinWindow;
+        }
       }
       if (src.lead == 0 && t0 + P <= s.N) {  // the usual case: aligned, all P tokens exist
         if constexpr (P == 1) {
