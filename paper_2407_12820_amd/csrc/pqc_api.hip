@@ -240,7 +240,7 @@ void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uin
                        s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));
   if (phases & 4u)
     hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G * s.slices + kCopyWgs + (ctx->append.key ? 1 : 0), units), dim3(256),
-                       (4 * s.nblkC + 2) * sizeof(int), st, s, ctx->ws, qt, kt, vt, out_idx, out_attn, ctx->append);
+                       finalize_lds_bytes(s, true), st, s, ctx->ws, qt, kt, vt, out_idx, out_attn, ctx->append);
 }
 
 template <typename T, int G>
@@ -278,7 +278,7 @@ void launch_indexed_tg(pqc_ctx* ctx, const void* q, const float* cent, const uin
                      s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes), cent,
                      pair_counts, ctx->append.key ? ctx->append.position : -1);
   hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G * s.slices + kCopyWgs + (ctx->append.key ? 1 : 0), units), dim3(256),
-                     (4 * s.nblkC + 2) * sizeof(int), st, s, ctx->ws, qt, kt, vt, out_idx, out_attn, ctx->append);
+                     finalize_lds_bytes(s, true), st, s, ctx->ws, qt, kt, vt, out_idx, out_attn, ctx->append);
 }
 
 template <typename T>
@@ -586,7 +586,7 @@ int pqc_topk(pqc_ctx* ctx, const float* scores, int32_t* out_idx, void* stream) 
   launch_hist<float, ScoreChunks>(s, ctx->ws, nof, nof, static_cast<const void*>(scores), 0, st);
   hipLaunchKernelGGL((select_kernel<float, 1, ScoreChunks, false>), dim3(s.nblkC, units), dim3(256), s.tokC * sizeof(unsigned short), st,
                      s, ctx->ws, nof, nof, nof, static_cast<const void*>(scores));
-  hipLaunchKernelGGL((finalize_kernel<float, 1, false>), dim3(1 + kCopyWgs, units), dim3(256), (4 * s.nblkC + 2) * sizeof(int), st, s,
+  hipLaunchKernelGGL((finalize_kernel<float, 1, false>), dim3(1 + kCopyWgs, units), dim3(256), finalize_lds_bytes(s, false), st, s,
                      ctx->ws, nof, nof, nof, out_idx, static_cast<float*>(nullptr), AppendArgs{nullptr, nullptr, nullptr, 0, nullptr});
   rc = check_launch(ctx);
   if (rc == PQC_OK) {

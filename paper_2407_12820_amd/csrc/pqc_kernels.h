@@ -666,10 +666,17 @@ __device__ __forceinline__ float block_sum(float v, float* sm /* [NT/64] */) {
 
 constexpr int kHdrPerThread = kCandRec / 256;  // candidate record headers per thread
 constexpr int kAccPer = 8;                     // partial states a thread keeps in flight at once (every eighth state is its own)
-constexpr int kWarmPer = 4;                    // candidates per thread whose V rows are brought into the cache before the ranking knows which it needs
+constexpr int kVPer = 8;                       // candidate records per thread whose V values are requested before the ranking knows which are admitted
+constexpr int kRankStep = 8;                    // composites read per step of the ranking loop
+constexpr int kFoldRanks = 96;                 // admitted rows whose terms meet in LDS by rank (beyond: fetched by rank from the records)
 constexpr int kMaxSlices = 4;                  // workgroups per query head, at most (32 output dimensions each)
 constexpr int kIdxLists = 4;                   // staged index lists a wave copies with loads issued up front
 constexpr int kCopyWgs = 4;                    // copy workgroups per unit
+
+// dynamic LDS of finalize_kernel
+inline size_t finalize_lds_bytes(const Shape& s, bool attn) {
+  return (size_t)(4 * s.nblkC + 2) * sizeof(int) + (attn ? (size_t)kFoldRanks * (kD / s.slices) * sizeof(float) : 0);
+}
 
 // The code of one appended token per unit (Section 3.1: nearest centroid of each partition): nothing in the
 // step depends on it, so one more workgroup per unit of the finalize kernel computes it beside the others.
@@ -722,13 +729,15 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
     if (c == 0 && ap.pair_counts) ap.pair_counts[(size_t)u * s.C * s.C + (abest[0] & 0xffu) + s.C * (abest[1] & 0xffu)] += 1u;
     return;
   }
-  extern __shared__ int dyn[];  // pre_sel[nblkC+1], pre_cand[nblkC+1], pm[nblkC], pl[nblkC]
+  extern __shared__ int dyn[];  // pre_sel[nblkC+1], pre_cand[nblkC+1], pm[nblkC], pl[nblkC], terms[kFoldRanks][kD/slices] (finalize_lds_bytes)
   __shared__ int scan_sm[2 * NW + 1];
   __shared__ float fsm[NW];
   __shared__ int ism[2 * NW];
-  __shared__ unsigned long long comp[kCandRec];  // candidate composites, in record order
+  __shared__ unsigned long long comp[kCandRec + kRankStep];  // candidate composites, in record order
   __shared__ float lgk[kCandRec];                // by rank: logit, then softmax weight of the admitted ones
   __shared__ unsigned short ordv[kCandRec];      // by rank: record
+  __shared__ unsigned short rankv[kCandRec];     // by record: rank
+  __shared__ unsigned mkey;                      // order-preserving key of the largest logit (states and admitted rows)
   __shared__ unsigned rhist[256];
   __shared__ int digit_sm[2];
   __shared__ int rows_sm[NT];
@@ -742,6 +751,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
   int* pre_cand = dyn + (s.nblkC + 1);
   float* pm = reinterpret_cast<float*>(dyn + 2 * (s.nblkC + 1));
   float* pl = pm + s.nblkC;
+  float* terms = pl + s.nblkC;  // [kFoldRanks][dimensions of the workgroup]: weighted V values of the admitted rows, by rank
   const int2* cnt = ws.stage_cnt + (size_t)u * s.nblkC;
   const unsigned long long* stage_u = ws.stage + (size_t)u * s.nblkC * s.stageStride;
   int* out = out_idx + (size_t)u * s.Ktot;
@@ -847,18 +857,17 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
   const int2 cnt0 = cnt[jc];  // list sizes of the first NT select workgroups
   float2 ml0 = make_float2(kNegBig, 0.0f);
   float a0[kAccPer];  // this thread's first states: ps, ps + nps, ...
+  float vv0[kVPer];   // V values of the candidate records ps, ps + nps, ... (this thread's dimension)
   if constexpr (ATTN) {
     ml0 = pml[jc];
 #pragma unroll
     for (int x = 0; x < kAccPer; ++x)  // states that do not exist re-read the first one (a cache hit, no extra traffic)
       a0[x] = pacc[((size_t)(ps + nps * x < s.nblkC ? ps + nps * x : 0) * G + hq) * kD + d];
-    // the V rows of the first candidates, this workgroup's dimensions: nothing is done with them here, but the rows
-    // the ranking picks further down are then found in the cache instead of in memory
+    // the V values of the first candidates (in order of arrival), this workgroup's dimensions: which of them are
+    // admitted is known only after the ranking, but requested now they are here by then
 #pragma unroll
-    for (int x = 0; x < kWarmPer; ++x) {
-      const float warm = load_as_float<T>(reinterpret_cast<const T*>(cv.v) + (size_t)(ps + nps * x) * kD, d);
-      asm volatile("" ::"v"(warm));
-    }
+    for (int x = 0; x < kVPer; ++x)
+      vv0[x] = load_as_float<T>(reinterpret_cast<const T*>(cv.v) + (size_t)(ps + nps * x) * kD, d);
   }
   PQC_LOADS_ISSUED();
   float mpart = kNegBig;  // largest maximum of the partial states
@@ -908,6 +917,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
 
   if (n_cand <= kCandRec) {
     // rank every candidate (count of larger composites); the admitted ones are the `need` best
+    const bool meet = ATTN && need <= kFoldRanks;  // the admitted rows' terms meet in LDS, by rank
     if (need > 0) {
 #pragma unroll
       for (int x = 1; x < kHdrPerThread; ++x) {
@@ -918,9 +928,12 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
           rl[x] = ATTN ? cv.logit[hq * kCandRec + x * NT + tid] : 0.0f;
         }
       }
+      // (entries up to the next multiple of kRankStep are zero, which ranks behind everything: the loop below reads
+      // kRankStep composites at a time, because one LDS read per step is a chain of latencies)
 #pragma unroll
       for (int x = 0; x < kHdrPerThread; ++x)
-        if (x * NT + tid < n_cand) comp[x * NT + tid] = rc[x];
+        if (x * NT + tid < n_cand + kRankStep) comp[x * NT + tid] = x * NT + tid < n_cand ? rc[x] : 0ull;
+      if (tid == 0) mkey = score_key(mpart);
       __syncthreads();
 #pragma unroll
       for (int x = 0; x < kHdrPerThread; ++x) {
@@ -928,11 +941,20 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
         if (k < n_cand) {
           const unsigned long long mine = rc[x];
           int rank = 0;
-          for (int j = 0; j < n_cand; ++j) rank += comp[j] > mine ? 1 : 0;
+          for (int j0 = 0; j0 < n_cand; j0 += kRankStep) {
+            unsigned long long c[kRankStep];
+#pragma unroll
+            for (int y = 0; y < kRankStep; ++y) c[y] = comp[j0 + y];
+#pragma unroll
+            for (int y = 0; y < kRankStep; ++y) rank += c[y] > mine ? 1 : 0;
+          }
+          rankv[k] = (unsigned short)rank;
           if (rank < need) {
             if (blockIdx.x == 0 && s.I + n_above + rank < s.Ktot) out[s.I + n_above + rank] = composite_token(mine);  // best first
-            lgk[rank] = rl[x] * s.scale_log2e;
+            const float lg = rl[x] * s.scale_log2e;
+            lgk[rank] = lg;
             ordv[rank] = (unsigned short)k;
+            if constexpr (ATTN) atomicMax(&mkey, score_key(lg));
           }
         }
       }
@@ -941,10 +963,29 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
     if constexpr (ATTN) {
       // out[d] = (sum_j w_j acc_j[d] + sum_r p_r V_r[d]) / l with w_j = exp2(m_j - m*), p_r = exp2(logit_r - m*):
       // nps threads per dimension, thread ps taking the states j = ps (mod nps) and the admitted rows r = ps (mod nps),
-      // each in ascending order; the nps sums are added in order.  Every thread finds m* by itself (the states' maximum
-      // came with the totals above, the admitted logits are few), and the threads of dimension 0 sum l alongside.
-      float mstar = mpart;
-      for (int k = 0; k < need; ++k) mstar = fmaxf(mstar, lgk[k]);
+      // each in ascending order; the nps sums are added in order.  m* is the larger of the states' maximum (it came
+      // with the totals above) and the admitted logits' maximum (an LDS maximum taken while ranking); the threads of
+      // dimension 0 sum l alongside.
+      const float mstar = need > 0 ? key_score(mkey) : mpart;
+      if (meet && need > 0) {
+        // the V values requested up front belong to the records ps + nps x in order of arrival; each admitted one's
+        // term goes to the row of its rank, so that the sums below run in rank order whatever the order of arrival
+        for (int k0 = 0; k0 < n_cand; k0 += nps * kVPer) {
+          if (k0 > 0) {  // rare: more candidates than the up-front loads cover
+#pragma unroll
+            for (int x = 0; x < kVPer; ++x)
+              vv0[x] = load_as_float<T>(reinterpret_cast<const T*>(cv.v) + (size_t)min(k0 + ps + nps * x, kCandRec - 1) * kD, d);
+          }
+#pragma unroll
+          for (int x = 0; x < kVPer; ++x) {
+            const int k = k0 + ps + nps * x;
+            if (k < n_cand) {
+              const int r = rankv[k];
+              if (r < need) terms[r * dims + dl] = __builtin_amdgcn_exp2f(lgk[r] - mstar) * vv0[x];
+            }
+          }
+        }
+      }
       float acc = 0.0f, lsum = 0.0f;
 #pragma unroll
       for (int x = 0; x < kAccPer; ++x) {
@@ -969,18 +1010,37 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
           }
         }
       }
-      for (int r0 = ps; r0 < need; r0 += nps * kAccPer) {
-        float vv[kAccPer];
+      if (meet) {
+        if (need > 0) __syncthreads();  // (need is uniform over the workgroup)
+        for (int r0 = ps; r0 < need; r0 += nps * 4) {
+          float t[4], lg[4];
 #pragma unroll
-        for (int x = 0; x < kAccPer; ++x)
-          vv[x] = load_as_float<T>(reinterpret_cast<const T*>(cv.v) + (size_t)ordv[min(r0 + nps * x, need - 1)] * kD, d);
+          for (int x = 0; x < 4; ++x) {
+            const int r = min(r0 + nps * x, need - 1);
+            t[x] = terms[r * dims + dl];
+            lg[x] = lgk[r];
+          }
 #pragma unroll
-        for (int x = 0; x < kAccPer; ++x) {
-          const int r = r0 + nps * x;
-          if (r < need) {
-            const float p = __builtin_amdgcn_exp2f(lgk[r] - mstar);
-            acc = fmaf(p, vv[x], acc);
-            lsum += p;
+          for (int x = 0; x < 4; ++x)
+            if (r0 + nps * x < need) {
+              acc += t[x];
+              lsum += __builtin_amdgcn_exp2f(lg[x] - mstar);
+            }
+        }
+      } else {
+        // more admitted rows than the LDS rows hold (a large tie class at the threshold): fetched by rank
+        for (int r0 = ps; r0 < need; r0 += nps * kAccPer) {
+          float vv[kAccPer];
+#pragma unroll
+          for (int x = 0; x < kAccPer; ++x)
+            vv[x] = load_as_float<T>(reinterpret_cast<const T*>(cv.v) + (size_t)ordv[min(r0 + nps * x, need - 1)] * kD, d);
+#pragma unroll
+          for (int x = 0; x < kAccPer; ++x) {
+            const int r = r0 + nps * x;
+            if (r < need) {
+              acc += __builtin_amdgcn_exp2f(lgk[r] - mstar) * vv[x];
+              lsum += __builtin_amdgcn_exp2f(lgk[r] - mstar);
+            }
           }
         }
       }
@@ -989,11 +1049,19 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       __syncthreads();
       PQC_MARK(ws, 2, 2);
       if (tid < dims) {
-        float tot = slice_sm[tid], lstar = lsm[0];
-        for (int x = 1; x < nps; ++x) {
-          tot += slice_sm[x * dims + tid];
-          lstar += lsm[x];
+        float ts[8], ls[8];  // nps <= 8
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          ts[x] = slice_sm[min(x, nps - 1) * dims + tid];
+          ls[x] = lsm[min(x, nps - 1)];
         }
+        float tot = ts[0], lstar = ls[0];
+#pragma unroll
+        for (int x = 1; x < 8; ++x)
+          if (x < nps) {
+            tot += ts[x];
+            lstar += ls[x];
+          }
         out_attn[((size_t)b * s.Hq + (size_t)g * G + hq) * kD + dims * sl + tid] = tot / lstar;
       }
       PQC_MARK(ws, 2, 3);
