@@ -360,13 +360,38 @@ __device__ __forceinline__ float2 build_lut(const T* __restrict__ q /* [G][kD] o
       const float* cr = tile + ec * RS;
       float p = 0.0f;
       if constexpr (RS % 4 == 0) {
+        // Few entries, so few busy waves and nothing to hide the LDS latency behind: the operands are read two
+        // stages of four 16-byte pieces ahead of the chain (left alone the compiler reads one piece ahead and the
+        // chain waits for LDS at every fourth step).
+        constexpr int kStages = Dm / 16;
+        const f32x4_t* qv4 = reinterpret_cast<const f32x4_t*>(qj);
+        const f32x4_t* cv4 = reinterpret_cast<const f32x4_t*>(cr);
+        f32x4_t qa[2][4], ca[2][4];
 #pragma unroll
-        for (int x = 0; x < Dm / 4; ++x) {
-          const float4 qq = reinterpret_cast<const float4*>(qj)[x], cc = reinterpret_cast<const float4*>(cr)[x];
-          p = __fmaf_rn(qq.x, cc.x, p);
-          p = __fmaf_rn(qq.y, cc.y, p);
-          p = __fmaf_rn(qq.z, cc.z, p);
-          p = __fmaf_rn(qq.w, cc.w, p);
+        for (int st = 0; st < 2 && st < kStages; ++st)
+#pragma unroll
+          for (int y = 0; y < 4; ++y) {
+            qa[st][y] = qv4[st * 4 + y];
+            ca[st][y] = cv4[st * 4 + y];
+          }
+#pragma unroll
+        for (int st = 0; st < kStages; ++st) {
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int y = 0; y < 4; ++y) {
+            p = __fmaf_rn(qa[st & 1][y][0], ca[st & 1][y][0], p);
+            p = __fmaf_rn(qa[st & 1][y][1], ca[st & 1][y][1], p);
+            p = __fmaf_rn(qa[st & 1][y][2], ca[st & 1][y][2], p);
+            p = __fmaf_rn(qa[st & 1][y][3], ca[st & 1][y][3], p);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          if (st + 2 < kStages) {
+#pragma unroll
+            for (int y = 0; y < 4; ++y) {
+              qa[st & 1][y] = qv4[(st + 2) * 4 + y];
+              ca[st & 1][y] = cv4[(st + 2) * 4 + y];
+            }
+          }
         }
       } else {
 #pragma unroll
