@@ -4,6 +4,8 @@ oracle on the same seeded inputs.  Index sets must match exactly (near-ties with
 sides rank the same fp32 scores); attention outputs within 2e-3 (bf16 inputs) or
 1e-5 (fp32 inputs) of the double-precision oracle, relative to the head's largest
 output magnitude."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -11,7 +13,7 @@ import torch
 import oracle
 from paper_2407_12820_amd import workloads as wl
 
-from parity_utils import ATTN_TOL, attn_error, build_problem, check_indices, check_structure
+from parity_utils import ATTN_TOL, attn_error, build_problem, check_indices, check_structure, unit_slice
 
 pytestmark = pytest.mark.gpu
 
@@ -234,6 +236,37 @@ def test_all_scores_equal_takes_lowest_indices(pqc):
     idx, out = run_decode(pqc, p)
     assert np.all(np.sort(idx[0, 0, 4:1504]) == np.arange(4, 1504))
     full_check(p, idx, out)
+
+
+@pytest.mark.parametrize("batch", [1, 32], ids=["2units", "64units"])
+@pytest.mark.parametrize("admitted", [1, 63, 64, 65, 96, 97, 150])
+def test_any_number_of_a_tie_class_is_admitted(pqc, admitted, batch):
+    # One partition of 16 centroids: 16 distinct scores, classes of about 190 tokens.  K is set so that unit 0 must
+    # admit exactly `admitted` tokens of the class at the threshold (lowest indices first); the other units admit
+    # whatever the same K means for them.  The counts bracket the sizes at which the finalize kernel changes the way
+    # it fetches the admitted rows; 2 and 64 units give it four workgroups and one workgroup per query head.
+    base = _small(pq_m=1, pq_centroids=16, batch=batch)
+    p0 = build_problem(base, seed=6)
+    q1, c1, cd1, _, _ = unit_slice(p0, 0)
+    s32, _ = oracle.scores(q1, base.dtype, c1, cd1)
+    mid = s32[0, 0, base.n_init:base.n_tokens - base.n_local]
+    values, counts = np.unique(mid, return_counts=True)
+    above = 0
+    for val, cnt in zip(values[::-1], counts[::-1]):  # classes from the largest score down
+        if cnt > admitted and above > 100:
+            break
+        above += int(cnt)
+    else:
+        pytest.skip("no tie class large enough")
+    w = dataclasses.replace(base, topk=above + admitted)
+    print(f"[case] tie class of {cnt}, {above} tokens above it, K={w.topk}, units={batch * 2}", flush=True)
+    p = type(p0)(w, p0.q, p0.k, p0.v, p0.centroids, p0.codes, p0.checked_units)
+    idx, out = run_decode(pqc, p)
+    full_check(p, idx, out)
+    klass = np.flatnonzero(s32[0, 0] == val)
+    klass = klass[(klass >= w.n_init) & (klass < w.n_tokens - w.n_local)]
+    got = np.sort(idx[0, 0, w.n_init:w.n_init + w.topk])
+    assert np.intersect1d(got, klass).tolist() == klass[:admitted].tolist()
 
 
 @pytest.mark.parametrize("sample_value", [-1.0, 10.0])
