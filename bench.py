@@ -308,8 +308,18 @@ def main() -> int:
         del src, dst
 
     # PQ construction on the GPU (not part of the decode step): K-Means over all cached keys of one layer
+    # bytes a build must move: every round reads all keys twice (assignment, centroid sums) and writes and reads the
+    # codes; one more assignment at the end; flops of the assignments (tokens x centroids x 128 multiply-adds)
+    units = w.batch * w.n_kv_heads
+    passes = 2 * w.kmeans_iters + 1
+    build_bytes = units * passes * w.n_tokens * (w.head_dim * w.elem_bytes + w.pq_m)
+    build_flops = units * (w.kmeans_iters + 1) * 2.0 * w.n_tokens * w.pq_centroids * w.head_dim
+    build_s = float(np.median(build_ms)) * 1e-3
     result["pq_build"] = {"ms_per_layer": round(float(np.median(build_ms)), 3), "kmeans_iters": w.kmeans_iters,
-                          "note": "host-timed pqc_pq_build (K-Means with kmeans_iters rounds), median over the input sets"}
+                          "algorithmic_bytes": build_bytes, "hbm_frac": round(build_bytes / build_s / 1e9 / HBM_PEAK_GBPS, 4),
+                          "assignment_tflops": round(build_flops / build_s / 1e12, 1),
+                          "note": "host-timed pqc_pq_build (K-Means with kmeans_iters rounds), median over the input sets; "
+                                  "not part of the decode step"}
 
     if with_cpu:
         check, t_first, (cent_h, codes_h, scale) = against_oracle(w, ctx, sets[0], host0, out_idx, out_attn)
