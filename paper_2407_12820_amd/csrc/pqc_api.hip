@@ -735,12 +735,14 @@ int pq_build_t(const BuildPlan& bp, const T* keys, const int32_t* init_idx, int 
     launch_assign<T>(s, keys, (int64_t)s.cap * kD, s.N, 0, cent, codes, st);
     hipLaunchKernelGGL(pq_zero_kernel, dim3((unsigned)((nacc + 255) / 256)), dim3(256), 0, st, sums, nacc);
     {
-      const dim3 grid((s.N + kAccumTok - 1) / kAccumTok, uj);
+      const int tpw = accum_tokens_per_wg(s.C);
+      const dim3 grid((s.N + tpw - 1) / tpw, uj);
+      const size_t lds = (size_t)tpw * sizeof(unsigned short);
       switch (s.Dm) {
-        case 16: hipLaunchKernelGGL((pq_accum_kernel<T, 16>), grid, dim3(256), 0, st, s, keys, codes, sums, counts); break;
-        case 32: hipLaunchKernelGGL((pq_accum_kernel<T, 32>), grid, dim3(256), 0, st, s, keys, codes, sums, counts); break;
-        case 64: hipLaunchKernelGGL((pq_accum_kernel<T, 64>), grid, dim3(256), 0, st, s, keys, codes, sums, counts); break;
-        default: hipLaunchKernelGGL((pq_accum_kernel<T, 128>), grid, dim3(256), 0, st, s, keys, codes, sums, counts); break;
+        case 16: hipLaunchKernelGGL((pq_accum_kernel<T, 16>), grid, dim3(256), lds, st, s, keys, codes, sums, counts); break;
+        case 32: hipLaunchKernelGGL((pq_accum_kernel<T, 32>), grid, dim3(256), lds, st, s, keys, codes, sums, counts); break;
+        case 64: hipLaunchKernelGGL((pq_accum_kernel<T, 64>), grid, dim3(256), lds, st, s, keys, codes, sums, counts); break;
+        default: hipLaunchKernelGGL((pq_accum_kernel<T, 128>), grid, dim3(256), lds, st, s, keys, codes, sums, counts); break;
       }
     }
     hipLaunchKernelGGL(pq_mean_kernel, dim3((unsigned)((ncent + 255) / 256)), dim3(256), 0, st, s, sums, counts, cent);

@@ -15,7 +15,6 @@ namespace pqc {
 
 constexpr int kFixShift = 20;
 constexpr int kAssignTok = 256;   // tokens per workgroup of the assignment kernel
-constexpr int kAccumTok = 2048;   // tokens per workgroup of the accumulation kernel
 
 struct BuildShape {
   int units, N, M, C, Dm;
@@ -252,62 +251,115 @@ __global__ void pq_zero_kernel(unsigned long long* p, size_t n) {
 }
 
 // sums[u][j][c][e] += fix(keys[u][t][j*Dm+e]) for every token t with code c; counts[u][j][c] += 1.
-// Lanes run over the dimensions of the sub-vector: a group of min(Dm, 64) lanes takes one
-// token at a time, reads its sub-vector in one coalesced piece and adds it to the LDS
-// accumulators of the token's centroid (the lanes of a group hit distinct addresses).  LDS
-// holds 64 KiB worth of centroids at a time (all of them except for 256 centroids of 128
-// dimensions); integer adds commute, so the result does not depend on the order in which
-// waves run.
-constexpr int kAccumLdsWords = 8192;  // 64-bit accumulators in LDS
+// A workgroup first sorts its tokens by code (a counting sort in LDS: one 32-bit atomic per token), then each wave
+// takes centroids in turn and sums the centroid's members in registers: a lane loads 16 bytes of a member's
+// sub-vector (8 bf16 or 4 fp32 values), a group of Dm*sizeof(T)/16 lanes covers one member and a wave several
+// members per load; the lane groups' partial sums meet in a wave-private LDS tile.  (Adding every value to an LDS
+// accumulator with an atomic, as a first version did, is bound by the LDS atomic rate of about one lane per clock.)
+// Sums are 64-bit integers of the values in fixed point (2^-20), so the result does not depend on the order of
+// the members, of the waves or of the workgroups.
+__host__ __device__ constexpr int accum_tokens_per_wg(int C) { return 32 * C < 2048 ? 2048 : (32 * C > 8192 ? 8192 : 32 * C); }
 template <typename T, int DM>
 __global__ __launch_bounds__(256) void pq_accum_kernel(BuildShape s, const T* __restrict__ keys,
                                                        const uint8_t* __restrict__ codes,
                                                        unsigned long long* __restrict__ sums,
                                                        unsigned* __restrict__ counts) {
-  constexpr int LPT = DM >= 64 ? 64 : DM;  // lanes per token
-  constexpr int EPL = DM / LPT;            // elements per lane
-  constexpr int TPW = 64 / LPT;            // tokens a wave handles at a time
-  constexpr int U = 16;                    // tokens per lane group in flight
-  __shared__ unsigned long long acc[kAccumLdsWords];
+  constexpr int EPV = 16 / (int)sizeof(T);  // values per lane
+  constexpr int LPT = DM / EPV;             // lanes per member
+  constexpr int MPW = 64 / LPT;             // members a wave loads at a time
+  constexpr int U = 4;                      // such loads in flight
+  constexpr int NW = 4;
+  static_assert(DM % EPV == 0 && LPT >= 1 && LPT <= 64, "a sub-vector is a whole number of 16-byte pieces");
+  extern __shared__ unsigned short order[];  // [tokens per workgroup] token offsets, sorted by code
   __shared__ unsigned cnt[256];
+  __shared__ int start[257];
+  __shared__ int scan_sm[2 * NW + 1];
+  __shared__ long long part[NW][MPW * DM];   // per wave: [member slot][dimension]
   const int uj = blockIdx.y, u = uj / s.M, j = uj % s.M, tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6, sub = lane % LPT, slot = lane / LPT;
-  const int t0 = blockIdx.x * kAccumTok, t1 = min(t0 + kAccumTok, s.N);
-  const int cg = min(s.C, kAccumLdsWords / DM);  // centroids per pass
-  const int step = 4 * TPW;                      // tokens the workgroup takes per round
-  for (int c0 = 0; c0 < s.C; c0 += cg) {
-    const int nc = min(cg, s.C - c0);
-    __syncthreads();
-    for (int i = tid; i < nc * DM; i += 256) acc[i] = 0ull;
-    if (tid < nc) cnt[tid] = 0u;
-    __syncthreads();
-    for (int tb = t0 + w * TPW + slot; tb < t1; tb += U * step) {
-      int c[U];
-      float xv[U][EPL];
+  const int tpw = accum_tokens_per_wg(s.C);
+  const int t0 = blockIdx.x * tpw, nt = min(tpw, s.N - t0);
+  const uint8_t* cp = codes + ((size_t)u * s.cap + t0) * s.M + j;
+  // ---- counting sort of the workgroup's tokens by code
+  cnt[tid] = 0u;
+  __syncthreads();
+  for (int t = tid; t < nt; t += 256) {
+    const unsigned c = cp[(size_t)t * s.M];
+    if (c < (unsigned)s.C) atomicAdd(&cnt[c], 1u);  // (a code that names no centroid is left out)
+  }
+  __syncthreads();
+  {
+    const int mine = (int)cnt[tid];
+    int total;
+    const int ex = block_exclusive_scan<256>(mine, &total, scan_sm);
+    start[tid] = ex;
+    if (tid == 255) start[256] = total;
+    cnt[tid] = (unsigned)ex;  // now the bucket's fill position
+  }
+  __syncthreads();
+  for (int t = tid; t < nt; t += 256) {
+    const unsigned c = cp[(size_t)t * s.M];
+    if (c < (unsigned)s.C) order[atomicAdd(&cnt[c], 1u)] = (unsigned short)t;
+  }
+  __syncthreads();
+  // ---- one centroid at a time per wave
+  const T* kbase = keys + ((size_t)u * s.cap + t0) * kD + j * DM + sub * EPV;
+  long long* mypart = part[w];
+  for (int c = w; c < s.C; c += NW) {
+    const int base = start[c], n = start[c + 1] - base;  // wave-uniform
+    if (n == 0) continue;
+    long long acc[EPV];
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) acc[e] = 0;
+    for (int m0 = 0; m0 < n; m0 += MPW * U) {
+      uint4 raw[U];
 #pragma unroll
       for (int k = 0; k < U; ++k) {
-        const int t = min(tb + k * step, t1 - 1);  // clamped: straight-line loads, masked below
-        c[k] = (int)codes[((size_t)u * s.cap + t) * s.M + j] - c0;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e)
-          xv[k][e] = load_as_float<T>(keys, ((size_t)u * s.cap + t) * kD + j * DM + sub + e * LPT);
+        const int t = order[base + min(m0 + k * MPW + slot, n - 1)];  // clamped: straight-line loads, masked below
+        raw[k] = *reinterpret_cast<const uint4*>(kbase + (size_t)t * kD);
       }
 #pragma unroll
       for (int k = 0; k < U; ++k) {
-        if (tb + k * step < t1 && c[k] >= 0 && c[k] < nc) {
+        if (m0 + k * MPW + slot < n) {
+          const unsigned rw[4] = {raw[k].x, raw[k].y, raw[k].z, raw[k].w};
+          float x[EPV];
+          if constexpr (sizeof(T) == 2) {
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) {
-            const long long fx = __float2ll_rn(xv[k][e] * (float)(1 << kFixShift));
-            atomicAdd(&acc[c[k] * DM + sub + e * LPT], (unsigned long long)fx);
+            for (int e = 0; e < 4; ++e) {
+              x[2 * e] = __uint_as_float(rw[e] << 16);
+              x[2 * e + 1] = __uint_as_float(rw[e] & 0xffff0000u);
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] = __uint_as_float(rw[e]);
           }
-          if (sub == 0) atomicAdd(&cnt[c[k]], 1u);
+#pragma unroll
+          for (int e = 0; e < EPV; ++e) {
+            const float xs = x[e] * (float)(1 << kFixShift);
+            // the usual case in 32-bit arithmetic (a 64-bit conversion is a long instruction sequence)
+            long long fx = (long long)__float2int_rn(xs);
+            if (__builtin_expect(!(fabsf(xs) < 2147483520.0f), 0)) fx = __float2ll_rn(xs);  // |x| >= 2048, or not a number
+            acc[e] += fx;
+          }
         }
       }
     }
-    __syncthreads();
-    for (int i = tid; i < nc * DM; i += 256)
-      if (acc[i]) atomicAdd(&sums[((size_t)uj * s.C + c0) * DM + i], acc[i]);
-    if (tid < nc && cnt[tid]) atomicAdd(&counts[(size_t)uj * s.C + c0 + tid], cnt[tid]);
+    // the lane groups' sums meet in the wave's tile; then one lane per dimension adds them up
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) mypart[slot * DM + sub * EPV + e] = acc[e];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int used = min(MPW, n);  // slots beyond the members hold zeros; skipping them is only quicker
+    for (int d = lane; d < DM; d += 64) {
+      long long tot = 0;
+      for (int sl = 0; sl < used; ++sl) tot += mypart[sl * DM + d];
+      if (tot) atomicAdd(&sums[((size_t)uj * s.C + c) * DM + d], (unsigned long long)tot);
+    }
+    if (lane == 0) atomicAdd(&counts[(size_t)uj * s.C + c], (unsigned)n);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
 }
 

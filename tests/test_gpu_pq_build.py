@@ -70,6 +70,41 @@ def test_assign_and_one_update_match_oracle(pqc, name):
     assert n0 + n1 <= 1e-3 * cd1_ref.size
 
 
+@pytest.mark.parametrize("name", ["tiny_f32", "llama8b_32k", "batch8_32k"])
+def test_centroid_update_with_keys_of_large_magnitude(pqc, name):
+    # The centroid sums are taken in fixed point; values of 2048 and more take another way through the kernel than
+    # small ones.  A tenth of the tokens is scaled into that range, a few far beyond it, with both signs.  Expected:
+    # the member means (double precision) under the codes the GPU itself assigned in round 0, so that no near-tie
+    # between two centroids can blur the comparison.
+    w = wl.get(name, **CASES[name])
+    print(f"[case] pq update, large keys {w}", flush=True)
+    d = wl.generate(w, seed=13)
+    rng = np.random.default_rng(13)
+    kf = wl.to_f32(d["k"], w.dtype).copy()
+    big = rng.random(kf.shape[:3]) < 0.1
+    kf[big] *= 1500.0
+    huge = rng.random(kf.shape[:3]) < 0.002
+    kf[huge] *= -3.0e5
+    keys_h = np.ascontiguousarray(kf, dtype=np.float32) if w.dtype == "f32" else wl.f32_to_bf16_bits(kf)
+    kf = wl.to_f32(keys_h, w.dtype)
+    assert np.abs(kf).max() > 1e6 and (np.abs(kf) >= 2048).mean() > 0.01
+    init = wl.kmeans_init_indices(w, seed=13)
+    keys, init_d = pqc.to_device(keys_h, w.dtype, DEV), torch.from_numpy(init).to(DEV)
+    c0, cd0 = pqc.pq_build(w, keys, init_d, iters=0)
+    c1, _ = pqc.pq_build(w, keys, init_d, iters=1)
+    torch.cuda.synchronize()
+    c0, cd0, c1 = c0.cpu().numpy(), cd0.cpu().numpy(), c1.cpu().numpy()
+    Dm = w.sub_dim
+    for b in range(w.batch):
+        for g in range(w.n_kv_heads):
+            for j in range(w.pq_m):
+                x = kf[b, g, :, j * Dm:(j + 1) * Dm].astype(np.float64)
+                for c in range(w.pq_centroids):
+                    members = cd0[b, g, :, j] == c
+                    want = x[members].mean(0) if members.any() else c0[b, g, j, c].astype(np.float64)
+                    np.testing.assert_allclose(c1[b, g, j, c], want, rtol=2e-6, atol=2e-6, err_msg=f"{(b, g, j, c)}")
+
+
 @pytest.mark.parametrize("name", ["llama8b_32k", "llama70b_128k"])
 def test_kmeans_converges_like_the_oracle(pqc, name):
     w = wl.get(name, batch=1, n_tokens=4000)
