@@ -225,6 +225,22 @@ void launch_hist(const Shape& s, const Workspace& ws, const T* q, const float* c
   }
 }
 
+template <typename T, int G>
+void launch_finalize(pqc_ctx* ctx, const T* qt, const T* kt, const T* vt, int32_t* out_idx, float* out_attn, hipStream_t st) {
+  const Shape& s = ctx->plan.s;
+  const dim3 grid(G * s.slices + kCopyWgs + (ctx->append.key ? 1 : 0), (unsigned)(s.B * s.Hkv));
+  // Tokens that share all their codes share a score: with few distinct code words the tie class at the threshold is
+  // large (131072 tokens over 64 x 64 code pairs: up to 70 candidates), and the kernel requests more records up front.
+  double words = 1.0;
+  for (int j = 0; j < s.M; ++j) words *= s.C;
+  if (s.slices == kMaxSlices && s.N >= 16.0 * words)
+    hipLaunchKernelGGL((finalize_kernel<T, G, true, true>), grid, dim3(256), finalize_lds_bytes(s, true), st, s, ctx->ws, qt, kt, vt,
+                       out_idx, out_attn, ctx->append);
+  else
+    hipLaunchKernelGGL((finalize_kernel<T, G, true, false>), grid, dim3(256), finalize_lds_bytes(s, true), st, s, ctx->ws, qt, kt, vt,
+                       out_idx, out_attn, ctx->append);
+}
+
 // phases: bit k set = launch kernel k of the decode path (0 histogram, 1 select + attention, 2 finalize)
 template <typename T, int G, int M>
 void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uint8_t* codes, const void* k,
@@ -239,8 +255,7 @@ void launch_decode_tgm(pqc_ctx* ctx, const void* q, const float* cent, const uin
     hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<M>, true>), dim3(s.nblkC, units), dim3(256),
                        s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes));
   if (phases & 4u)
-    hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G * s.slices + kCopyWgs + (ctx->append.key ? 1 : 0), units), dim3(256),
-                       finalize_lds_bytes(s, true), st, s, ctx->ws, qt, kt, vt, out_idx, out_attn, ctx->append);
+    launch_finalize<T, G>(ctx, qt, kt, vt, out_idx, out_attn, st);
 }
 
 template <typename T, int G>
@@ -277,8 +292,7 @@ void launch_indexed_tg(pqc_ctx* ctx, const void* q, const float* cent, const uin
   hipLaunchKernelGGL((select_kernel<T, G, CodeChunks<2>, true, true>), dim3(s.nblkC, units), dim3(256),
                      s.tokC * sizeof(unsigned short), st, s, ctx->ws, qt, kt, vt, static_cast<const void*>(codes), cent,
                      pair_counts, ctx->append.key ? ctx->append.position : -1);
-  hipLaunchKernelGGL((finalize_kernel<T, G, true>), dim3(G * s.slices + kCopyWgs + (ctx->append.key ? 1 : 0), units), dim3(256),
-                     finalize_lds_bytes(s, true), st, s, ctx->ws, qt, kt, vt, out_idx, out_attn, ctx->append);
+  launch_finalize<T, G>(ctx, qt, kt, vt, out_idx, out_attn, st);
 }
 
 template <typename T>

@@ -666,7 +666,9 @@ __device__ __forceinline__ float block_sum(float v, float* sm /* [NT/64] */) {
 
 constexpr int kHdrPerThread = kCandRec / 256;  // candidate record headers per thread
 constexpr int kAccPer = 8;                     // partial states a thread keeps in flight at once (every eighth state is its own)
-constexpr int kVPer = 8;                       // candidate records per thread whose V values are requested before the ranking knows which are admitted
+constexpr int kVPer = 12;                      // candidate records per thread whose V values are requested before the ranking knows which are admitted (96 records
+                                               // with eight threads per dimension: tie classes of two-partition tables reach 70 tokens at 128K)
+constexpr int kVPerFew = 8;                    // the same with fewer threads per dimension (many units; there the tie classes are small)
 constexpr int kRankStep = 8;                    // composites read per step of the ranking loop
 constexpr int kFoldRanks = 96;                 // admitted rows whose terms meet in LDS by rank (beyond: fetched by rank from the records)
 constexpr int kMaxSlices = 4;                  // workgroups per query head, at most (32 output dimensions each)
@@ -688,12 +690,14 @@ struct AppendArgs {
   unsigned* pair_counts;  // two partitions: [units][C*C] counts that gain the token's code pair, or null
 };
 
-template <typename T, int G, bool ATTN>
+// WIDE: four workgroups per head (eight threads per output dimension); they request more candidate records up front.
+template <typename T, int G, bool ATTN, bool WIDE = false>
 __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, const T* __restrict__ q,
                                                        const T* __restrict__ kc, const T* __restrict__ vc,
                                                        int* __restrict__ out_idx, float* __restrict__ out_attn, AppendArgs ap) {
   constexpr int NT = 256, NW = 4;
   constexpr int heads = ATTN ? G : 1;
+  constexpr int VPER = WIDE ? kVPer : kVPerFew;
   const int SL = ATTN ? s.slices : 1;  // head workgroups per head
   if ((int)blockIdx.x == heads * SL + kCopyWgs) {
     // -------------------------------------------------------------- append workgroup
@@ -857,7 +861,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
   const int2 cnt0 = cnt[jc];  // list sizes of the first NT select workgroups
   float2 ml0 = make_float2(kNegBig, 0.0f);
   float a0[kAccPer];  // this thread's first states: ps, ps + nps, ...
-  float vv0[kVPer];   // V values of the candidate records ps, ps + nps, ... (this thread's dimension)
+  float vv0[VPER];    // V values of the candidate records ps, ps + nps, ... (this thread's dimension)
   if constexpr (ATTN) {
     ml0 = pml[jc];
 #pragma unroll
@@ -866,7 +870,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
     // the V values of the first candidates (in order of arrival), this workgroup's dimensions: which of them are
     // admitted is known only after the ranking, but requested now they are here by then
 #pragma unroll
-    for (int x = 0; x < kVPer; ++x)
+    for (int x = 0; x < VPER; ++x)
       vv0[x] = load_as_float<T>(reinterpret_cast<const T*>(cv.v) + (size_t)(ps + nps * x) * kD, d);
   }
   PQC_LOADS_ISSUED();
@@ -970,14 +974,14 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       if (meet && need > 0) {
         // the V values requested up front belong to the records ps + nps x in order of arrival; each admitted one's
         // term goes to the row of its rank, so that the sums below run in rank order whatever the order of arrival
-        for (int k0 = 0; k0 < n_cand; k0 += nps * kVPer) {
+        for (int k0 = 0; k0 < n_cand; k0 += nps * VPER) {
           if (k0 > 0) {  // rare: more candidates than the up-front loads cover
 #pragma unroll
-            for (int x = 0; x < kVPer; ++x)
+            for (int x = 0; x < VPER; ++x)
               vv0[x] = load_as_float<T>(reinterpret_cast<const T*>(cv.v) + (size_t)min(k0 + ps + nps * x, kCandRec - 1) * kD, d);
           }
 #pragma unroll
-          for (int x = 0; x < kVPer; ++x) {
+          for (int x = 0; x < VPER; ++x) {
             const int k = k0 + ps + nps * x;
             if (k < n_cand) {
               const int r = rankv[k];
