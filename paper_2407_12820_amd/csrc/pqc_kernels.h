@@ -669,6 +669,7 @@ constexpr int kAccPer = 8;                     // partial states a thread keeps 
 constexpr int kVPer = 12;                      // candidate records per thread whose V values are requested before the ranking knows which are admitted (96 records
                                                // with eight threads per dimension: tie classes of two-partition tables reach 70 tokens at 128K)
 constexpr int kVPerFew = 8;                    // the same with fewer threads per dimension (many units; there the tie classes are small)
+constexpr int kManyCand = 4096;                // candidates whose composites the path for large tie classes keeps in LDS
 constexpr int kRankStep = 8;                    // composites read per step of the ranking loop
 constexpr int kFoldRanks = 96;                 // admitted rows whose terms meet in LDS by rank (beyond: fetched by rank from the records)
 constexpr int kMaxSlices = 4;                  // workgroups per query head, at most (32 output dimensions each)
@@ -677,7 +678,9 @@ constexpr int kCopyWgs = 4;                    // copy workgroups per unit
 
 // dynamic LDS of finalize_kernel
 inline size_t finalize_lds_bytes(const Shape& s, bool attn) {
-  return (size_t)(4 * s.nblkC + 2) * sizeof(int) + (attn ? (size_t)kFoldRanks * (kD / s.slices) * sizeof(float) : 0);
+  const size_t terms = attn ? (size_t)kFoldRanks * (kD / s.slices) * sizeof(float) : 0;
+  const size_t many = (size_t)kManyCand * (sizeof(unsigned long long) + sizeof(int));  // the same region, when a unit has more than kCandRec candidates
+  return (size_t)(4 * s.nblkC + 2) * sizeof(int) + (terms > many ? terms : many);
 }
 
 // The code of one appended token per unit (Section 3.1: nearest centroid of each partition): nothing in the
@@ -733,7 +736,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
     if (c == 0 && ap.pair_counts) ap.pair_counts[(size_t)u * s.C * s.C + (abest[0] & 0xffu) + s.C * (abest[1] & 0xffu)] += 1u;
     return;
   }
-  extern __shared__ int dyn[];  // pre_sel[nblkC+1], pre_cand[nblkC+1], pm[nblkC], pl[nblkC], terms[kFoldRanks][kD/slices] (finalize_lds_bytes)
+  extern __shared__ int dyn[];  // pre_sel[nblkC+1], pre_cand[nblkC+1], pm[nblkC], pl[nblkC], then terms[kFoldRanks][kD/slices] or, with
+                                // more than kCandRec candidates, their composites and the admitted tokens (finalize_lds_bytes)
   __shared__ int scan_sm[2 * NW + 1];
   __shared__ float fsm[NW];
   __shared__ int ism[2 * NW];
@@ -1086,15 +1090,54 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       }
       return lo;
     };
-    auto cand_at = [&](int i) -> unsigned long long {
+    auto cand_global = [&](int i) -> unsigned long long {
       const int j = owner(i);
       return stage_u[(size_t)j * s.stageStride + s.tokC - 1 - (i - pre_cand[j])];
     };
+    // Up to kManyCand composites are fetched once into LDS (every pass over them would otherwise be a chain of
+    // memory round trips); the bytes that all of them share (the whole score, when the candidates are one tie
+    // class) need no radix pass.
+    unsigned long long* gcomp = reinterpret_cast<unsigned long long*>(terms);  // [kManyCand]
+    int* gtok = reinterpret_cast<int*>(gcomp + kManyCand);                     // [kManyCand] admitted tokens, in candidate order
+    const bool cached = n_cand <= kManyCand;
+    unsigned long long varying = ~0ull, common = 0ull;
+    if (cached && need > 0) {
+      unsigned long long a_and = ~0ull, a_or = 0ull;
+      for (int i0 = 0; i0 < n_cand; i0 += 4 * NT) {
+        unsigned long long c[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) c[x] = cand_global(min(i0 + x * NT + tid, n_cand - 1));
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          const int i = i0 + x * NT + tid;
+          if (i < n_cand) {
+            gcomp[i] = c[x];
+            a_and &= c[x];
+            a_or |= c[x];
+          }
+        }
+      }
+      if (tid < 4) rhist[tid] = tid < 2 ? 0xffffffffu : 0u;
+      __syncthreads();
+      atomicAnd(&rhist[0], (unsigned)a_and);
+      atomicAnd(&rhist[1], (unsigned)(a_and >> 32));
+      atomicOr(&rhist[2], (unsigned)a_or);
+      atomicOr(&rhist[3], (unsigned)(a_or >> 32));
+      __syncthreads();
+      common = ((unsigned long long)rhist[1] << 32) | rhist[0];
+      varying = common ^ (((unsigned long long)rhist[3] << 32) | rhist[2]);
+      __syncthreads();
+    }
+    auto cand_at = [&](int i) -> unsigned long long { return cached ? gcomp[i] : cand_global(i); };
     unsigned long long thr = ~0ull;
     if (need > 0) {
       unsigned long long prefix = 0;
       int want = need;
       for (int shift = 56; shift >= 0; shift -= 8) {
+        if (((varying >> shift) & 0xffull) == 0) {  // uniform: every candidate has this byte
+          prefix |= common & (0xffull << shift);
+          continue;
+        }
         rhist[tid] = 0u;
         __syncthreads();
         for (int i = tid; i < n_cand; i += NT) {
@@ -1118,7 +1161,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       }
       thr = prefix;
     }
-    // admitted candidates in token order, NT candidates per round: indices out, rows attended
+    // admitted candidates in token order: indices out, rows attended (all at once when they fit the LDS list, else
+    // NT candidates per round)
     AttnState<1> st;
     st.init();
     float qr[1][8];
@@ -1132,16 +1176,25 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, Workspace ws, co
       int tot;
       const int pos = block_exclusive_scan<NT>(flag, &tot, scan_sm);
       if (flag) {
-        rows_sm[pos] = composite_token(c);
+        if (cached) gtok[carry + pos] = composite_token(c); else rows_sm[pos] = composite_token(c);
         if (hq == 0 && s.I + n_above + carry + pos < s.Ktot) out[s.I + n_above + carry + pos] = composite_token(c);
       }
+      if (!cached) {
+        __syncthreads();
+        if constexpr (ATTN) {
+          auto row_at = [&](int p) -> int { return rows_sm[p]; };
+          attend_rows<T, 1, 4>(kc + (size_t)u * s.cap * kD, vc + (size_t)u * s.cap * kD, s.N, row_at, tot, w * 16, NW * 16, qr, st);
+        }
+        __syncthreads();
+      }
+      carry += tot;
+    }
+    if (cached) {
       __syncthreads();
       if constexpr (ATTN) {
-        auto row_at = [&](int p) -> int { return rows_sm[p]; };
-        attend_rows<T, 1, 4>(kc + (size_t)u * s.cap * kD, vc + (size_t)u * s.cap * kD, s.N, row_at, tot, w * 16, NW * 16, qr, st);
+        auto row_at = [&](int p) -> int { return gtok[p]; };
+        attend_rows<T, 1, 4>(kc + (size_t)u * s.cap * kD, vc + (size_t)u * s.cap * kD, s.N, row_at, carry, w * 16, NW * 16, qr, st);
       }
-      __syncthreads();
-      carry += tot;
     }
     if constexpr (ATTN) {
       stash_wave_state<T, 1>(st, red);
